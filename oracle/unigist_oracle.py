@@ -1,0 +1,251 @@
+"""Plain fp64 definition of UniGist's gist-masked causal attention (CPU, numpy).
+
+THIS IS TEST INFRASTRUCTURE.  It is the yardstick the HIP kernels are compared
+against; it is slow on purpose, shares no code with the kernels and must never
+be imported by the product package.
+
+What it follows
+---------------
+* Sequence layout: the gist-augmented sequence of Sec. 4.1, Eq. 2 with no sink
+  prefix (s = 0): r raw tokens, one gist, r raw tokens, one gist, ...  With
+  0-based positions a position p holds a gist iff (p + 1) % (r + 1) == 0.  A
+  trailing group of fewer than r raw tokens has no closing gist.
+* Visible set: Sec. 4.1, Eq. 3 -- (gists U local window) intersected with the
+  causal set {j <= t}, the same rule for raw and gist queries.  The local window
+  is read as a per-token sliding window counted in interleaved positions:
+  key j is inside the window of query i iff 0 <= i - j < W.  (The paper words the
+  window in whole gist units; the sliding reading is the one the workload
+  definitions of this build fix.)
+* Everything else is ordinary softmax attention: S = Q K^T / sqrt(D), masked
+  entries are -inf, P = softmax over keys, out = P V, lse = ln sum_j exp(S_ij).
+  The gradients are the exact derivative of l = sum(out * dout).
+* Decode (Sec. 4.3, "Inference"): one query over a cache from which the
+  invisible raw tokens have already been removed, so every cached key counts.
+
+There is no tiling, no skipping and no reordering here.  Long sequences are
+handled a block of query rows at a time purely so that the L x L score matrix
+is never resident; every row is still scored against every key it is allowed
+to be scored against and masked by evaluating the predicate pair by pair.
+
+Pins (tests/test_oracle_*.py): hand-derived visible sets, closed-form pair
+counts, brute-force loops on tiny inputs, W >= L == causal library attention,
+r >= L == banded library attention, q == 0 closed form, finite differences,
+library autograd.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+__all__ = [
+    "is_gist", "visible", "mask_rows", "count_visible",
+    "attn_fwd_head", "attn_bwd_head", "attn_fwd", "attn_bwd",
+    "attn_fwd_rows", "attn_dq_rows", "decode", "compressed_cache_positions",
+]
+
+
+# --------------------------------------------------------------------------
+# layout and mask (Eq. 2, Eq. 3)
+# --------------------------------------------------------------------------
+def is_gist(p, r):
+    """True where 0-based position p holds a gist token (Eq. 2 with s = 0).
+
+    r is the compression ratio (raw tokens per gist).  Python ints are used for
+    r + 1 so that a huge r ("no gists at all") cannot overflow.
+    """
+    p = np.asarray(p, dtype=np.int64)
+    period = int(r) + 1
+    return (p + 1) % period == 0
+
+
+def visible(i, j, r, W):
+    """Eq. 3 with the sliding-window reading: may query i attend to key j?"""
+    i = np.asarray(i, dtype=np.int64)
+    j = np.asarray(j, dtype=np.int64)
+    causal = j <= i
+    in_window = (i - j) < int(W)
+    return causal & (is_gist(j, r) | in_window)
+
+
+def mask_rows(rows, L, r, W):
+    """Boolean [len(rows), L] matrix of visible(i, j) for the given query rows."""
+    rows = np.asarray(rows, dtype=np.int64)
+    cols = np.arange(L, dtype=np.int64)
+    return visible(rows[:, None], cols[None, :], r, W)
+
+
+def count_visible(L, r, W, block=1024):
+    """Number of visible (i, j) pairs, by evaluating the predicate on every pair."""
+    total = 0
+    for i0 in range(0, L, block):
+        rows = np.arange(i0, min(L, i0 + block))
+        total += int(np.count_nonzero(mask_rows(rows, L, r, W)))
+    return total
+
+
+# --------------------------------------------------------------------------
+# one head, a set of query rows against all keys
+# --------------------------------------------------------------------------
+def _softmax_rows(q_rows, k, rows, r, W):
+    """Scores, mask and softmax of the given query rows against every key.
+
+    Returns P [n, L] and lse [n]; masked entries of P are exactly 0.
+    """
+    L, D = k.shape
+    S = (q_rows @ k.T) / math.sqrt(D)
+    M = mask_rows(rows, L, r, W)
+    S = np.where(M, S, -np.inf)
+    m = S.max(axis=1)
+    E = np.exp(S - m[:, None])
+    Z = E.sum(axis=1)
+    P = E / Z[:, None]
+    lse = m + np.log(Z)
+    return P, lse
+
+
+def attn_fwd_head(q, k, v, r, W, block=512):
+    """Forward for one head.  q, k, v: float64 [L, D].  Returns out [L, D], lse [L]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    L = q.shape[0]
+    out = np.empty((L, v.shape[1]))
+    lse = np.empty(L)
+    for i0 in range(0, L, block):
+        rows = np.arange(i0, min(L, i0 + block))
+        P, lse[rows] = _softmax_rows(q[rows], k, rows, r, W)
+        out[rows] = P @ v
+    return out, lse
+
+
+def attn_bwd_head(q, k, v, dout, r, W, block=512):
+    """Gradients of l = sum(out * dout) for one head.
+
+    dV_j = sum_i P_ij dO_i;  dP_ij = dO_i . v_j;  delta_i = sum_j P_ij dP_ij;
+    dS_ij = P_ij (dP_ij - delta_i);  dQ_i = sum_j dS_ij k_j / sqrt(D);
+    dK_j = sum_i dS_ij q_i / sqrt(D).
+    Returns dq, dk, dv (all [L, D]).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    L, D = q.shape
+    inv = 1.0 / math.sqrt(D)
+    dq = np.empty((L, D))
+    dk = np.zeros((L, D))
+    dv = np.zeros((L, D))
+    for i0 in range(0, L, block):
+        rows = np.arange(i0, min(L, i0 + block))
+        P, _ = _softmax_rows(q[rows], k, rows, r, W)
+        dO = dout[rows]
+        dv += P.T @ dO
+        dP = dO @ v.T
+        delta = (P * dP).sum(axis=1)
+        dS = P * (dP - delta[:, None])
+        dq[rows] = (dS @ k) * inv
+        dk += (dS.T @ q[rows]) * inv
+    return dq, dk, dv
+
+
+# --------------------------------------------------------------------------
+# [B, H, L, D] tensors with grouped-query heads
+# --------------------------------------------------------------------------
+def _kv_head(h, Hq, Hkv):
+    assert Hq % Hkv == 0
+    return h // (Hq // Hkv)
+
+
+def attn_fwd(q, k, v, r, W, block=512):
+    """q [B,Hq,L,D], k/v [B,Hkv,L,D]  ->  out [B,Hq,L,D], lse [B,Hq,L] (float64)."""
+    q = np.asarray(q, dtype=np.float64)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    out = np.empty((B, Hq, L, D))
+    lse = np.empty((B, Hq, L))
+    for b in range(B):
+        for h in range(Hq):
+            g = _kv_head(h, Hq, Hkv)
+            out[b, h], lse[b, h] = attn_fwd_head(q[b, h], k[b, g], v[b, g], r, W, block)
+    return out, lse
+
+
+def attn_bwd(q, k, v, dout, r, W, block=512):
+    """Returns dq [B,Hq,L,D], dk, dv [B,Hkv,L,D]; dk/dv summed over the q heads of a group."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    dq = np.empty((B, Hq, L, D))
+    dk = np.zeros((B, Hkv, L, D))
+    dv = np.zeros((B, Hkv, L, D))
+    for b in range(B):
+        for h in range(Hq):
+            g = _kv_head(h, Hq, Hkv)
+            dq[b, h], dk_h, dv_h = attn_bwd_head(q[b, h], k[b, g], v[b, g], dout[b, h], r, W, block)
+            dk[b, g] += dk_h
+            dv[b, g] += dv_h
+    return dq, dk, dv
+
+
+# --------------------------------------------------------------------------
+# sampled rows (out, lse and dq of a row depend on that row of q/dout only)
+# --------------------------------------------------------------------------
+def attn_fwd_rows(q, k, v, rows, r, W):
+    """One head: out and lse for a chosen set of query rows.  q, k, v [L, D]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    rows = np.asarray(rows, dtype=np.int64)
+    P, lse = _softmax_rows(q[rows], k, rows, r, W)
+    return P @ v, lse
+
+
+def attn_dq_rows(q, k, v, dout, rows, r, W):
+    """One head: dq for a chosen set of query rows."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    rows = np.asarray(rows, dtype=np.int64)
+    D = q.shape[1]
+    P, _ = _softmax_rows(q[rows], k, rows, r, W)
+    dP = dout[rows] @ v.T
+    delta = (P * dP).sum(axis=1)
+    dS = P * (dP - delta[:, None])
+    return (dS @ k) / math.sqrt(D)
+
+
+# --------------------------------------------------------------------------
+# decode over the compressed cache (Sec. 4.3)
+# --------------------------------------------------------------------------
+def compressed_cache_positions(t, r, W):
+    """Positions a cache holds when position t is the query (Fig. 4): every gist
+    up to t plus the raw tokens still inside t's window.  Ascending order."""
+    j = np.arange(t + 1, dtype=np.int64)
+    return j[visible(np.int64(t), j, r, W)]
+
+
+def decode(q, kcache, vcache, seqlens=None):
+    """q [B,Hq,D]; kcache, vcache [B,Hkv,Lk,D]; seqlens [B] or None (= all Lk).
+
+    Every cached key of a sequence is visible.  Returns out [B,Hq,D], lse [B,Hq].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    kcache = np.asarray(kcache, dtype=np.float64)
+    vcache = np.asarray(vcache, dtype=np.float64)
+    B, Hq, D = q.shape
+    Hkv, Lk = kcache.shape[1], kcache.shape[2]
+    out = np.empty((B, Hq, D))
+    lse = np.empty((B, Hq))
+    for b in range(B):
+        n = Lk if seqlens is None else int(seqlens[b])
+        for h in range(Hq):
+            g = _kv_head(h, Hq, Hkv)
+            s = (kcache[b, g, :n] @ q[b, h]) / math.sqrt(D)
+            m = s.max()
+            e = np.exp(s - m)
+            z = e.sum()
+            out[b, h] = (e / z) @ vcache[b, g, :n]
+            lse[b, h] = m + math.log(z)
+    return out, lse

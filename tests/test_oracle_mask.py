@@ -1,0 +1,88 @@
+"""Pins for the oracle's layout and mask predicate (Sec. 4.1, Eq. 2 and Eq. 3)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from conftest import GOLDEN
+
+
+def _read_rows(path):
+    with open(path) as f:
+        return [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def test_hand_derived_visible_sets():
+    rows = _read_rows(os.path.join(GOLDEN, "visible_sets_L10_r4_W3.txt"))
+    M = oracle.mask_rows(np.arange(10), 10, 4, 3)
+    assert len(rows) == 10
+    for ln in rows:
+        i, keys = ln.split(":")
+        want = sorted(int(t) for t in keys.split())
+        got = np.nonzero(M[int(i)])[0].tolist()
+        assert got == want, (i, got, want)
+
+
+def test_gist_positions_follow_eq2():
+    # r raw tokens then one gist, repeated; trailing partial unit has no gist
+    r, L = 4, 23
+    layout = []
+    while len(layout) < L:
+        layout += ["x"] * r + ["g"]
+    layout = layout[:L]
+    got = oracle.is_gist(np.arange(L), r)
+    assert got.tolist() == [c == "g" for c in layout]
+    assert int(got.sum()) == L // (r + 1)
+
+
+@pytest.mark.parametrize("line", _read_rows(os.path.join(GOLDEN, "n_vis_closed_form.txt")))
+def test_pair_counts_match_closed_form(line):
+    L, r, W, want = (int(t) for t in line.split())
+    if L > 40000:
+        # 1.7e10 pairs is too slow pair by pair: count per row on a strided row sample
+        # and compare each row with the closed form instead.
+        rows = np.unique(np.concatenate([np.arange(0, L, 997), [W - 1, W, W + r, L - 1]]))
+        M = oracle.mask_rows(rows, L, r, W)
+        got = M.sum(axis=1)
+        wantrow = np.minimum(rows + 1, W) + np.maximum(0, (rows - W + 1) // (r + 1))
+        assert np.array_equal(got, wantrow)
+        return
+    assert oracle.count_visible(L, r, W) == want
+
+
+def test_window_covering_everything_is_causal():
+    L = 97
+    for W in (L, L + 5, 10**9):
+        M = oracle.mask_rows(np.arange(L), L, 4, W)
+        assert np.array_equal(M, np.tril(np.ones((L, L), dtype=bool)))
+
+
+def test_no_gists_is_a_band():
+    L, W = 101, 7
+    for r in (L, L + 3, 2**31 - 1):
+        M = oracle.mask_rows(np.arange(L), L, r, W)
+        band = np.tril(np.ones((L, L), dtype=bool)) & ~np.tril(np.ones((L, L), dtype=bool), -W)
+        assert np.array_equal(M, band)
+
+
+def test_every_row_sees_itself_and_is_causal():
+    L = 64
+    for r, W in [(1, 1), (4, 1), (4, 5), (8, 17), (3, 64)]:
+        M = oracle.mask_rows(np.arange(L), L, r, W)
+        assert M.diagonal().all()
+        assert not np.triu(M, 1).any()
+        # every earlier gist is visible, every raw key outside the window is not
+        g = oracle.is_gist(np.arange(L), r)
+        for i in range(L):
+            for j in range(i + 1):
+                assert M[i, j] == (g[j] or i - j < W)
+
+
+def test_compressed_cache_positions():
+    # t = 9 in the micro-example sees {4, 7, 8, 9}
+    assert oracle.compressed_cache_positions(9, 4, 3).tolist() == [4, 7, 8, 9]
+    # cache size = window + gists left of it
+    t, r, W = 147455, 8, 1024
+    pos = oracle.compressed_cache_positions(t, r, W)
+    assert len(pos) == W + (t - W + 1) // (r + 1)
