@@ -1,0 +1,146 @@
+/*
+ * libunigist -- gist-masked causal attention for AMD MI355X (gfx950).
+ *
+ * The operation is the sparse autoregressive attention of UniGist (Sec. 4.1):
+ * the input sequence already carries one gist token after every r raw tokens
+ * (Eq. 2, no sink prefix), positions are 0-based, and
+ *
+ *     gist(p)  <=>  (p + 1) % (r + 1) == 0
+ *     vis(i,j) <=>  j <= i  and  ( gist(j)  or  i - j < W )            (Eq. 3)
+ *
+ * i.e. a query attends to itself, to every earlier gist and to the raw tokens
+ * among the W most recent positions (sliding window counted in interleaved
+ * positions).  The same rule holds for raw and gist queries.  r >= L means "no
+ * gists" (pure sliding window); W >= L means full causal attention.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     allocates and frees no device memory, keeps no state, does not synchronise:
+ *     work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns at once.
+ *   - Tensors are contiguous, head-major: q, out, dout, dq are [B, Hq, L, D];
+ *     k, v, dk, dv are [B, Hkv, L, D]; lse is [B, Hq, L] float.  D is innermost.
+ *     Query head h reads kv head h / (Hq / Hkv).
+ *   - dt selects the element type of q/k/v/out/dout/dq/dk/dv: bf16 (MFMA kernels,
+ *     fp32 accumulation and softmax) or fp32 (plain-ALU debug kernels).  lse and
+ *     the workspace are always fp32.
+ *   - The softmax scale is 1/sqrt(D) and lse = ln sum_j exp(scale * q_i . k_j)
+ *     over the visible j (natural log).
+ *   - Outputs are fully overwritten; they need no initialisation.
+ *   - Errors are return codes.  Nothing is launched unless UNIGIST_OK is returned,
+ *     except that UNIGIST_ELAUNCH reports a HIP launch failure.
+ */
+#ifndef UNIGIST_H
+#define UNIGIST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    UNIGIST_OK = 0,
+    UNIGIST_EINVAL = 1,       /* null pointer, non-positive size, Hq % Hkv != 0, workspace too small */
+    UNIGIST_EUNSUPPORTED = 2, /* head dim or dtype the kernels are not built for */
+    UNIGIST_ELAUNCH = 3       /* HIP reported an error at launch */
+} unigist_status;
+
+typedef enum { UNIGIST_BF16 = 0, UNIGIST_F32 = 1 } unigist_dtype;
+
+/* Human-readable name of a status code (static storage). */
+const char* unigist_status_str(unigist_status s);
+
+/*
+ * Forward (Sec. 4.1 Eq. 3 mask, Sec. 4.2 block skipping):
+ *   out_i = sum_j softmax_j(scale * q_i . k_j | vis(i,j)) v_j,   lse_i as above.
+ * q, k, v: in.  out [B,Hq,L,D] (dt), lse [B,Hq,L] (float): out.
+ * Requires B, Hq, Hkv, L, W >= 1, r >= 1, Hq % Hkv == 0, D in {64, 128}.
+ */
+unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                                int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                unigist_dtype dt, void* hip_stream);
+
+/*
+ * Backward of l = sum(out * dout) through the forward above.
+ * q, k, v, out, lse: the forward's inputs and outputs (in).  dout: in.
+ * dq [B,Hq,L,D], dk, dv [B,Hkv,L,D] (dt): out; dk and dv are summed over the
+ * Hq/Hkv query heads sharing a kv head.  No atomics are used, so results are
+ * bitwise reproducible run to run.
+ * workspace: device scratch of at least unigist_attn_bwd_workspace(...) bytes,
+ * 256-byte aligned, contents undefined on entry and exit.
+ */
+unigist_status unigist_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                                const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
+/* Bytes of workspace unigist_attn_bwd needs for this shape (0 on invalid arguments). */
+size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                  unigist_dtype dt);
+
+/*
+ * Decode over the compressed KV cache (Sec. 4.3, Fig. 4): the raw tokens that have
+ * left the window were physically removed, so every cached key of a sequence is
+ * visible; the order of the keys in the cache is irrelevant.
+ *   q [B,Hq,D]; kcache, vcache [B,Hkv,Lk_max,D] (dt): in.
+ *   seqlens: device int32 [B], number of valid keys per sequence (each in
+ *            [1, Lk_max]); NULL means Lk_max for all.
+ *   out [B,Hq,D] (dt): out.  lse [B,Hq] float: out, may be NULL.
+ * Split-K over the keys with a log-sum-exp combine (FlashDecoding style).
+ * workspace: at least unigist_decode_workspace(...) bytes, 256-byte aligned.
+ */
+unigist_status unigist_decode(const void* q, const void* kcache, const void* vcache, void* out,
+                              float* lse, int B, int Hq, int Hkv, int Lk_max, const int* seqlens,
+                              int D, unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt);
+
+/*
+ * Block map (Sec. 4.2: with a fixed compression ratio the visible blocks are known in
+ * closed form and need not be stored; this builder materialises them on the HOST for
+ * tests and for the live-tile report).  The sequence is cut into query tiles of Bm rows
+ * and key tiles of Bn columns.  Query tile t walks two disjoint phases:
+ *   window phase: the contiguous key tiles win_first[t] .. win_last[t] (inclusive), pairs
+ *                 inside them are subject to the full predicate vis(i,j);
+ *   gist phase:   the first n_far_gists[t] gists of the sequence, taken as a compact
+ *                 list (gist g sits at position (r+1)g + r), Bn per tile; every one of
+ *                 them lies left of the window phase and is visible to every row of t.
+ * Transposed view, for the dK/dV pass: window key tile c is visited by query tiles
+ * qt_first[c] .. qt_last[c]; compact gist tile g by query tiles gist_qt_first[g] ..
+ * n_qtiles-1 (== n_qtiles if none).
+ * All arrays are host memory owned by the map; free with unigist_blockmap_free.
+ */
+typedef struct unigist_blockmap {
+    int L, r, W, Bm, Bn;
+    int n_qtiles;        /* ceil(L / Bm) */
+    int n_ktiles;        /* ceil(L / Bn) */
+    int n_gists;         /* floor(L / (r+1)) */
+    int n_gtiles;        /* compact gist tiles any query tile visits */
+    int* win_first;      /* [n_qtiles] */
+    int* win_last;       /* [n_qtiles] */
+    int* n_far_gists;    /* [n_qtiles] */
+    int* n_full;         /* [n_qtiles] window tiles needing no mask */
+    int* qt_first;       /* [n_ktiles] */
+    int* qt_last;        /* [n_ktiles] */
+    int* gist_qt_first;  /* [n_gtiles] */
+    int64_t live_tiles;    /* window + gist tiles over all query tiles */
+    int64_t masked_tiles;  /* of those, window tiles that need the in-tile mask */
+    int64_t causal_tiles;  /* tiles a dense causal kernel would visit at the same Bm, Bn */
+    int64_t n_vis;         /* visible pairs, closed form */
+} unigist_blockmap;
+
+/* Requires L, W, Bm, Bn >= 1, r >= 1.  *out is set only on UNIGIST_OK. */
+unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, int Bn, unigist_blockmap** out);
+void unigist_blockmap_free(unigist_blockmap* m);
+
+/* Tile sizes the forward / backward kernels use for head dim D (for the live-tile report). */
+void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIGIST_H */

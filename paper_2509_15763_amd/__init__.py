@@ -1,0 +1,14 @@
+"""libunigist: gist-masked causal attention (UniGist, Sec. 4.1-4.3) for MI355X.
+
+All arithmetic runs in the HIP kernels of `libunigist.so`; this package only
+marshals arguments (PyTorch supplies device memory and streams).  Importing the
+package does not load the library; the first call does, and fails loudly if the
+library has not been built.
+"""
+from .binding import (  # noqa: F401
+    UNIGIST_BF16, UNIGIST_F32, UnigistError, lib_path, load,
+    unigist_attn_fwd, unigist_attn_bwd, unigist_attn_bwd_workspace,
+    unigist_decode, unigist_decode_workspace, unigist_blockmap_build,
+    unigist_status_str, unigist_tile_sizes,
+    attn_fwd, attn_bwd, decode, n_vis,
+)

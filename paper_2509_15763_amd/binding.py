@@ -1,0 +1,214 @@
+"""ctypes binding of libunigist.so.  Same names as the C ABI (include/unigist.h);
+argument marshalling only.  Tensors are torch tensors on the GPU; nothing here
+computes anything and there is no CPU fallback."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+UNIGIST_BF16 = 0
+UNIGIST_F32 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = [
+    "unigist_status_str", "unigist_attn_fwd", "unigist_attn_bwd", "unigist_attn_bwd_workspace",
+    "unigist_decode", "unigist_decode_workspace", "unigist_blockmap_build", "unigist_blockmap_free",
+    "unigist_tile_sizes",
+]
+
+
+class UnigistError(RuntimeError):
+    pass
+
+
+class _BlockMap(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("L", "r", "W", "Bm", "Bn", "n_qtiles", "n_ktiles", "n_gists", "n_gtiles")] + \
+               [(n, C.POINTER(C.c_int)) for n in ("win_first", "win_last", "n_far_gists", "n_full", "qt_first",
+                                                   "qt_last", "gist_qt_first")] + \
+               [(n, C.c_int64) for n in ("live_tiles", "masked_tiles", "causal_tiles", "n_vis")]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libunigist.so")
+
+
+def load():
+    """Load libunigist.so (once).  Raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise UnigistError(f"{path} is missing: build it with `python -m paper_2509_15763_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = C.CDLL(path)
+    vp, ip, sz, fp = C.c_void_p, C.c_int, C.c_size_t, C.c_void_p
+    lib.unigist_status_str.restype = C.c_char_p
+    lib.unigist_status_str.argtypes = [ip]
+    lib.unigist_attn_fwd.restype = ip
+    lib.unigist_attn_fwd.argtypes = [vp, vp, vp, vp, fp] + [ip] * 7 + [ip, vp]
+    lib.unigist_attn_bwd.restype = ip
+    lib.unigist_attn_bwd.argtypes = [vp] * 9 + [ip] * 7 + [ip, vp, sz, vp]
+    lib.unigist_attn_bwd_workspace.restype = sz
+    lib.unigist_attn_bwd_workspace.argtypes = [ip] * 7 + [ip]
+    lib.unigist_decode.restype = ip
+    lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
+    lib.unigist_decode_workspace.restype = sz
+    lib.unigist_decode_workspace.argtypes = [ip] * 5 + [ip]
+    lib.unigist_blockmap_build.restype = ip
+    lib.unigist_blockmap_build.argtypes = [ip] * 5 + [C.POINTER(C.POINTER(_BlockMap))]
+    lib.unigist_blockmap_free.restype = None
+    lib.unigist_blockmap_free.argtypes = [C.POINTER(_BlockMap)]
+    lib.unigist_tile_sizes.restype = None
+    lib.unigist_tile_sizes.argtypes = [ip, ip, C.POINTER(ip), C.POINTER(ip)]
+    _LIB = lib
+    return lib
+
+
+def _check(st: int, what: str):
+    if st != 0:
+        raise UnigistError(f"{what}: {unigist_status_str(st)} (status {st})")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return UNIGIST_BF16
+    if t.dtype == torch.float32:
+        return UNIGIST_F32
+    raise UnigistError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise UnigistError("libunigist takes device tensors only (no CPU path)")
+        if not t.is_contiguous():
+            raise UnigistError("tensors must be contiguous [B,H,L,D]")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ---------------------------------------------------------------- raw ABI, same names
+def unigist_status_str(st: int) -> str:
+    return load().unigist_status_str(int(st)).decode()
+
+
+def unigist_attn_fwd(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, dt, stream=None) -> int:
+    return load().unigist_attn_fwd(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, dt, stream)
+
+
+def unigist_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws, ws_bytes, stream=None) -> int:
+    return load().unigist_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws, ws_bytes,
+                                   stream)
+
+
+def unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt) -> int:
+    return load().unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt)
+
+
+def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream=None) -> int:
+    return load().unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream)
+
+
+def unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt) -> int:
+    return load().unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt)
+
+
+def unigist_tile_sizes(D, dt):
+    bm, bn = C.c_int(0), C.c_int(0)
+    load().unigist_tile_sizes(D, dt, C.byref(bm), C.byref(bn))
+    return bm.value, bn.value
+
+
+def unigist_blockmap_build(L, r, W, Bm, Bn) -> dict:
+    """Host block map as a dict of python lists / ints (the C object is freed before returning)."""
+    p = C.POINTER(_BlockMap)()
+    _check(load().unigist_blockmap_build(L, r, W, Bm, Bn, C.byref(p)), "unigist_blockmap_build")
+    try:
+        m = p.contents
+        d = {n: getattr(m, n) for n in ("L", "r", "W", "Bm", "Bn", "n_qtiles", "n_ktiles", "n_gists", "n_gtiles",
+                                        "live_tiles", "masked_tiles", "causal_tiles", "n_vis")}
+        for n in ("win_first", "win_last", "n_far_gists", "n_full"):
+            d[n] = [getattr(m, n)[i] for i in range(m.n_qtiles)]
+        for n in ("qt_first", "qt_last"):
+            d[n] = [getattr(m, n)[i] for i in range(m.n_ktiles)]
+        d["gist_qt_first"] = [m.gist_qt_first[i] for i in range(m.n_gtiles)]
+        return d
+    finally:
+        load().unigist_blockmap_free(p)
+
+
+def n_vis(L, r, W) -> int:
+    """Visible (query, key) pairs of one head: the unit the FLOP counts are quoted in."""
+    return unigist_blockmap_build(L, r, W, 128, 128)["n_vis"]
+
+
+# ---------------------------------------------------------------- conveniences (allocate outputs, check status)
+def attn_fwd(q, k, v, r, W):
+    """q [B,Hq,L,D], k/v [B,Hkv,L,D] on the GPU -> out [B,Hq,L,D], lse [B,Hq,L] fp32."""
+    _dev(q, k, v)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape != (B, Hkv, L, D) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise UnigistError("q/k/v shapes or dtypes disagree")
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, L, device=q.device, dtype=torch.float32)
+    _check(unigist_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                            B, Hq, Hkv, L, D, int(r), int(W), _dt(q), _stream()), "unigist_attn_fwd")
+    return out, lse
+
+
+def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None):
+    """-> dq [B,Hq,L,D], dk, dv [B,Hkv,L,D]."""
+    _dev(q, k, v, out, lse, dout)
+    B, Hq, L, D = q.shape
+    Hkv = k.shape[1]
+    dt = _dt(q)
+    if out.shape != q.shape or dout.shape != q.shape or lse.shape != (B, Hq, L) or lse.dtype != torch.float32:
+        raise UnigistError("out/dout/lse shapes or dtypes disagree")
+    if k.shape != (B, Hkv, L, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:
+        raise UnigistError("q/k/v/out/dout shapes or dtypes disagree")
+    need = unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, int(r), int(W), dt)
+    if need == 0:
+        raise UnigistError("unigist_attn_bwd_workspace: invalid or unsupported shape")
+    if workspace is None:
+        workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    _check(unigist_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(),
+                            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D, int(r), int(W), dt,
+                            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
+           "unigist_attn_bwd")
+    return dq, dk, dv
+
+
+def decode(q, kcache, vcache, seqlens=None, want_lse=True, workspace=None):
+    """q [B,Hq,D], kcache/vcache [B,Hkv,Lk,D], seqlens int32 [B] on the GPU or None -> out [B,Hq,D], lse [B,Hq]."""
+    _dev(q, kcache, vcache, seqlens)
+    B, Hq, D = q.shape
+    Hkv, Lk = kcache.shape[1], kcache.shape[2]
+    dt = _dt(q)
+    if kcache.shape != (B, Hkv, Lk, D) or vcache.shape != kcache.shape or kcache.dtype != q.dtype or vcache.dtype != q.dtype:
+        raise UnigistError("q/kcache/vcache shapes or dtypes disagree")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or seqlens.shape != (B,)):
+        raise UnigistError("seqlens must be int32 [B]")
+    need = unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt)
+    if need == 0:
+        raise UnigistError("unigist_decode_workspace: invalid or unsupported shape")
+    if workspace is None:
+        workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, device=q.device, dtype=torch.float32) if want_lse else None
+    _check(unigist_decode(q.data_ptr(), kcache.data_ptr(), vcache.data_ptr(), out.data_ptr(),
+                          lse.data_ptr() if want_lse else None, B, Hq, Hkv, Lk,
+                          seqlens.data_ptr() if seqlens is not None else None, D, dt,
+                          workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
+           "unigist_decode")
+    return out, lse

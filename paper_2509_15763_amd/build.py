@@ -1,0 +1,64 @@
+"""Builds libunigist.so (HIP, gfx950 only) in-tree with hipcc.
+
+Run as `python -m paper_2509_15763_amd.build` or through `__graft_entry__.build()`.
+hipcc cross-compiles without a GPU.  Objects go to `_build/` (not committed); the
+shared library lands next to this file so that it travels with the source tree.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libunigist.so")
+SOURCES = ["api.cpp", "blockmap.cpp", "attn_simple.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "decode.hip"]
+
+FLAGS = [
+    "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    # packed fp32 VALU ops are kept off on purpose (see the build notes of this library)
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def _hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found: libunigist needs the ROCm toolchain")
+    return exe
+
+
+def _compile(src: str, objdir: str, extra) -> str:
+    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
+    warn = "\n".join(ln for ln in r.stderr.splitlines() if "packed-fp32-ops" not in ln and ln.strip())
+    if warn:
+        sys.stderr.write(warn + "\n")
+    return obj
+
+
+def build_library(extra_flags=(), jobs: int = 6) -> str:
+    objdir = os.path.join(ROOT, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(lambda s: _compile(s, objdir, list(extra_flags)), SOURCES))
+    tmp = LIB + ".tmp"
+    r = subprocess.run([_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", tmp],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library())

@@ -1,0 +1,128 @@
+// C ABI of libunigist: argument validation and dispatch.  No device memory is
+// allocated here and nothing synchronises; kernels are enqueued on the caller's stream.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "common.h"
+
+using namespace unigist;
+
+namespace {
+
+constexpr int kMaxL = 1 << 24;  // index arithmetic in the kernels is 32-bit per head
+
+bool plain_alu_forced() {
+    const char* e = getenv("UNIGIST_DEBUG_PLAIN_ALU");
+    return e && e[0] == '1';
+}
+
+unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1 || D < 1 || r < 1 || W < 1) return UNIGIST_EINVAL;
+    if (Hq % Hkv != 0) return UNIGIST_EINVAL;
+    if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
+    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (L > kMaxL || B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
+    return UNIGIST_OK;
+}
+
+AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W) {
+    AttnShape s;
+    s.B = B;
+    s.Hq = Hq;
+    s.Hkv = Hkv;
+    s.L = L;
+    s.D = D;
+    s.rp1 = r >= L ? L + 1 : r + 1;  // r >= L: no position holds a gist
+    s.W = W > L ? L : W;
+    s.scale = 1.0f / sqrtf((float)D);
+    return s;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" const char* unigist_status_str(unigist_status s) {
+    switch (s) {
+        case UNIGIST_OK: return "ok";
+        case UNIGIST_EINVAL: return "invalid argument";
+        case UNIGIST_EUNSUPPORTED: return "unsupported head dim, dtype or size";
+        case UNIGIST_ELAUNCH: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+extern "C" void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn) {
+    (void)D;
+    if (Bm) *Bm = dt == UNIGIST_BF16 ? 128 : 64;
+    if (Bn) *Bn = dt == UNIGIST_BF16 ? 64 : 1;
+}
+
+extern "C" unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                                           int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
+                                           void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t e;
+    if (dt == UNIGIST_BF16 && !plain_alu_forced())
+        e = launch_fwd_mfma(q, k, v, out, lse, s, stream);
+    else
+        e = launch_fwd_simple(q, k, v, out, lse, s, dt, stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                             unigist_dtype dt) {
+    if (check_attn(B, Hq, Hkv, L, D, r, W, dt) != UNIGIST_OK) return 0;
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    size_t delta = align256((size_t)B * Hq * L * sizeof(float));
+    size_t mfma = dt == UNIGIST_BF16 ? bwd_mfma_workspace(s) : 0;
+    return delta > mfma ? delta : mfma;
+}
+
+extern "C" unigist_status unigist_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                                           const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                           int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
+    if (workspace_bytes < unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt)) return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t e;
+    if (dt == UNIGIST_BF16 && !plain_alu_forced())
+        e = launch_bwd_mfma(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, stream);
+    else
+        e = launch_bwd_simple(q, k, v, out, lse, dout, dq, dk, dv, (float*)workspace, s, dt, stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || Hq % Hkv != 0) return 0;
+    if ((D != 64 && D != 128) || (dt != UNIGIST_BF16 && dt != UNIGIST_F32)) return 0;
+    const int ns = decode_num_splits(B, Hq, Hkv, Lk_max);
+    return align256((size_t)B * Hq * ns * (D + 2) * sizeof(float));
+}
+
+extern "C" unigist_status unigist_decode(const void* q, const void* kcache, const void* vcache, void* out,
+                                         float* lse, int B, int Hq, int Hkv, int Lk_max, const int* seqlens, int D,
+                                         unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                         void* hip_stream) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || D < 1) return UNIGIST_EINVAL;
+    if (Hq % Hkv != 0) return UNIGIST_EINVAL;
+    if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
+    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
+    if (!q || !kcache || !vcache || !out || !workspace) return UNIGIST_EINVAL;
+    if (workspace_bytes < unigist_decode_workspace(B, Hq, Hkv, Lk_max, D, dt)) return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    hipError_t e = launch_decode(q, kcache, vcache, out, lse, B, Hq, Hkv, Lk_max, seqlens, D, dt,
+                                 (float*)workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}

@@ -1,0 +1,293 @@
+// Forward kernel of gist-masked attention for gfx950: bf16 MFMA, fp32 online softmax.
+//
+// Mask (Sec. 4.1, Eq. 3): query i sees key j <= i iff j holds a gist or i - j < W.
+// Block skipping (Sec. 4.2) is done without moving any data: a query tile walks
+//   1. the compact list of gists left of its window (gist g sits at row (r+1)g + r of
+//      K/V, gathered by address arithmetic while staging the tile; all of them are
+//      visible to every row, so no mask), then
+//   2. the contiguous key tiles from the window's first tile to the diagonal, where the
+//      full predicate is applied only on tiles that can contain an invisible pair.
+//
+// Work split: one workgroup = 128 query rows of one head, 4 waves x 32 rows; 64 keys
+// per step.  Scores are computed transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16,
+// so that one lane owns one query column: row max and row sum are in-lane reductions
+// plus one exchange between the wave's halves, and the accumulator registers of S^T are
+// already the B operand of O^T += V^T P^T.  V^T fragments come straight out of the
+// row-major V tile in LDS through ds_read_b64_tr_b16.
+#include "common.h"
+
+namespace unigist {
+namespace {
+
+constexpr int BM = 128;  // query rows per workgroup
+constexpr int BN = 64;   // keys per step
+constexpr int NT = 256;  // threads
+
+__device__ __forceinline__ float other_half(float x) {
+    // value held by lane ^ 32
+    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false,
+                                              false);
+    // lanes < 32 find the partner's value in r[1], lanes >= 32 in r[0]; the other slot is their own
+    float a = __builtin_bit_cast(float, (unsigned)r[0]);
+    float b = __builtin_bit_cast(float, (unsigned)r[1]);
+    return (threadIdx.x & 32) ? a : b;
+}
+
+template <int D>
+struct FwdSmem {
+    static constexpr int KSTR = D + 8;   // row strides in elements: skew rows over the LDS banks
+    static constexpr int VSTR = D + 16;
+    bf16_t k[BN * KSTR];
+    bf16_t v[BN * VSTR];
+};
+
+template <int D>
+__global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                     const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
+                                                     float* __restrict__ lse, AttnShape s, int nq) {
+    constexpr int KS = D / 16;        // k-steps of the score MFMA
+    constexpr int DB = D / 32;        // 32-row blocks of O^T
+    constexpr int CH = D / 8;         // 16-byte chunks per row
+    constexpr int RPP = NT / CH;      // rows staged per pass
+    constexpr int PASSES = BN / RPP;  // passes per tile
+    constexpr int KSTR = FwdSmem<D>::KSTR, VSTR = FwdSmem<D>::VSTR;
+    __shared__ __attribute__((aligned(16))) FwdSmem<D> sm;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, w = tid >> 6;
+    const int c32 = lane & 31, h = lane >> 5;
+
+    // ---- which (batch, head, query tile): heads of one kv group stay on one XCD, long tiles first
+    const int G = s.Hq / s.Hkv;
+    const int NP = s.B * s.Hkv;
+    int n = blockIdx.x, g, pr, qt;
+    if ((NP & 7) == 0) {
+        const int xcd = n & 7, mm = n >> 3;
+        g = mm % G;
+        const int rest = mm / G;
+        const int pb = rest % (NP >> 3);
+        qt = nq - 1 - rest / (NP >> 3);
+        pr = xcd + 8 * pb;
+    } else {
+        g = n % G;
+        const int rest = n / G;
+        pr = rest % NP;
+        qt = nq - 1 - rest / NP;
+    }
+    const int b = pr / s.Hkv, hk = pr % s.Hkv;
+    const int hq = hk * G + g;
+
+    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int i0 = qt * BM;
+    const int i1 = min(L, i0 + BM) - 1;
+    const int qrow = i0 + 32 * w + c32;      // this lane's query row
+    const int qrow_ld = min(qrow, L - 1);    // rows past the end shadow the last row and are never stored
+    const int wrow0 = i0 + 32 * w;           // first row of the wave
+
+    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * L * D;
+    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * L * D;
+
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow][16 ks + 8 h .. +7]
+    bf16x8 qf[KS];
+    {
+        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * L + qrow_ld) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+    }
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
+
+    // ---- tile walk
+    const int lo = max(0, i0 - W + 1);
+    const int wfirst = lo / BN;            // first window key tile
+    const int nfar = (wfirst * BN) / rp1;  // gists strictly left of the window phase
+    const int ngt = (nfar + BN - 1) / BN;
+    const int nwin = i1 / BN - wfirst + 1;
+    const int ntiles = ngt + nwin;
+
+    // staging: thread copies PASSES 16-byte chunks of K and of V per tile
+    const int srow = tid / CH, scol = (tid % CH) * 8;
+    u32x4 kreg[PASSES], vreg[PASSES];
+    auto fetch = [&](int it) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int rr = p * RPP + srow;
+            int row;
+            if (it < ngt) {
+                const int gi = min(it * BN + rr, nfar - 1);
+                row = gi * rp1 + rp1 - 1;
+            } else {
+                row = min((wfirst + it - ngt) * BN + rr, L - 1);
+            }
+            kreg[p] = *(const u32x4*)(kb + (size_t)row * D + scol);
+            vreg[p] = *(const u32x4*)(vb + (size_t)row * D + scol);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int rr = p * RPP + srow;
+            *(u32x4*)(&sm.k[rr * KSTR + scol]) = kreg[p];
+            *(u32x4*)(&sm.v[rr * VSTR + scol]) = vreg[p];
+        }
+    };
+
+    fetch(0);
+    for (int it = 0; it < ntiles; ++it) {
+        __syncthreads();  // everyone is done reading the previous tile
+        stash();
+        __syncthreads();
+        if (it + 1 < ntiles) fetch(it + 1);
+
+        const bool gist_tile = it < ngt;
+        const int j0 = gist_tile ? it * BN : (wfirst + it - ngt) * BN;  // compact index or position
+        // a window tile entirely right of this wave's rows contributes nothing
+        if (!gist_tile && j0 > wrow0 + 31) continue;
+
+        // ---- S^T = K Q^T : two 32-key blocks
+        f32x16 sa[2];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sa[kb2][i] = 0.f;
+            const bf16_t* kp = &sm.k[(32 * kb2 + c32) * KSTR + 8 * h];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 a = *(const bf16x8*)(kp + 16 * ks);
+                sa[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sa[kb2], 0, 0, 0);
+            }
+        }
+
+        // ---- mask.  Accumulator element i of block kb2 is key  j0 + 32 kb2 + 8 (i/4) + 4 h + i%4.
+        bool masked;
+        if (gist_tile) {
+            masked = j0 + BN > nfar;  // tail of the compact list
+            if (masked) {
+                const int lim = nfar - j0 - 4 * h;  // element visible iff its offset < lim
+#pragma unroll
+                for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
+                        if (off >= lim) sa[kb2][i] = -INFINITY;
+                    }
+            }
+        } else {
+            // unmasked iff all keys are causal for the wave's first row and in the window of its last row
+            masked = !(j0 + BN - 1 <= wrow0 && wrow0 + 31 - j0 < W);
+            if (masked) {
+                // bit t of gm: key j0 + 4h + t holds a gist.  One modulo per lane, shared by ballot.
+                const unsigned long long gbits = __builtin_amdgcn_ballot_w64((j0 + lane + 1) % rp1 == 0);
+                const unsigned long long gm = gbits >> (4 * h);
+                const int d0 = qrow - (j0 + 4 * h);  // distance to the lane's first key
+#pragma unroll
+                for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
+                        const int dist = d0 - off;  // i - j
+                        const bool in_win = (unsigned)dist < (unsigned)W;
+                        const bool gist_ok = dist >= 0 && ((gm >> off) & 1ull);
+                        if (!(in_win || gist_ok)) sa[kb2][i] = -INFINITY;
+                    }
+            }
+        }
+
+        // ---- online softmax (per query column = per lane, halves exchange once)
+        float mx = sa[0][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa[0][i]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[1][i]);
+        mx = fmaxf(mx, other_half(mx));
+        const float m_new = fmaxf(m, mx);
+        const float m_use = (masked && m_new == -INFINITY) ? 0.f : m_new;
+        const float mc = m_use * c;
+        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0ull) {
+            const float alpha = __builtin_amdgcn_exp2f(m * c - mc);  // m = -inf gives 0
+            l *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        }
+        m = m_new;
+
+        uint32_t pk[2][8];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
+                l += p0 + p1;
+                pk[kb2][i / 2] = pack_bf16x2(p0, p1);
+            }
+
+        // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
+        const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int g0 = 0; g0 < 4; g0 += 2) {
+                u32x4 pb4;
+                pb4[0] = pk[kb2][2 * g0];
+                pb4[1] = pk[kb2][2 * g0 + 1];
+                pb4[2] = pk[kb2][2 * g0 + 2];
+                pb4[3] = pk[kb2][2 * g0 + 3];
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, pb4);
+                const int krow = 32 * kb2 + 8 * g0 + 4 * h + (p16 >> 2);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16_t* vp = &sm.v[krow * VSTR + 32 * db + 16 * gi2 + 4 * (p16 & 3)];
+                    s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)vp);
+                    s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(vp + 8 * VSTR));
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
+                }
+            }
+    }
+
+    // ---- epilogue: normalise, store O (row qrow, d = 32 db + 8 (i/4) + 4 h + i%4) and LSE
+    const float lt = l + other_half(l);
+    const float inv = 1.f / lt;
+    if (qrow < L) {
+        bf16_t* op = out + (((size_t)b * s.Hq + hq) * L + qrow) * D + 4 * h;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                u32x2 w2;
+                w2[0] = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+                w2[1] = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+                *(u32x2*)(op + 32 * db + 8 * i4) = w2;
+            }
+        if (h == 0) lse[((size_t)b * s.Hq + hq) * L + qrow] = m * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
+                           hipStream_t st) {
+    const int nq = (s.L + BM - 1) / BM;
+    const long nblk = (long)nq * s.Hq * s.B;
+    if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
+    if (s.D == 64)
+        fwd_mfma_kernel<64><<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                 (bf16_t*)out, lse, s, nq);
+    else
+        fwd_mfma_kernel<128><<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                  (bf16_t*)out, lse, s, nq);
+    return hipGetLastError();
+}
+
+}  // namespace unigist

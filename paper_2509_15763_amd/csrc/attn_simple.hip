@@ -1,0 +1,252 @@
+// Plain-ALU kernels for gist-masked attention: the fp32 debug build of the library.
+//
+// One thread owns one query row (forward, dQ) or one key row (dK/dV) and walks the
+// rows on the other side one at a time.  The 64 lanes of a wave walk in lockstep
+// over the union of their ranges, so every K/V (or Q/dO) row is fetched with a
+// wave-uniform address, and apply the visibility rule of Sec. 4.1, Eq. 3 per pair.
+// No tiles, no MFMA, fp32 accumulation throughout; slow, but short enough to
+// check by eye.  The bf16 instantiations exist so that the MFMA kernels can be
+// cross-checked against them on the GPU.
+#include "common.h"
+
+namespace unigist {
+namespace {
+
+constexpr int kRows = 64;  // rows per workgroup == one wave
+
+template <typename T, int D>
+__device__ __forceinline__ void load_row(const T* __restrict__ p, float (&x)[D]) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) x[d] = Elem<T>::load(p + d);
+}
+
+__device__ __forceinline__ bool is_gist(int p, int rp1) { return (p + 1) % rp1 == 0; }
+
+// ---------------------------------------------------------------- forward
+template <typename T, int D>
+__global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                          const T* __restrict__ v, T* __restrict__ out,
+                                                          float* __restrict__ lse, AttnShape s) {
+    __shared__ float qs[D][kRows];
+    const int lane = threadIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (s.Hq / s.Hkv);
+    const int i_first = blockIdx.x * kRows;
+    const int i_last = min(s.L, i_first + kRows) - 1;
+    const int i = min(i_first + lane, s.L - 1);  // lanes past the end shadow the last row, never store
+    const bool live = i_first + lane < s.L;
+    const size_t qoff = (((size_t)b * s.Hq + h) * s.L + i) * D;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.L * D;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.L * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
+
+    float o[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) o[d] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    auto visit = [&](int j) {
+        const T* kr = kb + (size_t)j * D;
+        float sc = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) sc += qs[d][lane] * Elem<T>::load(kr + d);
+        if (sc > m) {
+            float a = expf(m - sc);
+            l *= a;
+#pragma unroll
+            for (int d = 0; d < D; ++d) o[d] *= a;
+            m = sc;
+        }
+        float p = expf(sc - m);
+        l += p;
+        const T* vr = vb + (size_t)j * D;
+#pragma unroll
+        for (int d = 0; d < D; ++d) o[d] += p * Elem<T>::load(vr + d);
+    };
+
+    // gists left of every window of this wave's rows, then the union of the windows
+    const int lo_wave = max(0, i_first - s.W + 1);
+    const int ng_wave = lo_wave / s.rp1;  // gists at positions < lo_wave
+    for (int g = 0; g < ng_wave; ++g) visit(g * s.rp1 + s.rp1 - 1);
+    for (int j = lo_wave; j <= i_last; ++j) {
+        bool ok = j <= i && (is_gist(j, s.rp1) || i - j < s.W);
+        if (ok) visit(j);
+    }
+    if (live) {
+        float inv = 1.f / l;
+#pragma unroll
+        for (int d = 0; d < D; ++d) Elem<T>::store(out + qoff + d, o[d] * inv);
+        lse[((size_t)b * s.Hq + h) * s.L + i] = m + logf(l);
+    }
+}
+
+// ---------------------------------------------------------------- dQ (+ delta)
+template <typename T, int D>
+__global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                         const T* __restrict__ v, const T* __restrict__ out,
+                                                         const float* __restrict__ lse, const T* __restrict__ dout,
+                                                         T* __restrict__ dq, float* __restrict__ delta, AttnShape s) {
+    __shared__ float qs[D][kRows];
+    __shared__ float dos[D][kRows];
+    const int lane = threadIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (s.Hq / s.Hkv);
+    const int i_first = blockIdx.x * kRows;
+    const int i_last = min(s.L, i_first + kRows) - 1;
+    const int i = min(i_first + lane, s.L - 1);
+    const bool live = i_first + lane < s.L;
+    const size_t row = ((size_t)b * s.Hq + h) * s.L + i;
+    const size_t qoff = row * D;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.L * D;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.L * D;
+    float dl = 0.f;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
+        float g = Elem<T>::load(dout + qoff + d);
+        dos[d][lane] = g;
+        dl += g * Elem<T>::load(out + qoff + d);
+    }
+    const float ls = lse[row];
+    if (live) delta[row] = dl;
+
+    float acc[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) acc[d] = 0.f;
+
+    auto visit = [&](int j) {
+        const T* kr = kb + (size_t)j * D;
+        const T* vr = vb + (size_t)j * D;
+        float sc = 0.f, dp = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            sc += qs[d][lane] * Elem<T>::load(kr + d);
+            dp += dos[d][lane] * Elem<T>::load(vr + d);
+        }
+        float ds = expf(sc - ls) * (dp - dl);
+#pragma unroll
+        for (int d = 0; d < D; ++d) acc[d] += ds * Elem<T>::load(kr + d);
+    };
+
+    const int lo_wave = max(0, i_first - s.W + 1);
+    const int ng_wave = lo_wave / s.rp1;
+    for (int g = 0; g < ng_wave; ++g) visit(g * s.rp1 + s.rp1 - 1);
+    for (int j = lo_wave; j <= i_last; ++j) {
+        bool ok = j <= i && (is_gist(j, s.rp1) || i - j < s.W);
+        if (ok) visit(j);
+    }
+    if (live) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) Elem<T>::store(dq + qoff + d, acc[d] * s.scale);
+    }
+}
+
+// ---------------------------------------------------------------- dK, dV
+template <typename T, int D>
+__global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                           const T* __restrict__ v, const float* __restrict__ lse,
+                                                           const T* __restrict__ dout, const float* __restrict__ delta,
+                                                           T* __restrict__ dk, T* __restrict__ dv, AttnShape s) {
+    __shared__ float ks[D][kRows];
+    __shared__ float vs[D][kRows];
+    const int lane = threadIdx.x;
+    const int hk = blockIdx.y, b = blockIdx.z;
+    const int group = s.Hq / s.Hkv;
+    const int j_first = blockIdx.x * kRows;
+    const int j_last = min(s.L, j_first + kRows) - 1;
+    const int j = min(j_first + lane, s.L - 1);
+    const bool live = j_first + lane < s.L;
+    const size_t koff = (((size_t)b * s.Hkv + hk) * s.L + j) * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        ks[d][lane] = Elem<T>::load(k + koff + d) * s.scale;
+        vs[d][lane] = Elem<T>::load(v + koff + d);
+    }
+    const bool gist_j = is_gist(j, s.rp1);
+    // does any key of this block hold a gist?  then later rows without bound see it
+    const int first_gist = ((j_first + s.rp1) / s.rp1) * s.rp1 - 1;  // first gist position >= j_first
+    const bool any_gist = first_gist <= j_last;
+    const int i_end = any_gist ? s.L - 1 : min(s.L - 1, j_last + s.W - 1);
+
+    float ak[D], av[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) ak[d] = av[d] = 0.f;
+
+    for (int g = 0; g < group; ++g) {
+        const int h = hk * group + g;
+        const size_t base = ((size_t)b * s.Hq + h) * s.L;
+        for (int i = j_first; i <= i_end; ++i) {
+            bool ok = j <= i && (gist_j || i - j < s.W);
+            if (!ok) continue;
+            const T* qr = q + (base + i) * D;
+            const T* gr = dout + (base + i) * D;
+            float sc = 0.f, dp = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                sc += ks[d][lane] * Elem<T>::load(qr + d);
+                dp += vs[d][lane] * Elem<T>::load(gr + d);
+            }
+            float p = expf(sc - lse[base + i]);
+            float ds = p * (dp - delta[base + i]);
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                av[d] += p * Elem<T>::load(gr + d);
+                ak[d] += ds * Elem<T>::load(qr + d);
+            }
+        }
+    }
+    if (live) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            Elem<T>::store(dk + koff + d, ak[d] * s.scale);
+            Elem<T>::store(dv + koff + d, av[d]);
+        }
+    }
+}
+
+template <typename T, int D>
+hipError_t fwd_launch(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
+                      hipStream_t st) {
+    dim3 grid((s.L + kRows - 1) / kRows, s.Hq, s.B);
+    fwd_simple_kernel<T, D><<<grid, kRows, 0, st>>>((const T*)q, (const T*)k, (const T*)v, (T*)out, lse, s);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t bwd_launch(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                      const void* dout, void* dq, void* dk, void* dv, float* delta, const AttnShape& s,
+                      hipStream_t st) {
+    dim3 gq((s.L + kRows - 1) / kRows, s.Hq, s.B);
+    dq_simple_kernel<T, D><<<gq, kRows, 0, st>>>((const T*)q, (const T*)k, (const T*)v, (const T*)out, lse,
+                                                 (const T*)dout, (T*)dq, delta, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 gk((s.L + kRows - 1) / kRows, s.Hkv, s.B);
+    dkdv_simple_kernel<T, D><<<gk, kRows, 0, st>>>((const T*)q, (const T*)k, (const T*)v, lse, (const T*)dout,
+                                                   delta, (T*)dk, (T*)dv, s);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,
+                             const AttnShape& s, unigist_dtype dt, hipStream_t st) {
+    if (dt == UNIGIST_F32)
+        return s.D == 64 ? fwd_launch<float, 64>(q, k, v, out, lse, s, st)
+                         : fwd_launch<float, 128>(q, k, v, out, lse, s, st);
+    return s.D == 64 ? fwd_launch<bf16_t, 64>(q, k, v, out, lse, s, st)
+                     : fwd_launch<bf16_t, 128>(q, k, v, out, lse, s, st);
+}
+
+hipError_t launch_bwd_simple(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                             const void* dout, void* dq, void* dk, void* dv, float* delta, const AttnShape& s,
+                             unigist_dtype dt, hipStream_t st) {
+    if (dt == UNIGIST_F32)
+        return s.D == 64 ? bwd_launch<float, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
+                         : bwd_launch<float, 128>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st);
+    return s.D == 64 ? bwd_launch<bf16_t, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
+                     : bwd_launch<bf16_t, 128>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st);
+}
+
+}  // namespace unigist

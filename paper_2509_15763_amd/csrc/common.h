@@ -1,0 +1,73 @@
+// Internal helpers shared by the libunigist translation units (host + device).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "unigist.h"
+
+namespace unigist {
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// round-to-nearest-even f32 -> bf16 (inputs are finite in this library)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// two floats -> packed bf16 pair (lo = a, hi = b), RNE, one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    f32x2 x;
+    x[0] = a;
+    x[1] = b;
+    bf16x2 y = __builtin_convertvector(x, bf16x2);
+    return __builtin_bit_cast(uint32_t, y);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// Shape of one attention problem as the kernels see it.
+struct AttnShape {
+    int B, Hq, Hkv, L, D;
+    int rp1;  // r + 1, clamped to L + 1 when there are no gists (so (p+1) % rp1 == 0 never holds)
+    int W;    // clamped to L
+    float scale;
+};
+
+// --- launchers implemented in the .hip files (all enqueue on `st`, return hipGetLastError) ---
+hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,
+                             const AttnShape& s, unigist_dtype dt, hipStream_t st);
+hipError_t launch_bwd_simple(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                             const void* dout, void* dq, void* dk, void* dv, float* delta,
+                             const AttnShape& s, unigist_dtype dt, hipStream_t st);
+hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
+                           const AttnShape& s, hipStream_t st);
+size_t bwd_mfma_workspace(const AttnShape& s);
+hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, void* dq, void* dk, void* dv, void* ws,
+                           const AttnShape& s, hipStream_t st);
+int decode_num_splits(int B, int Hq, int Hkv, int Lk);
+hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                         int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
+                         float* ws, hipStream_t st);
+
+}  // namespace unigist

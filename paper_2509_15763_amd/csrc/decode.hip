@@ -1,0 +1,238 @@
+// Split-K decode over the compressed KV cache (Sec. 4.3 of the paper: after the raw
+// tokens outside the window have been dropped, a new token attends to every cached
+// key; the paper notes this is compatible with FlashDecoding-style split-K).
+//
+// The op streams K and V once from HBM: 4 flops per byte, so it is bandwidth bound.
+// Layout of the work:
+//   grid = (splits, kv heads or q heads, B), 256 threads.
+//   A workgroup owns one contiguous slice of one sequence's keys for one kv head and
+//   serves all G = Hq/Hkv query heads of that group from the same K/V bytes.
+//   16 lanes share one key row (each holds D/16 contiguous elements, a 16-byte load
+//   for bf16 D=128), so a wave covers 4 rows per load and the workgroup's 4 waves
+//   cover 16 adjacent rows (4 KB contiguous for bf16 D=128).
+//   Each 16-lane group keeps its own running (max, sum, acc) per query head; the 16
+//   groups of a workgroup are merged through LDS and the slice's partial result goes
+//   to the workspace as (m, l, acc[D]).  A second kernel merges the slices:
+//   lse = ln sum_s l_s e^{m_s}, out = sum_s e^{m_s - m} acc_s / sum_s e^{m_s - m} l_s.
+#include "common.h"
+
+namespace unigist {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kLanesPerRow = 16;
+constexpr int kRowsPerIter = kThreads / kLanesPerRow;  // 16
+constexpr int kUnroll = 4;
+
+template <typename T, int E> struct RowChunk;  // E contiguous elements of a row -> float[E]
+template <int E> struct RowChunk<bf16_t, E> {
+    static __device__ __forceinline__ void load(const bf16_t* p, float (&x)[E]) {
+        if constexpr (E == 8) {
+            u32x4 r = *(const u32x4*)p;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                x[2 * t] = __uint_as_float(r[t] << 16);
+                x[2 * t + 1] = __uint_as_float(r[t] & 0xffff0000u);
+            }
+        } else {
+            u32x2 r = *(const u32x2*)p;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                x[2 * t] = __uint_as_float(r[t] << 16);
+                x[2 * t + 1] = __uint_as_float(r[t] & 0xffff0000u);
+            }
+        }
+    }
+};
+template <int E> struct RowChunk<float, E> {
+    static __device__ __forceinline__ void load(const float* p, float (&x)[E]) {
+#pragma unroll
+        for (int t = 0; t < E; t += 4) {
+            f32x4 r = *(const f32x4*)(p + t);
+            x[t] = r[0];
+            x[t + 1] = r[1];
+            x[t + 2] = r[2];
+            x[t + 3] = r[3];
+        }
+    }
+};
+
+// sum over the 16 lanes of a DPP row; every lane ends with the total
+__device__ __forceinline__ float row16_sum(float x) {
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xf, 0xf, false));  // row_half_mirror
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xf, 0xf, false));  // row_mirror
+    return x;
+}
+
+// workspace layout per (b, hq, split): [m, l, acc[D]] floats
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restrict__ q, const T* __restrict__ kc,
+                                                               const T* __restrict__ vc, const int* __restrict__ seqlens,
+                                                               float* __restrict__ ws, int Hq, int Hkv, int Lk,
+                                                               int nsplit, float scale) {
+    constexpr int E = D / kLanesPerRow;
+    const int tid = threadIdx.x;
+    const int sub = tid % kLanesPerRow;  // which D/16 chunk of a row
+    const int grp = tid / kLanesPerRow;  // which of the 16 rows per iteration
+    const int split = blockIdx.x, b = blockIdx.z;
+    // G query heads share kv head hk; with G == 1 the grid runs over query heads
+    const int hq0 = blockIdx.y * G;
+    const int hk = hq0 / (Hq / Hkv);
+    const int n = seqlens ? seqlens[b] : Lk;
+    const int per = (((n + nsplit - 1) / nsplit) + kRowsPerIter - 1) / kRowsPerIter * kRowsPerIter;
+    const int k0 = split * per;
+    const int k1 = min(n, k0 + per);
+
+    float qr[G][E], acc[G][E], m[G], l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        RowChunk<T, E>::load(q + ((size_t)b * Hq + hq0 + g) * D + sub * E, qr[g]);
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            qr[g][e] *= scale;
+            acc[g][e] = 0.f;
+        }
+    }
+    const T* kb = kc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
+    const T* vb = vc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
+
+    for (int base = k0; base < k1; base += kRowsPerIter * kUnroll) {
+        float kx[kUnroll][E], vx[kUnroll][E];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int row = base + u * kRowsPerIter + grp;
+            ok[u] = row < k1;
+            int rr = ok[u] ? row : k0;  // k0 < k1 <= n whenever this loop runs: always in bounds
+            RowChunk<T, E>::load(kb + (size_t)rr * D, kx[u]);
+            RowChunk<T, E>::load(vb + (size_t)rr * D, vx[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) s += qr[g][e] * kx[u][e];
+                s = row16_sum(s);
+                if (ok[u]) {
+                    if (s > m[g]) {
+                        float a = __expf(m[g] - s);
+                        l[g] *= a;
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[g][e] *= a;
+                        m[g] = s;
+                    }
+                    float p = __expf(s - m[g]);
+                    l[g] += p;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[g][e] += p * vx[u][e];
+                }
+            }
+        }
+    }
+
+    // merge the 16 row groups of the workgroup
+    __shared__ float sm[G][kRowsPerIter];
+    __shared__ float sl[G][kRowsPerIter];
+    __shared__ float sacc[G][kRowsPerIter][D];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (sub == 0) {
+            sm[g][grp] = m[g];
+            sl[g][grp] = l[g];
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) sacc[g][grp][sub * E + e] = acc[g][e];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * D; idx += kThreads) {
+        const int g = idx / D, d = idx % D;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kRowsPerIter; ++t) mm = fmaxf(mm, sm[g][t]);
+        float ll = 0.f, a = 0.f;
+        if (mm > -INFINITY) {
+#pragma unroll
+            for (int t = 0; t < kRowsPerIter; ++t) {
+                float w = __expf(sm[g][t] - mm);  // exp(-inf) = 0 for groups that saw no key
+                ll += w * sl[g][t];
+                a += w * sacc[g][t][d];
+            }
+        }
+        float* o = ws + (((size_t)b * Hq + hq0 + g) * nsplit + split) * (D + 2);
+        if (d == 0) {
+            o[0] = mm;
+            o[1] = ll;
+        }
+        o[2 + d] = a;
+    }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ ws, T* __restrict__ out,
+                                                          float* __restrict__ lse, int nsplit) {
+    const int bh = blockIdx.x, d = threadIdx.x;
+    const float* p = ws + (size_t)bh * nsplit * (D + 2);
+    float mm = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, p[s * (D + 2)]);
+    float ll = 0.f, a = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        float w = __expf(p[s * (D + 2)] - mm);
+        ll += w * p[s * (D + 2) + 1];
+        a += w * p[s * (D + 2) + 2 + d];
+    }
+    Elem<T>::store(out + (size_t)bh * D + d, a / ll);
+    if (lse && d == 0) lse[bh] = mm + __logf(ll);
+}
+
+template <typename T, int D>
+hipError_t decode_launch(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
+                         int Hkv, int Lk, const int* seqlens, float* ws, hipStream_t st) {
+    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
+    const float scale = 1.0f / sqrtf((float)D);
+    const int G = Hq / Hkv;
+    if (G == 4) {
+        dim3 grid(nsplit, Hkv, B);
+        decode_split_kernel<T, D, 4><<<grid, kThreads, 0, st>>>((const T*)q, (const T*)kc, (const T*)vc, seqlens, ws,
+                                                                Hq, Hkv, Lk, nsplit, scale);
+    } else {
+        dim3 grid(nsplit, Hq, B);
+        decode_split_kernel<T, D, 1><<<grid, kThreads, 0, st>>>((const T*)q, (const T*)kc, (const T*)vc, seqlens, ws,
+                                                                Hq, Hkv, Lk, nsplit, scale);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_combine_kernel<T, D><<<B * Hq, D, 0, st>>>(ws, (T*)out, lse, nsplit);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Enough slices to put several workgroups on each of the 256 CUs, but never slices
+// shorter than 256 keys.
+int decode_num_splits(int B, int Hq, int Hkv, int Lk) {
+    const int G = Hq / Hkv;
+    const long units = (long)B * (G == 4 ? Hkv : Hq);
+    long want = (2048 + units - 1) / units;
+    long cap = (Lk + 255) / 256;
+    long n = want < cap ? want : cap;
+    if (n < 1) n = 1;
+    if (n > 64) n = 64;
+    return (int)n;
+}
+
+hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
+                         int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt, float* ws, hipStream_t st) {
+    if (dt == UNIGIST_F32)
+        return D == 64 ? decode_launch<float, 64>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                       : decode_launch<float, 128>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+    return D == 64 ? decode_launch<bf16_t, 64>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                   : decode_launch<bf16_t, 128>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+}
+
+}  // namespace unigist

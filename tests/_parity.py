@@ -1,0 +1,39 @@
+"""Helpers for the GPU parity tests: run the oracle on the same seeded tensors and
+measure the errors the tolerances are stated in."""
+import numpy as np
+import torch
+
+import oracle
+
+# Tolerances (see the arithmetic notes in the design document):
+#   bf16 inputs, fp32 accumulation: max-abs error on out <= 1e-2, relative L2 error on
+#   dq/dk/dv <= 2e-2; fp32 debug build: <= 1e-5 for all of them.
+TOL_OUT_BF16 = 1e-2
+TOL_LSE_BF16 = 1e-2
+TOL_GRAD_BF16 = 2e-2
+TOL_F32 = 1e-5
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of a (bf16 or fp32) tensor to float64 on the host."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def max_abs(a, b) -> float:
+    return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)))) if np.size(a) else 0.0
+
+
+def rel_l2(a, b) -> float:
+    """||a - b|| / ||b|| with b the oracle."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = float(np.linalg.norm(b))
+    num = float(np.linalg.norm(a - b))
+    return num / den if den > 0 else num
+
+
+def oracle_fwd_bwd(q, k, v, dout, r, W):
+    qn, kn, vn, don = (to_np(t) for t in (q, k, v, dout))
+    out, lse = oracle.attn_fwd(qn, kn, vn, r, W)
+    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W)
+    return out, lse, dq, dk, dv

@@ -1,0 +1,97 @@
+"""The C-ABI library loads and exports what include/unigist.h declares; argument
+validation is exercised through calls that return before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2509_15763_amd as u
+from paper_2509_15763_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "unigist.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(unigist_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = u.load()
+    names = _declared()
+    assert "unigist_attn_fwd" in names and "unigist_decode" in names and len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_binding_has_the_same_names():
+    for n in _declared():
+        if n == "unigist_blockmap_free":
+            continue  # the binding frees the map itself
+        assert callable(getattr(u, n)), n
+
+
+def test_status_strings():
+    assert u.unigist_status_str(0) == "ok"
+    assert "invalid" in u.unigist_status_str(1)
+    assert "unsupported" in u.unigist_status_str(2)
+    assert "launch" in u.unigist_status_str(3).lower()
+
+
+FAKE = 0x1000  # non-null pointer that is never dereferenced: every call below fails validation first
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), None),
+    (dict(B=0), 1), (dict(L=0), 1), (dict(W=0), 1), (dict(r=0), 1), (dict(Hq=6, Hkv=4), 1),
+    (dict(D=96), 2), (dict(dt=7), 2), (dict(L=(1 << 24) + 1), 2),
+])
+def test_attn_argument_validation(kw, want):
+    a = dict(B=1, Hq=4, Hkv=2, L=64, D=64, r=4, W=8, dt=0)
+    a.update(kw)
+    shape = (a["B"], a["Hq"], a["Hkv"], a["L"], a["D"], a["r"], a["W"], a["dt"])
+    if want is None:
+        # valid shape but null tensors -> EINVAL, still nothing launched
+        assert u.unigist_attn_fwd(None, None, None, None, None, *shape) == 1
+        assert u.unigist_attn_bwd_workspace(*shape) > 0
+        assert u.unigist_attn_bwd(*([FAKE] * 9), *shape, None, 0) == 1
+        assert u.unigist_attn_bwd(*([FAKE] * 9), *shape, FAKE + 0x100 - 0x1000 % 256, 16) == 1  # too small
+        return
+    assert u.unigist_attn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, *shape) == want
+    assert u.unigist_attn_bwd(*([FAKE] * 9), *shape, FAKE, 1 << 40) == want
+    assert u.unigist_attn_bwd_workspace(*shape) == 0
+
+
+def test_decode_argument_validation():
+    ok = dict(B=2, Hq=4, Hkv=2, Lk=100, D=128, dt=0)
+    ws = u.unigist_decode_workspace(*ok.values())
+    assert ws > 0 and ws % 256 == 0
+
+    def call(ws_ptr=0x10000, ws_bytes=1 << 40, q=FAKE, **kw):
+        a = dict(ok)
+        a.update(kw)
+        return u.unigist_decode(q, FAKE, FAKE, FAKE, None, a["B"], a["Hq"], a["Hkv"], a["Lk"], None, a["D"], a["dt"],
+                                ws_ptr, ws_bytes)
+    assert call(q=None) == 1
+    assert call(B=0) == 1 and call(Lk=0) == 1 and call(Hq=3) == 1
+    assert call(D=32) == 2 and call(dt=5) == 2
+    assert call(ws_bytes=ws - 1) == 1
+    assert call(ws_ptr=0x10010) == 1  # misaligned workspace
+    assert u.unigist_decode_workspace(2, 3, 2, 100, 128, 0) == 0
+
+
+def test_cpu_tensors_are_refused():
+    import torch
+    q = torch.zeros(1, 1, 8, 64)
+    with pytest.raises(u.UnigistError):
+        u.attn_fwd(q, q, q, 4, 4)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(u.UnigistError, match="no fallback"):
+        binding.load()

@@ -1,0 +1,84 @@
+"""The block map (Sec. 4.2: visible blocks in closed form) against the oracle's mask:
+every visible pair lies in exactly one (phase, tile), skipped tiles hold no visible pair,
+tiles flagged as needing no mask are fully visible, and the transposed view is the
+exact transpose."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_15763_amd as u
+
+CASES = [
+    (10, 4, 3, 4, 4), (200, 4, 16, 32, 16), (257, 4, 40, 32, 32), (300, 2, 7, 64, 16), (513, 8, 100, 128, 64),
+    (384, 4, 1000, 64, 64),      # window covers everything: causal
+    (300, 10**6, 33, 32, 16),    # no gists: sliding window
+    (129, 1, 1, 16, 8), (640, 16, 64, 128, 64), (100, 3, 5, 128, 64),
+]
+
+
+@pytest.mark.parametrize("L,r,W,Bm,Bn", CASES)
+def test_coverage_is_exact(L, r, W, Bm, Bn):
+    m = u.unigist_blockmap_build(L, r, W, Bm, Bn)
+    M = oracle.mask_rows(np.arange(L), L, r, W)
+    cover = np.zeros((L, L), dtype=np.int32)
+    live = masked = 0
+    for t in range(m["n_qtiles"]):
+        rows = slice(t * Bm, min(L, (t + 1) * Bm))
+        i0, i1 = rows.start, rows.stop - 1
+        # window phase: the predicate applies inside the tile
+        nfull = 0
+        for c in range(m["win_first"][t], m["win_last"][t] + 1):
+            cols = slice(c * Bn, min(L, (c + 1) * Bn))
+            sub = M[rows, cols]
+            assert sub.any(), "a live window tile must hold a visible pair"
+            cover[rows, cols] += sub
+            full = (c + 1) * Bn - 1 <= i0 and i1 - c * Bn < min(W, L)
+            if full:
+                assert sub.all() and cols.stop - cols.start == Bn
+                nfull += 1
+            live += 1
+        assert nfull == m["n_full"][t]
+        masked += (m["win_last"][t] - m["win_first"][t] + 1) - nfull
+        # gist phase: compact gists, all visible to all rows of the tile
+        nfar = m["n_far_gists"][t]
+        pos = np.arange(nfar) * (r + 1) + r
+        assert (pos < m["win_first"][t] * Bn).all()
+        assert M[rows][:, pos].all()
+        cover[rows.start:rows.stop, pos] += 1
+        live += -(-nfar // Bn)
+        # nothing visible is left of the window phase except those gists
+        left = M[rows, : m["win_first"][t] * Bn].copy()
+        left[:, pos] = False
+        assert not left.any()
+    assert np.array_equal(cover, M.astype(np.int32))
+    assert live == m["live_tiles"] and masked == m["masked_tiles"]
+    assert m["n_vis"] == int(M.sum())
+    assert m["n_gists"] == (0 if r >= L else L // (r + 1))
+    assert m["causal_tiles"] == sum(min(L, (t + 1) * Bm - 0) - 1 >= 0 and ((min(L, (t + 1) * Bm) - 1) // Bn + 1)
+                                    for t in range(m["n_qtiles"]))
+
+
+@pytest.mark.parametrize("L,r,W,Bm,Bn", CASES)
+def test_transposed_view(L, r, W, Bm, Bn):
+    m = u.unigist_blockmap_build(L, r, W, Bm, Bn)
+    for c in range(m["n_ktiles"]):
+        ts = [t for t in range(m["n_qtiles"]) if m["win_first"][t] <= c <= m["win_last"][t]]
+        assert ts and ts == list(range(m["qt_first"][c], m["qt_last"][c] + 1))
+    for g in range(m["n_gtiles"]):
+        ts = [t for t in range(m["n_qtiles"]) if m["n_far_gists"][t] > g * Bn]
+        assert ts == list(range(m["gist_qt_first"][g], m["n_qtiles"]))
+    assert m["n_gtiles"] == -(-max(m["n_far_gists"]) // Bn)
+
+
+def test_benchmark_shapes():
+    # 128 x 128 tiles on the 32K shape: 8 493 of 32 896 causal tiles are visited
+    m = u.unigist_blockmap_build(32768, 4, 1024, 128, 128)
+    assert (m["live_tiles"], m["causal_tiles"], m["n_vis"]) == (8493, 32896, 133789286)
+    m = u.unigist_blockmap_build(131072, 8, 2048, 128, 128)
+    assert (m["live_tiles"], m["causal_tiles"], m["n_vis"]) == (74112, 524800, 1191133184)
+
+
+def test_invalid_arguments():
+    for bad in [(0, 4, 4, 8, 8), (8, 0, 4, 8, 8), (8, 4, 0, 8, 8), (8, 4, 4, 0, 8), (8, 4, 4, 8, 0)]:
+        with pytest.raises(u.UnigistError):
+            u.unigist_blockmap_build(*bad)

@@ -1,0 +1,81 @@
+"""GPU parity: unigist_attn_fwd / unigist_attn_bwd (through the C ABI) against the fp64 oracle,
+element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_15763_amd as u
+from paper_2509_15763_amd import synth
+from _parity import (TOL_F32, TOL_GRAD_BF16, TOL_LSE_BF16, TOL_OUT_BF16, max_abs, oracle_fwd_bwd, rel_l2, to_np)
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(q, k, v, dout, r, W):
+    qd, kd, vd, dod = (t.cuda() for t in (q, k, v, dout))
+    out, lse = u.attn_fwd(qd, kd, vd, r, W)
+    dq, dk, dv = u.attn_bwd(qd, kd, vd, out, lse, dod, r, W)
+    torch.cuda.synchronize()
+    return out, lse, dq, dk, dv
+
+
+def check(case, got, want, dtype):
+    out, lse, dq, dk, dv = got
+    o_o, o_l, o_dq, o_dk, o_dv = want
+    errs = dict(out=max_abs(to_np(out), o_o), lse=max_abs(to_np(lse), o_l), dq=rel_l2(to_np(dq), o_dq),
+                dk=rel_l2(to_np(dk), o_dk), dv=rel_l2(to_np(dv), o_dv))
+    print(case, {k: f"{v:.3e}" for k, v in errs.items()}, flush=True)
+    for t in (out, lse, dq, dk, dv):
+        assert torch.isfinite(t.float()).all(), case
+    if dtype == torch.float32:
+        assert errs["out"] <= TOL_F32 and errs["lse"] <= TOL_F32, (case, errs)
+        assert max(errs["dq"], errs["dk"], errs["dv"]) <= TOL_F32, (case, errs)
+    else:
+        assert errs["out"] <= TOL_OUT_BF16 and errs["lse"] <= TOL_LSE_BF16, (case, errs)
+        assert max(errs["dq"], errs["dk"], errs["dv"]) <= TOL_GRAD_BF16, (case, errs)
+
+
+# B, Hq, Hkv, L, D, r, W
+SMALL = [
+    (1, 1, 1, 1024, 64, 4, 128),      # config 1
+    (2, 4, 2, 333, 64, 4, 40),        # GQA, ragged tail, several tiles
+    (1, 4, 1, 700, 128, 8, 100),      # D = 128, group of 4
+    (1, 2, 2, 257, 128, 2, 1),        # W = 1: only self + gists
+    (1, 2, 1, 384, 64, 4, 10**6),     # window >= L: full causal
+    (1, 2, 1, 300, 128, 2**31 - 2, 33),  # no gists: sliding window
+    (1, 1, 1, 1, 64, 4, 4),           # a single token
+    (1, 2, 2, 63, 128, 1, 3),         # r = 1: every other token is a gist
+    (1, 8, 8, 200, 64, 16, 64),       # 8 kv heads: XCD-aware block order
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,L,D,r,W", SMALL)
+def test_small_shapes_match_oracle(B, Hq, Hkv, L, D, r, W, dtype):
+    case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} {dtype}"
+    print("case", case, flush=True)
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, dtype=dtype, seed=0)
+    got = run_gpu(q, k, v, dout, r, W)
+    check(case, got, oracle_fwd_bwd(q, k, v, dout, r, W), dtype)
+
+
+def test_runs_are_bitwise_reproducible():
+    q, k, v, dout = synth.attn_inputs(1, 4, 2, 700, 128, seed=3)
+    a = run_gpu(q, k, v, dout, 4, 64)
+    b = run_gpu(q, k, v, dout, 4, 64)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_zero_queries_closed_form():
+    # q = 0: lse_i = ln n_vis(i) exactly in the mask, out_i = mean of the visible values
+    B, Hq, Hkv, L, D, r, W = 1, 2, 1, 900, 128, 4, 70
+    _, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=5)
+    q = torch.zeros(B, Hq, L, D, dtype=torch.bfloat16)
+    out, lse = u.attn_fwd(q.cuda(), k.cuda(), v.cuda(), r, W)
+    i = np.arange(L)
+    nvis = np.minimum(i + 1, W) + np.maximum(0, (i - W + 1) // (r + 1))
+    assert max_abs(to_np(lse)[0, 0], np.log(nvis)) < 1e-5
+    o, _ = oracle.attn_fwd(to_np(q), to_np(k), to_np(v), r, W)
+    assert max_abs(to_np(out), o) < 1e-2

@@ -1,0 +1,47 @@
+"""GPU parity: unigist_decode (through the C ABI) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_15763_amd as u
+from paper_2509_15763_amd import synth
+from _parity import TOL_F32, TOL_LSE_BF16, TOL_OUT_BF16, max_abs, to_np
+
+pytestmark = pytest.mark.gpu
+
+# B, Hq, Hkv, Lk, D, ragged
+CASES = [
+    (3, 8, 2, 1000, 128, False), (3, 8, 2, 1000, 128, True), (2, 4, 4, 257, 64, True), (1, 32, 8, 5000, 128, False),
+    (2, 6, 2, 300, 128, True), (1, 1, 1, 1, 64, False), (5, 16, 2, 77, 64, True),
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,Lk,D,ragged", CASES)
+def test_decode_matches_oracle(B, Hq, Hkv, Lk, D, ragged, dtype):
+    print("case", B, Hq, Hkv, Lk, D, ragged, dtype, flush=True)
+    q, kc, vc = synth.decode_inputs(B, Hq, Hkv, Lk, D, dtype=dtype, seed=1)
+    sl = synth.ragged_seqlens(B, Lk, seed=2) if ragged else None
+    out, lse = u.decode(q.cuda(), kc.cuda(), vc.cuda(), None if sl is None else sl.cuda())
+    torch.cuda.synchronize()
+    o, l = oracle.decode(to_np(q), to_np(kc), to_np(vc), None if sl is None else sl.numpy())
+    eo, el = max_abs(to_np(out), o), max_abs(to_np(lse), l)
+    print(f"  out {eo:.3e} lse {el:.3e}", flush=True)
+    if dtype == torch.float32:
+        assert eo <= TOL_F32 and el <= TOL_F32
+    else:
+        assert eo <= TOL_OUT_BF16 and el <= TOL_LSE_BF16
+
+
+def test_decode_equals_last_row_of_the_training_kernel():
+    # the cache a generation loop would hold at position t, fed to decode, must give row t of the forward
+    L, D, r, W = 2000, 128, 8, 100
+    q, k, v, _ = synth.attn_inputs(1, 4, 1, L, D, seed=7)
+    out, lse = u.attn_fwd(q.cuda(), k.cuda(), v.cuda(), r, W)
+    t = L - 1
+    pos = torch.from_numpy(oracle.compressed_cache_positions(t, r, W))
+    kc, vc = k[:, :, pos].contiguous(), v[:, :, pos].contiguous()
+    o2, l2 = u.decode(q[:, :, t].contiguous().cuda(), kc.cuda(), vc.cuda())
+    assert max_abs(to_np(o2), to_np(out[:, :, t])) <= 1e-2
+    assert max_abs(to_np(l2), to_np(lse[:, :, t])) <= 1e-3
