@@ -40,7 +40,7 @@ import numpy as np
 __all__ = [
     "is_gist", "visible", "mask_rows", "count_visible",
     "attn_fwd_head", "attn_bwd_head", "attn_fwd", "attn_bwd",
-    "attn_fwd_rows", "attn_dq_rows", "decode", "compressed_cache_positions",
+    "attn_fwd_rows", "attn_dq_rows", "attn_dkdv_cols", "decode", "compressed_cache_positions",
 ]
 
 
@@ -214,6 +214,33 @@ def attn_dq_rows(q, k, v, dout, rows, r, W):
     delta = (P * dP).sum(axis=1)
     dS = P * (dP - delta[:, None])
     return (dS @ k) / math.sqrt(D)
+
+
+def attn_dkdv_cols(q, k, v, dout, cols, r, W, row_lo=0, row_hi=None, block=512):
+    """One query head: what the query rows row_lo .. row_hi-1 add to dK and dV of the chosen key
+    columns.  Same formulas as attn_bwd_head, with the sums over i restricted to those rows and
+    only the requested columns of dS and P kept.  Summing the results over disjoint row ranges
+    that cover 0 .. L-1 (and over the query heads of a group) gives dK[cols], dV[cols]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    cols = np.asarray(cols, dtype=np.int64)
+    L, D = q.shape
+    row_hi = L if row_hi is None else row_hi
+    dk = np.zeros((len(cols), D))
+    dv = np.zeros((len(cols), D))
+    for i0 in range(row_lo, row_hi, block):
+        rows = np.arange(i0, min(row_hi, i0 + block))
+        P, _ = _softmax_rows(q[rows], k, rows, r, W)
+        dO = dout[rows]
+        dP = dO @ v.T
+        delta = (P * dP).sum(axis=1)
+        Pc = P[:, cols]
+        dSc = Pc * (dP[:, cols] - delta[:, None])
+        dv += Pc.T @ dO
+        dk += (dSc.T @ q[rows]) / math.sqrt(D)
+    return dk, dv
 
 
 # --------------------------------------------------------------------------

@@ -23,6 +23,9 @@ FLAGS = [
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
     # packed fp32 VALU ops are kept off on purpose (see the build notes of this library)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep MFMA accumulators in ordinary VGPRs: the softmax works on them with VALU ops, and
+    # the AGPR form costs a copy in each direction per element
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -1,17 +1,558 @@
-// Backward of gist-masked attention, bf16 path (placeholder wiring: routes to the
-// plain-ALU kernels until the MFMA kernels land).
-#include "common.h"
+// Backward kernels of gist-masked attention for gfx950 (bf16 MFMA, fp32 accumulation), no atomics.
+//
+// With P_ij = exp(scale S_ij - lse_i) on the visible pairs of Sec. 4.1, Eq. 3:
+//   delta_i = dO_i . O_i                      dV_j = sum_i P_ij dO_i
+//   dP_ij   = dO_i . V_j                      dS_ij = P_ij (dP_ij - delta_i)
+//   dQ_i    = scale sum_j dS_ij K_j           dK_j = scale sum_i dS_ij Q_i   (summed over the q heads of a group)
+//
+// Launch sequence (all on the caller's stream):
+//   1. delta_kernel         delta = rowsum(dO * O)
+//   2. dkdv_kernel<GIST>    one workgroup per (compact gist tile, segment of query chunks): the pairs whose
+//                           gist lies left of the query chunk's window phase; fp32 partials to the workspace
+//   3. gist_reduce_kernel   sums the segments of a gist tile in a fixed order
+//   4. dkdv_kernel<WINDOW>  one workgroup per contiguous 128-key tile: the pairs of the window phase; its
+//                           epilogue adds the reduced gist-phase sums to the gist rows and writes dK, dV
+//   5. dq_kernel            one workgroup per 128-query tile, same tile walk as the forward
+// Every (query, key) pair is handled by exactly one of the two dkdv phases: a query chunk c (64 rows) sees
+// the gists at positions < far(c) = floor(max(0, 64c - W + 1) / 128) * 128 in the gist phase and every key
+// >= far(c) in the window phase.
+//
+// dkdv: a wave owns 32 keys (one lane = one key), K and V fragments stay in registers, Q / dO chunks are
+// staged in LDS and read both row-wise (S = Q K^T, dP = dO V^T) and through transposing LDS reads
+// (dV^T += dO^T P, dK^T += Q^T dS); the S/dP accumulators are already the B operands of the last two.
+// dq: forward-shaped; S^T = K Q^T and dP^T = V dO^T per lane-owned query, dQ^T += K^T dS^T.
+#include "mfma_common.h"
 
 namespace unigist {
+namespace {
 
-size_t bwd_mfma_workspace(const AttnShape& s) {
-    return (((size_t)s.B * s.Hq * s.L * sizeof(float)) + 255) & ~(size_t)255;
+constexpr int NT = 256;
+constexpr int BNK = 128;  // keys per dkdv workgroup
+constexpr int MQ = 64;    // query rows per dkdv step
+constexpr int BMQ = 128;  // query rows per dq workgroup
+constexpr int BNQ = 64;   // keys per dq step
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct BwdPlan {
+    int NC;      // query chunks of MQ rows
+    int n_gt;    // compact gist tiles (BNK gists each) seen by some chunk
+    int segc;    // chunks per segment
+    int nseg;    // segments
+    size_t off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
+};
+
+__host__ __device__ inline int far_of_chunk(int c, int W) {
+    int lo = c * MQ - W + 1;
+    if (lo < 0) lo = 0;
+    return (lo / BNK) * BNK;
 }
+
+// first chunk whose gist phase reaches into compact gist tile gt
+__host__ __device__ inline int first_chunk_of_gtile(int gt, int rp1, int W) {
+    const long long y = (long long)(BNK * gt + 1) * rp1;       // far(c) must be >= y
+    const long long x = (y + BNK - 1) / BNK * BNK;             // ... and is a multiple of BNK
+    return (int)((x + W - 1 + MQ - 1) / MQ);
+}
+
+BwdPlan make_plan(const AttnShape& s) {
+    BwdPlan p;
+    p.NC = (s.L + MQ - 1) / MQ;
+    const int nfar_max = far_of_chunk(p.NC - 1, s.W) / s.rp1;
+    p.n_gt = (nfar_max + BNK - 1) / BNK;
+    p.segc = 64;
+    while ((p.NC + p.segc - 1) / p.segc > 16) p.segc *= 2;
+    p.nseg = (p.NC + p.segc - 1) / p.segc;
+    const size_t a = 255;
+    size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
+    p.off_part = off;
+    off += (size_t)s.B * s.Hkv * p.n_gt * p.nseg * 2 * s.D * BNK * sizeof(float);
+    off = (off + a) & ~a;
+    p.off_comp = off;
+    off += (size_t)s.B * s.Hkv * p.n_gt * 2 * s.D * BNK * sizeof(float);
+    p.total = (off + a) & ~a;
+    return p;
+}
+
+// ------------------------------------------------------------------ 1. delta
+template <int D>
+__global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
+                                                  float* __restrict__ delta, long nrows) {
+    constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
+    const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;
+    const int sub = threadIdx.x % LPR;
+    float acc = 0.f;
+    if (row < nrows) {
+        u32x4 a = *(const u32x4*)(out + row * D + sub * 8);
+        u32x4 b = *(const u32x4*)(dout + row * D + sub * 8);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            acc += __uint_as_float(a[t] << 16) * __uint_as_float(b[t] << 16);
+            acc += __uint_as_float(a[t] & 0xffff0000u) * __uint_as_float(b[t] & 0xffff0000u);
+        }
+    }
+    // reduce over the LPR lanes of a row (LPR is 8 or 16, rows are aligned to LPR lanes)
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
+    if (row < nrows && sub == 0) delta[row] = acc;
+}
+
+// ------------------------------------------------------------------ 2./4. dK, dV
+template <int D>
+struct DkdvSmem {
+    static constexpr int STR = D + 8;  // row stride in elements
+    bf16_t q[MQ * STR];
+    bf16_t g[MQ * STR];  // dO
+    float lse[MQ];
+    float delta[MQ];
+};
+
+template <int D, bool GIST>
+__global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                 const bf16_t* __restrict__ v, const float* __restrict__ lse,
+                                                 const bf16_t* __restrict__ dout, const float* __restrict__ delta,
+                                                 bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                                 float* __restrict__ part, const float* __restrict__ comp,
+                                                 AttnShape s, BwdPlan pl) {
+    constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
+    constexpr int RPP = NT / CH, PASSES = MQ / RPP;
+    constexpr int STR = DkdvSmem<D>::STR;
+    __shared__ __attribute__((aligned(16))) DkdvSmem<D> sm;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int hk = blockIdx.y, b = blockIdx.z;
+    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int G = s.Hq / s.Hkv;
+    const float c = s.scale * kLog2e;
+
+    // ---- which keys, which query chunks
+    int tile, c_lo, c_hi;  // chunks c_lo .. c_hi inclusive
+    int seg = 0;
+    if (GIST) {
+        tile = blockIdx.x / pl.nseg;
+        seg = blockIdx.x % pl.nseg;
+        const int cf = first_chunk_of_gtile(tile, rp1, W);
+        c_lo = max(cf, seg * pl.segc);
+        c_hi = min(pl.NC, (seg + 1) * pl.segc) - 1;
+        if (c_lo > c_hi) return;  // this segment lies before the tile becomes visible (uniform exit)
+    } else {
+        tile = blockIdx.x;
+        const int j0 = tile * BNK;
+        c_lo = j0 / MQ;
+        c_hi = min((long long)pl.NC - 1, ((long long)j0 + BNK + W - 2) / MQ);
+    }
+    const int key0 = tile * BNK + 32 * w;      // first key (position, or compact gist index) of the wave
+    const int key = key0 + c32;                // this lane's key
+    int krow;                                  // row of K/V holding it
+    if (GIST) {
+        const int gtot = L / rp1;              // >= 1 whenever a gist workgroup exists
+        krow = min(key, gtot - 1) * rp1 + rp1 - 1;
+    } else {
+        krow = min(key, L - 1);
+    }
+    const bool gist_lane = GIST ? true : ((key + 1) % rp1 == 0);
+
+    // ---- K, V fragments (B operands): lane holds K[key][16 ks + 8h .. +7]
+    bf16x8 kf[KS], vf[KS];
+    {
+        const size_t base = (((size_t)b * s.Hkv + hk) * L + krow) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *(const bf16x8*)(k + base + 16 * ks);
+            vf[ks] = *(const bf16x8*)(v + base + 16 * ks);
+        }
+    }
+    f32x16 akT[DB], avT[DB];  // dK^T, dV^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        akT[db] = zero16();
+        avT[db] = zero16();
+    }
+
+    // ---- staging of the Q / dO chunk
+    const int srow = tid / CH, scol = (tid % CH) * 8;
+    u32x4 qreg[PASSES], greg[PASSES];
+    float sreg = 0.f;  // threads 0..63: lse of row tid; 64..127: delta of row tid - 64
+    const int nch = c_hi - c_lo + 1;
+    const int nsteps = nch * G;
+    auto fetch = [&](int step) {
+        const int g = step / nch, cc = c_lo + step % nch;
+        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = min(cc * MQ + p * RPP + srow, L - 1);
+            qreg[p] = *(const u32x4*)(q + (hb + row) * D + scol);
+            greg[p] = *(const u32x4*)(dout + (hb + row) * D + scol);
+        }
+        if (tid < 2 * MQ) {
+            const int row = min(cc * MQ + (tid & (MQ - 1)), L - 1);
+            sreg = tid < MQ ? lse[hb + row] * kLog2e : delta[hb + row];
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int rr = p * RPP + srow;
+            *(u32x4*)(&sm.q[rr * STR + scol]) = qreg[p];
+            *(u32x4*)(&sm.g[rr * STR + scol]) = greg[p];
+        }
+        if (tid < MQ) sm.lse[tid] = sreg;
+        else if (tid < 2 * MQ) sm.delta[tid - MQ] = sreg;
+    };
+
+    fetch(0);
+    for (int step = 0; step < nsteps; ++step) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (step + 1 < nsteps) fetch(step + 1);
+        const int cc = c_lo + step % nch;
+        const int q0 = cc * MQ;
+
+        int nfar = 0;
+        if (GIST) nfar = far_of_chunk(cc, W) / rp1;  // compact gists visible to this chunk: index < nfar
+
+#pragma unroll
+        for (int qb = 0; qb < MQ / 32; ++qb) {
+            const int qb0 = q0 + 32 * qb;  // first query row of the block
+            if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
+
+            // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
+            f32x16 sa = zero16(), dp = zero16();
+            {
+                const bf16_t* qp = &sm.q[(32 * qb + c32) * STR + 8 * h];
+                const bf16_t* gp = &sm.g[(32 * qb + c32) * STR + 8 * h];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    sa = mfma32(*(const bf16x8*)(qp + 16 * ks), kf[ks], sa);
+                    dp = mfma32(*(const bf16x8*)(gp + 16 * ks), vf[ks], dp);
+                }
+            }
+            // ---- P and dS
+            bool masked;
+            if (GIST) masked = key0 + 31 >= nfar || qb0 + 31 >= L;
+            else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < W && qb0 + 31 < L);
+            const int d0 = qb0 + 4 * h - key;  // distance of the lane's first query to its key
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 l4 = *(const f32x4*)(&sm.lse[32 * qb + 8 * i4 + 4 * h]);
+                const f32x4 d4 = *(const f32x4*)(&sm.delta[32 * qb + 8 * i4 + 4 * h]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int i = 4 * i4 + t;
+                    float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -l4[t]));
+                    if (masked) {
+                        const int off = 8 * i4 + t;
+                        bool ok;
+                        if (GIST) {
+                            ok = key < nfar && qb0 + 4 * h + off < L;
+                        } else {
+                            const int dist = d0 + off;  // i - j
+                            ok = ((unsigned)dist < (unsigned)W || (gist_lane && dist >= 0)) && qb0 + 4 * h + off < L;
+                        }
+                        p = ok ? p : 0.f;
+                    }
+                    sa[i] = p;
+                    dp[i] = p * (dp[i] - d4[t]);
+                }
+            }
+            // ---- dV^T += dO^T P,  dK^T += Q^T dS   (16 queries per MFMA)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 pb = pack8(sa, 8 * kk);
+                const bf16x8 sb = pack8(dp, 8 * kk);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    avT[db] = mfma32(tr16_frag(sm.g, STR, 32 * qb + 16 * kk, 32 * db), pb, avT[db]);
+                    akT[db] = mfma32(tr16_frag(sm.q, STR, 32 * qb + 16 * kk, 32 * db), sb, akT[db]);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue
+    if (GIST) {
+        // fp32 partials, transposed: [dK^T | dV^T][d][BNK keys]
+        float* o = part + ((((size_t)b * s.Hkv + hk) * pl.n_gt + tile) * pl.nseg + seg) * (2 * D * BNK) + 32 * w + c32;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int d = 32 * db + 8 * (i / 4) + 4 * h + (i % 4);
+                o[(size_t)d * BNK] = akT[db][i] * s.scale;
+                o[(size_t)(D + d) * BNK] = avT[db][i];
+            }
+    } else {
+        if (gist_lane && pl.n_gt > 0) {
+            // add what the gist phase collected for this row (zero if no chunk saw it from afar)
+            const int gi = (key + 1) / rp1 - 1;
+            const int gt = gi / BNK;
+            if (gt < pl.n_gt && key < L) {
+                const float* cp = comp + (((size_t)b * s.Hkv + hk) * pl.n_gt + gt) * (2 * D * BNK) + gi % BNK;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int d = 32 * db + 8 * (i / 4) + 4 * h + (i % 4);
+                        akT[db][i] = akT[db][i] * s.scale + cp[(size_t)d * BNK];
+                        avT[db][i] += cp[(size_t)(D + d) * BNK];
+                    }
+            } else {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) akT[db][i] *= s.scale;
+            }
+        } else {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) akT[db][i] *= s.scale;
+        }
+        if (key < L) {
+            const size_t base = (((size_t)b * s.Hkv + hk) * L + key) * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    u32x2 a, bb;
+                    a[0] = pack_bf16x2(akT[db][4 * i4], akT[db][4 * i4 + 1]);
+                    a[1] = pack_bf16x2(akT[db][4 * i4 + 2], akT[db][4 * i4 + 3]);
+                    bb[0] = pack_bf16x2(avT[db][4 * i4], avT[db][4 * i4 + 1]);
+                    bb[1] = pack_bf16x2(avT[db][4 * i4 + 2], avT[db][4 * i4 + 3]);
+                    *(u32x2*)(dk + base + 32 * db + 8 * i4) = a;
+                    *(u32x2*)(dv + base + 32 * db + 8 * i4) = bb;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 3. sum the segments of each gist tile
+__global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict__ part, float* __restrict__ comp,
+                                                        int n_gt, int nseg, int segc, int NC, int rp1, int W,
+                                                        int per_tile) {
+    // grid: x = slices of a tile's 2*D*BNK floats, y = tile, z = (b, hk)
+    const int gt = blockIdx.y;
+    const size_t t = (size_t)blockIdx.z * n_gt + gt;
+    const int idx = blockIdx.x * NT + threadIdx.x;
+    if (idx >= per_tile) return;
+    const int cf = first_chunk_of_gtile(gt, rp1, W);
+    float acc = 0.f;
+    if (cf < NC)
+        for (int sg = cf / segc; sg < nseg; ++sg) acc += part[(t * nseg + sg) * per_tile + idx];
+    comp[t * per_tile + idx] = acc;
+}
+
+// ------------------------------------------------------------------ 5. dQ
+template <int D>
+struct DqSmem {
+    static constexpr int KSTR = D + 8;
+    static constexpr int VSTR = D + 8;
+    bf16_t k[BNQ * KSTR];
+    bf16_t v[BNQ * VSTR];
+};
+
+template <int D>
+__global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                               const bf16_t* __restrict__ v, const float* __restrict__ lse,
+                                               const bf16_t* __restrict__ dout, const float* __restrict__ delta,
+                                               bf16_t* __restrict__ dq, AttnShape s, int nq) {
+    constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
+    constexpr int RPP = NT / CH, PASSES = BNQ / RPP;
+    constexpr int KSTR = DqSmem<D>::KSTR, VSTR = DqSmem<D>::VSTR;
+    __shared__ __attribute__((aligned(16))) DqSmem<D> sm;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int G = s.Hq / s.Hkv, NP = s.B * s.Hkv;
+    int n = blockIdx.x, g, pr, qt;
+    if ((NP & 7) == 0) {
+        const int xcd = n & 7, mm = n >> 3;
+        g = mm % G;
+        const int rest = mm / G;
+        const int pb = rest % (NP >> 3);
+        qt = nq - 1 - rest / (NP >> 3);
+        pr = xcd + 8 * pb;
+    } else {
+        g = n % G;
+        const int rest = n / G;
+        pr = rest % NP;
+        qt = nq - 1 - rest / NP;
+    }
+    const int b = pr / s.Hkv, hk = pr % s.Hkv, hq = hk * G + g;
+    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
+    const int qrow = i0 + 32 * w + c32, qrow_ld = min(qrow, L - 1), wrow0 = i0 + 32 * w;
+    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * L * D;
+    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * L * D;
+    const float c = s.scale * kLog2e;
+
+    bf16x8 qf[KS], gf[KS];
+    const size_t rowoff = ((size_t)b * s.Hq + hq) * L + qrow_ld;
+    {
+        const bf16_t* qp = q + rowoff * D + 8 * h;
+        const bf16_t* gp = dout + rowoff * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+            gf[ks] = *(const bf16x8*)(gp + 16 * ks);
+        }
+    }
+    const float ls = lse[rowoff] * kLog2e;
+    const float dl = delta[rowoff];
+
+    f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[db] = zero16();
+
+    const int lo = max(0, i0 - W + 1);
+    const int wfirst = lo / BNQ;
+    const int nfar = (wfirst * BNQ) / rp1;
+    const int ngt = (nfar + BNQ - 1) / BNQ;
+    const int nwin = i1 / BNQ - wfirst + 1;
+    const int ntiles = ngt + nwin;
+
+    const int srow = tid / CH, scol = (tid % CH) * 8;
+    u32x4 kreg[PASSES], vreg[PASSES];
+    auto fetch = [&](int it) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int rr = p * RPP + srow;
+            int row;
+            if (it < ngt) row = min(it * BNQ + rr, nfar - 1) * rp1 + rp1 - 1;
+            else row = min((wfirst + it - ngt) * BNQ + rr, L - 1);
+            kreg[p] = *(const u32x4*)(kb + (size_t)row * D + scol);
+            vreg[p] = *(const u32x4*)(vb + (size_t)row * D + scol);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int rr = p * RPP + srow;
+            *(u32x4*)(&sm.k[rr * KSTR + scol]) = kreg[p];
+            *(u32x4*)(&sm.v[rr * VSTR + scol]) = vreg[p];
+        }
+    };
+
+    fetch(0);
+    for (int it = 0; it < ntiles; ++it) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (it + 1 < ntiles) fetch(it + 1);
+        const bool gist_tile = it < ngt;
+        const int j0 = gist_tile ? it * BNQ : (wfirst + it - ngt) * BNQ;
+        if (!gist_tile && j0 > wrow0 + 31) continue;
+
+        bool masked;
+        unsigned long long gm = 0ull;
+        if (gist_tile) {
+            masked = j0 + BNQ > nfar;
+        } else {
+            masked = !(j0 + BNQ - 1 <= wrow0 && wrow0 + 31 - j0 < W);
+            if (masked) gm = __builtin_amdgcn_ballot_w64((j0 + lane + 1) % rp1 == 0) >> (4 * h);
+        }
+        const int lim = nfar - j0 - 4 * h;
+        const int d0 = qrow - (j0 + 4 * h);
+
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            // S^T, dP^T for 32 keys: register i is key j0 + 32 kb2 + 8 (i/4) + 4h + i%4, lane = query
+            f32x16 sa = zero16(), dp = zero16();
+            const bf16_t* kp = &sm.k[(32 * kb2 + c32) * KSTR + 8 * h];
+            const bf16_t* vp = &sm.v[(32 * kb2 + c32) * VSTR + 8 * h];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                sa = mfma32(*(const bf16x8*)(kp + 16 * ks), qf[ks], sa);
+                dp = mfma32(*(const bf16x8*)(vp + 16 * ks), gf[ks], dp);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -ls));
+                if (masked) {
+                    const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
+                    bool ok;
+                    if (gist_tile) {
+                        ok = off < lim;
+                    } else {
+                        const int dist = d0 - off;
+                        ok = (unsigned)dist < (unsigned)W || (dist >= 0 && ((gm >> off) & 1ull));
+                    }
+                    p = ok ? p : 0.f;
+                }
+                dp[i] = p * (dp[i] - dl);
+            }
+            // dQ^T += K^T dS^T
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 sb = pack8(dp, 8 * kk);
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    acc[db] = mfma32(tr16_frag(sm.k, KSTR, 32 * kb2 + 16 * kk, 32 * db), sb, acc[db]);
+            }
+        }
+    }
+
+    if (qrow < L) {
+        bf16_t* op = dq + rowoff * D + 4 * h;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                u32x2 w2;
+                w2[0] = pack_bf16x2(acc[db][4 * i4] * s.scale, acc[db][4 * i4 + 1] * s.scale);
+                w2[1] = pack_bf16x2(acc[db][4 * i4 + 2] * s.scale, acc[db][4 * i4 + 3] * s.scale);
+                *(u32x2*)(op + 32 * db + 8 * i4) = w2;
+            }
+    }
+}
+
+template <int D>
+hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* out, const float* lse,
+                      const bf16_t* dout, bf16_t* dq, bf16_t* dk, bf16_t* dv, char* ws, const AttnShape& s,
+                      hipStream_t st) {
+    const BwdPlan pl = make_plan(s);
+    float* delta = (float*)ws;
+    float* part = (float*)(ws + pl.off_part);
+    float* comp = (float*)(ws + pl.off_comp);
+    hipError_t e;
+    {
+        constexpr int rows_per_blk = NT / (D / 8);
+        const long nrows = (long)s.B * s.Hq * s.L;
+        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(out, dout, delta, nrows);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (pl.n_gt > 0) {
+        dkdv_kernel<D, true><<<dim3(pl.n_gt * pl.nseg, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv, part,
+                                                                                 comp, s, pl);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        const int per_tile = 2 * D * BNK;
+        gist_reduce_kernel<<<dim3((per_tile + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
+            part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s.rp1, s.W, per_tile);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    dkdv_kernel<D, false><<<dim3((s.L + BNK - 1) / BNK, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv, part,
+                                                                                  comp, s, pl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int nq = (s.L + BMQ - 1) / BMQ;
+    const long nblk = (long)nq * s.Hq * s.B;
+    if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
+    dq_kernel<D><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse, dout, delta, dq, s, nq);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t bwd_mfma_workspace(const AttnShape& s) { return make_plan(s).total; }
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
                            hipStream_t st) {
-    return launch_bwd_simple(q, k, v, out, lse, dout, dq, dk, dv, (float*)ws, s, UNIGIST_BF16, st);
+    if (s.D == 64)
+        return bwd_launch<64>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
+                              (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, st);
+    return bwd_launch<128>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
+                           (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, st);
 }
 
 }  // namespace unigist

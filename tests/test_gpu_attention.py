@@ -60,6 +60,41 @@ def test_small_shapes_match_oracle(B, Hq, Hkv, L, D, r, W, dtype):
     check(case, got, oracle_fwd_bwd(q, k, v, dout, r, W), dtype)
 
 
+# mid sizes: several 128-row tiles, many compact gist tiles, more than one segment of query
+# chunks in the gist phase of dK/dV (L > 4096), ragged tails in L, in the gist list and in W
+MID = [
+    (1, 2, 1, 9001, 64, 4, 300),
+    (1, 4, 1, 5000, 128, 2, 129),
+    (2, 4, 2, 4500, 128, 8, 1024),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,D,r,W", MID)
+def test_mid_shapes_match_oracle(B, Hq, Hkv, L, D, r, W):
+    case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} bf16"
+    print("case", case, flush=True)
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=11)
+    got = run_gpu(q, k, v, dout, r, W)
+    check(case, got, oracle_fwd_bwd(q, k, v, dout, r, W), torch.bfloat16)
+
+
+def test_plain_alu_and_mfma_kernels_agree():
+    # the two independent GPU implementations on a shape the oracle would need minutes for
+    import os
+    B, Hq, Hkv, L, D, r, W = 1, 8, 2, 20000, 128, 4, 1024
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=12)
+    a = run_gpu(q, k, v, dout, r, W)
+    os.environ["UNIGIST_DEBUG_PLAIN_ALU"] = "1"
+    try:
+        b = run_gpu(q, k, v, dout, r, W)
+    finally:
+        os.environ["UNIGIST_DEBUG_PLAIN_ALU"] = "0"
+    assert max_abs(to_np(a[0]), to_np(b[0])) <= 3.2e-2  # two bf16 roundings of values up to 4
+    assert max_abs(to_np(a[1]), to_np(b[1])) <= 1e-4
+    for x, y in zip(a[2:], b[2:]):
+        assert rel_l2(to_np(x), to_np(y)) <= 1e-2
+
+
 def test_runs_are_bitwise_reproducible():
     q, k, v, dout = synth.attn_inputs(1, 4, 2, 700, 128, seed=3)
     a = run_gpu(q, k, v, dout, 4, 64)

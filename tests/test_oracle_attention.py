@@ -147,6 +147,20 @@ def test_backward_matches_library_autograd():
     np.testing.assert_allclose(oracle.attn_dq_rows(q, k, v, do, [3, 50, 89], r, W), dq[[3, 50, 89]], rtol=0, atol=1e-13)
 
 
+def test_column_sampled_backward_equals_full_backward():
+    L, D, r, W = 150, 8, 4, 17
+    q, k, v, do = (_rand((L, D), s) for s in (50, 51, 52, 53))
+    _, dk, dv = oracle.attn_bwd_head(q, k, v, do, r, W)
+    cols = [0, 4, 9, 77, 78, 79, 149]
+    a = oracle.attn_dkdv_cols(q, k, v, do, cols, r, W, 0, 60, block=16)
+    b = oracle.attn_dkdv_cols(q, k, v, do, cols, r, W, 60, None, block=64)
+    np.testing.assert_allclose(a[0] + b[0], dk[cols], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(a[1] + b[1], dv[cols], rtol=0, atol=1e-13)
+    # rows before a raw key or outside its window add nothing
+    z = oracle.attn_dkdv_cols(q, k, v, do, [78], r, W, 78 + W, None)
+    assert not z[0].any() and not z[1].any()
+
+
 def test_backward_structural_zeros():
     # dout non-zero only on rows i >= j0 + W: raw keys j <= j0 get no gradient, gists do
     L, D, r, W, j0 = 80, 4, 4, 6, 30
