@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of libunigist on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one forward plus one backward of gist-masked attention on the 32K-token GQA
+workload (B=1, Hq=32, Hkv=8, D=128, L=32768, r=4, W=1024, bf16, synthetic N(0,1) inputs
+already resident in HBM).  The headline value is TFLOP/s counted over the visible
+(query, key) pairs only: 4*D flops per pair forward, 10*D backward, recompute not counted.
+The backward is issued one stage at a time with HIP events between the stages (all on
+torch's current stream, which is the stream the kernels run on), so every kernel's
+duration is measured live inside the timed region.  The decode op (a serving-path call on
+a different workload: 64 sequences x 17 408 cached keys) is timed in its own region and
+reported beside it with its HBM roofline.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2509_15763_amd as u  # noqa: E402
+from paper_2509_15763_amd import synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
+WORKLOAD = "cfg2_llama8b_32k"
+
+# HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+# what the same counters read for a plain copy); see profiles/.  None = not measured yet.
+TRAFFIC_BYTES = {"fwd": None, "dkdv_gist": None, "dkdv_window": None, "dq": None, "decode": None}
+
+
+def pair_counts(L, r, W):
+    """Visible pairs per head, split the way the dK/dV pass splits them: a 64-row query chunk
+    c reaches the gists left of far(c) = floor(max(0, 64c - W + 1) / 128) * 128 in the gist
+    phase and everything else in the window phase."""
+    nvis = u.n_vis(L, r, W)
+    rp1 = r + 1 if r < L else L + 1
+    far_pairs = 0
+    for c in range((L + 63) // 64):
+        rows = min(L, 64 * c + 64) - 64 * c
+        far = (max(0, 64 * c - min(W, L) + 1) // 128) * 128
+        far_pairs += rows * (far // rp1)
+    return nvis, far_pairs
+
+
+def cpu_baseline(cfg, budget_s=12.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: blocks of 512
+    query rows spread over the sequence, forward and backward, head after head, until about
+    `budget_s` seconds of CPU work are done.  Its cost per row does not depend on the row (every
+    key is scored), so the sample is representative."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    L, D, r, W, G = cfg["L"], cfg["D"], cfg["r"], cfg["W"], cfg["Hq"] // cfg["Hkv"]
+    q, k, v, do = synth.attn_inputs(1, G, 1, L, D, seed=0)
+    kn, vn = k[0, 0].double().numpy(), v[0, 0].double().numpy()
+    starts = [int(x) for x in np.linspace(0, L - 512, 8)]
+    pairs = nblocks = 0
+    t0 = time.perf_counter()
+    for h in range(G):
+        qn, don = q[0, h].double().numpy(), do[0, h].double().numpy()
+        for s0 in starts:
+            rows = np.arange(s0, s0 + 512)
+            oracle.attn_fwd_rows(qn, kn, vn, rows, r, W)
+            oracle.attn_bwd_head(qn, kn, vn, don, r, W, block=512, row_lo=s0, row_hi=s0 + 512)
+            pairs += int(np.sum(np.minimum(rows + 1, W) + np.maximum(0, (rows - W + 1) // (r + 1))))
+            nblocks += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": 14.0 * D * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{nblocks} blocks of 512 query rows spread over the {L} positions of up to {G} query heads "
+                      f"(one kv group), fwd+bwd, dense fp64 numpy, {dt:.1f} s of CPU work; flops counted on "
+                      f"visible pairs only (4*D fwd + 10*D bwd per pair)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; libunigist has no CPU path")
+
+    cfg = dict(synth.WORKLOADS[WORKLOAD])
+    B, Hq, Hkv, L, D, r, W = (cfg[n] for n in ("B", "Hq", "Hkv", "L", "D", "r", "W"))
+    dev = "cuda"
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=0, device=dev)
+    nvis, far_pairs = pair_counts(L, r, W)
+    flops_fwd = 4.0 * D * nvis * B * Hq
+    flops_bwd = 10.0 * D * nvis * B * Hq
+    ws = torch.empty(u.unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, u.UNIGIST_BF16), device=dev, dtype=torch.uint8)
+    grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+    stage_names = ["delta", "dkdv_gist", "gist_reduce", "dkdv_window", "dq"]
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        out, lse = u.attn_fwd(q, k, v, r, W)
+        if events is not None:
+            events[1].record()
+        for n, name in enumerate(stage_names):
+            u.attn_bwd(q, k, v, out, lse, dout, r, W, workspace=ws, stages=u.BWD_STAGES[name], grads=grads)
+            if events is not None:
+                events[2 + n].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    names = ["fwd"] + stage_names
+    ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
+    fwd_ms = ms["fwd"]
+    bwd_ms = sum(ms[n] for n in stage_names)
+    step_ms = evs[0][0].elapsed_time(evs[-1][6]) / args.steps
+
+    # dominant kernel and its roofline: algorithmic flops of that launch / its measured duration.
+    # dK/dV kernels: S, dP, dV, dK = 8*D per pair they own; dQ kernel: only dQ is new work (2*D per
+    # pair), its recomputed S and dP are overhead and not counted.
+    alg = {"fwd": flops_fwd, "dkdv_gist": 8.0 * D * far_pairs * B * Hq,
+           "dkdv_window": 8.0 * D * (nvis - far_pairs) * B * Hq, "dq": 2.0 * D * nvis * B * Hq}
+    dom = max(alg, key=lambda n: ms[n])
+    achieved = alg[dom] / ms[dom] / 1e9
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom),
+                "avg_ms": ms[dom], "alg_flops_per_launch": alg[dom]}
+
+    # decode on its own workload, its own timed region
+    dc = synth.WORKLOADS["cfg5_decode"]
+    dq_, dk_, dv_ = synth.decode_inputs(dc["B"], dc["Hq"], dc["Hkv"], dc["Lk"], dc["D"], seed=0, device=dev)
+    dws = torch.empty(u.unigist_decode_workspace(dc["B"], dc["Hq"], dc["Hkv"], dc["Lk"], dc["D"], u.UNIGIST_BF16),
+                      device=dev, dtype=torch.uint8)
+    for _ in range(3):
+        u.decode(dq_, dk_, dv_, workspace=dws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nd = 20
+    e0.record()
+    for _ in range(nd):
+        u.decode(dq_, dk_, dv_, workspace=dws)
+    e1.record()
+    torch.cuda.synchronize()
+    dec_ms = e0.elapsed_time(e1) / nd
+    dec_bytes = 2.0 * dc["B"] * dc["Hkv"] * dc["Lk"] * dc["D"] * 2
+    dec_gbs = dec_bytes / dec_ms / 1e6
+    del dq_, dk_, dv_, dws
+
+    bm, bn = u.unigist_tile_sizes(D, u.UNIGIST_BF16)
+    m = u.unigist_blockmap_build(L, r, W, bm, bn)
+    value = (flops_fwd + flops_bwd) / step_ms / 1e9
+    res = {
+        "metric": "gist-attn fwd+bwd TFLOP/s (unmasked) @32K GQA; % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOAD, "B": B, "Hq": Hq, "Hkv": Hkv, "L": L, "D": D, "r": r, "W": W,
+                   "visible_pairs_per_head": nvis, "live_tile_fraction": m["live_tiles"] / m["causal_tiles"]},
+        "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "fwd": {"ms": fwd_ms, "tflops": flops_fwd / fwd_ms / 1e9, "pct_of_peak": flops_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS * 100},
+        "bwd": {"ms": bwd_ms, "tflops": flops_bwd / bwd_ms / 1e9, "pct_of_peak": flops_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS * 100,
+                "stage_ms": {n: ms[n] for n in stage_names}},
+        "wall_ms_per_step": wall_ms,
+        "roofline": roofline,
+        "decode": {"workload": "cfg5_decode", "ms": dec_ms, "roofline": {
+            "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
+            "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes}},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -77,6 +77,32 @@ unigist_status unigist_attn_bwd(const void* q, const void* k, const void* v, con
                                 unigist_dtype dt, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/*
+ * The same backward, restricted to some of its stream-ordered stages (for per-kernel timing and
+ * debugging).  `stages` is a bit mask; the stages depend on each other in this order, so a caller
+ * running them one by one must keep the order and the same workspace:
+ *   UNIGIST_BWD_DELTA        delta_i = dO_i . O_i                      (Sec. 4.1 softmax backward)
+ *   UNIGIST_BWD_DKDV_GIST    dK/dV of the pairs whose gist lies left of the query's window phase
+ *   UNIGIST_BWD_GIST_REDUCE  fixed-order sum of that phase's partial results
+ *   UNIGIST_BWD_DKDV_WINDOW  dK/dV of the window phase, adds the gist phase, writes dk and dv
+ *   UNIGIST_BWD_DQ           writes dq
+ * unigist_attn_bwd is this call with UNIGIST_BWD_ALL.  Masks other than UNIGIST_BWD_ALL are
+ * supported for bf16 only (UNIGIST_EUNSUPPORTED otherwise); stages == 0 is UNIGIST_EINVAL.
+ */
+enum {
+    UNIGIST_BWD_DELTA = 1,
+    UNIGIST_BWD_DKDV_GIST = 2,
+    UNIGIST_BWD_GIST_REDUCE = 4,
+    UNIGIST_BWD_DKDV_WINDOW = 8,
+    UNIGIST_BWD_DQ = 16,
+    UNIGIST_BWD_ALL = 31
+};
+unigist_status unigist_attn_bwd_stages(const void* q, const void* k, const void* v, const void* out,
+                                       const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                       int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                       unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                       unsigned stages, void* hip_stream);
+
 /* Bytes of workspace unigist_attn_bwd needs for this shape (0 on invalid arguments). */
 size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
                                   unigist_dtype dt);

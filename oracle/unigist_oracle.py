@@ -118,25 +118,27 @@ def attn_fwd_head(q, k, v, r, W, block=512):
     return out, lse
 
 
-def attn_bwd_head(q, k, v, dout, r, W, block=512):
+def attn_bwd_head(q, k, v, dout, r, W, block=512, row_lo=0, row_hi=None):
     """Gradients of l = sum(out * dout) for one head.
 
     dV_j = sum_i P_ij dO_i;  dP_ij = dO_i . v_j;  delta_i = sum_j P_ij dP_ij;
     dS_ij = P_ij (dP_ij - delta_i);  dQ_i = sum_j dS_ij k_j / sqrt(D);
     dK_j = sum_i dS_ij q_i / sqrt(D).
-    Returns dq, dk, dv (all [L, D]).
+    Returns dq, dk, dv (all [L, D]).  With row_lo/row_hi only those query rows are
+    processed: dq is filled for them (zero elsewhere) and dk, dv hold their share of the sums.
     """
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     dout = np.asarray(dout, dtype=np.float64)
     L, D = q.shape
+    row_hi = L if row_hi is None else row_hi
     inv = 1.0 / math.sqrt(D)
-    dq = np.empty((L, D))
+    dq = np.zeros((L, D))
     dk = np.zeros((L, D))
     dv = np.zeros((L, D))
-    for i0 in range(0, L, block):
-        rows = np.arange(i0, min(L, i0 + block))
+    for i0 in range(row_lo, row_hi, block):
+        rows = np.arange(i0, min(row_hi, i0 + block))
         P, _ = _softmax_rows(q[rows], k, rows, r, W)
         dO = dout[rows]
         dv += P.T @ dO

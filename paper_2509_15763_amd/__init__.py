@@ -7,7 +7,8 @@ library has not been built.
 """
 from .binding import (  # noqa: F401
     UNIGIST_BF16, UNIGIST_F32, UnigistError, lib_path, load,
-    unigist_attn_fwd, unigist_attn_bwd, unigist_attn_bwd_workspace,
+    unigist_attn_fwd, unigist_attn_bwd, unigist_attn_bwd_stages, unigist_attn_bwd_workspace,
+    BWD_STAGES, UNIGIST_BWD_ALL,
     unigist_decode, unigist_decode_workspace, unigist_blockmap_build,
     unigist_status_str, unigist_tile_sizes,
     attn_fwd, attn_bwd, decode, n_vis,

@@ -10,12 +10,15 @@ import torch
 
 UNIGIST_BF16 = 0
 UNIGIST_F32 = 1
+BWD_STAGES = {"delta": 1, "dkdv_gist": 2, "gist_reduce": 4, "dkdv_window": 8, "dq": 16}
+UNIGIST_BWD_ALL = 31
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = [
-    "unigist_status_str", "unigist_attn_fwd", "unigist_attn_bwd", "unigist_attn_bwd_workspace",
+    "unigist_status_str", "unigist_attn_fwd", "unigist_attn_bwd", "unigist_attn_bwd_stages",
+    "unigist_attn_bwd_workspace",
     "unigist_decode", "unigist_decode_workspace", "unigist_blockmap_build", "unigist_blockmap_free",
     "unigist_tile_sizes",
 ]
@@ -53,6 +56,8 @@ def load():
     lib.unigist_attn_fwd.argtypes = [vp, vp, vp, vp, fp] + [ip] * 7 + [ip, vp]
     lib.unigist_attn_bwd.restype = ip
     lib.unigist_attn_bwd.argtypes = [vp] * 9 + [ip] * 7 + [ip, vp, sz, vp]
+    lib.unigist_attn_bwd_stages.restype = ip
+    lib.unigist_attn_bwd_stages.argtypes = [vp] * 9 + [ip] * 7 + [ip, vp, sz, C.c_uint, vp]
     lib.unigist_attn_bwd_workspace.restype = sz
     lib.unigist_attn_bwd_workspace.argtypes = [ip] * 7 + [ip]
     lib.unigist_decode.restype = ip
@@ -108,6 +113,12 @@ def unigist_attn_fwd(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, dt, stream=None)
 def unigist_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws, ws_bytes, stream=None) -> int:
     return load().unigist_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws, ws_bytes,
                                    stream)
+
+
+def unigist_attn_bwd_stages(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws, ws_bytes, stages,
+                            stream=None) -> int:
+    return load().unigist_attn_bwd_stages(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, ws,
+                                          ws_bytes, stages, stream)
 
 
 def unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt) -> int:
@@ -166,8 +177,9 @@ def attn_fwd(q, k, v, r, W):
     return out, lse
 
 
-def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None):
-    """-> dq [B,Hq,L,D], dk, dv [B,Hkv,L,D]."""
+def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_ALL, grads=None):
+    """-> dq [B,Hq,L,D], dk, dv [B,Hkv,L,D].  `stages`/`grads` let a caller run the backward one
+    stage at a time into the same output tensors (per-kernel timing)."""
     _dev(q, k, v, out, lse, dout)
     B, Hq, L, D = q.shape
     Hkv = k.shape[1]
@@ -181,10 +193,11 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None):
         raise UnigistError("unigist_attn_bwd_workspace: invalid or unsupported shape")
     if workspace is None:
         workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    _check(unigist_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(),
-                            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D, int(r), int(W), dt,
-                            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
+    dq, dk, dv = grads if grads is not None else (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+    _check(unigist_attn_bwd_stages(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                   dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D,
+                                   int(r), int(W), dt, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), int(stages), _stream()),
            "unigist_attn_bwd")
     return dq, dk, dv
 

@@ -84,23 +84,35 @@ extern "C" size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int 
     return delta > mfma ? delta : mfma;
 }
 
-extern "C" unigist_status unigist_attn_bwd(const void* q, const void* k, const void* v, const void* out,
-                                           const float* lse, const void* dout, void* dq, void* dk, void* dv,
-                                           int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
-                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+extern "C" unigist_status unigist_attn_bwd_stages(const void* q, const void* k, const void* v, const void* out,
+                                                  const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                                  int B, int Hq, int Hkv, int L, int D, int r, int W,
+                                                  unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                                  unsigned stages, void* hip_stream) {
     unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
+    if (stages == 0 || (stages & ~(unsigned)UNIGIST_BWD_ALL)) return UNIGIST_EINVAL;
     if (workspace_bytes < unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt)) return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
     const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e;
-    if (dt == UNIGIST_BF16 && !plain_alu_forced())
-        e = launch_bwd_mfma(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, stream);
-    else
+    if (dt == UNIGIST_BF16 && !plain_alu_forced()) {
+        e = launch_bwd_mfma(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, stages, stream);
+    } else {
+        if (stages != UNIGIST_BWD_ALL) return UNIGIST_EUNSUPPORTED;
         e = launch_bwd_simple(q, k, v, out, lse, dout, dq, dk, dv, (float*)workspace, s, dt, stream);
+    }
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" unigist_status unigist_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                                           const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                           int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return unigist_attn_bwd_stages(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, dt, workspace,
+                                   workspace_bytes, UNIGIST_BWD_ALL, hip_stream);
 }
 
 extern "C" size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt) {

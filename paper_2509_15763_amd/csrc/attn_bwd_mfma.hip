@@ -510,30 +510,35 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
 template <int D>
 hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* out, const float* lse,
                       const bf16_t* dout, bf16_t* dq, bf16_t* dk, bf16_t* dv, char* ws, const AttnShape& s,
-                      hipStream_t st) {
+                      unsigned stages, hipStream_t st) {
     const BwdPlan pl = make_plan(s);
     float* delta = (float*)ws;
     float* part = (float*)(ws + pl.off_part);
     float* comp = (float*)(ws + pl.off_comp);
     hipError_t e;
-    {
+    if (stages & UNIGIST_BWD_DELTA) {
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.B * s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(out, dout, delta, nrows);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    if (pl.n_gt > 0) {
+    if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
         dkdv_kernel<D, true><<<dim3(pl.n_gt * pl.nseg, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv, part,
                                                                                  comp, s, pl);
         if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (pl.n_gt > 0 && (stages & UNIGIST_BWD_GIST_REDUCE)) {
         const int per_tile = 2 * D * BNK;
         gist_reduce_kernel<<<dim3((per_tile + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
             part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s.rp1, s.W, per_tile);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    dkdv_kernel<D, false><<<dim3((s.L + BNK - 1) / BNK, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv, part,
-                                                                                  comp, s, pl);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (stages & UNIGIST_BWD_DKDV_WINDOW) {
+        dkdv_kernel<D, false><<<dim3((s.L + BNK - 1) / BNK, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv,
+                                                                                      part, comp, s, pl);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (!(stages & UNIGIST_BWD_DQ)) return hipSuccess;
     const int nq = (s.L + BMQ - 1) / BMQ;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
@@ -547,12 +552,12 @@ size_t bwd_mfma_workspace(const AttnShape& s) { return make_plan(s).total; }
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
-                           hipStream_t st) {
+                           unsigned stages, hipStream_t st) {
     if (s.D == 64)
         return bwd_launch<64>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
-                              (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, st);
+                              (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, stages, st);
     return bwd_launch<128>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
-                           (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, st);
+                           (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, stages, st);
 }
 
 }  // namespace unigist

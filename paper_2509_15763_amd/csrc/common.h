@@ -64,7 +64,7 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
 size_t bwd_mfma_workspace(const AttnShape& s);
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws,
-                           const AttnShape& s, hipStream_t st);
+                           const AttnShape& s, unsigned stages, hipStream_t st);
 int decode_num_splits(int B, int Hq, int Hkv, int Lk);
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
