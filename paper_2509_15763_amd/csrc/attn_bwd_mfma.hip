@@ -38,7 +38,7 @@ struct BwdPlan {
     int n_gt;    // compact gist tiles (BNK gists each) seen by some chunk
     int segc;    // chunks per segment
     int nseg;    // segments
-    size_t off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
+    size_t off_lse2, off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
 };
 
 __host__ __device__ inline int far_of_chunk(int c, int W) {
@@ -64,6 +64,8 @@ BwdPlan make_plan(const AttnShape& s) {
     p.nseg = (p.NC + p.segc - 1) / p.segc;
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
+    p.off_lse2 = off;  // lse * log2(e), written by the delta pass
+    off += ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_part = off;
     off += (size_t)s.B * s.Hkv * p.n_gt * p.nseg * 2 * s.D * BNK * sizeof(float);
     off = (off + a) & ~a;
@@ -76,7 +78,8 @@ BwdPlan make_plan(const AttnShape& s) {
 // ------------------------------------------------------------------ 1. delta
 template <int D>
 __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
-                                                  float* __restrict__ delta, long nrows) {
+                                                  const float* __restrict__ lse, float* __restrict__ delta,
+                                                  float* __restrict__ lse2, long nrows) {
     constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
     const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;
     const int sub = threadIdx.x % LPR;
@@ -93,50 +96,70 @@ __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ ou
     // reduce over the LPR lanes of a row (LPR is 8 or 16, rows are aligned to LPR lanes)
 #pragma unroll
     for (int off = 1; off < LPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
-    if (row < nrows && sub == 0) delta[row] = acc;
+    if (row < nrows && sub == 0) {
+        delta[row] = acc;
+        lse2[row] = lse[row] * kLog2e;  // the exponent base the dK/dV and dQ kernels subtract
+    }
 }
 
 // ------------------------------------------------------------------ 2./4. dK, dV
 template <int D>
 struct DkdvSmem {
-    static constexpr int STR = D + 8;  // row stride in elements
-    bf16_t q[MQ * STR];
-    bf16_t g[MQ * STR];  // dO
-    float lse[MQ];
-    float delta[MQ];
+    // two stages of a 64-row Q chunk and dO chunk (rows unpadded, 16-byte chunks swizzled), plus the
+    // rows' lse * log2(e) and delta
+    char q[2][MQ * D * 2];
+    char g[2][MQ * D * 2];
+    float lse2[2][MQ];
+    float delta[2][MQ];
 };
 
 template <int D, bool GIST>
-__global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                 const bf16_t* __restrict__ v, const float* __restrict__ lse,
-                                                 const bf16_t* __restrict__ dout, const float* __restrict__ delta,
-                                                 bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
-                                                 float* __restrict__ part, const float* __restrict__ comp,
-                                                 AttnShape s, BwdPlan pl) {
+__global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                    const bf16_t* __restrict__ v, const float* __restrict__ lse2,
+                                                    const bf16_t* __restrict__ dout, const float* __restrict__ delta,
+                                                    bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                                    float* __restrict__ part, const float* __restrict__ comp,
+                                                    AttnShape s, BwdPlan pl) {
     constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
-    constexpr int RPP = NT / CH, PASSES = MQ / RPP;
-    constexpr int STR = DkdvSmem<D>::STR;
-    __shared__ __attribute__((aligned(16))) DkdvSmem<D> sm;
+    constexpr int RPI = 64 / CH;        // chunk rows covered by one direct-load instruction
+    constexpr int IPW = MQ / RPI / 4;   // such instructions per wave, per matrix, per step
+    constexpr int ROWB = CH * 16;       // bytes per row
+    __shared__ __attribute__((aligned(1024))) DkdvSmem<D> sm;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
-    const int hk = blockIdx.y, b = blockIdx.z;
     const int L = s.L, W = s.W, rp1 = s.rp1;
     const int G = s.Hq / s.Hkv;
     const float c = s.scale * kLog2e;
+
+    // ---- which (batch, kv head) and which unit of work.  Workgroup ids go round-robin over the 8
+    // XCDs, so with id % 8 selecting the (batch, kv head) pair every XCD gets the same amount of work
+    // and one head's Q/dO stream stays in one XCD's L2.
+    const int NP = s.B * s.Hkv;
+    int n = blockIdx.x, pr, unit;
+    if ((NP & 7) == 0) {
+        const int mm = n >> 3;
+        pr = (n & 7) + 8 * (mm % (NP >> 3));
+        unit = mm / (NP >> 3);
+    } else {
+        pr = n % NP;
+        unit = n / NP;
+    }
+    const int b = pr / s.Hkv, hk = pr % s.Hkv;
 
     // ---- which keys, which query chunks
     int tile, c_lo, c_hi;  // chunks c_lo .. c_hi inclusive
     int seg = 0;
     if (GIST) {
-        tile = blockIdx.x / pl.nseg;
-        seg = blockIdx.x % pl.nseg;
+        tile = unit / pl.nseg;
+        seg = pl.nseg - 1 - unit % pl.nseg;
         const int cf = first_chunk_of_gtile(tile, rp1, W);
         c_lo = max(cf, seg * pl.segc);
         c_hi = min(pl.NC, (seg + 1) * pl.segc) - 1;
         if (c_lo > c_hi) return;  // this segment lies before the tile becomes visible (uniform exit)
     } else {
-        tile = blockIdx.x;
+        tile = unit;
         const int j0 = tile * BNK;
         c_lo = j0 / MQ;
         c_hi = min((long long)pl.NC - 1, ((long long)j0 + BNK + W - 2) / MQ);
@@ -169,43 +192,42 @@ __global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, 
         avT[db] = zero16();
     }
 
-    // ---- staging of the Q / dO chunk
-    const int srow = tid / CH, scol = (tid % CH) * 8;
-    u32x4 qreg[PASSES], greg[PASSES];
-    float sreg = 0.f;  // threads 0..63: lse of row tid; 64..127: delta of row tid - 64
+    // ---- staging of the Q / dO chunk: direct global->LDS loads
     const int nch = c_hi - c_lo + 1;
     const int nsteps = nch * G;
-    auto fetch = [&](int step) {
+    const int lrow = lane / CH;
+    auto issue = [&](int step, int buf) {
         const int g = step / nch, cc = c_lo + step % nch;
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int row = min(cc * MQ + p * RPP + srow, L - 1);
-            qreg[p] = *(const u32x4*)(q + (hb + row) * D + scol);
-            greg[p] = *(const u32x4*)(dout + (hb + row) * D + scol);
+        for (int i = 0; i < IPW; ++i) {
+            const int rr = (w * IPW + i) * RPI + lrow;
+            const int row = min(cc * MQ + rr, L - 1);
+            const int ch = (lane % CH) ^ swz<CH>(rr);
+            const size_t off = (hb + row) * D + ch * 8;
+            g2l16(q + off, &sm.q[buf][(w * IPW + i) * 1024]);
+            g2l16(dout + off, &sm.g[buf][(w * IPW + i) * 1024]);
         }
-        if (tid < 2 * MQ) {
-            const int row = min(cc * MQ + (tid & (MQ - 1)), L - 1);
-            sreg = tid < MQ ? lse[hb + row] * kLog2e : delta[hb + row];
+        if (w < 2) {  // wave 0: the 64 rows' lse2, wave 1: their delta (one 4-byte direct load per lane)
+            const int row = min(cc * MQ + lane, L - 1);
+            const float* src = (w == 0 ? lse2 : delta) + hb + row;
+            float* dst = w == 0 ? sm.lse2[buf] : sm.delta[buf];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
         }
     };
-    auto stash = [&]() {
+    int roff[KS];  // row-wise read of chunk row c32 (+32 qb), 16-byte chunk 2 ks + h
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int rr = p * RPP + srow;
-            *(u32x4*)(&sm.q[rr * STR + scol]) = qreg[p];
-            *(u32x4*)(&sm.g[rr * STR + scol]) = greg[p];
-        }
-        if (tid < MQ) sm.lse[tid] = sreg;
-        else if (tid < 2 * MQ) sm.delta[tid - MQ] = sreg;
-    };
+    for (int ks = 0; ks < KS; ++ks) roff[ks] = swz_off<CH>(c32, 2 * ks + h);
 
-    fetch(0);
+    issue(0, 0);
     for (int step = 0; step < nsteps; ++step) {
+        wait_vmem();
         __syncthreads();
-        stash();
-        __syncthreads();
-        if (step + 1 < nsteps) fetch(step + 1);
+        if (step + 1 < nsteps) issue(step + 1, (step + 1) & 1);
+        const int bi = step & 1;
+        const char* qt = sm.q[bi];
+        const char* gt = sm.g[bi];
         const int cc = c_lo + step % nch;
         const int q0 = cc * MQ;
 
@@ -219,14 +241,10 @@ __global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, 
 
             // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
             f32x16 sa = zero16(), dp = zero16();
-            {
-                const bf16_t* qp = &sm.q[(32 * qb + c32) * STR + 8 * h];
-                const bf16_t* gp = &sm.g[(32 * qb + c32) * STR + 8 * h];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    sa = mfma32(*(const bf16x8*)(qp + 16 * ks), kf[ks], sa);
-                    dp = mfma32(*(const bf16x8*)(gp + 16 * ks), vf[ks], dp);
-                }
+            for (int ks = 0; ks < KS; ++ks) {
+                sa = mfma32(*(const bf16x8*)(qt + 32 * qb * ROWB + roff[ks]), kf[ks], sa);
+                dp = mfma32(*(const bf16x8*)(gt + 32 * qb * ROWB + roff[ks]), vf[ks], dp);
             }
             // ---- P and dS
             bool masked;
@@ -235,8 +253,8 @@ __global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, 
             const int d0 = qb0 + 4 * h - key;  // distance of the lane's first query to its key
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 l4 = *(const f32x4*)(&sm.lse[32 * qb + 8 * i4 + 4 * h]);
-                const f32x4 d4 = *(const f32x4*)(&sm.delta[32 * qb + 8 * i4 + 4 * h]);
+                const f32x4 l4 = *(const f32x4*)(&sm.lse2[bi][32 * qb + 8 * i4 + 4 * h]);
+                const f32x4 d4 = *(const f32x4*)(&sm.delta[bi][32 * qb + 8 * i4 + 4 * h]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i = 4 * i4 + t;
@@ -263,8 +281,8 @@ __global__ __launch_bounds__(NT) void dkdv_kernel(const bf16_t* __restrict__ q, 
                 const bf16x8 sb = pack8(dp, 8 * kk);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    avT[db] = mfma32(tr16_frag(sm.g, STR, 32 * qb + 16 * kk, 32 * db), pb, avT[db]);
-                    akT[db] = mfma32(tr16_frag(sm.q, STR, 32 * qb + 16 * kk, 32 * db), sb, akT[db]);
+                    avT[db] = mfma32(tr16_frag_swz<CH>(gt, 32 * qb + 16 * kk, db), pb, avT[db]);
+                    akT[db] = mfma32(tr16_frag_swz<CH>(qt, 32 * qb + 16 * kk, db), sb, akT[db]);
                 }
             }
         }
@@ -346,8 +364,8 @@ __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict
 // ------------------------------------------------------------------ 5. dQ
 template <int D>
 struct DqSmem {
-    static constexpr int KSTR = D + 8;
-    static constexpr int VSTR = D + 8;
+    static constexpr int KSTR = D + 16;  // read row-wise and through transposing reads
+    static constexpr int VSTR = D + 8;   // read row-wise only
     bf16_t k[BNQ * KSTR];
     bf16_t v[BNQ * VSTR];
 };
@@ -513,17 +531,19 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
                       unsigned stages, hipStream_t st) {
     const BwdPlan pl = make_plan(s);
     float* delta = (float*)ws;
+    float* lse2 = (float*)(ws + pl.off_lse2);
     float* part = (float*)(ws + pl.off_part);
     float* comp = (float*)(ws + pl.off_comp);
     hipError_t e;
     if (stages & UNIGIST_BWD_DELTA) {
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.B * s.Hq * s.L;
-        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(out, dout, delta, nrows);
+        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(out, dout, lse, delta,
+                                                                                                    lse2, nrows);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
-        dkdv_kernel<D, true><<<dim3(pl.n_gt * pl.nseg, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv, part,
+        dkdv_kernel<D, true><<<dim3((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B)), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part,
                                                                                  comp, s, pl);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -534,7 +554,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & UNIGIST_BWD_DKDV_WINDOW) {
-        dkdv_kernel<D, false><<<dim3((s.L + BNK - 1) / BNK, s.Hkv, s.B), NT, 0, st>>>(q, k, v, lse, dout, delta, dk, dv,
+        dkdv_kernel<D, false><<<dim3((unsigned)((long)((s.L + BNK - 1) / BNK) * s.Hkv * s.B)), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
                                                                                       part, comp, s, pl);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }

@@ -13,8 +13,9 @@
 // so that one lane owns one query column: row max and row sum are in-lane reductions
 // plus one exchange between the wave's halves, and the accumulator registers of S^T are
 // already the B operand of O^T += V^T P^T.  V^T fragments come straight out of the
-// row-major V tile in LDS through ds_read_b64_tr_b16.
-#include "common.h"
+// row-major V tile in LDS through ds_read_b64_tr_b16.  K/V tiles are staged with direct
+// global->LDS loads into two LDS stages (one barrier per step), 16-byte chunks swizzled.
+#include "mfma_common.h"
 
 namespace unigist {
 namespace {
@@ -23,35 +24,23 @@ constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 64;   // keys per step
 constexpr int NT = 256;  // threads
 
-__device__ __forceinline__ float other_half(float x) {
-    // value held by lane ^ 32
-    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false,
-                                              false);
-    // lanes < 32 find the partner's value in r[1], lanes >= 32 in r[0]; the other slot is their own
-    float a = __builtin_bit_cast(float, (unsigned)r[0]);
-    float b = __builtin_bit_cast(float, (unsigned)r[1]);
-    return (threadIdx.x & 32) ? a : b;
-}
-
 template <int D>
 struct FwdSmem {
-    static constexpr int KSTR = D + 8;   // row strides in elements: skew rows over the LDS banks
-    static constexpr int VSTR = D + 16;
-    bf16_t k[BN * KSTR];
-    bf16_t v[BN * VSTR];
+    // two stages of a K tile and a V tile, rows unpadded, 16-byte chunks swizzled (see swz())
+    char k[2][BN * D * 2];
+    char v[2][BN * D * 2];
 };
 
 template <int D>
-__global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                     const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
-                                                     float* __restrict__ lse, AttnShape s, int nq) {
-    constexpr int KS = D / 16;        // k-steps of the score MFMA
-    constexpr int DB = D / 32;        // 32-row blocks of O^T
-    constexpr int CH = D / 8;         // 16-byte chunks per row
-    constexpr int RPP = NT / CH;      // rows staged per pass
-    constexpr int PASSES = BN / RPP;  // passes per tile
-    constexpr int KSTR = FwdSmem<D>::KSTR, VSTR = FwdSmem<D>::VSTR;
-    __shared__ __attribute__((aligned(16))) FwdSmem<D> sm;
+__global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                        const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
+                                                        float* __restrict__ lse, AttnShape s, int nq) {
+    constexpr int KS = D / 16;            // k-steps of the score MFMA
+    constexpr int DB = D / 32;            // 32-row blocks of O^T
+    constexpr int CH = D / 8;             // 16-byte chunks per row
+    constexpr int RPI = 64 / CH;          // tile rows covered by one direct-load instruction
+    constexpr int IPW = BN / RPI / 4;     // such instructions per wave, per matrix, per tile
+    __shared__ __attribute__((aligned(1024))) FwdSmem<D> sm;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
@@ -97,9 +86,7 @@ __global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__
 
     f32x16 o[DB];
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    for (int db = 0; db < DB; ++db) o[db] = zero16();
     float m = -INFINITY, l = 0.f;
     const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
 
@@ -111,39 +98,34 @@ __global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__
     const int nwin = i1 / BN - wfirst + 1;
     const int ntiles = ngt + nwin;
 
-    // staging: thread copies PASSES 16-byte chunks of K and of V per tile
-    const int srow = tid / CH, scol = (tid % CH) * 8;
-    u32x4 kreg[PASSES], vreg[PASSES];
-    auto fetch = [&](int it) {
+    // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row
+    const int lrow = lane / CH;                       // row within the instruction's group of RPI rows
+    auto issue = [&](int it, int buf) {
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int rr = p * RPP + srow;
+        for (int i = 0; i < IPW; ++i) {
+            const int rr = (w * IPW + i) * RPI + lrow;  // tile row
             int row;
-            if (it < ngt) {
-                const int gi = min(it * BN + rr, nfar - 1);
-                row = gi * rp1 + rp1 - 1;
-            } else {
-                row = min((wfirst + it - ngt) * BN + rr, L - 1);
-            }
-            kreg[p] = *(const u32x4*)(kb + (size_t)row * D + scol);
-            vreg[p] = *(const u32x4*)(vb + (size_t)row * D + scol);
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int rr = p * RPP + srow;
-            *(u32x4*)(&sm.k[rr * KSTR + scol]) = kreg[p];
-            *(u32x4*)(&sm.v[rr * VSTR + scol]) = vreg[p];
+            if (it < ngt) row = min(it * BN + rr, nfar - 1) * rp1 + rp1 - 1;
+            else row = min((wfirst + it - ngt) * BN + rr, L - 1);
+            const int ch = (lane % CH) ^ swz<CH>(rr);
+            const size_t off = (size_t)row * D + ch * 8;
+            g2l16(kb + off, &sm.k[buf][(w * IPW + i) * 1024]);
+            g2l16(vb + off, &sm.v[buf][(w * IPW + i) * 1024]);
         }
     };
 
-    fetch(0);
+    // per-lane LDS offsets that do not depend on the tile
+    int koff[KS];  // row-wise read of K row c32 (+32), chunk 2 ks + h
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = swz_off<CH>(c32, 2 * ks + h);
+
+    issue(0, 0);
     for (int it = 0; it < ntiles; ++it) {
-        __syncthreads();  // everyone is done reading the previous tile
-        stash();
-        __syncthreads();
-        if (it + 1 < ntiles) fetch(it + 1);
+        wait_vmem();      // this wave's part of tile `it` has landed
+        __syncthreads();  // ... and everyone's; everyone is also done reading the other stage
+        if (it + 1 < ntiles) issue(it + 1, (it + 1) & 1);
+        const char* kt = sm.k[it & 1];
+        const char* vt = sm.v[it & 1];
 
         const bool gist_tile = it < ngt;
         const int j0 = gist_tile ? it * BN : (wfirst + it - ngt) * BN;  // compact index or position
@@ -154,13 +136,11 @@ __global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__
         f32x16 sa[2];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sa[kb2][i] = 0.f;
-            const bf16_t* kp = &sm.k[(32 * kb2 + c32) * KSTR + 8 * h];
+            sa[kb2] = zero16();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 a = *(const bf16x8*)(kp + 16 * ks);
-                sa[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sa[kb2], 0, 0, 0);
+                bf16x8 a = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + koff[ks]);
+                sa[kb2] = mfma32(a, qf[ks], sa[kb2]);
             }
         }
 
@@ -219,40 +199,24 @@ __global__ __launch_bounds__(NT) void fwd_mfma_kernel(const bf16_t* __restrict__
         }
         m = m_new;
 
-        uint32_t pk[2][8];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
-                l += p0 + p1;
-                pk[kb2][i / 2] = pack_bf16x2(p0, p1);
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
+                l += p;
+                sa[kb2][i] = p;
             }
 
         // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
-        const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int g0 = 0; g0 < 4; g0 += 2) {
-                u32x4 pb4;
-                pb4[0] = pk[kb2][2 * g0];
-                pb4[1] = pk[kb2][2 * g0 + 1];
-                pb4[2] = pk[kb2][2 * g0 + 2];
-                pb4[3] = pk[kb2][2 * g0 + 3];
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pb4);
-                const int krow = 32 * kb2 + 8 * g0 + 4 * h + (p16 >> 2);
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 pb = pack8(sa[kb2], 8 * kk);
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16_t* vp = &sm.v[krow * VSTR + 32 * db + 16 * gi2 + 4 * (p16 & 3)];
-                    s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)vp);
-                    s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (s16x4 __attribute__((address_space(3)))*)(vp + 8 * VSTR));
-                    typedef __attribute__((ext_vector_type(8))) short s16x8;
-                    s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
-                }
+                for (int db = 0; db < DB; ++db)
+                    o[db] = mfma32(tr16_frag_swz<CH>(vt, 32 * kb2 + 16 * kk, db), pb, o[db]);
             }
     }
 

@@ -50,6 +50,50 @@ __device__ __forceinline__ bf16x8 tr16_frag(const bf16_t* tile, int stride, int 
     return __builtin_bit_cast(bf16x8, a);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Tiles staged with direct global->LDS loads (global_load_lds_dwordx4).
+// One such instruction makes a wave write 64 x 16 B = 1 KB of consecutive LDS, so rows cannot be
+// padded; bank conflicts are avoided by permuting the 16-byte chunks of each row instead: chunk
+// ch of tile row r is stored at chunk position ch ^ swz(r).  With swz even and periodic in 8 rows
+// (of 256 B) the 8 lanes of a row-wise 16-byte read and the 4 rows of a transposing read each fall
+// on distinct banks.  CH = chunks per row (D / 8).
+template <int CH>
+__device__ __forceinline__ int swz(int r) { return 2 * ((r * CH / 16) % (CH / 2)); }
+
+// byte offset of (row r, chunk ch) inside a swizzled tile
+template <int CH>
+__device__ __forceinline__ int swz_off(int r, int ch) { return r * (CH * 16) + ((ch ^ swz<CH>(r)) << 4); }
+
+// issue one 1 KB direct load: lane `lane` fetches 16 bytes from `src` into lds_base + 16 * lane
+__device__ __forceinline__ void g2l16(const void* src, void* lds_base_uniform) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)lds_base_uniform, 16, 0, 0);
+}
+
+// wait until this wave's outstanding vector-memory operations (direct loads included) are done
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// A operand X^T from a swizzled tile: same contract as tr16_frag (rows row0 + 4h + {0..3} and + 8,
+// column col0 + lane % 32), row0 a multiple of 8 and col0 a multiple of 32.  `lane_off` is
+// tr_lane_off<CH>() of the calling lane, `db` = col0 / 32.
+template <int CH>
+__device__ __forceinline__ int tr_lane_row() {
+    const int lane = threadIdx.x & 63;
+    return 4 * (lane >> 5) + ((lane & 15) >> 2);
+}
+template <int CH>
+__device__ __forceinline__ bf16x8 tr16_frag_swz(const char* tile, int row0, int db) {
+    const int lane = threadIdx.x & 63;
+    const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
+    const int rl = tr_lane_row<CH>();                       // row within the aligned group of 8
+    const int ch = 4 * db + 2 * gi2 + ((p16 & 3) >> 1);       // 16-byte chunk holding the 4 elements
+    const char* p = tile + (row0 + rl) * (CH * 16) + ((ch ^ swz<CH>(rl)) << 4) + (p16 & 1) * 8;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * CH * 16));
+    s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, a);
+}
+
 // 8 consecutive C registers (starting at i0) -> bf16 B operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int i0) {
     u32x4 r;
