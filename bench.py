@@ -36,7 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": None, "dkdv_gist": None, "dkdv_window": None, "dq": None, "decode": None}
+TRAFFIC_BYTES = {"fwd": 1065364825, "dkdv_gist": 4816499917, "dkdv_window": 3153686867, "dq": 1344108365,
+                 "decode": 4567950612}
 
 
 def pair_counts(L, r, W):
@@ -96,6 +97,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                         "can be scaled by what they read for a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1")
@@ -124,6 +128,13 @@ def main():
             if events is not None:
                 events[2 + n].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, device=dev, dtype=torch.uint8).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
