@@ -152,8 +152,10 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     int tile, c_lo, c_hi;  // chunks c_lo .. c_hi inclusive
     int seg = 0;
     if (GIST) {
-        tile = unit / pl.nseg;
-        seg = pl.nseg - 1 - unit % pl.nseg;
+        // segment-major, late (fully populated) segments first: the workgroups running together on an
+        // XCD then stream the same Q/dO chunks of the same head through its L2
+        seg = pl.nseg - 1 - unit / pl.n_gt;
+        tile = unit % pl.n_gt;
         const int cf = first_chunk_of_gtile(tile, rp1, W);
         c_lo = max(cf, seg * pl.segc);
         c_hi = min(pl.NC, (seg + 1) * pl.segc) - 1;
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         int nfar = 0;
         if (GIST) nfar = far_of_chunk(cc, W) / rp1;  // compact gists visible to this chunk: index < nfar
 
-#pragma unroll
+#pragma unroll 1
         for (int qb = 0; qb < MQ / 32; ++qb) {
             const int qb0 = q0 + 32 * qb;  // first query row of the block
             if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
