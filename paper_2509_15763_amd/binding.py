@@ -36,7 +36,8 @@ class _BlockMap(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libunigist.so")
+    """The in-tree library, or the one UNIGIST_LIB points at (for comparing builds)."""
+    return os.environ.get("UNIGIST_LIB") or os.path.join(_HERE, "libunigist.so")
 
 
 def load():

@@ -10,7 +10,7 @@ using namespace unigist;
 
 namespace {
 
-constexpr int kMaxL = 1 << 24;  // index arithmetic in the kernels is 32-bit per head
+constexpr int kMaxL = 1 << 23;  // per-head byte offsets (L * D * 2) are kept in 32 bits inside the kernels
 
 bool plain_alu_forced() {
     const char* e = getenv("UNIGIST_DEBUG_PLAIN_ALU");

@@ -15,6 +15,8 @@
 // already the B operand of O^T += V^T P^T.  V^T fragments come straight out of the
 // row-major V tile in LDS through ds_read_b64_tr_b16.  K/V tiles are staged with direct
 // global->LDS loads into two LDS stages (one barrier per step), 16-byte chunks swizzled.
+#include <type_traits>
+
 #include "mfma_common.h"
 
 namespace unigist {
@@ -98,19 +100,31 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
     const int nwin = i1 / BN - wfirst + 1;
     const int ntiles = ngt + nwin;
 
-    // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row
-    const int lrow = lane / CH;                       // row within the instruction's group of RPI rows
+    // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row.
+    // Per load slot the lane keeps the row it fetches in the first gist tile and in the first window
+    // tile; tile `it` is a fixed stride further, clamped to the last valid row of its phase.
+    const int lrow = lane / CH;
+    const int wv = __builtin_amdgcn_readfirstlane(w);
+    int choff[IPW];  // byte offset of the lane's (swizzled) chunk inside its row, per load slot
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    const int grow_max = (nfar - 1) * rp1 + rp1 - 1;  // last far gist (unused when nfar == 0)
+    const char* kbytes = (const char*)kb;
+    const char* vbytes = (const char*)vb;
     auto issue = [&](int it, int buf) {
+        // row of tile row rr: gist phase (it * BN + rr) * rp1 + rp1 - 1, window phase (wfirst + it - ngt) * BN + rr,
+        // i.e. rr * mul + add with wave-uniform mul and add; clamped to the last valid row of the phase
+        const bool gphase = it < ngt;
+        const int mul = gphase ? rp1 : 1;
+        const int add = gphase ? it * BN * rp1 + rp1 - 1 : (wfirst + it - ngt) * BN;
+        const int lim = gphase ? grow_max : L - 1;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
-            const int rr = (w * IPW + i) * RPI + lrow;  // tile row
-            int row;
-            if (it < ngt) row = min(it * BN + rr, nfar - 1) * rp1 + rp1 - 1;
-            else row = min((wfirst + it - ngt) * BN + rr, L - 1);
-            const int ch = (lane % CH) ^ swz<CH>(rr);
-            const size_t off = (size_t)row * D + ch * 8;
-            g2l16(kb + off, &sm.k[buf][(w * IPW + i) * 1024]);
-            g2l16(vb + off, &sm.v[buf][(w * IPW + i) * 1024]);
+            const int rr = (wv * IPW + i) * RPI + lrow;
+            const int row = min(rr * mul + add, lim);
+            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
+            g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
+            g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
         }
     };
 
@@ -118,19 +132,20 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
     int koff[KS];  // row-wise read of K row c32 (+32), chunk 2 ks + h
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) koff[ks] = swz_off<CH>(c32, 2 * ks + h);
+    int voff[DB];  // transposing read of V, 32-column block db
+#pragma unroll
+    for (int db = 0; db < DB; ++db) voff[db] = tr_lane_off<CH>(db);
 
-    issue(0, 0);
-    for (int it = 0; it < ntiles; ++it) {
-        wait_vmem();      // this wave's part of tile `it` has landed
-        __syncthreads();  // ... and everyone's; everyone is also done reading the other stage
-        if (it + 1 < ntiles) issue(it + 1, (it + 1) & 1);
-        const char* kt = sm.k[it & 1];
-        const char* vt = sm.v[it & 1];
-
+    // one step of the walk on LDS stage BUF (a compile-time constant, so that every LDS address is a
+    // per-lane register plus an immediate)
+    auto tile_step = [&](auto bufc, int it) {
+        constexpr int BUF = decltype(bufc)::value;
+        const char* kt = sm.k[BUF];
+        const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
         const int j0 = gist_tile ? it * BN : (wfirst + it - ngt) * BN;  // compact index or position
         // a window tile entirely right of this wave's rows contributes nothing
-        if (!gist_tile && j0 > wrow0 + 31) continue;
+        if (!gist_tile && j0 > wrow0 + 31) return;
 
         // ---- S^T = K Q^T : two 32-key blocks
         f32x16 sa[2];
@@ -199,13 +214,17 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
         }
         m = m_new;
 
+        // P = exp2(c S - c m): summed in fp32 for the row sum (lse stays fp32-accurate), rounded to bf16
+        // for the second MFMA
+        u32x4 pk[2][2];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
-                l += p;
-                sa[kb2][i] = p;
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
+                l += p0 + p1;
+                pk[kb2][i / 8][(i / 2) % 4] = pack_bf16x2(p0, p1);
             }
 
         // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
@@ -213,11 +232,25 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
         for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 pb = pack8(sa[kb2], 8 * kk);
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[kb2][kk]);
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
-                    o[db] = mfma32(tr16_frag_swz<CH>(vt, 32 * kb2 + 16 * kk, db), pb, o[db]);
+                    o[db] = mfma32(tr16_frag_at<CH>(vt + voff[db], 32 * kb2 + 16 * kk), pb, o[db]);
             }
+    };
+
+    issue(0, 0);
+    for (int it = 0; it < ntiles; it += 2) {
+        wait_vmem();      // this wave's part of tile `it` has landed
+        __syncthreads();  // ... and everyone's; everyone is also done reading the other stage
+        if (it + 1 < ntiles) issue(it + 1, 1);
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < ntiles) {
+            wait_vmem();
+            __syncthreads();
+            if (it + 2 < ntiles) issue(it + 2, 0);
+            tile_step(std::integral_constant<int, 1>{}, it + 1);
+        }
     }
 
     // ---- epilogue: normalise, store O (row qrow, d = 32 db + 8 (i/4) + 4 h + i%4) and LSE

@@ -94,6 +94,26 @@ __device__ __forceinline__ bf16x8 tr16_frag_swz(const char* tile, int row0, int 
     return __builtin_bit_cast(bf16x8, a);
 }
 
+// The same with the address split into a per-lane register and compile-time parts: the lane part
+// tr_lane_off<CH>(db) is computed once per kernel, the rows (a multiple of 8) and the LDS stage become
+// immediates of the two ds_read_b64_tr_b16.
+template <int CH>
+__device__ __forceinline__ int tr_lane_off(int db) {
+    const int lane = threadIdx.x & 63;
+    const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
+    const int rl = tr_lane_row<CH>();
+    const int ch = 4 * db + 2 * gi2 + ((p16 & 3) >> 1);
+    return rl * (CH * 16) + ((ch ^ swz<CH>(rl)) << 4) + (p16 & 1) * 8;
+}
+template <int CH>
+__device__ __forceinline__ bf16x8 tr16_frag_at(const char* tile_plus_lane_off, int row0) {
+    const char* a = tile_plus_lane_off + row0 * (CH * 16);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)a);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 8 * CH * 16));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // 8 consecutive C registers (starting at i0) -> bf16 B operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int i0) {
     u32x4 r;

@@ -47,7 +47,7 @@ FAKE = 0x1000  # non-null pointer that is never dereferenced: every call below f
 @pytest.mark.parametrize("kw,want", [
     (dict(), None),
     (dict(B=0), 1), (dict(L=0), 1), (dict(W=0), 1), (dict(r=0), 1), (dict(Hq=6, Hkv=4), 1),
-    (dict(D=96), 2), (dict(dt=7), 2), (dict(L=(1 << 24) + 1), 2),
+    (dict(D=96), 2), (dict(dt=7), 2), (dict(L=(1 << 23) + 1), 2),
 ])
 def test_attn_argument_validation(kw, want):
     a = dict(B=1, Hq=4, Hkv=2, L=64, D=64, r=4, W=8, dt=0)
