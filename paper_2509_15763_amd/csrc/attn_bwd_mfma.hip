@@ -21,6 +21,8 @@
 // staged in LDS and read both row-wise (S = Q K^T, dP = dO V^T) and through transposing LDS reads
 // (dV^T += dO^T P, dK^T += Q^T dS); the S/dP accumulators are already the B operands of the last two.
 // dq: forward-shaped; S^T = K Q^T and dP^T = V dO^T per lane-owned query, dQ^T += K^T dS^T.
+#include <type_traits>
+
 #include "mfma_common.h"
 
 namespace unigist {
@@ -366,21 +368,20 @@ __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict
 // ------------------------------------------------------------------ 5. dQ
 template <int D>
 struct DqSmem {
-    static constexpr int KSTR = D + 16;  // read row-wise and through transposing reads
-    static constexpr int VSTR = D + 8;   // read row-wise only
-    bf16_t k[BNQ * KSTR];
-    bf16_t v[BNQ * VSTR];
+    // two stages of a K tile and a V tile, rows unpadded, 16-byte chunks swizzled
+    char k[2][BNQ * D * 2];
+    char v[2][BNQ * D * 2];
 };
 
 template <int D>
-__global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                               const bf16_t* __restrict__ v, const float* __restrict__ lse,
-                                               const bf16_t* __restrict__ dout, const float* __restrict__ delta,
-                                               bf16_t* __restrict__ dq, AttnShape s, int nq) {
+__global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                  const bf16_t* __restrict__ v, const float* __restrict__ lse2,
+                                                  const bf16_t* __restrict__ dout, const float* __restrict__ delta,
+                                                  bf16_t* __restrict__ dq, AttnShape s, int nq) {
     constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
-    constexpr int RPP = NT / CH, PASSES = BNQ / RPP;
-    constexpr int KSTR = DqSmem<D>::KSTR, VSTR = DqSmem<D>::VSTR;
-    __shared__ __attribute__((aligned(16))) DqSmem<D> sm;
+    constexpr int RPI = 64 / CH;
+    constexpr int IPW = BNQ / RPI / 4;
+    __shared__ __attribute__((aligned(1024))) DqSmem<D> sm;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int c32 = lane & 31, h = lane >> 5;
@@ -403,8 +404,8 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
     const int L = s.L, W = s.W, rp1 = s.rp1;
     const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
     const int qrow = i0 + 32 * w + c32, qrow_ld = min(qrow, L - 1), wrow0 = i0 + 32 * w;
-    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * L * D;
-    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * L * D;
+    const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * L * D);
+    const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * L * D);
     const float c = s.scale * kLog2e;
 
     bf16x8 qf[KS], gf[KS];
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
             gf[ks] = *(const bf16x8*)(gp + 16 * ks);
         }
     }
-    const float ls = lse[rowoff] * kLog2e;
+    const float ls = lse2[rowoff];
     const float dl = delta[rowoff];
 
     f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
@@ -432,37 +433,41 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
     const int nwin = i1 / BNQ - wfirst + 1;
     const int ntiles = ngt + nwin;
 
-    const int srow = tid / CH, scol = (tid % CH) * 8;
-    u32x4 kreg[PASSES], vreg[PASSES];
-    auto fetch = [&](int it) {
+    // ---- staging (same scheme as the forward kernel)
+    const int lrow = lane / CH;
+    const int wv = __builtin_amdgcn_readfirstlane(w);
+    int choff[IPW];
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int rr = p * RPP + srow;
-            int row;
-            if (it < ngt) row = min(it * BNQ + rr, nfar - 1) * rp1 + rp1 - 1;
-            else row = min((wfirst + it - ngt) * BNQ + rr, L - 1);
-            kreg[p] = *(const u32x4*)(kb + (size_t)row * D + scol);
-            vreg[p] = *(const u32x4*)(vb + (size_t)row * D + scol);
+    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    const int grow_max = (nfar - 1) * rp1 + rp1 - 1;
+    auto issue = [&](int it, int buf) {
+        const bool gphase = it < ngt;
+        const int mul = gphase ? rp1 : 1;
+        const int add = gphase ? it * BNQ * rp1 + rp1 - 1 : (wfirst + it - ngt) * BNQ;
+        const int lim = gphase ? grow_max : L - 1;
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+            const int rr = (wv * IPW + i) * RPI + lrow;
+            const int row = min(rr * mul + add, lim);
+            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];
+            g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
+            g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
         }
     };
-    auto stash = [&]() {
+    int roff[KS];  // row-wise read of tile row c32 (+32), chunk 2 ks + h
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int rr = p * RPP + srow;
-            *(u32x4*)(&sm.k[rr * KSTR + scol]) = kreg[p];
-            *(u32x4*)(&sm.v[rr * VSTR + scol]) = vreg[p];
-        }
-    };
+    for (int ks = 0; ks < KS; ++ks) roff[ks] = swz_off<CH>(c32, 2 * ks + h);
+    int toff[DB];  // transposing read of K, 32-column block db
+#pragma unroll
+    for (int db = 0; db < DB; ++db) toff[db] = tr_lane_off<CH>(db);
 
-    fetch(0);
-    for (int it = 0; it < ntiles; ++it) {
-        __syncthreads();
-        stash();
-        __syncthreads();
-        if (it + 1 < ntiles) fetch(it + 1);
+    auto tile_step = [&](auto bufc, int it) {
+        constexpr int BUF = decltype(bufc)::value;
+        const char* kt = sm.k[BUF];
+        const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
         const int j0 = gist_tile ? it * BNQ : (wfirst + it - ngt) * BNQ;
-        if (!gist_tile && j0 > wrow0 + 31) continue;
+        if (!gist_tile && j0 > wrow0 + 31) return;
 
         bool masked;
         unsigned long long gm = 0ull;
@@ -479,12 +484,10 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             // S^T, dP^T for 32 keys: register i is key j0 + 32 kb2 + 8 (i/4) + 4h + i%4, lane = query
             f32x16 sa = zero16(), dp = zero16();
-            const bf16_t* kp = &sm.k[(32 * kb2 + c32) * KSTR + 8 * h];
-            const bf16_t* vp = &sm.v[(32 * kb2 + c32) * VSTR + 8 * h];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                sa = mfma32(*(const bf16x8*)(kp + 16 * ks), qf[ks], sa);
-                dp = mfma32(*(const bf16x8*)(vp + 16 * ks), gf[ks], dp);
+                sa = mfma32(*(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks]), qf[ks], sa);
+                dp = mfma32(*(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks]), gf[ks], dp);
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -508,8 +511,22 @@ __global__ __launch_bounds__(NT) void dq_kernel(const bf16_t* __restrict__ q, co
                 const bf16x8 sb = pack8(dp, 8 * kk);
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
-                    acc[db] = mfma32(tr16_frag(sm.k, KSTR, 32 * kb2 + 16 * kk, 32 * db), sb, acc[db]);
+                    acc[db] = mfma32(tr16_frag_at<CH>(kt + toff[db], 32 * kb2 + 16 * kk), sb, acc[db]);
             }
+        }
+    };
+
+    issue(0, 0);
+    for (int it = 0; it < ntiles; it += 2) {
+        wait_vmem();
+        __syncthreads();
+        if (it + 1 < ntiles) issue(it + 1, 1);
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < ntiles) {
+            wait_vmem();
+            __syncthreads();
+            if (it + 2 < ntiles) issue(it + 2, 0);
+            tile_step(std::integral_constant<int, 1>{}, it + 1);
         }
     }
 
@@ -564,7 +581,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     const int nq = (s.L + BMQ - 1) / BMQ;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
-    dq_kernel<D><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse, dout, delta, dq, s, nq);
+    dq_kernel<D><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
     return hipGetLastError();
 }
 
