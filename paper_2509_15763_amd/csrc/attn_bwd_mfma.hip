@@ -200,17 +200,23 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     const int nch = c_hi - c_lo + 1;
     const int nsteps = nch * G;
     const int lrow = lane / CH;
-    auto issue = [&](int step, int buf) {
+    int rrow[IPW], choff[IPW];  // chunk row and byte offset of the lane's (swizzled) 16-byte chunk, per load slot
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+        rrow[i] = (w * IPW + i) * RPI + lrow;
+        choff[i] = ((lane % CH) ^ swz<CH>(rrow[i])) * 16;
+    }
+    auto issue = [&](int step, int buf) __attribute__((always_inline)) {
         const int g = step / nch, cc = c_lo + step % nch;
-        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;
+        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform
+        const char* qh = (const char*)(q + hb * D);
+        const char* gh = (const char*)(dout + hb * D);
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
-            const int rr = (w * IPW + i) * RPI + lrow;
-            const int row = min(cc * MQ + rr, L - 1);
-            const int ch = (lane % CH) ^ swz<CH>(rr);
-            const size_t off = (hb + row) * D + ch * 8;
-            g2l16(q + off, &sm.q[buf][(w * IPW + i) * 1024]);
-            g2l16(dout + off, &sm.g[buf][(w * IPW + i) * 1024]);
+            const int row = min(cc * MQ + rrow[i], L - 1);
+            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
+            g2l16(qh + off, &sm.q[buf][(w * IPW + i) * 1024]);
+            g2l16(gh + off, &sm.g[buf][(w * IPW + i) * 1024]);
         }
         if (w < 2) {  // wave 0: the 64 rows' lse2, wave 1: their delta (one 4-byte direct load per lane)
             const int row = min(cc * MQ + lane, L - 1);
@@ -223,15 +229,15 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     int roff[KS];  // row-wise read of chunk row c32 (+32 qb), 16-byte chunk 2 ks + h
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) roff[ks] = swz_off<CH>(c32, 2 * ks + h);
+    int toff[DB];  // transposing reads, 32-column block db
+#pragma unroll
+    for (int db = 0; db < DB; ++db) toff[db] = tr_lane_off<CH>(db);
 
-    issue(0, 0);
-    for (int step = 0; step < nsteps; ++step) {
-        wait_vmem();
-        __syncthreads();
-        if (step + 1 < nsteps) issue(step + 1, (step + 1) & 1);
-        const int bi = step & 1;
-        const char* qt = sm.q[bi];
-        const char* gt = sm.g[bi];
+    // one step on LDS stage BUF (a compile-time constant: LDS addresses = lane register + immediate)
+    auto do_step = [&](auto bufc, int step) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(bufc)::value;
+        const char* qt = sm.q[BUF];
+        const char* gt = sm.g[BUF];
         const int cc = c_lo + step % nch;
         const int q0 = cc * MQ;
 
@@ -257,8 +263,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             const int d0 = qb0 + 4 * h - key;  // distance of the lane's first query to its key
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 l4 = *(const f32x4*)(&sm.lse2[bi][32 * qb + 8 * i4 + 4 * h]);
-                const f32x4 d4 = *(const f32x4*)(&sm.delta[bi][32 * qb + 8 * i4 + 4 * h]);
+                const f32x4 l4 = *(const f32x4*)(&sm.lse2[BUF][32 * qb + 8 * i4 + 4 * h]);
+                const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 8 * i4 + 4 * h]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int i = 4 * i4 + t;
@@ -285,10 +291,24 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 const bf16x8 sb = pack8(dp, 8 * kk);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    avT[db] = mfma32(tr16_frag_swz<CH>(gt, 32 * qb + 16 * kk, db), pb, avT[db]);
-                    akT[db] = mfma32(tr16_frag_swz<CH>(qt, 32 * qb + 16 * kk, db), sb, akT[db]);
+                    avT[db] = mfma32(tr16_frag_at<CH>(gt + toff[db] + 32 * qb * ROWB, 16 * kk), pb, avT[db]);
+                    akT[db] = mfma32(tr16_frag_at<CH>(qt + toff[db] + 32 * qb * ROWB, 16 * kk), sb, akT[db]);
                 }
             }
+        }
+    };
+
+    issue(0, 0);
+    for (int step = 0; step < nsteps; step += 2) {
+        wait_vmem();
+        __syncthreads();
+        if (step + 1 < nsteps) issue(step + 1, 1);
+        do_step(std::integral_constant<int, 0>{}, step);
+        if (step + 1 < nsteps) {
+            wait_vmem();
+            __syncthreads();
+            if (step + 2 < nsteps) issue(step + 2, 0);
+            do_step(std::integral_constant<int, 1>{}, step + 1);
         }
     }
 

@@ -23,7 +23,7 @@ namespace unigist {
 namespace {
 
 constexpr int BM = 128;  // query rows per workgroup
-constexpr int BN = 64;   // keys per step
+constexpr int BN = 32;   // keys per step
 constexpr int NT = 256;  // threads
 
 template <int D>
@@ -34,7 +34,7 @@ struct FwdSmem {
 };
 
 template <int D>
-__global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
                                                         float* __restrict__ lse, AttnShape s, int nq) {
     constexpr int KS = D / 16;            // k-steps of the score MFMA
@@ -42,6 +42,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
     constexpr int CH = D / 8;             // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // tile rows covered by one direct-load instruction
     constexpr int IPW = BN / RPI / 4;     // such instructions per wave, per matrix, per tile
+    constexpr int NKB = BN / 32;          // 32-key blocks per step
     __shared__ __attribute__((aligned(1024))) FwdSmem<D> sm;
 
     const int tid = threadIdx.x;
@@ -148,9 +149,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
         if (!gist_tile && j0 > wrow0 + 31) return;
 
         // ---- S^T = K Q^T : two 32-key blocks
-        f32x16 sa[2];
+        f32x16 sa[NKB];
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
+        for (int kb2 = 0; kb2 < NKB; ++kb2) {
             sa[kb2] = zero16();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
             if (masked) {
                 const int lim = nfar - j0 - 4 * h;  // element visible iff its offset < lim
 #pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
+                for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
                 const unsigned long long gm = gbits >> (4 * h);
                 const int d0 = qrow - (j0 + 4 * h);  // distance to the lane's first key
 #pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
+                for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
@@ -197,9 +198,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
         // ---- online softmax (per query column = per lane, halves exchange once)
         float mx = sa[0][0];
 #pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa[0][i]);
+        for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[1][i]);
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[kb2][i]);
         mx = fmaxf(mx, other_half(mx));
         const float m_new = fmaxf(m, mx);
         const float m_use = (masked && m_new == -INFINITY) ? 0.f : m_new;
@@ -216,9 +217,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
 
         // P = exp2(c S - c m): summed in fp32 for the row sum (lse stays fp32-accurate), rounded to bf16
         // for the second MFMA
-        u32x4 pk[2][2];
+        u32x4 pk[NKB][2];
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_kernel(const bf16_t* __restric
 
         // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
+        for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[kb2][kk]);
