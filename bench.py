@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1065364825, "dkdv_gist": 4816499917, "dkdv_window": 3153686867, "dq": 1344108365,
-                 "decode": 4567950612}
+TRAFFIC_BYTES = {"fwd": 1065364865, "dkdv_gist": 4683680013, "dkdv_window": 3126411827, "dq": 1344108325,
+                 "decode": 4567950611}
 
 
 def pair_counts(L, r, W):
@@ -54,7 +54,7 @@ def pair_counts(L, r, W):
     return nvis, far_pairs
 
 
-def cpu_baseline(cfg, budget_s=12.0):
+def cpu_baseline(cfg, budget_s=15.0):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: blocks of 512
     query rows spread over the sequence, forward and backward, head after head, until about
     `budget_s` seconds of CPU work are done.  Its cost per row does not depend on the row (every
@@ -69,7 +69,7 @@ def cpu_baseline(cfg, budget_s=12.0):
     L, D, r, W, G = cfg["L"], cfg["D"], cfg["r"], cfg["W"], cfg["Hq"] // cfg["Hkv"]
     q, k, v, do = synth.attn_inputs(1, G, 1, L, D, seed=0)
     kn, vn = k[0, 0].double().numpy(), v[0, 0].double().numpy()
-    starts = [int(x) for x in np.linspace(0, L - 512, 8)]
+    starts = [int(x) for x in np.linspace(0, L - 512, 12)]
     pairs = nblocks = 0
     t0 = time.perf_counter()
     for h in range(G):
