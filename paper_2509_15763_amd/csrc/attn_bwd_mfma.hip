@@ -61,8 +61,8 @@ BwdPlan make_plan(const AttnShape& s) {
     p.NC = (s.L + MQ - 1) / MQ;
     const int nfar_max = far_of_chunk(p.NC - 1, s.W) / s.rp1;
     p.n_gt = (nfar_max + BNK - 1) / BNK;
-    p.segc = 64;
-    while ((p.NC + p.segc - 1) / p.segc > 16) p.segc *= 2;
+    p.segc = 32;  // 32 chunks x Hq/Hkv heads = 128 steps per workgroup: short enough to balance the last round
+    while ((p.NC + p.segc - 1) / p.segc > 32) p.segc *= 2;
     p.nseg = (p.NC + p.segc - 1) / p.segc;
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
