@@ -126,6 +126,38 @@ unigist_status unigist_decode(const void* q, const void* kcache, const void* vca
 size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt);
 
 /*
+ * Compressed KV cache (Sec. 4.3, Fig. 4: raw tokens outside the local window are never attended to again
+ * and can be dropped, chunk by chunk while prefilling and token by token while decoding).
+ *
+ * Cache layout per (batch, kv head): `cap` rows of D elements, [B, Hkv, cap, D].  In state (s, t) the first
+ * floor(s / (r+1)) rows hold the gists at positions < s (gist g in row g) and the next t - s + 1 rows hold
+ * the positions s .. t.  unigist_cache_rows(s, t, r) is the number of rows in use.  A query at position
+ * i >= t needs s <= max(0, i - W + 1).  The empty cache is (s, t) = (0, -1).
+ *
+ * unigist_cache_update: state (s_old, t_old) in kc_in/vc_in plus n_new new rows k_new/v_new
+ * ([B, Hkv, new_rows, D], positions t_old+1 .. t_old+n_new, n_new <= new_rows) -> state
+ * (s_new, t_old + n_new) in kc_out/vc_out.  Requires 0 <= s_old <= s_new <= t_old + n_new + 1, t_old >= s_old - 1,
+ * enough capacity, and out buffers that do not overlap the inputs.  kc_in/vc_in may be NULL for the empty
+ * cache, k_new/v_new when n_new == 0.  A gather: bit-exact copies, both dtypes.
+ */
+int unigist_cache_rows(int s, int t, int r);
+unigist_status unigist_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
+                                    const void* k_new, const void* v_new, int n_new, int new_rows,
+                                    void* kc_out, void* vc_out, int s_new, int cap_out,
+                                    int B, int Hkv, int D, int r, unigist_dtype dt, void* hip_stream);
+
+/*
+ * Chunk-wise prefill (Sec. 4.3: the prompt is encoded chunk by chunk with the training kernel, dropping
+ * the invisible tokens after each chunk).  q holds the C query rows at positions p0 .. p0+C-1, [B, Hq, C, D];
+ * kc/vc are caches in state (s, p0+C-1), i.e. already updated with the chunk's own keys, with
+ * s <= max(0, p0 - W + 1).  out [B, Hq, C, D], lse [B, Hq, C]: exactly the rows p0 .. p0+C-1 of
+ * unigist_attn_fwd on the whole sequence.  bf16 only (UNIGIST_EUNSUPPORTED otherwise).
+ */
+unigist_status unigist_prefill_chunk(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                     int B, int Hq, int Hkv, int C, int D, int r, int W,
+                                     int p0, int s, int cap, unigist_dtype dt, void* hip_stream);
+
+/*
  * Block map (Sec. 4.2: with a fixed compression ratio the visible blocks are known in
  * closed form and need not be stored; this builder materialises them on the HOST for
  * tests and for the live-tile report).  The sequence is cut into query tiles of Bm rows

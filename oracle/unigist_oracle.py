@@ -41,6 +41,7 @@ __all__ = [
     "is_gist", "visible", "mask_rows", "count_visible",
     "attn_fwd_head", "attn_bwd_head", "attn_fwd", "attn_bwd",
     "attn_fwd_rows", "attn_dq_rows", "attn_dkdv_cols", "decode", "compressed_cache_positions",
+    "cache_positions",
 ]
 
 
@@ -253,6 +254,15 @@ def compressed_cache_positions(t, r, W):
     up to t plus the raw tokens still inside t's window.  Ascending order."""
     j = np.arange(t + 1, dtype=np.int64)
     return j[visible(np.int64(t), j, r, W)]
+
+
+def cache_positions(s, t, r):
+    """Positions a compressed cache in state (s, t) holds, in row order (Sec. 4.3, Fig. 4): the gists
+    that lie left of position s, then every position s .. t.  With s = max(0, t - W + 1) this is the
+    visible set of query t."""
+    j = np.arange(t + 1, dtype=np.int64)
+    keep = (j >= s) | is_gist(j, r)
+    return j[keep]
 
 
 def decode(q, kcache, vcache, seqlens=None):

@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     BWD_STAGES, UNIGIST_BWD_ALL,
     unigist_decode, unigist_decode_workspace, unigist_blockmap_build,
     unigist_status_str, unigist_tile_sizes,
-    attn_fwd, attn_bwd, decode, n_vis,
+    unigist_cache_rows, unigist_cache_update, unigist_prefill_chunk,
+    attn_fwd, attn_bwd, decode, n_vis, KVCache, prefill_chunk,
 )

@@ -20,7 +20,7 @@ EXPORTS = [
     "unigist_status_str", "unigist_attn_fwd", "unigist_attn_bwd", "unigist_attn_bwd_stages",
     "unigist_attn_bwd_workspace",
     "unigist_decode", "unigist_decode_workspace", "unigist_blockmap_build", "unigist_blockmap_free",
-    "unigist_tile_sizes",
+    "unigist_tile_sizes", "unigist_cache_rows", "unigist_cache_update", "unigist_prefill_chunk",
 ]
 
 
@@ -69,6 +69,12 @@ def load():
     lib.unigist_blockmap_build.argtypes = [ip] * 5 + [C.POINTER(C.POINTER(_BlockMap))]
     lib.unigist_blockmap_free.restype = None
     lib.unigist_blockmap_free.argtypes = [C.POINTER(_BlockMap)]
+    lib.unigist_cache_rows.restype = ip
+    lib.unigist_cache_rows.argtypes = [ip, ip, ip]
+    lib.unigist_cache_update.restype = ip
+    lib.unigist_cache_update.argtypes = [vp, vp, ip, ip, ip, vp, vp, ip, ip, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
+    lib.unigist_prefill_chunk.restype = ip
+    lib.unigist_prefill_chunk.argtypes = [vp, vp, vp, vp, fp] + [ip] * 10 + [ip, vp]
     lib.unigist_tile_sizes.restype = None
     lib.unigist_tile_sizes.argtypes = [ip, ip, C.POINTER(ip), C.POINTER(ip)]
     _LIB = lib
@@ -132,6 +138,20 @@ def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_b
 
 def unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt) -> int:
     return load().unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt)
+
+
+def unigist_cache_rows(s, t, r) -> int:
+    return load().unigist_cache_rows(s, t, r)
+
+
+def unigist_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out, vc_out, s_new,
+                         cap_out, B, Hkv, D, r, dt, stream=None) -> int:
+    return load().unigist_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
+                                       vc_out, s_new, cap_out, B, Hkv, D, r, dt, stream)
+
+
+def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream=None) -> int:
+    return load().unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream)
 
 
 def unigist_tile_sizes(D, dt):
@@ -225,4 +245,52 @@ def decode(q, kcache, vcache, seqlens=None, want_lse=True, workspace=None):
                           seqlens.data_ptr() if seqlens is not None else None, D, dt,
                           workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
            "unigist_decode")
+    return out, lse
+
+
+class KVCache:
+    """Two ping-pong [B, Hkv, cap, D] buffers and the state (s, t) of the compressed cache; thin host-side
+    bookkeeping around unigist_cache_update (no arithmetic)."""
+
+    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda"):
+        self.B, self.Hkv, self.cap, self.D, self.r = B, Hkv, cap, D, int(r)
+        self.k = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
+        self.v = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
+        self.cur, self.s, self.t = 0, 0, -1
+
+    @property
+    def rows(self) -> int:
+        return unigist_cache_rows(self.s, self.t, self.r)
+
+    @property
+    def kc(self):
+        return self.k[self.cur]
+
+    @property
+    def vc(self):
+        return self.v[self.cur]
+
+    def update(self, k_new=None, v_new=None, s_new=None):
+        """Append k_new/v_new ([B, Hkv, n, D], the next n positions) and move the window start to s_new."""
+        n = 0 if k_new is None else k_new.shape[2]
+        if n:
+            _dev(k_new, v_new)
+        s_new = self.s if s_new is None else int(s_new)
+        nxt = 1 - self.cur
+        _check(unigist_cache_update(self.k[self.cur].data_ptr(), self.v[self.cur].data_ptr(), self.s, self.t, self.cap,
+                                    k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
+                                    self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), s_new, self.cap,
+                                    self.B, self.Hkv, self.D, self.r, _dt(self.k[0]), _stream()), "unigist_cache_update")
+        self.cur, self.s, self.t = nxt, s_new, self.t + n
+
+
+def prefill_chunk(q, cache: "KVCache", r, W, p0):
+    """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse."""
+    _dev(q)
+    B, Hq, C, D = q.shape
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, C, device=q.device, dtype=torch.float32)
+    _check(unigist_prefill_chunk(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                 B, Hq, cache.Hkv, C, D, int(r), int(W), int(p0), cache.s, cache.cap, _dt(q), _stream()),
+           "unigist_prefill_chunk")
     return out, lse

@@ -69,20 +69,23 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const int b = pr / s.Hkv, hk = pr % s.Hkv;
     const int hq = hk * G + g;
 
+    // Positions are absolute; q/out/lse hold the rows qpos0 .. L-1, K/V hold ngb compact gist rows followed
+    // by the positions s0 .. L-1 (training: everything from position 0, no compact rows).
     const int L = s.L, W = s.W, rp1 = s.rp1;
-    const int i0 = qt * BM;
+    const int qpos0 = s.qpos0, s0 = s.s0, ngb = s.ngb;
+    const int i0 = qpos0 + qt * BM;
     const int i1 = min(L, i0 + BM) - 1;
     const int qrow = i0 + 32 * w + c32;      // this lane's query row
     const int qrow_ld = min(qrow, L - 1);    // rows past the end shadow the last row and are never stored
     const int wrow0 = i0 + 32 * w;           // first row of the wave
 
-    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * L * D;
-    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * L * D;
+    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
+    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow][16 ks + 8 h .. +7]
     bf16x8 qf[KS];
     {
-        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * L + qrow_ld) * D + 8 * h;
+        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.Lq + (qrow_ld - qpos0)) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
@@ -95,10 +98,10 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
     // ---- tile walk
     const int lo = max(0, i0 - W + 1);
-    const int wfirst = lo / BN;            // first window key tile
-    const int nfar = (wfirst * BN) / rp1;  // gists strictly left of the window phase
+    const int wstart = max((lo / BN) * BN, s0);  // first position of the window phase
+    const int nfar = wstart / rp1;                // gists strictly left of the window phase
     const int ngt = (nfar + BN - 1) / BN;
-    const int nwin = i1 / BN - wfirst + 1;
+    const int nwin = (i1 - wstart) / BN + 1;
     const int ntiles = ngt + nwin;
 
     // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row.
@@ -113,16 +116,21 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const char* kbytes = (const char*)kb;
     const char* vbytes = (const char*)vb;
     auto issue = [&](int it, int buf) {
-        // row of tile row rr: gist phase (it * BN + rr) * rp1 + rp1 - 1, window phase (wfirst + it - ngt) * BN + rr,
-        // i.e. rr * mul + add with wave-uniform mul and add; clamped to the last valid row of the phase
+        // position of tile row rr: gist phase (it * BN + rr) * rp1 + rp1 - 1, window phase wstart + (it - ngt) * BN + rr,
+        // i.e. rr * mul + add with wave-uniform mul and add, clamped to the last valid position of the phase.
+        // Its row in the buffer: position - s0 + ngb, except for the gists in front (gist g < ngb sits in row g).
         const bool gphase = it < ngt;
         const int mul = gphase ? rp1 : 1;
-        const int add = gphase ? it * BN * rp1 + rp1 - 1 : (wfirst + it - ngt) * BN;
+        const int add = gphase ? it * BN * rp1 + rp1 - 1 : wstart + (it - ngt) * BN;
         const int lim = gphase ? grow_max : L - 1;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int rr = (wv * IPW + i) * RPI + lrow;
-            const int row = min(rr * mul + add, lim);
+            int row = min(rr * mul + add, lim) - s0 + ngb;
+            if (gphase) {
+                const int gi = min(it * BN + rr, nfar - 1);
+                if (gi < ngb) row = gi;
+            }
             const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         const char* kt = sm.k[BUF];
         const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
-        const int j0 = gist_tile ? it * BN : (wfirst + it - ngt) * BN;  // compact index or position
+        const int j0 = gist_tile ? it * BN : wstart + (it - ngt) * BN;  // compact index or position
         // a window tile entirely right of this wave's rows contributes nothing
         if (!gist_tile && j0 > wrow0 + 31) return;
 
@@ -258,7 +266,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const float lt = l + other_half(l);
     const float inv = 1.f / lt;
     if (qrow < L) {
-        bf16_t* op = out + (((size_t)b * s.Hq + hq) * L + qrow) * D + 4 * h;
+        const size_t orow = ((size_t)b * s.Hq + hq) * s.Lq + (qrow - qpos0);
+        bf16_t* op = out + orow * D + 4 * h;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -268,7 +277,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
                 w2[1] = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
                 *(u32x2*)(op + 32 * db + 8 * i4) = w2;
             }
-        if (h == 0) lse[((size_t)b * s.Hq + hq) * L + qrow] = m * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
+        if (h == 0) lse[orow] = m * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
     }
 }
 
@@ -276,7 +285,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
 hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
                            hipStream_t st) {
-    const int nq = (s.L + BM - 1) / BM;
+    const int nq = (s.Lq + BM - 1) / BM;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
     if (s.D == 64)

@@ -51,6 +51,13 @@ struct AttnShape {
     int rp1;  // r + 1, clamped to L + 1 when there are no gists (so (p+1) % rp1 == 0 never holds)
     int W;    // clamped to L
     float scale;
+    // Forward only: the query rows and the K/V rows may be a view of the L positions (chunk-wise prefill
+    // over a compressed cache).  Training passes the identity view.
+    int Lq;       // query rows held by q/out/lse per head
+    int qpos0;    // position of query row 0; the queries are positions qpos0 .. qpos0 + Lq - 1 (= L - 1)
+    int kv_rows;  // rows per head in the K/V buffers
+    int s0;       // first position stored in the window region of K/V
+    int ngb;      // rows in front of it: the gists at positions < s0, compact (gist g in row g)
 };
 
 // --- launchers implemented in the .hip files (all enqueue on `st`, return hipGetLastError) ---
@@ -66,6 +73,10 @@ hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const vo
                            const void* dout, void* dq, void* dk, void* dv, void* ws,
                            const AttnShape& s, unsigned stages, hipStream_t st);
 int decode_num_splits(int B, int Hq, int Hkv, int Lk);
+hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
+                               const void* k_new, const void* v_new, int n_new, int new_rows,
+                               void* kc_out, void* vc_out, int s_new, int cap_out,
+                               int BH, int D, int rp1, int elem_bytes, hipStream_t st);
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
                          float* ws, hipStream_t st);

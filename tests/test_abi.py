@@ -95,3 +95,30 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(u.UnigistError, match="no fallback"):
         binding.load()
+
+
+def test_cache_argument_validation():
+    assert u.unigist_cache_rows(0, -1, 4) == 0 and u.unigist_cache_rows(5, 9, 4) == 6
+    assert u.unigist_cache_rows(10, 3, 4) == -1 and u.unigist_cache_rows(-1, 3, 4) == -1
+
+    def call(**kw):
+        a = dict(kc_in=FAKE, vc_in=FAKE, s_old=0, t_old=9, cap_in=64, k_new=FAKE, v_new=FAKE, n_new=4, new_rows=4,
+                 kc_out=FAKE, vc_out=FAKE, s_new=5, cap_out=64, B=1, Hkv=2, D=128, r=4, dt=0)
+        a.update(kw)
+        return u.unigist_cache_update(*a.values())
+    assert call(s_new=15) == 1          # beyond t_new + 1
+    assert call(s_old=3, s_new=2) == 1  # the window start never moves left
+    assert call(cap_out=8) == 1         # 1 gist + 9 rows do not fit
+    assert call(n_new=5) == 1           # more rows than the new buffer holds
+    assert call(kc_out=None) == 1 and call(k_new=None) == 1 and call(kc_in=None) == 1
+    assert call(D=96) == 2 and call(dt=3) == 2
+    # prefill: f32 is not built, sizes are checked before anything is launched
+    p = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, p0=500, s=401,
+             cap=1024, dt=1)
+    assert u.unigist_prefill_chunk(*p.values()) == 2
+    p.update(dt=0, s=402)
+    assert u.unigist_prefill_chunk(*p.values()) == 1
+    p.update(s=401, cap=100)
+    assert u.unigist_prefill_chunk(*p.values()) == 1
+    p.update(cap=1024, q=None)
+    assert u.unigist_prefill_chunk(*p.values()) == 1

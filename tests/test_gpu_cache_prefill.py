@@ -1,0 +1,94 @@
+"""GPU parity of the compressed-cache maintenance and the chunk-wise prefill (Sec. 4.3, Fig. 4) against
+the oracle: the cache after any sequence of appends/evictions equals a direct gather of the positions the
+oracle says the state holds (bit-exact); every prefill chunk equals the same rows of the one-pass
+attention over the whole sequence; decode on the cache left by the prefill equals the last row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_15763_amd as u
+from paper_2509_15763_amd import synth
+from _parity import TOL_LSE_BF16, TOL_OUT_BF16, max_abs, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "f32"])
+@pytest.mark.parametrize("B,Hkv,D,r,L", [(2, 2, 128, 4, 700), (1, 3, 64, 8, 513), (1, 1, 128, 1, 64), (2, 1, 64, 10**6, 300)])
+def test_cache_updates_are_exact_gathers(B, Hkv, D, r, L, dtype):
+    print("case", B, Hkv, D, r, L, dtype, flush=True)
+    _, k, v, _ = synth.attn_inputs(B, Hkv, Hkv, L, D, dtype=dtype, seed=21)
+    kd, vd = k.cuda(), v.cuda()
+    cache = u.KVCache(B, Hkv, L, D, r, dtype=dtype)
+    rng = np.random.default_rng(5)
+    steps = 0
+    while cache.t < L - 1:
+        n = int(min(L - 1 - cache.t, rng.choice([0, 1, 3, 64, 200])))
+        s_new = int(rng.integers(cache.s, cache.t + n + 2))     # anywhere up to "keep gists only"
+        lo, hi = cache.t + 1, cache.t + 1 + n
+        cache.update(kd[:, :, lo:hi].contiguous() if n else None, vd[:, :, lo:hi].contiguous() if n else None, s_new)
+        pos = torch.from_numpy(oracle.cache_positions(cache.s, cache.t, r))
+        assert cache.rows == len(pos)
+        assert torch.equal(cache.kc[:, :, :cache.rows].cpu(), k[:, :, pos])
+        assert torch.equal(cache.vc[:, :, :cache.rows].cpu(), v[:, :, pos])
+        steps += 1
+    assert steps >= 1
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,D,r,W,C", [
+    (1, 4, 1, 3000, 128, 4, 256, 512),      # several chunks, window shorter than a chunk
+    (2, 4, 2, 2500, 128, 8, 1024, 1000),    # ragged last chunk, window longer than a chunk
+    (1, 2, 2, 1100, 64, 4, 100, 300),       # D = 64
+    (1, 2, 1, 900, 128, 2**31 - 2, 50, 256),  # no gists
+])
+def test_chunkwise_prefill_equals_one_pass(B, Hq, Hkv, L, D, r, W, C):
+    case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} C{C}"
+    print("case", case, flush=True)
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=22)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    full_out, full_lse = u.attn_fwd(qd, kd, vd, r, W)
+    cap = u.unigist_cache_rows(0, L - 1, r)                # generous: nothing would need to be dropped
+    cache = u.KVCache(B, Hkv, cap, D, r)
+    outs, lses, max_rows = [], [], 0
+    for p0 in range(0, L, C):
+        n = min(C, L - p0)
+        # append the chunk's keys, drop what no query of this chunk (or later) can see any more
+        cache.update(kd[:, :, p0:p0 + n].contiguous(), vd[:, :, p0:p0 + n].contiguous(), max(0, p0 - W + 1))
+        max_rows = max(max_rows, cache.rows)
+        o, l = u.prefill_chunk(qd[:, :, p0:p0 + n].contiguous(), cache, r, W, p0)
+        outs.append(o)
+        lses.append(l)
+    out, lse = torch.cat(outs, dim=2), torch.cat(lses, dim=2)
+    torch.cuda.synchronize()
+    # same kernel, same visible sets: only the order of the key tiles may differ
+    assert max_abs(to_np(out), to_np(full_out)) <= 1.6e-2 and max_abs(to_np(lse), to_np(full_lse)) <= 1e-4
+    # against the oracle on sampled rows of the whole sequence
+    rows = np.unique(np.concatenate([[0, C - 1, C, min(L - 1, C + 1), L - 1], np.random.default_rng(1).integers(0, L, 24)]))
+    for b, h in [(0, 0), (B - 1, Hq - 1)]:
+        g = h // (Hq // Hkv)
+        o, l = oracle.attn_fwd_rows(to_np(q[b, h]), to_np(k[b, g]), to_np(v[b, g]), rows, r, W)
+        assert max_abs(to_np(out[b, h])[rows], o) <= TOL_OUT_BF16, case
+        assert max_abs(to_np(lse[b, h])[rows], l) <= TOL_LSE_BF16, case
+    # the cache never held more than window + chunk + gists rows
+    assert max_rows <= W + C + L // (min(r, L) + 1) + 1
+    # decode the last position on the cache the prefill left behind, evicted down to its window
+    t = L - 1
+    cache.update(None, None, max(0, t - W + 1))
+    sl = torch.full((B,), cache.rows, dtype=torch.int32, device="cuda")
+    o2, l2 = u.decode(qd[:, :, t].contiguous(), cache.kc, cache.vc, sl)
+    od, ld = oracle.decode(to_np(q[:, :, t]), to_np(cache.kc[:, :, :cache.rows]), to_np(cache.vc[:, :, :cache.rows]))
+    assert max_abs(to_np(o2), od) <= TOL_OUT_BF16 and max_abs(to_np(l2), ld) <= TOL_LSE_BF16
+    assert max_abs(to_np(o2), to_np(full_out[:, :, t])) <= 1.6e-2
+
+
+def test_prefill_rejects_a_cache_that_dropped_too_much():
+    B, Hq, Hkv, D, r, W, C, p0 = 1, 2, 1, 128, 4, 100, 64, 500
+    cap = 1024
+    z = torch.zeros(B, Hkv, cap, D, dtype=torch.bfloat16, device="cuda")
+    q = torch.zeros(B, Hq, C, D, dtype=torch.bfloat16, device="cuda")
+    out, lse = torch.empty_like(q), torch.empty(B, Hq, C, device="cuda")
+    args = lambda s: (q.data_ptr(), z.data_ptr(), z.data_ptr(), out.data_ptr(), lse.data_ptr(), B, Hq, Hkv, C, D, r, W, p0, s, cap, 0)
+    assert u.unigist_prefill_chunk(*args(p0 - W + 1)) == 0
+    assert u.unigist_prefill_chunk(*args(p0 - W + 2)) == 1      # first query would miss a raw token
+    torch.cuda.synchronize()

@@ -86,3 +86,17 @@ def test_compressed_cache_positions():
     t, r, W = 147455, 8, 1024
     pos = oracle.compressed_cache_positions(t, r, W)
     assert len(pos) == W + (t - W + 1) // (r + 1)
+
+
+def test_cache_state_holds_the_visible_set():
+    # state (s, t) with s at the window start of query t holds exactly what query t may see (Eq. 3),
+    # and a later window start only ever drops raw tokens
+    for r, W in [(4, 3), (4, 16), (8, 5), (2, 1)]:
+        for t in (0, 1, 7, 40, 123):
+            s = max(0, t - W + 1)
+            assert np.array_equal(oracle.cache_positions(s, t, r), oracle.compressed_cache_positions(t, r, W))
+            wide = oracle.cache_positions(max(0, s - 5), t, r)
+            dropped = np.setdiff1d(wide, oracle.cache_positions(s, t, r))
+            assert not oracle.is_gist(dropped, r).any()
+    assert oracle.cache_positions(5, 9, 4).tolist() == [4, 5, 6, 7, 8, 9]
+    assert oracle.cache_positions(0, -1, 4).tolist() == []
