@@ -36,20 +36,6 @@ __device__ __forceinline__ float other_half(float x) {
     return (threadIdx.x & 32) ? a : b;
 }
 
-// A operand X^T[n][slots] for a row-major LDS tile X[row][col] (stride `stride` elements):
-// lane gets, for column n = col0 + lane % 32, the 8 rows row0 + 4h + {0,1,2,3} and row0 + 8 + 4h + {0,1,2,3}.
-// Two ds_read_b64_tr_b16: within each 16-lane group, lane p passes the address of
-// X[r + p/4][c + 4 (p%4)] and receives X[r .. r+3][c + p].
-__device__ __forceinline__ bf16x8 tr16_frag(const bf16_t* tile, int stride, int row0, int col0) {
-    const int lane = threadIdx.x & 63;
-    const int p16 = lane & 15, gi2 = (lane >> 4) & 1, h = lane >> 5;
-    const bf16_t* p = tile + (row0 + 4 * h + (p16 >> 2)) * stride + col0 + 16 * gi2 + 4 * (p16 & 3);
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * stride));
-    s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, a);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Tiles staged with direct global->LDS loads (global_load_lds_dwordx4).
 // One such instruction makes a wave write 64 x 16 B = 1 KB of consecutive LDS, so rows cannot be
@@ -73,30 +59,16 @@ __device__ __forceinline__ void g2l16(const void* src, void* lds_base_uniform) {
 // wait until this wave's outstanding vector-memory operations (direct loads included) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-// A operand X^T from a swizzled tile: same contract as tr16_frag (rows row0 + 4h + {0..3} and + 8,
-// column col0 + lane % 32), row0 a multiple of 8 and col0 a multiple of 32.  `lane_off` is
-// tr_lane_off<CH>() of the calling lane, `db` = col0 / 32.
 template <int CH>
 __device__ __forceinline__ int tr_lane_row() {
     const int lane = threadIdx.x & 63;
     return 4 * (lane >> 5) + ((lane & 15) >> 2);
 }
-template <int CH>
-__device__ __forceinline__ bf16x8 tr16_frag_swz(const char* tile, int row0, int db) {
-    const int lane = threadIdx.x & 63;
-    const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
-    const int rl = tr_lane_row<CH>();                       // row within the aligned group of 8
-    const int ch = 4 * db + 2 * gi2 + ((p16 & 3) >> 1);       // 16-byte chunk holding the 4 elements
-    const char* p = tile + (row0 + rl) * (CH * 16) + ((ch ^ swz<CH>(rl)) << 4) + (p16 & 1) * 8;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * CH * 16));
-    s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, a);
-}
-
-// The same with the address split into a per-lane register and compile-time parts: the lane part
-// tr_lane_off<CH>(db) is computed once per kernel, the rows (a multiple of 8) and the LDS stage become
-// immediates of the two ds_read_b64_tr_b16.
+// A operand X^T from a swizzled row-major LDS tile X[row][col]: the lane gets, for column col0 + lane % 32,
+// the 8 rows row0 + 4h + {0,1,2,3} and row0 + 8 + 4h + {0,1,2,3} (row0 a multiple of 8, col0 = 32 db) with two
+// ds_read_b64_tr_b16: within each 16-lane group, lane p passes the address of X[r + p/4][c + 4 (p%4)] and
+// receives X[r .. r+3][c + p].  The address is split into a per-lane register tr_lane_off<CH>(db),
+// computed once per kernel, and compile-time parts (rows, LDS stage) that become immediates.
 template <int CH>
 __device__ __forceinline__ int tr_lane_off(int db) {
     const int lane = threadIdx.x & 63;
