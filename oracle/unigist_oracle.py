@@ -6,16 +6,18 @@ be imported by the product package.
 
 What it follows
 ---------------
-* Sequence layout: the gist-augmented sequence of Sec. 4.1, Eq. 2 with no sink
-  prefix (s = 0): r raw tokens, one gist, r raw tokens, one gist, ...  With
-  0-based positions a position p holds a gist iff (p + 1) % (r + 1) == 0.  A
-  trailing group of fewer than r raw tokens has no closing gist.
+* Sequence layout: the gist-augmented sequence of Sec. 4.1, Eq. 2: an optional
+  prefix of sink tokens, then r raw tokens, one gist, r raw tokens, one gist, ...
+  With 0-based positions and no sinks a position p holds a gist iff
+  (p + 1) % (r + 1) == 0.  A trailing group of fewer than r raw tokens has no
+  closing gist.
 * Visible set: Sec. 4.1, Eq. 3 -- (gists U local window) intersected with the
   causal set {j <= t}, the same rule for raw and gist queries.  The local window
   is read as a per-token sliding window counted in interleaved positions:
   key j is inside the window of query i iff 0 <= i - j < W.  (The paper words the
   window in whole gist units; the sliding reading is the one the workload
-  definitions of this build fix.)
+  definitions of this build fix.  The unit-aligned wording and the sink prefix are
+  available through the keyword arguments sinks= and units=True.)
 * Everything else is ordinary softmax attention: S = Q K^T / sqrt(D), masked
   entries are -inf, P = softmax over keys, out = P V, lse = ln sum_j exp(S_ij).
   The gradients are the exact derivative of l = sum(out * dout).
@@ -48,53 +50,67 @@ __all__ = [
 # --------------------------------------------------------------------------
 # layout and mask (Eq. 2, Eq. 3)
 # --------------------------------------------------------------------------
-def is_gist(p, r):
-    """True where 0-based position p holds a gist token (Eq. 2 with s = 0).
+def is_gist(p, r, sinks=0):
+    """True where 0-based position p holds a gist token (Eq. 2): after `sinks` sink tokens the
+    sequence repeats r raw tokens followed by one gist.
 
     r is the compression ratio (raw tokens per gist).  Python ints are used for
     r + 1 so that a huge r ("no gists at all") cannot overflow.
     """
     p = np.asarray(p, dtype=np.int64)
     period = int(r) + 1
-    return (p + 1) % period == 0
+    return (p >= sinks) & ((p - sinks + 1) % period == 0)
 
 
-def visible(i, j, r, W):
-    """Eq. 3 with the sliding-window reading: may query i attend to key j?"""
+def visible(i, j, r, W, sinks=0, units=False):
+    """Eq. 3: may query i attend to key j?  Key j must be causal and be a sink, a gist, or inside the
+    local window of i.
+
+    units=False: the window is the W most recent positions (sliding per token) -- the reading the
+    workloads of this build use.  units=True: the window is worded as in Sec. 4.1: the gist unit that
+    contains i plus the W previous gist units (a unit = r raw tokens and the gist that follows them).
+    Sink queries (i < sinks) belong to no unit; they see the sinks up to themselves.
+    """
     i = np.asarray(i, dtype=np.int64)
     j = np.asarray(j, dtype=np.int64)
     causal = j <= i
-    in_window = (i - j) < int(W)
-    return causal & (is_gist(j, r) | in_window)
+    if units:
+        period = int(r) + 1
+        unit_i = (i - sinks) // period
+        unit_j = (j - sinks) // period
+        in_window = (i >= sinks) & (j >= sinks) & (unit_j >= unit_i - int(W))
+    else:
+        in_window = (i - j) < int(W)
+    return causal & ((j < sinks) | is_gist(j, r, sinks) | in_window)
 
 
-def mask_rows(rows, L, r, W):
+def mask_rows(rows, L, r, W, **mask):
     """Boolean [len(rows), L] matrix of visible(i, j) for the given query rows."""
     rows = np.asarray(rows, dtype=np.int64)
     cols = np.arange(L, dtype=np.int64)
-    return visible(rows[:, None], cols[None, :], r, W)
+    return visible(rows[:, None], cols[None, :], r, W, **mask)
 
 
-def count_visible(L, r, W, block=1024):
+def count_visible(L, r, W, block=1024, **mask):
     """Number of visible (i, j) pairs, by evaluating the predicate on every pair."""
     total = 0
     for i0 in range(0, L, block):
         rows = np.arange(i0, min(L, i0 + block))
-        total += int(np.count_nonzero(mask_rows(rows, L, r, W)))
+        total += int(np.count_nonzero(mask_rows(rows, L, r, W, **mask)))
     return total
 
 
 # --------------------------------------------------------------------------
 # one head, a set of query rows against all keys
 # --------------------------------------------------------------------------
-def _softmax_rows(q_rows, k, rows, r, W):
+def _softmax_rows(q_rows, k, rows, r, W, **mask):
     """Scores, mask and softmax of the given query rows against every key.
 
     Returns P [n, L] and lse [n]; masked entries of P are exactly 0.
     """
     L, D = k.shape
     S = (q_rows @ k.T) / math.sqrt(D)
-    M = mask_rows(rows, L, r, W)
+    M = mask_rows(rows, L, r, W, **mask)
     S = np.where(M, S, -np.inf)
     m = S.max(axis=1)
     E = np.exp(S - m[:, None])
@@ -104,7 +120,7 @@ def _softmax_rows(q_rows, k, rows, r, W):
     return P, lse
 
 
-def attn_fwd_head(q, k, v, r, W, block=512):
+def attn_fwd_head(q, k, v, r, W, block=512, **mask):
     """Forward for one head.  q, k, v: float64 [L, D].  Returns out [L, D], lse [L]."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -114,12 +130,12 @@ def attn_fwd_head(q, k, v, r, W, block=512):
     lse = np.empty(L)
     for i0 in range(0, L, block):
         rows = np.arange(i0, min(L, i0 + block))
-        P, lse[rows] = _softmax_rows(q[rows], k, rows, r, W)
+        P, lse[rows] = _softmax_rows(q[rows], k, rows, r, W, **mask)
         out[rows] = P @ v
     return out, lse
 
 
-def attn_bwd_head(q, k, v, dout, r, W, block=512, row_lo=0, row_hi=None):
+def attn_bwd_head(q, k, v, dout, r, W, block=512, row_lo=0, row_hi=None, **mask):
     """Gradients of l = sum(out * dout) for one head.
 
     dV_j = sum_i P_ij dO_i;  dP_ij = dO_i . v_j;  delta_i = sum_j P_ij dP_ij;
@@ -140,7 +156,7 @@ def attn_bwd_head(q, k, v, dout, r, W, block=512, row_lo=0, row_hi=None):
     dv = np.zeros((L, D))
     for i0 in range(row_lo, row_hi, block):
         rows = np.arange(i0, min(row_hi, i0 + block))
-        P, _ = _softmax_rows(q[rows], k, rows, r, W)
+        P, _ = _softmax_rows(q[rows], k, rows, r, W, **mask)
         dO = dout[rows]
         dv += P.T @ dO
         dP = dO @ v.T
@@ -159,7 +175,7 @@ def _kv_head(h, Hq, Hkv):
     return h // (Hq // Hkv)
 
 
-def attn_fwd(q, k, v, r, W, block=512):
+def attn_fwd(q, k, v, r, W, block=512, **mask):
     """q [B,Hq,L,D], k/v [B,Hkv,L,D]  ->  out [B,Hq,L,D], lse [B,Hq,L] (float64)."""
     q = np.asarray(q, dtype=np.float64)
     B, Hq, L, D = q.shape
@@ -169,11 +185,11 @@ def attn_fwd(q, k, v, r, W, block=512):
     for b in range(B):
         for h in range(Hq):
             g = _kv_head(h, Hq, Hkv)
-            out[b, h], lse[b, h] = attn_fwd_head(q[b, h], k[b, g], v[b, g], r, W, block)
+            out[b, h], lse[b, h] = attn_fwd_head(q[b, h], k[b, g], v[b, g], r, W, block, **mask)
     return out, lse
 
 
-def attn_bwd(q, k, v, dout, r, W, block=512):
+def attn_bwd(q, k, v, dout, r, W, block=512, **mask):
     """Returns dq [B,Hq,L,D], dk, dv [B,Hkv,L,D]; dk/dv summed over the q heads of a group."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -185,7 +201,7 @@ def attn_bwd(q, k, v, dout, r, W, block=512):
     for b in range(B):
         for h in range(Hq):
             g = _kv_head(h, Hq, Hkv)
-            dq[b, h], dk_h, dv_h = attn_bwd_head(q[b, h], k[b, g], v[b, g], dout[b, h], r, W, block)
+            dq[b, h], dk_h, dv_h = attn_bwd_head(q[b, h], k[b, g], v[b, g], dout[b, h], r, W, block, **mask)
             dk[b, g] += dk_h
             dv[b, g] += dv_h
     return dq, dk, dv
@@ -194,17 +210,17 @@ def attn_bwd(q, k, v, dout, r, W, block=512):
 # --------------------------------------------------------------------------
 # sampled rows (out, lse and dq of a row depend on that row of q/dout only)
 # --------------------------------------------------------------------------
-def attn_fwd_rows(q, k, v, rows, r, W):
+def attn_fwd_rows(q, k, v, rows, r, W, **mask):
     """One head: out and lse for a chosen set of query rows.  q, k, v [L, D]."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     rows = np.asarray(rows, dtype=np.int64)
-    P, lse = _softmax_rows(q[rows], k, rows, r, W)
+    P, lse = _softmax_rows(q[rows], k, rows, r, W, **mask)
     return P @ v, lse
 
 
-def attn_dq_rows(q, k, v, dout, rows, r, W):
+def attn_dq_rows(q, k, v, dout, rows, r, W, **mask):
     """One head: dq for a chosen set of query rows."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -212,14 +228,14 @@ def attn_dq_rows(q, k, v, dout, rows, r, W):
     dout = np.asarray(dout, dtype=np.float64)
     rows = np.asarray(rows, dtype=np.int64)
     D = q.shape[1]
-    P, _ = _softmax_rows(q[rows], k, rows, r, W)
+    P, _ = _softmax_rows(q[rows], k, rows, r, W, **mask)
     dP = dout[rows] @ v.T
     delta = (P * dP).sum(axis=1)
     dS = P * (dP - delta[:, None])
     return (dS @ k) / math.sqrt(D)
 
 
-def attn_dkdv_cols(q, k, v, dout, cols, r, W, row_lo=0, row_hi=None, block=512):
+def attn_dkdv_cols(q, k, v, dout, cols, r, W, row_lo=0, row_hi=None, block=512, **mask):
     """One query head: what the query rows row_lo .. row_hi-1 add to dK and dV of the chosen key
     columns.  Same formulas as attn_bwd_head, with the sums over i restricted to those rows and
     only the requested columns of dS and P kept.  Summing the results over disjoint row ranges
@@ -235,7 +251,7 @@ def attn_dkdv_cols(q, k, v, dout, cols, r, W, row_lo=0, row_hi=None, block=512):
     dv = np.zeros((len(cols), D))
     for i0 in range(row_lo, row_hi, block):
         rows = np.arange(i0, min(row_hi, i0 + block))
-        P, _ = _softmax_rows(q[rows], k, rows, r, W)
+        P, _ = _softmax_rows(q[rows], k, rows, r, W, **mask)
         dO = dout[rows]
         dP = dO @ v.T
         delta = (P * dP).sum(axis=1)

@@ -218,3 +218,27 @@ def test_decode_ragged_and_gqa_against_loops():
             want = [sum(e[j] * vc[b, g, j, d] for j in range(seqlens[b])) / z for d in range(D)]
             np.testing.assert_allclose(o[b, h], want, rtol=0, atol=1e-13)
             assert abs(l[b, h] - math.log(z)) < 1e-13
+
+
+def test_sinks_and_unit_window_thread_through_forward_and_backward():
+    # library attention + autograd with the explicitly built mask, and the rows/columns variants
+    L, D, r, k, S = 70, 8, 4, 1, 3
+    kw = dict(sinks=S, units=True)
+    q, kk, v, do = (_rand((L, D), s) for s in (60, 61, 62, 63))
+    M = oracle.mask_rows(np.arange(L), L, r, k, **kw)
+    assert M[40].sum() != oracle.mask_rows([40], L, r, k)[0].sum()          # the keyword arguments matter
+    tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (q, kk, v))
+    o = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], attn_mask=torch.from_numpy(M)[None])
+    (o[0] * torch.from_numpy(do)).sum().backward()
+    out, _ = oracle.attn_fwd_head(q, kk, v, r, k, **kw)
+    dq, dk, dv = oracle.attn_bwd_head(q, kk, v, do, r, k, block=16, **kw)
+    np.testing.assert_allclose(out, o[0].detach().numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dq, tq.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), rtol=0, atol=1e-12)
+    rows = [0, 2, 3, 40, 69]
+    np.testing.assert_allclose(oracle.attn_fwd_rows(q, kk, v, rows, r, k, **kw)[0], out[rows], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.attn_dq_rows(q, kk, v, do, rows, r, k, **kw), dq[rows], rtol=0, atol=1e-13)
+    a = oracle.attn_dkdv_cols(q, kk, v, do, [1, 7, 30], r, k, **kw)
+    np.testing.assert_allclose(a[0], dk[[1, 7, 30]], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(a[1], dv[[1, 7, 30]], rtol=0, atol=1e-13)

@@ -100,3 +100,39 @@ def test_cache_state_holds_the_visible_set():
             assert not oracle.is_gist(dropped, r).any()
     assert oracle.cache_positions(5, 9, 4).tolist() == [4, 5, 6, 7, 8, 9]
     assert oracle.cache_positions(0, -1, 4).tolist() == []
+
+
+def test_hand_derived_visible_sets_with_sinks_and_unit_window():
+    rows = _read_rows(os.path.join(GOLDEN, "visible_sets_L14_r2_sinks2_units1.txt"))
+    M = oracle.mask_rows(np.arange(14), 14, 2, 1, sinks=2, units=True)
+    assert len(rows) == 14
+    for ln in rows:
+        i, keys = ln.split(":")
+        assert np.nonzero(M[int(i)])[0].tolist() == sorted(int(t) for t in keys.split()), i
+
+
+def test_unit_window_is_sandwiched_between_sliding_windows():
+    # current unit + k previous units covers at least k(r+1)+1 and at most (k+1)(r+1) positions
+    L = 150
+    for r, k in [(4, 1), (4, 3), (2, 0), (8, 2)]:
+        U = oracle.mask_rows(np.arange(L), L, r, k, units=True)
+        small = oracle.mask_rows(np.arange(L), L, r, k * (r + 1) + 1)
+        big = oracle.mask_rows(np.arange(L), L, r, (k + 1) * (r + 1))
+        assert not (small & ~U).any() and not (U & ~big).any()
+        # rows at the end of a unit (gist queries) see exactly (k+1)(r+1) window positions
+        g = np.nonzero(oracle.is_gist(np.arange(L), r))[0]
+        assert np.array_equal(U[g], big[g])
+
+
+def test_sinks_are_always_visible_and_shift_the_layout():
+    L, r, S = 60, 4, 3
+    g = oracle.is_gist(np.arange(L), r, sinks=S)
+    assert np.nonzero(g)[0].tolist() == list(range(S + r, L, r + 1))
+    for units, W in [(False, 6), (True, 1)]:
+        M = oracle.mask_rows(np.arange(L), L, r, W, sinks=S, units=units)
+        assert M[:, :S].sum() == sum(min(i + 1, S) for i in range(L))      # every later row sees every sink
+        assert M.diagonal().all() and not np.triu(M, 1).any()
+        # with the sinks cut off the pattern is the sink-free one
+        assert np.array_equal(M[S:, S:], oracle.mask_rows(np.arange(L - S), L - S, r, W, units=units))
+    # a huge unit window is plain causal attention
+    assert np.array_equal(oracle.mask_rows(np.arange(L), L, r, 10**6, sinks=S, units=True), np.tril(np.ones((L, L), bool)))
