@@ -49,6 +49,14 @@ typedef enum {
 
 typedef enum { UNIGIST_BF16 = 0, UNIGIST_F32 = 1 } unigist_dtype;
 
+/*
+ * How the local window of Eq. 3 is counted (the *_ex entry points):
+ *   SLIDING  the W most recent positions (i - j < W), per token;
+ *   UNITS    as Sec. 4.1 words it: the gist unit that holds the query (r raw tokens and the gist closing
+ *            them) plus the W previous units, counted behind the sink prefix.
+ */
+typedef enum { UNIGIST_WINDOW_SLIDING = 0, UNIGIST_WINDOW_UNITS = 1 } unigist_window_mode;
+
 /* Human-readable name of a status code (static storage). */
 const char* unigist_status_str(unigist_status s);
 
@@ -61,6 +69,17 @@ const char* unigist_status_str(unigist_status s);
 unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                                 int B, int Hq, int Hkv, int L, int D, int r, int W,
                                 unigist_dtype dt, void* hip_stream);
+
+/*
+ * Forward with the full layout of Sec. 4.1: `sinks` >= 0 sink tokens precede the first gist unit (Eq. 2),
+ * so gist(p) <=> p >= sinks and (p - sinks + 1) % (r + 1) == 0, every sink is visible to all later
+ * queries, and `window_mode` (a unigist_window_mode) selects how W is counted.  A sink query belongs to
+ * no unit: in UNITS mode it sees the sinks up to itself.  sinks = 0 with SLIDING is unigist_attn_fwd.
+ * Everything else as unigist_attn_fwd; a negative `sinks` or an unknown mode is UNIGIST_EINVAL.
+ */
+unigist_status unigist_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, float* lse,
+                                   int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                   int window_mode, unigist_dtype dt, void* hip_stream);
 
 /*
  * Backward of l = sum(out * dout) through the forward above.
@@ -106,6 +125,19 @@ unigist_status unigist_attn_bwd_stages(const void* q, const void* k, const void*
 /* Bytes of workspace unigist_attn_bwd needs for this shape (0 on invalid arguments). */
 size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
                                   unigist_dtype dt);
+
+/*
+ * Backward through unigist_attn_fwd_ex (Sec. 4.1 layout with `sinks` and `window_mode`, see there); the
+ * other arguments, the stage mask and the workspace rules are those of unigist_attn_bwd_stages, with the
+ * workspace sized by unigist_attn_bwd_workspace_ex for the same (sinks, window_mode).
+ */
+unigist_status unigist_attn_bwd_ex(const void* q, const void* k, const void* v, const void* out,
+                                   const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                   int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                   int window_mode, unigist_dtype dt, void* workspace,
+                                   size_t workspace_bytes, unsigned stages, void* hip_stream);
+size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                     int window_mode, unigist_dtype dt);
 
 /*
  * Decode over the compressed KV cache (Sec. 4.3, Fig. 4): the raw tokens that have
@@ -189,10 +221,18 @@ typedef struct unigist_blockmap {
     int64_t masked_tiles;  /* of those, window tiles that need the in-tile mask */
     int64_t causal_tiles;  /* tiles a dense causal kernel would visit at the same Bm, Bn */
     int64_t n_vis;         /* visible pairs, closed form */
+    int sinks;             /* sink prefix (0 for unigist_blockmap_build) */
+    int window_mode;       /* unigist_window_mode */
 } unigist_blockmap;
 
 /* Requires L, W, Bm, Bn >= 1, r >= 1.  *out is set only on UNIGIST_OK. */
 unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, int Bn, unigist_blockmap** out);
+/*
+ * The same map for the layout of unigist_attn_fwd_ex.  The compact list then holds the sinks followed
+ * by the gists (n_far_gists, n_gtiles and gist_qt_first count both); n_gists still counts gists only.
+ */
+unigist_status unigist_blockmap_build_ex(int L, int r, int W, int sinks, int window_mode, int Bm, int Bn,
+                                         unigist_blockmap** out);
 void unigist_blockmap_free(unigist_blockmap* m);
 
 /* Tile sizes the forward / backward kernels use for head dim D (for the live-tile report). */

@@ -12,6 +12,8 @@ UNIGIST_BF16 = 0
 UNIGIST_F32 = 1
 BWD_STAGES = {"delta": 1, "dkdv_gist": 2, "gist_reduce": 4, "dkdv_window": 8, "dq": 16}
 UNIGIST_BWD_ALL = 31
+UNIGIST_WINDOW_SLIDING = 0
+UNIGIST_WINDOW_UNITS = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -21,6 +23,7 @@ EXPORTS = [
     "unigist_attn_bwd_workspace",
     "unigist_decode", "unigist_decode_workspace", "unigist_blockmap_build", "unigist_blockmap_free",
     "unigist_tile_sizes", "unigist_cache_rows", "unigist_cache_update", "unigist_prefill_chunk",
+    "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
 ]
 
 
@@ -32,7 +35,8 @@ class _BlockMap(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("L", "r", "W", "Bm", "Bn", "n_qtiles", "n_ktiles", "n_gists", "n_gtiles")] + \
                [(n, C.POINTER(C.c_int)) for n in ("win_first", "win_last", "n_far_gists", "n_full", "qt_first",
                                                    "qt_last", "gist_qt_first")] + \
-               [(n, C.c_int64) for n in ("live_tiles", "masked_tiles", "causal_tiles", "n_vis")]
+               [(n, C.c_int64) for n in ("live_tiles", "masked_tiles", "causal_tiles", "n_vis")] + \
+               [(n, C.c_int) for n in ("sinks", "window_mode")]
 
 
 def lib_path() -> str:
@@ -61,6 +65,14 @@ def load():
     lib.unigist_attn_bwd_stages.argtypes = [vp] * 9 + [ip] * 7 + [ip, vp, sz, C.c_uint, vp]
     lib.unigist_attn_bwd_workspace.restype = sz
     lib.unigist_attn_bwd_workspace.argtypes = [ip] * 7 + [ip]
+    lib.unigist_attn_fwd_ex.restype = ip
+    lib.unigist_attn_fwd_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [ip, vp]
+    lib.unigist_attn_bwd_ex.restype = ip
+    lib.unigist_attn_bwd_ex.argtypes = [vp] * 9 + [ip] * 9 + [ip, vp, sz, C.c_uint, vp]
+    lib.unigist_attn_bwd_workspace_ex.restype = sz
+    lib.unigist_attn_bwd_workspace_ex.argtypes = [ip] * 9 + [ip]
+    lib.unigist_blockmap_build_ex.restype = ip
+    lib.unigist_blockmap_build_ex.argtypes = [ip] * 7 + [C.POINTER(C.POINTER(_BlockMap))]
     lib.unigist_decode.restype = ip
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
     lib.unigist_decode_workspace.restype = sz
@@ -132,6 +144,20 @@ def unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt) -> int:
     return load().unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt)
 
 
+def unigist_attn_fwd_ex(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt, stream=None) -> int:
+    return load().unigist_attn_fwd_ex(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt, stream)
+
+
+def unigist_attn_bwd_ex(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt, ws,
+                        ws_bytes, stages, stream=None) -> int:
+    return load().unigist_attn_bwd_ex(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, sinks,
+                                      window_mode, dt, ws, ws_bytes, stages, stream)
+
+
+def unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt) -> int:
+    return load().unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt)
+
+
 def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream=None) -> int:
     return load().unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream)
 
@@ -164,10 +190,22 @@ def unigist_blockmap_build(L, r, W, Bm, Bn) -> dict:
     """Host block map as a dict of python lists / ints (the C object is freed before returning)."""
     p = C.POINTER(_BlockMap)()
     _check(load().unigist_blockmap_build(L, r, W, Bm, Bn, C.byref(p)), "unigist_blockmap_build")
+    return _blockmap_dict(p)
+
+
+def unigist_blockmap_build_ex(L, r, W, sinks, window_mode, Bm, Bn) -> dict:
+    p = C.POINTER(_BlockMap)()
+    _check(load().unigist_blockmap_build_ex(L, r, W, sinks, window_mode, Bm, Bn, C.byref(p)),
+           "unigist_blockmap_build_ex")
+    return _blockmap_dict(p)
+
+
+def _blockmap_dict(p) -> dict:
     try:
         m = p.contents
         d = {n: getattr(m, n) for n in ("L", "r", "W", "Bm", "Bn", "n_qtiles", "n_ktiles", "n_gists", "n_gtiles",
-                                        "live_tiles", "masked_tiles", "causal_tiles", "n_vis")}
+                                        "live_tiles", "masked_tiles", "causal_tiles", "n_vis", "sinks",
+                                        "window_mode")}
         for n in ("win_first", "win_last", "n_far_gists", "n_full"):
             d[n] = [getattr(m, n)[i] for i in range(m.n_qtiles)]
         for n in ("qt_first", "qt_last"):
@@ -178,13 +216,13 @@ def unigist_blockmap_build(L, r, W, Bm, Bn) -> dict:
         load().unigist_blockmap_free(p)
 
 
-def n_vis(L, r, W) -> int:
+def n_vis(L, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:
     """Visible (query, key) pairs of one head: the unit the FLOP counts are quoted in."""
-    return unigist_blockmap_build(L, r, W, 128, 128)["n_vis"]
+    return unigist_blockmap_build_ex(L, r, W, sinks, window_mode, 128, 128)["n_vis"]
 
 
 # ---------------------------------------------------------------- conveniences (allocate outputs, check status)
-def attn_fwd(q, k, v, r, W):
+def attn_fwd(q, k, v, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
     """q [B,Hq,L,D], k/v [B,Hkv,L,D] on the GPU -> out [B,Hq,L,D], lse [B,Hq,L] fp32."""
     _dev(q, k, v)
     B, Hq, L, D = q.shape
@@ -193,12 +231,14 @@ def attn_fwd(q, k, v, r, W):
         raise UnigistError("q/k/v shapes or dtypes disagree")
     out = torch.empty_like(q)
     lse = torch.empty(B, Hq, L, device=q.device, dtype=torch.float32)
-    _check(unigist_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                            B, Hq, Hkv, L, D, int(r), int(W), _dt(q), _stream()), "unigist_attn_fwd")
+    _check(unigist_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                               B, Hq, Hkv, L, D, int(r), int(W), int(sinks), int(window_mode), _dt(q), _stream()),
+           "unigist_attn_fwd_ex")
     return out, lse
 
 
-def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_ALL, grads=None):
+def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_ALL, grads=None, sinks=0,
+             window_mode=UNIGIST_WINDOW_SLIDING):
     """-> dq [B,Hq,L,D], dk, dv [B,Hkv,L,D].  `stages`/`grads` let a caller run the backward one
     stage at a time into the same output tensors (per-kernel timing)."""
     _dev(q, k, v, out, lse, dout)
@@ -209,17 +249,17 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_A
         raise UnigistError("out/dout/lse shapes or dtypes disagree")
     if k.shape != (B, Hkv, L, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:
         raise UnigistError("q/k/v/out/dout shapes or dtypes disagree")
-    need = unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, int(r), int(W), dt)
+    need = unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, int(r), int(W), int(sinks), int(window_mode), dt)
     if need == 0:
-        raise UnigistError("unigist_attn_bwd_workspace: invalid or unsupported shape")
+        raise UnigistError("unigist_attn_bwd_workspace_ex: invalid or unsupported shape")
     if workspace is None:
         workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
     dq, dk, dv = grads if grads is not None else (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
-    _check(unigist_attn_bwd_stages(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                                   dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D,
-                                   int(r), int(W), dt, workspace.data_ptr(),
-                                   workspace.numel() * workspace.element_size(), int(stages), _stream()),
-           "unigist_attn_bwd")
+    _check(unigist_attn_bwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                               dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D,
+                               int(r), int(W), int(sinks), int(window_mode), dt, workspace.data_ptr(),
+                               workspace.numel() * workspace.element_size(), int(stages), _stream()),
+           "unigist_attn_bwd_ex")
     return dq, dk, dv
 
 

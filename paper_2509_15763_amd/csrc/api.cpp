@@ -17,8 +17,10 @@ bool plain_alu_forced() {
     return e && e[0] == '1';
 }
 
-unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt) {
-    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1 || D < 1 || r < 1 || W < 1) return UNIGIST_EINVAL;
+unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt, int sinks = 0,
+                          int window_mode = UNIGIST_WINDOW_SLIDING) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || L < 1 || D < 1 || r < 1 || W < 1 || sinks < 0) return UNIGIST_EINVAL;
+    if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return UNIGIST_EINVAL;
     if (Hq % Hkv != 0) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
     if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
@@ -26,7 +28,8 @@ unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, un
     return UNIGIST_OK;
 }
 
-AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W) {
+AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks = 0,
+                     int window_mode = UNIGIST_WINDOW_SLIDING) {
     AttnShape s;
     s.B = B;
     s.Hq = Hq;
@@ -36,6 +39,8 @@ AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W) {
     s.rp1 = r >= L ? L + 1 : r + 1;  // r >= L: no position holds a gist
     s.W = W > L ? L : W;
     s.scale = 1.0f / sqrtf((float)D);
+    s.S = sinks > L ? L : sinks;
+    s.umode = window_mode == UNIGIST_WINDOW_UNITS;
     s.Lq = L;
     s.qpos0 = 0;
     s.kv_rows = L;
@@ -61,16 +66,22 @@ extern "C" const char* unigist_status_str(unigist_status s) {
 extern "C" void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn) {
     (void)D;
     if (Bm) *Bm = dt == UNIGIST_BF16 ? 128 : 64;
-    if (Bn) *Bn = dt == UNIGIST_BF16 ? 64 : 1;
+    if (Bn) *Bn = dt == UNIGIST_BF16 ? 32 : 1;
 }
 
 extern "C" unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                                            int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
                                            void* hip_stream) {
-    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt);
+    return unigist_attn_fwd_ex(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, 0, UNIGIST_WINDOW_SLIDING, dt, hip_stream);
+}
+
+extern "C" unigist_status unigist_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, float* lse,
+                                              int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                              int window_mode, unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt, sinks, window_mode);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
-    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e;
     if (dt == UNIGIST_BF16 && !plain_alu_forced())
@@ -82,8 +93,13 @@ extern "C" unigist_status unigist_attn_fwd(const void* q, const void* k, const v
 
 extern "C" size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
                                              unigist_dtype dt) {
-    if (check_attn(B, Hq, Hkv, L, D, r, W, dt) != UNIGIST_OK) return 0;
-    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    return unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, 0, UNIGIST_WINDOW_SLIDING, dt);
+}
+
+extern "C" size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                                int window_mode, unigist_dtype dt) {
+    if (check_attn(B, Hq, Hkv, L, D, r, W, dt, sinks, window_mode) != UNIGIST_OK) return 0;
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
     size_t delta = align256((size_t)B * Hq * L * sizeof(float));
     size_t mfma = dt == UNIGIST_BF16 ? bwd_mfma_workspace(s) : 0;
     return delta > mfma ? delta : mfma;
@@ -94,13 +110,23 @@ extern "C" unigist_status unigist_attn_bwd_stages(const void* q, const void* k, 
                                                   int B, int Hq, int Hkv, int L, int D, int r, int W,
                                                   unigist_dtype dt, void* workspace, size_t workspace_bytes,
                                                   unsigned stages, void* hip_stream) {
-    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt);
+    return unigist_attn_bwd_ex(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, 0,
+                               UNIGIST_WINDOW_SLIDING, dt, workspace, workspace_bytes, stages, hip_stream);
+}
+
+extern "C" unigist_status unigist_attn_bwd_ex(const void* q, const void* k, const void* v, const void* out,
+                                              const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                              int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                              int window_mode, unigist_dtype dt, void* workspace,
+                                              size_t workspace_bytes, unsigned stages, void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt, sinks, window_mode);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
     if (stages == 0 || (stages & ~(unsigned)UNIGIST_BWD_ALL)) return UNIGIST_EINVAL;
-    if (workspace_bytes < unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, dt)) return UNIGIST_EINVAL;
+    if (workspace_bytes < unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt))
+        return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
-    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W);
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e;
     if (dt == UNIGIST_BF16 && !plain_alu_forced()) {

@@ -14,8 +14,8 @@
 //                           epilogue adds the reduced gist-phase sums to the gist rows and writes dK, dV
 //   5. dq_kernel            one workgroup per 128-query tile, same tile walk as the forward
 // Every (query, key) pair is handled by exactly one of the two dkdv phases: a query chunk c (64 rows) sees
-// the gists at positions < far(c) = floor(max(0, 64c - W + 1) / 128) * 128 in the gist phase and every key
-// >= far(c) in the window phase.
+// the sinks and gists at positions < far(c) = floor(win_lo(64c) / 128) * 128 in the gist phase (win_lo = first
+// position of a row's local window) and every key >= far(c) in the window phase.
 //
 // dkdv: a wave owns 32 keys (one lane = one key), K and V fragments stay in registers, Q / dO chunks are
 // staged in LDS and read both row-wise (S = Q K^T, dP = dO V^T) and through transposing LDS reads
@@ -43,23 +43,47 @@ struct BwdPlan {
     size_t off_lse2, off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
 };
 
-__host__ __device__ inline int far_of_chunk(int c, int W) {
-    int lo = c * MQ - W + 1;
-    if (lo < 0) lo = 0;
-    return (lo / BNK) * BNK;
-}
+// A query chunk c (MQ rows from 64 c) reaches the always-visible positions (sinks, gists) left of far(c) in the
+// gist phase and everything from far(c) on in the window phase.  far is a multiple of BNK, non-decreasing in c.
+__host__ __device__ inline int far_of_chunk(const AttnShape& s, int c) { return (win_lo(s, c * MQ) / BNK) * BNK; }
+__host__ __device__ inline int nfar_of_chunk(const AttnShape& s, int c) { return count_always(s, far_of_chunk(s, c)); }
 
-// first chunk whose gist phase reaches into compact gist tile gt
-__host__ __device__ inline int first_chunk_of_gtile(int gt, int rp1, int W) {
-    const long long y = (long long)(BNK * gt + 1) * rp1;       // far(c) must be >= y
-    const long long x = (y + BNK - 1) / BNK * BNK;             // ... and is a multiple of BNK
-    return (int)((x + W - 1 + MQ - 1) / MQ);
+// first chunk in [0, NC] whose gist phase holds more than x entries (NC if none).  The x-th entry of the compact
+// list sits at position p, so the condition is far(c) > p; far is monotone in c and the search needs no division
+// in the sliding mode.
+__host__ __device__ inline int first_chunk_with_more_far(const AttnShape& s, int NC, int x) {
+    const int p = pos_of_always(s, x);
+    if (!s.umode) {  // win_lo(64 c) = 64 c - W + 1 has to reach the 128-boundary right of p
+        const long long c = ((long long)(p / BNK + 1) * BNK + s.W - 1 + MQ - 1) / MQ;
+        return c < NC ? (int)c : NC;
+    }
+    int lo = 0, hi = NC;  // answer in [lo, hi]
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (far_of_chunk(s, mid) > p) hi = mid;
+        else lo = mid + 1;
+    }
+    return lo;
+}
+// last chunk in [c0, NC) whose window phase still starts at or before position j0 (far <= j0); requires far(c0) <= j0
+__host__ __device__ inline int last_chunk_with_far_le(const AttnShape& s, int NC, int c0, int j0) {
+    if (!s.umode) {  // win_lo(64 c) = 64 c - W + 1 has to stay left of j0 + 128
+        const long long c = ((long long)j0 + BNK + s.W - 2) / MQ;
+        return c < NC - 1 ? (int)c : NC - 1;
+    }
+    int lo = c0, hi = NC - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (far_of_chunk(s, mid) <= j0) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
 }
 
 BwdPlan make_plan(const AttnShape& s) {
     BwdPlan p;
     p.NC = (s.L + MQ - 1) / MQ;
-    const int nfar_max = far_of_chunk(p.NC - 1, s.W) / s.rp1;
+    const int nfar_max = nfar_of_chunk(s, p.NC - 1);
     p.n_gt = (nfar_max + BNK - 1) / BNK;
     p.segc = 32;  // 32 chunks x Hq/Hkv heads = 128 steps per workgroup: short enough to balance the last round
     while ((p.NC + p.segc - 1) / p.segc > 32) p.segc *= 2;
@@ -115,13 +139,20 @@ struct DkdvSmem {
     float delta[2][MQ];
 };
 
-template <int D, bool GIST>
+// GEN = false (here and in dq_kernel) is the layout without sinks and with the sliding window: the mask
+// helpers then fold to their short forms at compile time.
+template <int D, bool GIST, bool GEN>
 __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                     const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                     const bf16_t* __restrict__ dout, const float* __restrict__ delta,
                                                     bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
                                                     float* __restrict__ part, const float* __restrict__ comp,
-                                                    AttnShape s, BwdPlan pl) {
+                                                    AttnShape s_arg, BwdPlan pl) {
+    AttnShape s = s_arg;
+    if constexpr (!GEN) {
+        s.S = 0;
+        s.umode = 0;
+    }
     constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
     constexpr int RPI = 64 / CH;        // chunk rows covered by one direct-load instruction
     constexpr int IPW = MQ / RPI / 4;   // such instructions per wave, per matrix, per step
@@ -131,7 +162,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, h = lane >> 5;
-    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int L = s.L;
     const int G = s.Hq / s.Hkv;
     const float c = s.scale * kLog2e;
 
@@ -158,7 +189,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         // XCD then stream the same Q/dO chunks of the same head through its L2
         seg = pl.nseg - 1 - unit / pl.n_gt;
         tile = unit % pl.n_gt;
-        const int cf = first_chunk_of_gtile(tile, rp1, W);
+        const int cf = first_chunk_with_more_far(s, pl.NC, tile * BNK);
         c_lo = max(cf, seg * pl.segc);
         c_hi = min(pl.NC, (seg + 1) * pl.segc) - 1;
         if (c_lo > c_hi) return;  // this segment lies before the tile becomes visible (uniform exit)
@@ -166,18 +197,24 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         tile = unit;
         const int j0 = tile * BNK;
         c_lo = j0 / MQ;
-        c_hi = min((long long)pl.NC - 1, ((long long)j0 + BNK + W - 2) / MQ);
+        c_hi = last_chunk_with_far_le(s, pl.NC, c_lo, j0);
     }
     const int key0 = tile * BNK + 32 * w;      // first key (position, or compact gist index) of the wave
     const int key = key0 + c32;                // this lane's key
     int krow;                                  // row of K/V holding it
     if (GIST) {
-        const int gtot = L / rp1;              // >= 1 whenever a gist workgroup exists
-        krow = min(key, gtot - 1) * rp1 + rp1 - 1;
+        const int atot = count_always(s, L);   // sinks + gists, >= 1 whenever a gist workgroup exists
+        krow = pos_of_always(s, min(key, atot - 1));
     } else {
         krow = min(key, L - 1);
     }
-    const bool gist_lane = GIST ? true : ((key + 1) % rp1 == 0);
+    const bool gist_lane = GIST ? true : is_always(s, key);       // a sink or a gist: visible to every later row
+    // the key stays in the window for span_j more rows (W - 1 for every key in the sliding mode)
+    int span_j = 0;
+    if constexpr (!GIST && GEN) span_j = key < L ? win_hi(s, key) - key : 0;
+    // last row that has the wave's first key in its window (rows >= L are excluded separately)
+    int hi_w0 = 0;
+    if constexpr (!GIST && GEN) hi_w0 = win_hi(s, min(key0, L - 1));
 
     // ---- K, V fragments (B operands): lane holds K[key][16 ks + 8h .. +7]
     bf16x8 kf[KS], vf[KS];
@@ -242,7 +279,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         const int q0 = cc * MQ;
 
         int nfar = 0;
-        if (GIST) nfar = far_of_chunk(cc, W) / rp1;  // compact gists visible to this chunk: index < nfar
+        if (GIST) nfar = nfar_of_chunk(s, cc);  // compact entries visible to this chunk: index < nfar
 
 #pragma unroll 1
         for (int qb = 0; qb < MQ / 32; ++qb) {
@@ -259,7 +296,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             // ---- P and dS
             bool masked;
             if (GIST) masked = key0 + 31 >= nfar || qb0 + 31 >= L;
-            else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < W && qb0 + 31 < L);
+            else if constexpr (GEN) masked = !(key0 + 31 <= qb0 && qb0 + 31 <= hi_w0 && qb0 + 31 < L);
+            else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < s.W && qb0 + 31 < L);
             const int d0 = qb0 + 4 * h - key;  // distance of the lane's first query to its key
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
@@ -276,7 +314,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                             ok = key < nfar && qb0 + 4 * h + off < L;
                         } else {
                             const int dist = d0 + off;  // i - j
-                            ok = ((unsigned)dist < (unsigned)W || (gist_lane && dist >= 0)) && qb0 + 4 * h + off < L;
+                            const bool in_win = GEN ? (unsigned)dist <= (unsigned)span_j : (unsigned)dist < (unsigned)s.W;
+                            ok = (in_win || (gist_lane && dist >= 0)) && qb0 + 4 * h + off < L;
                         }
                         p = ok ? p : 0.f;
                     }
@@ -327,7 +366,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     } else {
         if (gist_lane && pl.n_gt > 0) {
             // add what the gist phase collected for this row (zero if no chunk saw it from afar)
-            const int gi = (key + 1) / rp1 - 1;
+            const int gi = count_always(s, key);  // its index in the compact list of sinks and gists
             const int gt = gi / BNK;
             if (gt < pl.n_gt && key < L) {
                 const float* cp = comp + (((size_t)b * s.Hkv + hk) * pl.n_gt + gt) * (2 * D * BNK) + gi % BNK;
@@ -371,14 +410,14 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 
 // ------------------------------------------------------------------ 3. sum the segments of each gist tile
 __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict__ part, float* __restrict__ comp,
-                                                        int n_gt, int nseg, int segc, int NC, int rp1, int W,
+                                                        int n_gt, int nseg, int segc, int NC, AttnShape s,
                                                         int per_tile) {
     // grid: x = slices of a tile's 2*D*BNK floats, y = tile, z = (b, hk)
     const int gt = blockIdx.y;
     const size_t t = (size_t)blockIdx.z * n_gt + gt;
     const int idx = blockIdx.x * NT + threadIdx.x;
     if (idx >= per_tile) return;
-    const int cf = first_chunk_of_gtile(gt, rp1, W);
+    const int cf = first_chunk_with_more_far(s, NC, gt * BNK);
     float acc = 0.f;
     if (cf < NC)
         for (int sg = cf / segc; sg < nseg; ++sg) acc += part[(t * nseg + sg) * per_tile + idx];
@@ -393,11 +432,16 @@ struct DqSmem {
     char v[2][BNQ * D * 2];
 };
 
-template <int D>
+template <int D, bool GEN>
 __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                   const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ delta,
-                                                  bf16_t* __restrict__ dq, AttnShape s, int nq) {
+                                                  bf16_t* __restrict__ dq, AttnShape s_arg, int nq) {
+    AttnShape s = s_arg;
+    if constexpr (!GEN) {
+        s.S = 0;
+        s.umode = 0;
+    }
     constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
     constexpr int RPI = 64 / CH;
     constexpr int IPW = BNQ / RPI / 4;
@@ -421,7 +465,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         qt = nq - 1 - rest / NP;
     }
     const int b = pr / s.Hkv, hk = pr % s.Hkv, hq = hk * G + g;
-    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int L = s.L, rp1 = s.rp1;
     const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
     const int qrow = i0 + 32 * w + c32, qrow_ld = min(qrow, L - 1), wrow0 = i0 + 32 * w;
     const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * L * D);
@@ -446,12 +490,15 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[db] = zero16();
 
-    const int lo = max(0, i0 - W + 1);
-    const int wfirst = lo / BNQ;
-    const int nfar = (wfirst * BNQ) / rp1;
+    const int lo = win_lo(s, i0);
+    const int wstart = (lo / BNQ) * BNQ;          // first position of the window phase
+    const int nfar = count_always(s, wstart);      // sinks and gists strictly left of it
     const int ngt = (nfar + BNQ - 1) / BNQ;
-    const int nwin = i1 / BNQ - wfirst + 1;
+    const int nwin = (i1 - wstart) / BNQ + 1;
     const int ntiles = ngt + nwin;
+    const int span_q = qrow - win_lo(s, qrow);     // this lane's window reaches span_q positions back
+    const int lo_wlast = win_lo(s, wrow0 + 31);    // window start of the wave's last row
+    const int S = s.S;
 
     // ---- staging (same scheme as the forward kernel)
     const int lrow = lane / CH;
@@ -459,16 +506,18 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     int choff[IPW];
 #pragma unroll
     for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
-    const int grow_max = (nfar - 1) * rp1 + rp1 - 1;
     auto issue = [&](int it, int buf) {
         const bool gphase = it < ngt;
-        const int mul = gphase ? rp1 : 1;
-        const int add = gphase ? it * BNQ * rp1 + rp1 - 1 : (wfirst + it - ngt) * BNQ;
-        const int lim = gphase ? grow_max : L - 1;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int rr = (wv * IPW + i) * RPI + lrow;
-            const int row = min(rr * mul + add, lim);
+            int row;
+            if (gphase) {  // the (it * BNQ + rr)-th always-visible position, clamped to the last far one
+                const int c = min(it * BNQ + rr, nfar - 1);
+                row = c < S ? c : S + (c - S) * rp1 + rp1 - 1;
+            } else {
+                row = min(wstart + (it - ngt) * BNQ + rr, L - 1);
+            }
             const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
@@ -486,7 +535,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const char* kt = sm.k[BUF];
         const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
-        const int j0 = gist_tile ? it * BNQ : (wfirst + it - ngt) * BNQ;
+        const int j0 = gist_tile ? it * BNQ : wstart + (it - ngt) * BNQ;
         if (!gist_tile && j0 > wrow0 + 31) return;
 
         bool masked;
@@ -494,8 +543,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         if (gist_tile) {
             masked = j0 + BNQ > nfar;
         } else {
-            masked = !(j0 + BNQ - 1 <= wrow0 && wrow0 + 31 - j0 < W);
-            if (masked) gm = __builtin_amdgcn_ballot_w64((j0 + lane + 1) % rp1 == 0) >> (4 * h);
+            masked = !(j0 + BNQ - 1 <= wrow0 && j0 >= lo_wlast);
+            if (masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane)) >> (4 * h);
         }
         const int lim = nfar - j0 - 4 * h;
         const int d0 = qrow - (j0 + 4 * h);
@@ -519,7 +568,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
                         ok = off < lim;
                     } else {
                         const int dist = d0 - off;
-                        ok = (unsigned)dist < (unsigned)W || (dist >= 0 && ((gm >> off) & 1ull));
+                        ok = (unsigned)dist <= (unsigned)span_q || (dist >= 0 && ((gm >> off) & 1ull));
                     }
                     p = ok ? p : 0.f;
                 }
@@ -569,6 +618,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
                       const bf16_t* dout, bf16_t* dq, bf16_t* dk, bf16_t* dv, char* ws, const AttnShape& s,
                       unsigned stages, hipStream_t st) {
     const BwdPlan pl = make_plan(s);
+    const bool gen = s.S != 0 || s.umode != 0;
     float* delta = (float*)ws;
     float* lse2 = (float*)(ws + pl.off_lse2);
     float* part = (float*)(ws + pl.off_part);
@@ -582,26 +632,29 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
-        dkdv_kernel<D, true><<<dim3((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B)), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part,
-                                                                                 comp, s, pl);
+        const dim3 grid((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B));
+        if (gen) dkdv_kernel<D, true, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
+        else dkdv_kernel<D, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_GIST_REDUCE)) {
         const int per_tile = 2 * D * BNK;
         gist_reduce_kernel<<<dim3((per_tile + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
-            part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s.rp1, s.W, per_tile);
+            part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s, per_tile);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & UNIGIST_BWD_DKDV_WINDOW) {
-        dkdv_kernel<D, false><<<dim3((unsigned)((long)((s.L + BNK - 1) / BNK) * s.Hkv * s.B)), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                      part, comp, s, pl);
+        const dim3 grid((unsigned)((long)((s.L + BNK - 1) / BNK) * s.Hkv * s.B));
+        if (gen) dkdv_kernel<D, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
+        else dkdv_kernel<D, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (!(stages & UNIGIST_BWD_DQ)) return hipSuccess;
     const int nq = (s.L + BMQ - 1) / BMQ;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
-    dq_kernel<D><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
+    if (gen) dq_kernel<D, true><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
+    else dq_kernel<D, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
     return hipGetLastError();
 }
 

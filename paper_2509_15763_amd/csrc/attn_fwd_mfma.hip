@@ -1,6 +1,7 @@
 // Forward kernel of gist-masked attention for gfx950: bf16 MFMA, fp32 online softmax.
 //
-// Mask (Sec. 4.1, Eq. 3): query i sees key j <= i iff j holds a gist or i - j < W.
+// Mask (Sec. 4.1, Eq. 3): query i sees key j <= i iff j holds a sink or a gist, or j lies inside the local
+// window of i (the W most recent positions, or the gist unit of i plus the W previous units).
 // Block skipping (Sec. 4.2) is done without moving any data: a query tile walks
 //   1. the compact list of gists left of its window (gist g sits at row (r+1)g + r of
 //      K/V, gathered by address arithmetic while staging the tile; all of them are
@@ -33,10 +34,17 @@ struct FwdSmem {
     char v[2][BN * D * 2];
 };
 
-template <int D>
+// GEN = false is the layout without sinks and with the sliding window: the mask helpers then fold to their
+// short forms at compile time.
+template <int D, bool GEN>
 __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
-                                                        float* __restrict__ lse, AttnShape s, int nq) {
+                                                        float* __restrict__ lse, AttnShape s_arg, int nq) {
+    AttnShape s = s_arg;
+    if constexpr (!GEN) {
+        s.S = 0;
+        s.umode = 0;
+    }
     constexpr int KS = D / 16;            // k-steps of the score MFMA
     constexpr int DB = D / 32;            // 32-row blocks of O^T
     constexpr int CH = D / 8;             // 16-byte chunks per row
@@ -71,7 +79,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
     // Positions are absolute; q/out/lse hold the rows qpos0 .. L-1, K/V hold ngb compact gist rows followed
     // by the positions s0 .. L-1 (training: everything from position 0, no compact rows).
-    const int L = s.L, W = s.W, rp1 = s.rp1;
+    const int L = s.L, rp1 = s.rp1;
     const int qpos0 = s.qpos0, s0 = s.s0, ngb = s.ngb;
     const int i0 = qpos0 + qt * BM;
     const int i1 = min(L, i0 + BM) - 1;
@@ -97,39 +105,40 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
 
     // ---- tile walk
-    const int lo = max(0, i0 - W + 1);
+    const int lo = win_lo(s, i0);                 // leftmost position inside any window of the tile
     const int wstart = max((lo / BN) * BN, s0);  // first position of the window phase
-    const int nfar = wstart / rp1;                // gists strictly left of the window phase
+    const int nfar = count_always(s, wstart);     // sinks and gists strictly left of the window phase
     const int ngt = (nfar + BN - 1) / BN;
+    const int span_q = qrow - win_lo(s, qrow);    // this lane's window reaches span_q positions back
+    const int lo_wlast = win_lo(s, wrow0 + 31);   // window start of the wave's last row
     const int nwin = (i1 - wstart) / BN + 1;
     const int ntiles = ngt + nwin;
 
     // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row.
-    // Per load slot the lane keeps the row it fetches in the first gist tile and in the first window
-    // tile; tile `it` is a fixed stride further, clamped to the last valid row of its phase.
     const int lrow = lane / CH;
     const int wv = __builtin_amdgcn_readfirstlane(w);
     int choff[IPW];  // byte offset of the lane's (swizzled) chunk inside its row, per load slot
 #pragma unroll
     for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
-    const int grow_max = (nfar - 1) * rp1 + rp1 - 1;  // last far gist (unused when nfar == 0)
+    const int S = s.S;
     const char* kbytes = (const char*)kb;
     const char* vbytes = (const char*)vb;
     auto issue = [&](int it, int buf) {
-        // position of tile row rr: gist phase (it * BN + rr) * rp1 + rp1 - 1, window phase wstart + (it - ngt) * BN + rr,
-        // i.e. rr * mul + add with wave-uniform mul and add, clamped to the last valid position of the phase.
-        // Its row in the buffer: position - s0 + ngb, except for the gists in front (gist g < ngb sits in row g).
+        // Tile row rr is, in the gist phase, the (it * BN + rr)-th always-visible position (a sink, or gist g at
+        // S + (r+1) g + r), clamped to the last far one; in the window phase position wstart + (it - ngt) * BN + rr,
+        // clamped to the last position.  Its row in the buffer: position - s0 + ngb, except for the entries in
+        // front (entry c < ngb sits in row c).
         const bool gphase = it < ngt;
-        const int mul = gphase ? rp1 : 1;
-        const int add = gphase ? it * BN * rp1 + rp1 - 1 : wstart + (it - ngt) * BN;
-        const int lim = gphase ? grow_max : L - 1;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int rr = (wv * IPW + i) * RPI + lrow;
-            int row = min(rr * mul + add, lim) - s0 + ngb;
+            int row;
             if (gphase) {
-                const int gi = min(it * BN + rr, nfar - 1);
-                if (gi < ngb) row = gi;
+                const int c = min(it * BN + rr, nfar - 1);
+                const int pos = c < S ? c : S + (c - S) * rp1 + rp1 - 1;
+                row = c < ngb ? c : pos - s0 + ngb;
+            } else {
+                row = min(wstart + (it - ngt) * BN + rr, L - 1) - s0 + ngb;
             }
             const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
@@ -184,10 +193,10 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
             }
         } else {
             // unmasked iff all keys are causal for the wave's first row and in the window of its last row
-            masked = !(j0 + BN - 1 <= wrow0 && wrow0 + 31 - j0 < W);
+            masked = !(j0 + BN - 1 <= wrow0 && j0 >= lo_wlast);
             if (masked) {
-                // bit t of gm: key j0 + 4h + t holds a gist.  One modulo per lane, shared by ballot.
-                const unsigned long long gbits = __builtin_amdgcn_ballot_w64((j0 + lane + 1) % rp1 == 0);
+                // bit t of gm: key j0 + 4h + t holds a sink or a gist.  One modulo per lane, shared by ballot.
+                const unsigned long long gbits = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
                 const unsigned long long gm = gbits >> (4 * h);
                 const int d0 = qrow - (j0 + 4 * h);  // distance to the lane's first key
 #pragma unroll
@@ -196,7 +205,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
                     for (int i = 0; i < 16; ++i) {
                         const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
                         const int dist = d0 - off;  // i - j
-                        const bool in_win = (unsigned)dist < (unsigned)W;
+                        const bool in_win = (unsigned)dist <= (unsigned)span_q;
                         const bool gist_ok = dist >= 0 && ((gm >> off) & 1ull);
                         if (!(in_win || gist_ok)) sa[kb2][i] = -INFINITY;
                     }
@@ -288,12 +297,13 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
     const int nq = (s.Lq + BM - 1) / BM;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
-    if (s.D == 64)
-        fwd_mfma_kernel<64><<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                 (bf16_t*)out, lse, s, nq);
-    else
-        fwd_mfma_kernel<128><<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                  (bf16_t*)out, lse, s, nq);
+    const bool gen = s.S != 0 || s.umode != 0;
+    auto go = [&](auto kern) {
+        kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
+                                                  s, nq);
+    };
+    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true>) : go(fwd_mfma_kernel<64, false>);
+    else gen ? go(fwd_mfma_kernel<128, true>) : go(fwd_mfma_kernel<128, false>);
     return hipGetLastError();
 }
 

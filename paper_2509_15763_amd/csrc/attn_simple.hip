@@ -20,8 +20,6 @@ __device__ __forceinline__ void load_row(const T* __restrict__ p, float (&x)[D])
     for (int d = 0; d < D; ++d) x[d] = Elem<T>::load(p + d);
 }
 
-__device__ __forceinline__ bool is_gist(int p, int rp1) { return (p + 1) % rp1 == 0; }
-
 // ---------------------------------------------------------------- forward
 template <typename T, int D>
 __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__ q, const T* __restrict__ k,
@@ -65,12 +63,13 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
         for (int d = 0; d < D; ++d) o[d] += p * Elem<T>::load(vr + d);
     };
 
-    // gists left of every window of this wave's rows, then the union of the windows
-    const int lo_wave = max(0, i_first - s.W + 1);
-    const int ng_wave = lo_wave / s.rp1;  // gists at positions < lo_wave
-    for (int g = 0; g < ng_wave; ++g) visit(g * s.rp1 + s.rp1 - 1);
+    // sinks and gists left of every window of this wave's rows, then the union of the windows
+    const int lo_wave = win_lo(s, i_first);
+    const int lo_i = win_lo(s, i);
+    const int na_wave = count_always(s, lo_wave);  // always-visible positions < lo_wave
+    for (int g = 0; g < na_wave; ++g) visit(pos_of_always(s, g));
     for (int j = lo_wave; j <= i_last; ++j) {
-        bool ok = j <= i && (is_gist(j, s.rp1) || i - j < s.W);
+        bool ok = j <= i && (is_always(s, j) || j >= lo_i);
         if (ok) visit(j);
     }
     if (live) {
@@ -129,11 +128,12 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
         for (int d = 0; d < D; ++d) acc[d] += ds * Elem<T>::load(kr + d);
     };
 
-    const int lo_wave = max(0, i_first - s.W + 1);
-    const int ng_wave = lo_wave / s.rp1;
-    for (int g = 0; g < ng_wave; ++g) visit(g * s.rp1 + s.rp1 - 1);
+    const int lo_wave = win_lo(s, i_first);
+    const int lo_i = win_lo(s, i);
+    const int na_wave = count_always(s, lo_wave);
+    for (int g = 0; g < na_wave; ++g) visit(pos_of_always(s, g));
     for (int j = lo_wave; j <= i_last; ++j) {
-        bool ok = j <= i && (is_gist(j, s.rp1) || i - j < s.W);
+        bool ok = j <= i && (is_always(s, j) || j >= lo_i);
         if (ok) visit(j);
     }
     if (live) {
@@ -163,11 +163,12 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
         ks[d][lane] = Elem<T>::load(k + koff + d) * s.scale;
         vs[d][lane] = Elem<T>::load(v + koff + d);
     }
-    const bool gist_j = is_gist(j, s.rp1);
-    // does any key of this block hold a gist?  then later rows without bound see it
-    const int first_gist = ((j_first + s.rp1) / s.rp1) * s.rp1 - 1;  // first gist position >= j_first
-    const bool any_gist = first_gist <= j_last;
-    const int i_end = any_gist ? s.L - 1 : min(s.L - 1, j_last + s.W - 1);
+    const bool always_j = is_always(s, j);
+    const int hi_j = win_hi(s, j);
+    // does any key of this block hold a sink or a gist?  then every later row sees it
+    const int first_always = pos_of_always(s, count_always(s, j_first));  // first always-visible position >= j_first
+    const bool any_always = first_always <= j_last;
+    const int i_end = any_always ? s.L - 1 : win_hi(s, j_last);
 
     float ak[D], av[D];
 #pragma unroll
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
         const int h = hk * group + g;
         const size_t base = ((size_t)b * s.Hq + h) * s.L;
         for (int i = j_first; i <= i_end; ++i) {
-            bool ok = j <= i && (gist_j || i - j < s.W);
+            bool ok = j <= i && (always_j || i <= hi_j);
             if (!ok) continue;
             const T* qr = q + (base + i) * D;
             const T* gr = dout + (base + i) * D;

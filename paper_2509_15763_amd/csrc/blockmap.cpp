@@ -17,14 +17,36 @@ namespace {
 inline int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
 inline int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
 
+// The rule of Sec. 4.1 (Eq. 3) as interval arithmetic: a key j <= i is visible to query i iff it is a sink
+// or a gist, or lo(i) <= j, where lo(i) is the first position of the local window of i.
+struct Rule {
+    int64_t L, rp1, W, S;
+    bool units;
+    int64_t lo(int64_t i) const {
+        if (!units) return imax(0, i - W + 1);
+        if (i < S) return i;
+        return S + imax(0, (i - S) / rp1 - W) * rp1;
+    }
+    // sinks and gists at positions < x
+    int64_t always_below(int64_t x) const { return x <= S ? x : S + (x - S) / rp1; }
+};
+
 }  // namespace
 
 extern "C" unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, int Bn, unigist_blockmap** out) {
-    if (!out || L < 1 || r < 1 || W < 1 || Bm < 1 || Bn < 1) return UNIGIST_EINVAL;
+    return unigist_blockmap_build_ex(L, r, W, 0, UNIGIST_WINDOW_SLIDING, Bm, Bn, out);
+}
+
+extern "C" unigist_status unigist_blockmap_build_ex(int L, int r, int W, int sinks, int window_mode, int Bm, int Bn,
+                                                    unigist_blockmap** out) {
+    if (!out || L < 1 || r < 1 || W < 1 || Bm < 1 || Bn < 1 || sinks < 0) return UNIGIST_EINVAL;
+    if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return UNIGIST_EINVAL;
     unigist_blockmap* m = (unigist_blockmap*)calloc(1, sizeof(unigist_blockmap));
     if (!m) return UNIGIST_EINVAL;
     const int64_t rp1 = (int64_t)r + 1;
-    const int64_t Wc = imin(W, L);
+    const Rule rule{L, rp1, imin(W, L), imin(sinks, L), window_mode == UNIGIST_WINDOW_UNITS};
+    m->sinks = sinks;
+    m->window_mode = window_mode;
     m->L = L;
     m->r = r;
     m->W = W;
@@ -32,7 +54,7 @@ extern "C" unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, in
     m->Bn = Bn;
     m->n_qtiles = (int)(((int64_t)L + Bm - 1) / Bm);
     m->n_ktiles = (int)(((int64_t)L + Bn - 1) / Bn);
-    m->n_gists = (int)((int64_t)L / rp1);
+    m->n_gists = (int)(imax(0, (int64_t)L - rule.S) / rp1);
     m->win_first = (int*)calloc(m->n_qtiles, sizeof(int));
     m->win_last = (int*)calloc(m->n_qtiles, sizeof(int));
     m->n_far_gists = (int*)calloc(m->n_qtiles, sizeof(int));
@@ -44,11 +66,11 @@ extern "C" unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, in
     for (int t = 0; t < m->n_qtiles; ++t) {
         const int64_t i0 = (int64_t)t * Bm;
         const int64_t i1 = imin(L, i0 + Bm) - 1;
-        const int64_t lo = imax(0, i0 - Wc + 1);  // leftmost position inside any window of the tile
+        const int64_t lo = rule.lo(i0);  // leftmost position inside any window of the tile (lo is monotone)
         const int64_t ks = (lo / Bn) * Bn;        // window phase starts at a key-tile boundary
         m->win_first[t] = (int)(ks / Bn);
         m->win_last[t] = (int)(i1 / Bn);
-        const int64_t far = ks / rp1;  // gists at positions < ks
+        const int64_t far = rule.always_below(ks);  // sinks and gists at positions < ks
         m->n_far_gists[t] = (int)far;
         if (far > max_far) max_far = far;
         int full = 0;
@@ -56,7 +78,7 @@ extern "C" unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, in
             const int64_t j0 = (int64_t)c * Bn, j1 = j0 + Bn - 1;
             // no mask needed iff every key is causal for the first row and inside the
             // window of the last row
-            if (j1 <= i0 && i1 - j0 < Wc) ++full;
+            if (j1 <= i0 && rule.lo(i1) <= j0) ++full;
         }
         m->n_full[t] = full;
         const int64_t nwin = m->win_last[t] - m->win_first[t] + 1;
@@ -83,9 +105,9 @@ extern "C" unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, in
         for (int g = 0; g < ngt; ++g) m->gist_qt_first[g] = t;
     }
 
-    // visible pairs: keys inside the window plus gists strictly left of it, per row
+    // visible pairs: keys inside the window plus sinks and gists strictly left of it, per row
     int64_t nv = 0;
-    for (int64_t i = 0; i < L; ++i) nv += imin(i + 1, Wc) + imax(0, i - Wc + 1) / rp1;
+    for (int64_t i = 0; i < L; ++i) nv += i - rule.lo(i) + 1 + rule.always_below(rule.lo(i));
     m->n_vis = nv;
     *out = m;
     return UNIGIST_OK;

@@ -49,8 +49,10 @@ template <> struct Elem<bf16_t> {
 struct AttnShape {
     int B, Hq, Hkv, L, D;
     int rp1;  // r + 1, clamped to L + 1 when there are no gists (so (p+1) % rp1 == 0 never holds)
-    int W;    // clamped to L
+    int W;    // window: positions (sliding) or previous gist units (unit-aligned); clamped to L
     float scale;
+    int S;      // sink tokens in front of the first gist unit (Sec. 4.1); always visible
+    int umode;  // 0: sliding window of W positions; 1: the unit holding the query plus the W previous units
     // Forward only: the query rows and the K/V rows may be a view of the L positions (chunk-wise prefill
     // over a compressed cache).  Training passes the identity view.
     int Lq;       // query rows held by q/out/lse per head
@@ -59,6 +61,34 @@ struct AttnShape {
     int s0;       // first position stored in the window region of K/V
     int ngb;      // rows in front of it: the gists at positions < s0, compact (gist g in row g)
 };
+
+// ---- the visibility rule of Sec. 4.1 (Eq. 3) in the closed forms the kernels use.  A key j <= i is visible
+// to query i iff it is "always visible" (a sink or a gist) or win_lo(i) <= j, equivalently i <= win_hi(j).
+// first position inside the window of query i: non-decreasing in i and <= i
+__host__ __device__ inline int win_lo(const AttnShape& s, int i) {
+    if (!s.umode) {
+        const int lo = i - s.W + 1;
+        return lo < 0 ? 0 : lo;
+    }
+    if (i < s.S) return i;  // a sink query is in no unit: the sinks it sees are always visible anyway
+    long long u = (long long)((i - s.S) / s.rp1) - s.W;
+    if (u < 0) u = 0;
+    return s.S + (int)(u * s.rp1);
+}
+// last query position that still has key j inside its window (clamped to L - 1): non-decreasing in j, >= j
+__host__ __device__ inline int win_hi(const AttnShape& s, int j) {
+    long long h;
+    if (!s.umode) h = (long long)j + s.W - 1;
+    else if (j < s.S) h = j;
+    else h = (long long)s.S + ((long long)((j - s.S) / s.rp1) + s.W + 1) * s.rp1 - 1;
+    return h > s.L - 1 ? s.L - 1 : (int)h;
+}
+__host__ __device__ inline bool is_always(const AttnShape& s, int p) { return p < s.S || (p - s.S + 1) % s.rp1 == 0; }
+// number of always-visible positions < x, and the position of the c-th of them
+__host__ __device__ inline int count_always(const AttnShape& s, int x) { return x <= s.S ? x : s.S + (x - s.S) / s.rp1; }
+__host__ __device__ inline int pos_of_always(const AttnShape& s, int c) {
+    return c < s.S ? c : s.S + (c - s.S) * s.rp1 + s.rp1 - 1;
+}
 
 // --- launchers implemented in the .hip files (all enqueue on `st`, return hipGetLastError) ---
 hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,

@@ -32,8 +32,8 @@ def rel_l2(a, b) -> float:
     return num / den if den > 0 else num
 
 
-def oracle_fwd_bwd(q, k, v, dout, r, W):
+def oracle_fwd_bwd(q, k, v, dout, r, W, **mask):
     qn, kn, vn, don = (to_np(t) for t in (q, k, v, dout))
-    out, lse = oracle.attn_fwd(qn, kn, vn, r, W)
-    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W)
+    out, lse = oracle.attn_fwd(qn, kn, vn, r, W, **mask)
+    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W, **mask)
     return out, lse, dq, dk, dv

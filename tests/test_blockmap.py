@@ -16,10 +16,29 @@ CASES = [
 ]
 
 
+# (sinks, unit-aligned window) variants of the layout of Sec. 4.1; W then counts previous gist units
+EX = [(0, False), (3, False), (5, True), (0, True), (70, True)]
+
+
+def _window_start(i, r, W, sinks, units):
+    if not units:
+        return max(0, i - W + 1)
+    if i < sinks:
+        return i
+    return sinks + max(0, (i - sinks) // (r + 1) - W) * (r + 1)
+
+
+@pytest.mark.parametrize("sinks,units", EX)
 @pytest.mark.parametrize("L,r,W,Bm,Bn", CASES)
-def test_coverage_is_exact(L, r, W, Bm, Bn):
-    m = u.unigist_blockmap_build(L, r, W, Bm, Bn)
-    M = oracle.mask_rows(np.arange(L), L, r, W)
+def test_coverage_is_exact(L, r, W, Bm, Bn, sinks, units):
+    if units:
+        W = max(1, W // (r + 1)) if r < L else W
+    if sinks == 0 and not units:
+        m = u.unigist_blockmap_build(L, r, W, Bm, Bn)
+    else:
+        m = u.unigist_blockmap_build_ex(L, r, W, sinks, int(units), Bm, Bn)
+    assert (m["sinks"], m["window_mode"]) == (sinks, int(units))
+    M = oracle.mask_rows(np.arange(L), L, r, W, sinks=sinks, units=units)
     cover = np.zeros((L, L), dtype=np.int32)
     live = masked = 0
     for t in range(m["n_qtiles"]):
@@ -32,16 +51,17 @@ def test_coverage_is_exact(L, r, W, Bm, Bn):
             sub = M[rows, cols]
             assert sub.any(), "a live window tile must hold a visible pair"
             cover[rows, cols] += sub
-            full = (c + 1) * Bn - 1 <= i0 and i1 - c * Bn < min(W, L)
+            full = (c + 1) * Bn - 1 <= i0 and _window_start(i1, r, min(W, L), sinks, units) <= c * Bn
             if full:
                 assert sub.all() and cols.stop - cols.start == Bn
                 nfull += 1
             live += 1
         assert nfull == m["n_full"][t]
         masked += (m["win_last"][t] - m["win_first"][t] + 1) - nfull
-        # gist phase: compact gists, all visible to all rows of the tile
+        # gist phase: the compact list (sinks, then gists), all visible to all rows of the tile
         nfar = m["n_far_gists"][t]
-        pos = np.arange(nfar) * (r + 1) + r
+        ns = min(sinks, nfar)
+        pos = np.concatenate([np.arange(ns), sinks + np.arange(nfar - ns) * (r + 1) + r]).astype(np.int64)
         assert (pos < m["win_first"][t] * Bn).all()
         assert M[rows][:, pos].all()
         cover[rows.start:rows.stop, pos] += 1
@@ -53,7 +73,7 @@ def test_coverage_is_exact(L, r, W, Bm, Bn):
     assert np.array_equal(cover, M.astype(np.int32))
     assert live == m["live_tiles"] and masked == m["masked_tiles"]
     assert m["n_vis"] == int(M.sum())
-    assert m["n_gists"] == (0 if r >= L else L // (r + 1))
+    assert m["n_gists"] == (0 if r >= L else max(0, L - sinks) // (r + 1))
     assert m["causal_tiles"] == sum(min(L, (t + 1) * Bm - 0) - 1 >= 0 and ((min(L, (t + 1) * Bm) - 1) // Bn + 1)
                                     for t in range(m["n_qtiles"]))
 
@@ -82,3 +102,6 @@ def test_invalid_arguments():
     for bad in [(0, 4, 4, 8, 8), (8, 0, 4, 8, 8), (8, 4, 0, 8, 8), (8, 4, 4, 0, 8), (8, 4, 4, 8, 0)]:
         with pytest.raises(u.UnigistError):
             u.unigist_blockmap_build(*bad)
+    for bad in [(8, 4, 4, -1, 0, 8, 8), (8, 4, 4, 0, 2, 8, 8), (8, 4, 4, 0, -1, 8, 8)]:
+        with pytest.raises(u.UnigistError):
+            u.unigist_blockmap_build_ex(*bad)
