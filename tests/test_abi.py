@@ -65,6 +65,20 @@ def test_attn_argument_validation(kw, want):
     assert u.unigist_attn_bwd_workspace(*shape) == 0
 
 
+def test_ex_argument_validation():
+    # B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt
+    ok = (1, 4, 2, 64, 64, 4, 8, 3, 1, 0)
+    assert u.unigist_attn_bwd_workspace_ex(*ok) > 0
+    assert u.unigist_attn_fwd_ex(None, None, None, None, None, *ok) == 1  # null tensors
+    for bad in [(1, 4, 2, 64, 64, 4, 8, -1, 1, 0), (1, 4, 2, 64, 64, 4, 8, 3, 2, 0), (1, 4, 2, 64, 64, 4, 8, 3, -1, 0)]:
+        assert u.unigist_attn_bwd_workspace_ex(*bad) == 0
+        assert u.unigist_attn_fwd_ex(FAKE, FAKE, FAKE, FAKE, FAKE, *bad) == 1
+        assert u.unigist_attn_bwd_ex(*([FAKE] * 9), *bad, FAKE, 1 << 40, 31) == 1
+    # the workspace depends on the layout only through the number of compact (sink + gist) tiles
+    assert u.unigist_attn_bwd_workspace_ex(1, 4, 2, 4096, 64, 4, 8, 0, 0, 0) == u.unigist_attn_bwd_workspace(
+        1, 4, 2, 4096, 64, 4, 8, 0)
+
+
 def test_decode_argument_validation():
     ok = dict(B=2, Hq=4, Hkv=2, Lk=100, D=128, dt=0)
     ws = u.unigist_decode_workspace(*ok.values())
