@@ -236,27 +236,43 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     // ---- staging of the Q / dO chunk: direct global->LDS loads
     const int nch = c_hi - c_lo + 1;
     const int nsteps = nch * G;
-    const int lrow = lane / CH;
-    int rrow[IPW], choff[IPW];  // chunk row and byte offset of the lane's (swizzled) 16-byte chunk, per load slot
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-        rrow[i] = (w * IPW + i) * RPI + lrow;
-        choff[i] = ((lane % CH) ^ swz<CH>(rrow[i])) * 16;
-    }
+    // Load slot i of wave w covers the chunk rows (w * IPW + i) * RPI + lane / CH.  The swizzle repeats every 8 rows and
+    // w * IPW * RPI is a multiple of 8, so the lane's byte offset inside the slot's rows takes only NLP different
+    // values; everything else of the address is wave-uniform or an immediate.
+    // They are recomputed from the lane id at every use: kept in registers across the step they would be
+    // spilled, and a reload from scratch waits on the same counter as the direct loads still in flight.
+    constexpr int NLP = RPI >= 8 ? 1 : 8 / RPI;
     auto issue = [&](int step, int buf) __attribute__((always_inline)) {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));  // opaque: keeps the address arithmetic below inside this call
+        const int lrow_ = ln / CH;
+        int lanepart[NLP];
+#pragma unroll
+        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz<CH>(i * RPI + lrow_)) << 4);
         const int g = step / nch, cc = c_lo + step % nch;
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform
         const char* qh = (const char*)(q + hb * D);
         const char* gh = (const char*)(dout + hb * D);
+        if (cc * MQ + MQ <= L) {  // the whole chunk exists (wave-uniform)
+            const size_t cb = (size_t)(cc * MQ + w * IPW * RPI) * ROWB;
 #pragma unroll
-        for (int i = 0; i < IPW; ++i) {
-            const int row = min(cc * MQ + rrow[i], L - 1);
-            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
-            g2l16(qh + off, &sm.q[buf][(w * IPW + i) * 1024]);
-            g2l16(gh + off, &sm.g[buf][(w * IPW + i) * 1024]);
+            for (int i = 0; i < IPW; ++i) {
+                const unsigned off = (unsigned)lanepart[i % NLP] + (unsigned)(i * RPI * ROWB);
+                g2l16(qh + cb + off, &sm.q[buf][(w * IPW + i) * 1024]);
+                g2l16(gh + cb + off, &sm.g[buf][(w * IPW + i) * 1024]);
+            }
+        } else {  // last chunk of a ragged sequence: rows past the end shadow the last row
+#pragma unroll
+            for (int i = 0; i < IPW; ++i) {
+                const int rr = (w * IPW + i) * RPI + lrow_;
+                const int row = min(cc * MQ + rr, L - 1);
+                const unsigned off = (unsigned)row * (unsigned)ROWB + (unsigned)(lanepart[i % NLP] - lrow_ * ROWB);
+                g2l16(qh + off, &sm.q[buf][(w * IPW + i) * 1024]);
+                g2l16(gh + off, &sm.g[buf][(w * IPW + i) * 1024]);
+            }
         }
         if (w < 2) {  // wave 0: the 64 rows' lse2, wave 1: their delta (one 4-byte direct load per lane)
-            const int row = min(cc * MQ + lane, L - 1);
+            const int row = min(cc * MQ + ln, L - 1);
             const float* src = (w == 0 ? lse2 : delta) + hb + row;
             float* dst = w == 0 ? sm.lse2[buf] : sm.delta[buf];
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
