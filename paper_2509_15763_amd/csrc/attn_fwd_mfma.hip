@@ -26,6 +26,7 @@ namespace {
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 32;   // keys per step
 constexpr int NT = 256;  // threads
+constexpr float kLazy = 8.f;  // slack of the softmax reference, in exp2 units
 
 template <int D>
 struct FwdSmem {
@@ -219,18 +220,23 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[kb2][i]);
         mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m, mx);
-        const float m_use = (masked && m_new == -INFINITY) ? 0.f : m_new;
-        const float mc = m_use * c;
-        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0ull) {
-            const float alpha = __builtin_amdgcn_exp2f(m * c - mc);  // m = -inf gives 0
+        // The reference m of the exponent only has to bound the scores from above within a fixed margin, not be
+        // their exact maximum: it is raised (and O, l rescaled) only when a row's maximum exceeds it by more than
+        // kLazy in exp2 units, so P <= 2^kLazy and, after the first tiles, almost no step rescales.  The result
+        // is the same quotient O / l.  A row that has seen nothing yet has m = -inf and grows on its first score;
+        // -inf - (-inf) is NaN and compares false.
+        const bool grow = (mx - m) * c > kLazy;
+        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+            const float m_new = grow ? mx : m;
+            const float alpha = grow ? __builtin_amdgcn_exp2f((m - m_new) * c) : 1.f;  // m = -inf gives 0
             l *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+            m = m_new;
         }
-        m = m_new;
+        const float mc = (m == -INFINITY ? 0.f : m) * c;  // rows with nothing visible so far: every P is exp2(-inf) = 0
 
         // P = exp2(c S - c m): summed in fp32 for the row sum (lse stays fp32-accurate), rounded to bf16
         // for the second MFMA
