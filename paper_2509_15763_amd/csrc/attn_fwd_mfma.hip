@@ -178,20 +178,16 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
             }
         }
 
-        // ---- mask.  Accumulator element i of block kb2 is key  j0 + 32 kb2 + 8 (i/4) + 4 h + i%4.
+        // ---- mask.  Accumulator element i of block kb2 is key  j0 + 32 kb2 + 8 (i/4) + 4 h + i%4; bit
+        // 8 (i/4) + i%4 of vis[kb2] says whether this lane's query sees it.  Visible sets are bit ranges
+        // (the tail of the compact list; the window) plus, in the window phase, the sinks and gists.
         bool masked;
+        unsigned vis[NKB];
+        auto below = [](int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; };  // bits 0 .. n-1
         if (gist_tile) {
             masked = j0 + BN > nfar;  // tail of the compact list
-            if (masked) {
-                const int lim = nfar - j0 - 4 * h;  // element visible iff its offset < lim
 #pragma unroll
-                for (int kb2 = 0; kb2 < NKB; ++kb2)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
-                        if (off >= lim) sa[kb2][i] = -INFINITY;
-                    }
-            }
+            for (int kb2 = 0; kb2 < NKB; ++kb2) vis[kb2] = below(nfar - j0 - 4 * h - 32 * kb2);
         } else {
             // unmasked iff all keys are causal for the wave's first row and in the window of its last row
             masked = !(j0 + BN - 1 <= wrow0 && j0 >= lo_wlast);
@@ -201,16 +197,19 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
                 const unsigned long long gm = gbits >> (4 * h);
                 const int d0 = qrow - (j0 + 4 * h);  // distance to the lane's first key
 #pragma unroll
-                for (int kb2 = 0; kb2 < NKB; ++kb2)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
-                        const int dist = d0 - off;  // i - j
-                        const bool in_win = (unsigned)dist <= (unsigned)span_q;
-                        const bool gist_ok = dist >= 0 && ((gm >> off) & 1ull);
-                        if (!(in_win || gist_ok)) sa[kb2][i] = -INFINITY;
-                    }
+                for (int kb2 = 0; kb2 < NKB; ++kb2) {
+                    const int d = d0 - 32 * kb2;  // offsets d - span_q .. d are in the window, offsets <= d causal
+                    const unsigned causal = below(d + 1);
+                    vis[kb2] = (causal & ~below(d - span_q)) | (causal & (unsigned)(gm >> (32 * kb2)));
+                }
             }
+        }
+        if (masked) {
+#pragma unroll
+            for (int kb2 = 0; kb2 < NKB; ++kb2)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[kb2][i] = -INFINITY;
         }
 
         // ---- online softmax (per query column = per lane, halves exchange once)
