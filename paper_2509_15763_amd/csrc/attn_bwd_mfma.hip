@@ -35,6 +35,9 @@ constexpr int BMQ = 128;  // query rows per dq workgroup
 constexpr int BNQ = 64;   // keys per dq step
 constexpr float kLog2e = 1.4426950408889634f;
 
+// bits 0 .. n-1 set (none for n <= 0, all for n >= 32)
+__device__ __forceinline__ unsigned below_bits(int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; }
+
 struct BwdPlan {
     int NC;      // query chunks of MQ rows
     int n_gt;    // compact gist tiles (BNK gists each) seen by some chunk
@@ -314,30 +317,37 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             if (GIST) masked = key0 + 31 >= nfar || qb0 + 31 >= L;
             else if constexpr (GEN) masked = !(key0 + 31 <= qb0 && qb0 + 31 <= hi_w0 && qb0 + 31 < L);
             else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < s.W && qb0 + 31 < L);
-            const int d0 = qb0 + 4 * h - key;  // distance of the lane's first query to its key
+            // bit 8 (i/4) + i%4 of vis: does query qb0 + 4h + 8 (i/4) + i%4 see this lane's key?  The visible
+            // queries are a range of offsets (those inside the sequence; for a raw key those that still have it
+            // in their window), cut at the diagonal.
+            unsigned vis = ~0u;
+            if (masked) {
+                const unsigned inside = below_bits(L - qb0 - 4 * h);
+                if (GIST) {
+                    vis = key < nfar ? inside : 0u;
+                } else {
+                    const int d0 = qb0 + 4 * h - key;  // distance i - j of the lane's first query to its key
+                    const int span = GEN ? span_j : s.W - 1;
+                    const unsigned win = gist_lane ? ~0u : below_bits(span - d0 + 1);
+                    vis = inside & win & ~below_bits(-d0);
+                }
+            }
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 l4 = *(const f32x4*)(&sm.lse2[BUF][32 * qb + 8 * i4 + 4 * h]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) sa[4 * i4 + t] = __builtin_amdgcn_exp2f(fmaf(sa[4 * i4 + t], c, -l4[t]));
+            }
+            if (masked) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (!((vis >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
+            }
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 8 * i4 + 4 * h]);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int i = 4 * i4 + t;
-                    float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -l4[t]));
-                    if (masked) {
-                        const int off = 8 * i4 + t;
-                        bool ok;
-                        if (GIST) {
-                            ok = key < nfar && qb0 + 4 * h + off < L;
-                        } else {
-                            const int dist = d0 + off;  // i - j
-                            const bool in_win = GEN ? (unsigned)dist <= (unsigned)span_j : (unsigned)dist < (unsigned)s.W;
-                            ok = (in_win || (gist_lane && dist >= 0)) && qb0 + 4 * h + off < L;
-                        }
-                        p = ok ? p : 0.f;
-                    }
-                    sa[i] = p;
-                    dp[i] = p * (dp[i] - d4[t]);
-                }
+                for (int t = 0; t < 4; ++t) dp[4 * i4 + t] = sa[4 * i4 + t] * (dp[4 * i4 + t] - d4[t]);
             }
             // ---- dV^T += dO^T P,  dK^T += Q^T dS   (16 queries per MFMA)
 #pragma unroll
@@ -554,16 +564,27 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const int j0 = gist_tile ? it * BNQ : wstart + (it - ngt) * BNQ;
         if (!gist_tile && j0 > wrow0 + 31) return;
 
+        // bit 8 (i/4) + i%4 of vis[kb2]: does this lane's query see key j0 + 32 kb2 + 4h + 8 (i/4) + i%4?  Visible
+        // sets are bit ranges (the tail of the compact list; the window) plus, in the window phase, sinks and gists.
         bool masked;
-        unsigned long long gm = 0ull;
+        unsigned vis[2] = {~0u, ~0u};
         if (gist_tile) {
             masked = j0 + BNQ > nfar;
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2) vis[kb2] = below_bits(nfar - j0 - 4 * h - 32 * kb2);
         } else {
             masked = !(j0 + BNQ - 1 <= wrow0 && j0 >= lo_wlast);
-            if (masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane)) >> (4 * h);
+            if (masked) {
+                const unsigned long long gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane)) >> (4 * h);
+                const int d0 = qrow - (j0 + 4 * h);
+#pragma unroll
+                for (int kb2 = 0; kb2 < 2; ++kb2) {
+                    const int d = d0 - 32 * kb2;  // offsets d - span_q .. d are in the window, offsets <= d causal
+                    const unsigned causal = below_bits(d + 1);
+                    vis[kb2] = causal & (~below_bits(d - span_q) | (unsigned)(gm >> (32 * kb2)));
+                }
+            }
         }
-        const int lim = nfar - j0 - 4 * h;
-        const int d0 = qrow - (j0 + 4 * h);
 
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
@@ -575,21 +596,14 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
                 dp = mfma32(*(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks]), gf[ks], dp);
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -ls));
-                if (masked) {
-                    const int off = 32 * kb2 + 8 * (i / 4) + (i % 4);
-                    bool ok;
-                    if (gist_tile) {
-                        ok = off < lim;
-                    } else {
-                        const int dist = d0 - off;
-                        ok = (unsigned)dist <= (unsigned)span_q || (dist >= 0 && ((gm >> off) & 1ull));
-                    }
-                    p = ok ? p : 0.f;
-                }
-                dp[i] = p * (dp[i] - dl);
+            for (int i = 0; i < 16; ++i) sa[i] = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -ls));
+            if (masked) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
             }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dp[i] = sa[i] * (dp[i] - dl);
             // dQ^T += K^T dS^T
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
