@@ -282,12 +282,12 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                                              (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
         }
     };
-    int roff[KS];  // row-wise read of chunk row c32 (+32 qb), 16-byte chunk 2 ks + h
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) roff[ks] = swz_off<CH>(c32, 2 * ks + h);
-    int toff[DB];  // transposing reads, 32-column block db
-#pragma unroll
-    for (int db = 0; db < DB; ++db) toff[db] = tr_lane_off<CH>(db);
+    // Per-lane LDS offsets.  Row-wise read of chunk row c32 (+32 qb), 16-byte chunk 2 ks + h: the swizzle XORs
+    // the chunk bits, so the offset for k-step ks is roff0 ^ (ks << 5); likewise the transposing read of the
+    // 32-column block db sits at toff0 ^ (db << 6).  Only the two bases stay live across the kernel (registers
+    // are what this kernel is short of); the XORs are redone per query block.
+    const int roff0 = swz_off<CH>(c32, h);
+    const int toff0 = tr_lane_off<CH>(0);
 
     // one step on LDS stage BUF (a compile-time constant: LDS addresses = lane register + immediate)
     auto do_step = [&](auto bufc, int step) __attribute__((always_inline)) {
@@ -305,12 +305,16 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             const int qb0 = q0 + 32 * qb;  // first query row of the block
             if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
 
+            int rb = roff0, tb = toff0;
+            asm volatile("" : "+v"(rb), "+v"(tb));  // opaque: the derived offsets are not hoisted out of the loop
+
             // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
             f32x16 sa = zero16(), dp = zero16();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                sa = mfma32(*(const bf16x8*)(qt + 32 * qb * ROWB + roff[ks]), kf[ks], sa);
-                dp = mfma32(*(const bf16x8*)(gt + 32 * qb * ROWB + roff[ks]), vf[ks], dp);
+                const int ro = rb ^ (ks << 5);
+                sa = mfma32(*(const bf16x8*)(qt + 32 * qb * ROWB + ro), kf[ks], sa);
+                dp = mfma32(*(const bf16x8*)(gt + 32 * qb * ROWB + ro), vf[ks], dp);
             }
             // ---- P and dS
             bool masked;
@@ -356,8 +360,9 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 const bf16x8 sb = pack8(dp, 8 * kk);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    avT[db] = mfma32(tr16_frag_at<CH>(gt + toff[db] + 32 * qb * ROWB, 16 * kk), pb, avT[db]);
-                    akT[db] = mfma32(tr16_frag_at<CH>(qt + toff[db] + 32 * qb * ROWB, 16 * kk), sb, akT[db]);
+                    const int to = tb ^ (db << 6);
+                    avT[db] = mfma32(tr16_frag_at<CH>(gt + to + 32 * qb * ROWB, 16 * kk), pb, avT[db]);
+                    akT[db] = mfma32(tr16_frag_at<CH>(qt + to + 32 * qb * ROWB, 16 * kk), sb, akT[db]);
                 }
             }
         }
