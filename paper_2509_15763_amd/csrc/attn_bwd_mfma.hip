@@ -309,12 +309,31 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             asm volatile("" : "+v"(rb), "+v"(tb));  // opaque: the derived offsets are not hoisted out of the loop
 
             // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
+            // The fragment reads are issued PF k-steps ahead of the MFMAs that consume them; the scheduling
+            // barriers keep the compiler from sinking them back to just before their use, where every MFMA
+            // would wait for a full LDS round trip.
             f32x16 sa = zero16(), dp = zero16();
+            {
+                constexpr int PF = 2;
+                bf16x8 fq[KS], fg[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int ro = rb ^ (ks << 5);
-                sa = mfma32(*(const bf16x8*)(qt + 32 * qb * ROWB + ro), kf[ks], sa);
-                dp = mfma32(*(const bf16x8*)(gt + 32 * qb * ROWB + ro), vf[ks], dp);
+                for (int ks = 0; ks < PF; ++ks) {
+                    const int ro = rb ^ (ks << 5);
+                    fq[ks] = *(const bf16x8*)(qt + 32 * qb * ROWB + ro);
+                    fg[ks] = *(const bf16x8*)(gt + 32 * qb * ROWB + ro);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (ks + PF < KS) {
+                        const int ro = rb ^ ((ks + PF) << 5);
+                        fq[ks + PF] = *(const bf16x8*)(qt + 32 * qb * ROWB + ro);
+                        fg[ks + PF] = *(const bf16x8*)(gt + 32 * qb * ROWB + ro);
+                    }
+                    sa = mfma32(fq[ks], kf[ks], sa);
+                    dp = mfma32(fg[ks], vf[ks], dp);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             // ---- P and dS
             bool masked;
@@ -354,15 +373,29 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 for (int t = 0; t < 4; ++t) dp[4 * i4 + t] = sa[4 * i4 + t] * (dp[4 * i4 + t] - d4[t]);
             }
             // ---- dV^T += dO^T P,  dK^T += Q^T dS   (16 queries per MFMA)
+            bf16x8 pb[2], sb[2];
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 pb = pack8(sa, 8 * kk);
-                const bf16x8 sb = pack8(dp, 8 * kk);
+                pb[kk] = pack8(sa, 8 * kk);
+                sb[kk] = pack8(dp, 8 * kk);
+            }
+            {
+                constexpr int N = 2 * DB, PF = 2;  // N (kk, db) pairs, each one dO^T and one Q^T fragment
+                bf16x8 fg[N], fq[N];
+                auto fetch = [&](int n) __attribute__((always_inline)) {
+                    const int to = tb ^ ((n % DB) << 6);
+                    fg[n] = tr16_frag_at<CH>(gt + to + 32 * qb * ROWB, 16 * (n / DB));
+                    fq[n] = tr16_frag_at<CH>(qt + to + 32 * qb * ROWB, 16 * (n / DB));
+                };
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int to = tb ^ (db << 6);
-                    avT[db] = mfma32(tr16_frag_at<CH>(gt + to + 32 * qb * ROWB, 16 * kk), pb, avT[db]);
-                    akT[db] = mfma32(tr16_frag_at<CH>(qt + to + 32 * qb * ROWB, 16 * kk), sb, akT[db]);
+                for (int n = 0; n < PF; ++n) fetch(n);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int n = 0; n < N; ++n) {
+                    if (n + PF < N) fetch(n + PF);
+                    avT[n % DB] = mfma32(fg[n], pb[n / DB], avT[n % DB]);
+                    akT[n % DB] = mfma32(fq[n], sb[n / DB], akT[n % DB]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
