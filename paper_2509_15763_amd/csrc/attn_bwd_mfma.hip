@@ -380,7 +380,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 sb[kk] = pack8(dp, 8 * kk);
             }
             {
-                constexpr int N = 2 * DB, PF = 2;  // N (kk, db) pairs, each one dO^T and one Q^T fragment
+                constexpr int N = 2 * DB, PF = 3;  // N (kk, db) pairs, each one dO^T and one Q^T fragment
                 bf16x8 fg[N], fq[N];
                 auto fetch = [&](int n) __attribute__((always_inline)) {
                     const int to = tb ^ ((n % DB) << 6);
