@@ -33,6 +33,7 @@ constexpr int BNK = 128;  // keys per dkdv workgroup
 constexpr int MQ = 64;    // query rows per dkdv step
 constexpr int BMQ = 128;  // query rows per dq workgroup
 constexpr int BNQ = 64;   // keys per dq step
+constexpr int PFS = 2, PFT = 3;  // dq: LDS fragment reads issued this many MFMA groups ahead (S/dP phase, dQ phase)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // bits 0 .. n-1 set (none for n <= 0, all for n >= 32)
@@ -627,11 +628,26 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             // S^T, dP^T for 32 keys: register i is key j0 + 32 kb2 + 8 (i/4) + 4h + i%4, lane = query
+            // (fragment reads run PFS k-steps ahead of their MFMAs; the scheduling barriers keep them there)
             f32x16 sa = zero16(), dp = zero16();
+            {
+                bf16x8 fk[KS], fv[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                sa = mfma32(*(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks]), qf[ks], sa);
-                dp = mfma32(*(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks]), gf[ks], dp);
+                for (int ks = 0; ks < PFS; ++ks) {
+                    fk[ks] = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks]);
+                    fv[ks] = *(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (ks + PFS < KS) {
+                        fk[ks + PFS] = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks + PFS]);
+                        fv[ks + PFS] = *(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks + PFS]);
+                    }
+                    sa = mfma32(fk[ks], qf[ks], sa);
+                    dp = mfma32(fv[ks], gf[ks], dp);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) sa[i] = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -ls));
@@ -643,12 +659,21 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
 #pragma unroll
             for (int i = 0; i < 16; ++i) dp[i] = sa[i] * (dp[i] - dl);
             // dQ^T += K^T dS^T
+            {
+                constexpr int N = 2 * DB;  // (kk, db) pairs
+                bf16x8 sb[2], ft[N];
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 sb = pack8(dp, 8 * kk);
+                for (int kk = 0; kk < 2; ++kk) sb[kk] = pack8(dp, 8 * kk);
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    acc[db] = mfma32(tr16_frag_at<CH>(kt + toff[db], 32 * kb2 + 16 * kk), sb, acc[db]);
+                for (int n = 0; n < PFT; ++n) ft[n] = tr16_frag_at<CH>(kt + toff[n % DB], 32 * kb2 + 16 * (n / DB));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int n = 0; n < N; ++n) {
+                    if (n + PFT < N)
+                        ft[n + PFT] = tr16_frag_at<CH>(kt + toff[(n + PFT) % DB], 32 * kb2 + 16 * ((n + PFT) / DB));
+                    acc[n % DB] = mfma32(ft[n], sb[n / DB], acc[n % DB]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
     };
