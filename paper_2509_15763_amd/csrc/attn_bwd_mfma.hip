@@ -306,7 +306,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             const int qb0 = q0 + 32 * qb;  // first query row of the block
             if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
 
-            int rb = roff0, tb = toff0;
+            // offsets of this query block; the XORs below touch bits 5..7 only, the block offset bits >= 13
+            int rb = roff0 + 32 * qb * ROWB, tb = toff0 + 32 * qb * ROWB;
             asm volatile("" : "+v"(rb), "+v"(tb));  // opaque: the derived offsets are not hoisted out of the loop
 
             // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
@@ -320,16 +321,16 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 #pragma unroll
                 for (int ks = 0; ks < PF; ++ks) {
                     const int ro = rb ^ (ks << 5);
-                    fq[ks] = *(const bf16x8*)(qt + 32 * qb * ROWB + ro);
-                    fg[ks] = *(const bf16x8*)(gt + 32 * qb * ROWB + ro);
+                    fq[ks] = *(const bf16x8*)(qt + ro);
+                    fg[ks] = *(const bf16x8*)(gt + ro);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     if (ks + PF < KS) {
                         const int ro = rb ^ ((ks + PF) << 5);
-                        fq[ks + PF] = *(const bf16x8*)(qt + 32 * qb * ROWB + ro);
-                        fg[ks + PF] = *(const bf16x8*)(gt + 32 * qb * ROWB + ro);
+                        fq[ks + PF] = *(const bf16x8*)(qt + ro);
+                        fg[ks + PF] = *(const bf16x8*)(gt + ro);
                     }
                     sa = mfma32(fq[ks], kf[ks], sa);
                     dp = mfma32(fg[ks], vf[ks], dp);
@@ -385,8 +386,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 bf16x8 fg[N], fq[N];
                 auto fetch = [&](int n) __attribute__((always_inline)) {
                     const int to = tb ^ ((n % DB) << 6);
-                    fg[n] = tr16_frag_at<CH>(gt + to + 32 * qb * ROWB, 16 * (n / DB));
-                    fq[n] = tr16_frag_at<CH>(qt + to + 32 * qb * ROWB, 16 * (n / DB));
+                    fg[n] = tr16_frag_at<CH>(gt + to, 16 * (n / DB));
+                    fq[n] = tr16_frag_at<CH>(qt + to, 16 * (n / DB));
                 };
 #pragma unroll
                 for (int n = 0; n < PF; ++n) fetch(n);
