@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1065364865, "dkdv_gist": 4683680013, "dkdv_window": 3126411827, "dq": 1344108325,
-                 "decode": 4567950611}
+TRAFFIC_BYTES = {"fwd": 1038159917, "dkdv_gist": 2315305902, "dkdv_window": 1536651994, "dq": 1395925855,
+                 "decode": 4567961286}
 
 
 def pair_counts(L, r, W):
@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="skip the chunk-wise prefill region (profiling runs: it launches the forward kernel under the "
+                         "same name at a smaller size)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "can be scaled by what they read for a kernel of known traffic")
@@ -190,15 +193,17 @@ def main():
             n = min(C, L - p0)
             cache.update(k[:, :, p0:p0 + n].contiguous(), v[:, :, p0:p0 + n].contiguous(), max(0, p0 - W + 1))
             u.prefill_chunk(q[:, :, p0:p0 + n].contiguous(), cache, r, W, p0)
-    prefill_pass()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(3):
+    prefill_ms = None
+    if not args.no_prefill:
         prefill_pass()
-    e1.record()
-    torch.cuda.synchronize()
-    prefill_ms = e0.elapsed_time(e1) / 3
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            prefill_pass()
+        e1.record()
+        torch.cuda.synchronize()
+        prefill_ms = e0.elapsed_time(e1) / 3
 
     bm, bn = u.unigist_tile_sizes(D, u.UNIGIST_BF16)
     m = u.unigist_blockmap_build(L, r, W, bm, bn)
@@ -220,9 +225,10 @@ def main():
             "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
             "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes}},
     }
-    res["prefill"] = {"workload": f"{WORKLOAD} in {C}-token chunks through the compressed cache", "ms": prefill_ms,
-                      "tflops": flops_fwd / prefill_ms / 1e9,
-                      "note": "includes the slicing copies of q/k/v chunks and the cache updates"}
+    if prefill_ms is not None:
+        res["prefill"] = {"workload": f"{WORKLOAD} in {C}-token chunks through the compressed cache", "ms": prefill_ms,
+                          "tflops": flops_fwd / prefill_ms / 1e9,
+                          "note": "includes the slicing copies of q/k/v chunks and the cache updates"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))
