@@ -21,6 +21,9 @@ What it follows
 * Everything else is ordinary softmax attention: S = Q K^T / sqrt(D), masked
   entries are -inf, P = softmax over keys, out = P V, lse = ln sum_j exp(S_ij).
   The gradients are the exact derivative of l = sum(out * dout).
+* Packed documents (Sec. 5.1, cross-document masking): with the keyword cu=boundaries the predicate
+  additionally requires query and key to lie in the same document and counts positions from the
+  document's first token.
 * Decode (Sec. 4.3, "Inference"): one query over a cache from which the
   invisible raw tokens have already been removed, so every cached key counts.
 
@@ -84,11 +87,23 @@ def visible(i, j, r, W, sinks=0, units=False):
     return causal & ((j < sinks) | is_gist(j, r, sinks) | in_window)
 
 
-def mask_rows(rows, L, r, W, **mask):
-    """Boolean [len(rows), L] matrix of visible(i, j) for the given query rows."""
+def mask_rows(rows, L, r, W, cu=None, **mask):
+    """Boolean [len(rows), L] matrix of visible(i, j) for the given query rows.
+
+    cu (optional): document boundaries of a packed sequence, cu[0] = 0 <= cu[1] <= ... <= cu[-1] = L.
+    Then attention never crosses a boundary (cross-document masking, Sec. 5.1) and inside a document
+    the rule is the one above with positions counted from the document's first token, so the gist
+    period and the window restart there.
+    """
     rows = np.asarray(rows, dtype=np.int64)
     cols = np.arange(L, dtype=np.int64)
-    return visible(rows[:, None], cols[None, :], r, W, **mask)
+    if cu is None:
+        return visible(rows[:, None], cols[None, :], r, W, **mask)
+    cu = np.asarray(cu, dtype=np.int64)
+    doc_r = np.searchsorted(cu, rows, side="right") - 1   # the document holding each position
+    doc_c = np.searchsorted(cu, cols, side="right") - 1
+    same = doc_r[:, None] == doc_c[None, :]
+    return same & visible((rows - cu[doc_r])[:, None], (cols - cu[doc_c])[None, :], r, W, **mask)
 
 
 def count_visible(L, r, W, block=1024, **mask):

@@ -242,3 +242,41 @@ def test_sinks_and_unit_window_thread_through_forward_and_backward():
     a = oracle.attn_dkdv_cols(q, kk, v, do, [1, 7, 30], r, k, **kw)
     np.testing.assert_allclose(a[0], dk[[1, 7, 30]], rtol=0, atol=1e-13)
     np.testing.assert_allclose(a[1], dv[[1, 7, 30]], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- packed documents (cu=)
+def test_packed_attention_is_the_documents_side_by_side():
+    # dense evaluation with the packed predicate == each document through the (pinned) single-document path
+    rng = np.random.default_rng(7)
+    cu, r, W, D = [0, 37, 37, 90, 91, 150], 4, 9, 16
+    T = cu[-1]
+    q, k, v, do = (rng.standard_normal((1, 2, T, D)) for _ in range(4))
+    k, v = k[:, :1], v[:, :1]
+    out, lse = oracle.attn_fwd(q, k, v, r, W, cu=cu)
+    dq, dk, dv = oracle.attn_bwd(q, k, v, do, r, W, cu=cu)
+    for a, b in zip(cu[:-1], cu[1:]):
+        if a == b:
+            continue
+        o1, l1 = oracle.attn_fwd(q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], r, W)
+        g = oracle.attn_bwd(q[:, :, a:b], k[:, :, a:b], v[:, :, a:b], do[:, :, a:b], r, W)
+        assert np.allclose(out[:, :, a:b], o1, atol=1e-12) and np.allclose(lse[:, :, a:b], l1, atol=1e-12)
+        for x, y in zip((dq, dk, dv), g):
+            assert np.allclose(x[:, :, a:b], y, atol=1e-12)
+
+
+def test_packed_attention_against_library_sdpa_with_explicit_mask():
+    import torch
+    rng = np.random.default_rng(8)
+    cu, r, W, D = [0, 20, 53, 64], 3, 6, 8
+    T = cu[-1]
+    q, k, v = (rng.standard_normal((1, 1, T, D)) for _ in range(3))
+    out, _ = oracle.attn_fwd(q, k, v, r, W, cu=cu)
+    # mask written out pair by pair from the definition, not through the oracle's predicate
+    m = torch.zeros(T, T, dtype=torch.bool)
+    for i in range(T):
+        for j in range(i + 1):
+            d = max(c for c in cu[:-1] if c <= i)
+            if j >= d and (((j - d + 1) % (r + 1) == 0) or i - j < W):
+                m[i, j] = True
+    ref = torch.nn.functional.scaled_dot_product_attention(*(torch.from_numpy(x) for x in (q, k, v)), attn_mask=m)
+    assert np.allclose(out, ref.numpy(), atol=1e-12)

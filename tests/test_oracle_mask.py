@@ -136,3 +136,28 @@ def test_sinks_are_always_visible_and_shift_the_layout():
         assert np.array_equal(M[S:, S:], oracle.mask_rows(np.arange(L - S), L - S, r, W, units=units))
     # a huge unit window is plain causal attention
     assert np.array_equal(oracle.mask_rows(np.arange(L), L, r, 10**6, sinks=S, units=True), np.tril(np.ones((L, L), bool)))
+
+
+# ---------------------------------------------------------------- packed documents (cu=)
+def test_packed_hand_derived_visible_sets():
+    rows = _read_rows(os.path.join(GOLDEN, "visible_sets_packed_T11_r2_W2.txt"))
+    M = oracle.mask_rows(np.arange(11), 11, 2, 2, cu=[0, 4, 11])
+    assert len(rows) == 11
+    for ln in rows:
+        i, keys = ln.split(":")
+        assert np.nonzero(M[int(i)])[0].tolist() == sorted(int(t) for t in keys.split()), i
+
+
+@pytest.mark.parametrize("cu,r,W", [([0, 5, 5, 17, 18, 40], 3, 4), ([0, 64], 4, 9), ([0, 1, 2, 3], 1, 1),
+                                     ([0, 30, 61, 100], 4, 10**6), ([0, 33, 77], 10**6, 5)])
+def test_packed_mask_is_block_diagonal_of_the_single_document_masks(cu, r, W):
+    T = cu[-1]
+    M = oracle.mask_rows(np.arange(T), T, r, W, cu=cu)
+    want = np.zeros((T, T), dtype=bool)
+    for a, b in zip(cu[:-1], cu[1:]):
+        if b > a:
+            want[a:b, a:b] = oracle.mask_rows(np.arange(b - a), b - a, r, W)
+    assert np.array_equal(M, want)
+    # one document is the plain mask; every query sees itself
+    assert np.array_equal(oracle.mask_rows(np.arange(T), T, r, W, cu=[0, T]), oracle.mask_rows(np.arange(T), T, r, W))
+    assert M.diagonal().all()
