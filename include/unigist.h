@@ -140,6 +140,27 @@ size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r
                                      int window_mode, unigist_dtype dt);
 
 /*
+ * Packed documents (Sec. 5.1: several documents share one training sequence and attention never crosses a
+ * document boundary).  The tensors hold T tokens per head -- q, out, dout, dq [Hq, T, D]; k, v, dk, dv
+ * [Hkv, T, D]; lse [Hq, T] -- and document d occupies the rows cu_seqlens[d] .. cu_seqlens[d+1]-1.  Inside a
+ * document everything is as in unigist_attn_fwd / unigist_attn_bwd with L = its length: the gist period and
+ * the window restart at the document's first token.  cu_seqlens is a HOST array of ndocs + 1 ints,
+ * non-decreasing, cu_seqlens[0] = 0, cu_seqlens[ndocs] = T (UNIGIST_EINVAL otherwise); it is read before the
+ * call returns.  Empty documents are allowed.  The documents are processed one after the other on the stream
+ * and share the workspace (size from unigist_attn_bwd_varlen_workspace, 256-byte aligned).
+ */
+unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
+                                       int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                       int ndocs, unigist_dtype dt, void* hip_stream);
+unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out,
+                                       const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                       int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                       int ndocs, unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream);
+size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                         int ndocs, unigist_dtype dt);
+
+/*
  * Decode over the compressed KV cache (Sec. 4.3, Fig. 4): the raw tokens that have
  * left the window were physically removed, so every cached key of a sequence is
  * visible; the order of the keys in the cache is irrelevant.

@@ -14,5 +14,7 @@ from .binding import (  # noqa: F401
     unigist_cache_rows, unigist_cache_update, unigist_prefill_chunk,
     UNIGIST_WINDOW_SLIDING, UNIGIST_WINDOW_UNITS,
     unigist_attn_fwd_ex, unigist_attn_bwd_ex, unigist_attn_bwd_workspace_ex, unigist_blockmap_build_ex,
+    unigist_attn_fwd_varlen, unigist_attn_bwd_varlen, unigist_attn_bwd_varlen_workspace,
+    attn_fwd_varlen, attn_bwd_varlen,
     attn_fwd, attn_bwd, decode, n_vis, KVCache, prefill_chunk,
 )

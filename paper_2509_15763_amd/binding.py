@@ -24,6 +24,7 @@ EXPORTS = [
     "unigist_decode", "unigist_decode_workspace", "unigist_blockmap_build", "unigist_blockmap_free",
     "unigist_tile_sizes", "unigist_cache_rows", "unigist_cache_update", "unigist_prefill_chunk",
     "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
+    "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
 ]
 
 
@@ -73,6 +74,13 @@ def load():
     lib.unigist_attn_bwd_workspace_ex.argtypes = [ip] * 9 + [ip]
     lib.unigist_blockmap_build_ex.restype = ip
     lib.unigist_blockmap_build_ex.argtypes = [ip] * 7 + [C.POINTER(C.POINTER(_BlockMap))]
+    cup = C.POINTER(C.c_int)
+    lib.unigist_attn_fwd_varlen.restype = ip
+    lib.unigist_attn_fwd_varlen.argtypes = [vp, vp, vp, vp, fp] + [ip] * 6 + [cup, ip, ip, vp]
+    lib.unigist_attn_bwd_varlen.restype = ip
+    lib.unigist_attn_bwd_varlen.argtypes = [vp] * 9 + [ip] * 6 + [cup, ip, ip, vp, sz, vp]
+    lib.unigist_attn_bwd_varlen_workspace.restype = sz
+    lib.unigist_attn_bwd_varlen_workspace.argtypes = [ip] * 6 + [cup, ip, ip]
     lib.unigist_decode.restype = ip
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
     lib.unigist_decode_workspace.restype = sz
@@ -156,6 +164,31 @@ def unigist_attn_bwd_ex(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r
 
 def unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt) -> int:
     return load().unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt)
+
+
+def _cu(cu_seqlens):
+    """Host int array for the *_varlen calls (None stays a null pointer) and its document count."""
+    if cu_seqlens is None:
+        return None, 0
+    vals = [int(x) for x in cu_seqlens]
+    return (C.c_int * len(vals))(*vals), len(vals) - 1
+
+
+def unigist_attn_fwd_varlen(q, k, v, out, lse, Hq, Hkv, T, D, r, W, cu_seqlens, dt, stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_fwd_varlen(q, k, v, out, lse, Hq, Hkv, T, D, r, W, cu, nd, dt, stream)
+
+
+def unigist_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, cu_seqlens, dt, ws, ws_bytes,
+                            stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, cu, nd, dt, ws,
+                                          ws_bytes, stream)
+
+
+def unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, dt) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu, nd, dt)
 
 
 def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream=None) -> int:
@@ -260,6 +293,46 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_A
                                int(r), int(W), int(sinks), int(window_mode), dt, workspace.data_ptr(),
                                workspace.numel() * workspace.element_size(), int(stages), _stream()),
            "unigist_attn_bwd_ex")
+    return dq, dk, dv
+
+
+def attn_fwd_varlen(q, k, v, r, W, cu_seqlens):
+    """Packed documents: q [Hq,T,D], k/v [Hkv,T,D] on the GPU, cu_seqlens a host sequence -> out, lse [Hq,T]."""
+    _dev(q, k, v)
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    if k.shape != (Hkv, T, D) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise UnigistError("q/k/v shapes or dtypes disagree")
+    out = torch.empty_like(q)
+    lse = torch.empty(Hq, T, device=q.device, dtype=torch.float32)
+    _check(unigist_attn_fwd_varlen(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                   Hq, Hkv, T, D, int(r), int(W), cu_seqlens, _dt(q), _stream()),
+           "unigist_attn_fwd_varlen")
+    return out, lse
+
+
+def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None):
+    """-> dq [Hq,T,D], dk, dv [Hkv,T,D] for packed documents."""
+    _dev(q, k, v, out, lse, dout)
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    dt = _dt(q)
+    if out.shape != q.shape or dout.shape != q.shape or lse.shape != (Hq, T) or lse.dtype != torch.float32:
+        raise UnigistError("out/dout/lse shapes or dtypes disagree")
+    if k.shape != (Hkv, T, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:
+        raise UnigistError("q/k/v/out/dout shapes or dtypes disagree")
+    need = unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, int(r), int(W), cu_seqlens, dt)
+    if need == 0:
+        raise UnigistError("unigist_attn_bwd_varlen_workspace: invalid shape or document bounds")
+    if workspace is None:
+        workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    # rows of no document (none when cu_seqlens covers 0 .. T) would stay unwritten: start from zero
+    dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    _check(unigist_attn_bwd_varlen(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                   dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D,
+                                   int(r), int(W), cu_seqlens, dt, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream()),
+           "unigist_attn_bwd_varlen")
     return dq, dk, dv
 
 

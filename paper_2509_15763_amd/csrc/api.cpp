@@ -41,6 +41,8 @@ AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sin
     s.scale = 1.0f / sqrtf((float)D);
     s.S = sinks > L ? L : sinks;
     s.umode = window_mode == UNIGIST_WINDOW_UNITS;
+    s.qhs = L;
+    s.kvhs = L;
     s.Lq = L;
     s.qpos0 = 0;
     s.kv_rows = L;
@@ -217,10 +219,105 @@ extern "C" unigist_status unigist_prefill_chunk(const void* q, const void* kc, c
     const int rows = unigist_cache_rows(s, (int)Ltot - 1, r);
     if (rows < 0 || rows > cap) return UNIGIST_EINVAL;
     sh.Lq = C;
+    sh.qhs = C;
     sh.qpos0 = p0;
     sh.kv_rows = cap;
     sh.s0 = s;
     sh.ngb = s / sh.rp1;
     hipError_t e = launch_fwd_mfma(q, kc, vc, out, lse, sh, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+// ---------------------------------------------------------------- packed documents
+namespace {
+
+unigist_status check_docs(int Hq, int Hkv, int T, int D, int r, int W, const int* cu, int ndocs, unigist_dtype dt) {
+    if (!cu || ndocs < 1 || T < 1) return UNIGIST_EINVAL;
+    if (cu[0] != 0 || cu[ndocs] != T) return UNIGIST_EINVAL;
+    for (int d = 0; d < ndocs; ++d)
+        if (cu[d + 1] < cu[d]) return UNIGIST_EINVAL;
+    return check_attn(1, Hq, Hkv, T, D, r, W, dt);
+}
+
+// the document [c0, c0 + len) of a packed [H, T, D] buffer as a shape of its own
+AttnShape doc_shape(int Hq, int Hkv, int T, int D, int r, int W, int len) {
+    AttnShape s = make_shape(1, Hq, Hkv, len, D, r, W);
+    s.qhs = T;
+    s.kvhs = T;
+    s.kv_rows = T;
+    return s;
+}
+
+size_t elem_bytes(unigist_dtype dt) { return dt == UNIGIST_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
+                                                  int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                                  int ndocs, unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t eb = elem_bytes(dt);
+    for (int d = 0; d < ndocs; ++d) {
+        const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
+        if (len == 0) continue;
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
+        const size_t ro = (size_t)c0 * D * eb;  // byte offset of the document's first row inside a head
+        const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
+        char* od = (char*)out + ro;
+        hipError_t e;
+        if (dt == UNIGIST_BF16 && !plain_alu_forced())
+            e = launch_fwd_mfma(qd, kd, vd, od, lse + c0, s, stream);
+        else
+            e = launch_fwd_simple(qd, kd, vd, od, lse + c0, s, dt, stream);
+        if (e != hipSuccess) return UNIGIST_ELAUNCH;
+    }
+    return UNIGIST_OK;
+}
+
+extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                                    int ndocs, unigist_dtype dt) {
+    if (check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt) != UNIGIST_OK) return 0;
+    size_t need = 256;
+    for (int d = 0; d < ndocs; ++d) {
+        const int len = cu_seqlens[d + 1] - cu_seqlens[d];
+        if (len == 0) continue;
+        const size_t n = unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt);
+        if (n > need) need = n;
+    }
+    return need;
+}
+
+extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out,
+                                                  const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                                  int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
+                                                  int ndocs, unigist_dtype dt, void* workspace,
+                                                  size_t workspace_bytes, void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
+    if (workspace_bytes < unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt))
+        return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t eb = elem_bytes(dt);
+    for (int d = 0; d < ndocs; ++d) {
+        const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
+        if (len == 0) continue;
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
+        const size_t ro = (size_t)c0 * D * eb;
+        const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
+        const char *od = (const char*)out + ro, *gd = (const char*)dout + ro;
+        char *dqd = (char*)dq + ro, *dkd = (char*)dk + ro, *dvd = (char*)dv + ro;
+        hipError_t e;
+        // the documents run one after the other on the stream, so they can share the workspace
+        if (dt == UNIGIST_BF16 && !plain_alu_forced())
+            e = launch_bwd_mfma(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, workspace, s, UNIGIST_BWD_ALL, stream);
+        else
+            e = launch_bwd_simple(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, (float*)workspace, s, dt, stream);
+        if (e != hipSuccess) return UNIGIST_ELAUNCH;
+    }
+    return UNIGIST_OK;
 }

@@ -109,14 +109,15 @@ BwdPlan make_plan(const AttnShape& s) {
 template <int D>
 __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
                                                   const float* __restrict__ lse, float* __restrict__ delta,
-                                                  float* __restrict__ lse2, long nrows) {
+                                                  float* __restrict__ lse2, long nrows, int L, int qhs) {
     constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
-    const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;
+    const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;  // dense: (b, h, i) -> (b Hq + h) L + i
     const int sub = threadIdx.x % LPR;
+    const long grow = L == qhs ? row : (row / L) * qhs + row % L;        // the same row in the caller's tensors
     float acc = 0.f;
     if (row < nrows) {
-        u32x4 a = *(const u32x4*)(out + row * D + sub * 8);
-        u32x4 b = *(const u32x4*)(dout + row * D + sub * 8);
+        u32x4 a = *(const u32x4*)(out + grow * D + sub * 8);
+        u32x4 b = *(const u32x4*)(dout + grow * D + sub * 8);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             acc += __uint_as_float(a[t] << 16) * __uint_as_float(b[t] << 16);
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ ou
     for (int off = 1; off < LPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
     if (row < nrows && sub == 0) {
         delta[row] = acc;
-        lse2[row] = lse[row] * kLog2e;  // the exponent base the dK/dV and dQ kernels subtract
+        lse2[row] = lse[grow] * kLog2e;  // the exponent base the dK/dV and dQ kernels subtract
     }
 }
 
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     // ---- K, V fragments (B operands): lane holds K[key][16 ks + 8h .. +7]
     bf16x8 kf[KS], vf[KS];
     {
-        const size_t base = (((size_t)b * s.Hkv + hk) * L + krow) * D + 8 * h;
+        const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + krow) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             kf[ks] = *(const bf16x8*)(k + base + 16 * ks);
@@ -254,9 +255,10 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 #pragma unroll
         for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz<CH>(i * RPI + lrow_)) << 4);
         const int g = step / nch, cc = c_lo + step % nch;
-        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform
-        const char* qh = (const char*)(q + hb * D);
-        const char* gh = (const char*)(dout + hb * D);
+        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform; dense workspace rows
+        const size_t hg = ((size_t)b * s.Hq + hk * G + g) * s.qhs;       // the head in the caller's tensors
+        const char* qh = (const char*)(q + hg * D);
+        const char* gh = (const char*)(dout + hg * D);
         if (cc * MQ + MQ <= L) {  // the whole chunk exists (wave-uniform)
             const size_t cb = (size_t)(cc * MQ + w * IPW * RPI) * ROWB;
 #pragma unroll
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                 for (int i = 0; i < 16; ++i) akT[db][i] *= s.scale;
         }
         if (key < L) {
-            const size_t base = (((size_t)b * s.Hkv + hk) * L + key) * D + 4 * h;
+            const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + key) * D + 4 * h;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -534,12 +536,13 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int L = s.L, rp1 = s.rp1;
     const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
     const int qrow = i0 + 32 * w + c32, qrow_ld = min(qrow, L - 1), wrow0 = i0 + 32 * w;
-    const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * L * D);
-    const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * L * D);
+    const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
+    const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
     const float c = s.scale * kLog2e;
 
     bf16x8 qf[KS], gf[KS];
-    const size_t rowoff = ((size_t)b * s.Hq + hq) * L + qrow_ld;
+    const size_t rowoff = ((size_t)b * s.Hq + hq) * s.qhs + qrow_ld;  // in the caller's tensors
+    const size_t wrow = ((size_t)b * s.Hq + hq) * L + qrow_ld;        // in the dense workspace
     {
         const bf16_t* qp = q + rowoff * D + 8 * h;
         const bf16_t* gp = dout + rowoff * D + 8 * h;
@@ -549,8 +552,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
             gf[ks] = *(const bf16x8*)(gp + 16 * ks);
         }
     }
-    const float ls = lse2[rowoff];
-    const float dl = delta[rowoff];
+    const float ls = lse2[wrow];
+    const float dl = delta[wrow];
 
     f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
 #pragma unroll
@@ -721,8 +724,8 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     if (stages & UNIGIST_BWD_DELTA) {
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.B * s.Hq * s.L;
-        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(out, dout, lse, delta,
-                                                                                                    lse2, nrows);
+        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow][16 ks + 8 h .. +7]
     bf16x8 qf[KS];
     {
-        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.Lq + (qrow_ld - qpos0)) * D + 8 * h;
+        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld - qpos0)) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
     }
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const float lt = l + other_half(l);
     const float inv = 1.f / lt;
     if (qrow < L) {
-        const size_t orow = ((size_t)b * s.Hq + hq) * s.Lq + (qrow - qpos0);
+        const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow - qpos0);
         bf16_t* op = out + orow * D + 4 * h;
 #pragma unroll
         for (int db = 0; db < DB; ++db)

@@ -33,9 +33,9 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
     const int i_last = min(s.L, i_first + kRows) - 1;
     const int i = min(i_first + lane, s.L - 1);  // lanes past the end shadow the last row, never store
     const bool live = i_first + lane < s.L;
-    const size_t qoff = (((size_t)b * s.Hq + h) * s.L + i) * D;
-    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.L * D;
-    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.L * D;
+    const size_t qoff = (((size_t)b * s.Hq + h) * s.qhs + i) * D;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
 #pragma unroll
     for (int d = 0; d < D; ++d) qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
 
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
         float inv = 1.f / l;
 #pragma unroll
         for (int d = 0; d < D; ++d) Elem<T>::store(out + qoff + d, o[d] * inv);
-        lse[((size_t)b * s.Hq + h) * s.L + i] = m + logf(l);
+        lse[((size_t)b * s.Hq + h) * s.qhs + i] = m + logf(l);
     }
 }
 
@@ -95,10 +95,11 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
     const int i_last = min(s.L, i_first + kRows) - 1;
     const int i = min(i_first + lane, s.L - 1);
     const bool live = i_first + lane < s.L;
-    const size_t row = ((size_t)b * s.Hq + h) * s.L + i;
+    const size_t row = ((size_t)b * s.Hq + h) * s.qhs + i;   // in the caller's tensors
+    const size_t wrow = ((size_t)b * s.Hq + h) * s.L + i;    // in the dense workspace
     const size_t qoff = row * D;
-    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.L * D;
-    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.L * D;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
     float dl = 0.f;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
         dl += g * Elem<T>::load(out + qoff + d);
     }
     const float ls = lse[row];
-    if (live) delta[row] = dl;
+    if (live) delta[wrow] = dl;
 
     float acc[D];
 #pragma unroll
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
     const int j_last = min(s.L, j_first + kRows) - 1;
     const int j = min(j_first + lane, s.L - 1);
     const bool live = j_first + lane < s.L;
-    const size_t koff = (((size_t)b * s.Hkv + hk) * s.L + j) * D;
+    const size_t koff = (((size_t)b * s.Hkv + hk) * s.kvhs + j) * D;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
         ks[d][lane] = Elem<T>::load(k + koff + d) * s.scale;
@@ -176,7 +177,8 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
 
     for (int g = 0; g < group; ++g) {
         const int h = hk * group + g;
-        const size_t base = ((size_t)b * s.Hq + h) * s.L;
+        const size_t base = ((size_t)b * s.Hq + h) * s.qhs;  // caller's q, dout, lse
+        const size_t wbase = ((size_t)b * s.Hq + h) * s.L;   // workspace delta
         for (int i = j_first; i <= i_end; ++i) {
             bool ok = j <= i && (always_j || i <= hi_j);
             if (!ok) continue;
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
                 dp += vs[d][lane] * Elem<T>::load(gr + d);
             }
             float p = expf(sc - lse[base + i]);
-            float ds = p * (dp - delta[base + i]);
+            float ds = p * (dp - delta[wbase + i]);
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 av[d] += p * Elem<T>::load(gr + d);

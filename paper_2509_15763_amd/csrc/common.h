@@ -51,6 +51,10 @@ struct AttnShape {
     int rp1;  // r + 1, clamped to L + 1 when there are no gists (so (p+1) % rp1 == 0 never holds)
     int W;    // window: positions (sliding) or previous gist units (unit-aligned); clamped to L
     float scale;
+    // Rows between consecutive heads in the caller's tensors (q, out, dout, dq, lse: qhs; k, v, dk, dv: kvhs).
+    // Both are L for a plain [B, H, L, D] tensor; a document inside a packed buffer has L = its length and
+    // the strides of the whole buffer.  Workspace arrays are always dense (stride L).
+    int qhs, kvhs;
     int S;      // sink tokens in front of the first gist unit (Sec. 4.1); always visible
     int umode;  // 0: sliding window of W positions; 1: the unit holding the query plus the W previous units
     // Forward only: the query rows and the K/V rows may be a view of the L positions (chunk-wise prefill

@@ -79,6 +79,23 @@ def test_ex_argument_validation():
         1, 4, 2, 4096, 64, 4, 8, 0)
 
 
+def test_varlen_argument_validation():
+    ok = dict(Hq=4, Hkv=2, T=100, D=64, r=4, W=8)
+    cu = [0, 30, 30, 100]
+    args = tuple(ok.values())
+    assert u.unigist_attn_bwd_varlen_workspace(*args, cu, 0) > 0
+    assert u.unigist_attn_fwd_varlen(None, None, None, None, None, *args, cu, 0) == 1          # null tensors
+    assert u.unigist_attn_fwd_varlen(FAKE, FAKE, FAKE, FAKE, FAKE, *args, None, 0) == 1        # no boundaries
+    for bad in ([1, 30, 100], [0, 30, 99], [0, 60, 40, 100], [0, 30, 101]):
+        assert u.unigist_attn_fwd_varlen(FAKE, FAKE, FAKE, FAKE, FAKE, *args, bad, 0) == 1
+        assert u.unigist_attn_bwd_varlen_workspace(*args, bad, 0) == 0
+        assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, bad, 0, FAKE, 1 << 40) == 1
+    assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, cu, 0, FAKE, 16) == 1                # workspace too small
+    # the workspace is that of the longest document
+    assert u.unigist_attn_bwd_varlen_workspace(4, 2, 6000, 64, 4, 8, [0, 5000, 6000], 0) == \
+        u.unigist_attn_bwd_workspace(1, 4, 2, 5000, 64, 4, 8, 0)
+
+
 def test_decode_argument_validation():
     ok = dict(B=2, Hq=4, Hkv=2, Lk=100, D=128, dt=0)
     ws = u.unigist_decode_workspace(*ok.values())

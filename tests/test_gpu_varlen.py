@@ -1,0 +1,130 @@
+"""GPU parity of the *_varlen entry points: documents packed into one sequence, attention confined to each
+document (Sec. 5.1), against the fp64 oracle evaluated with the packed predicate on the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_15763_amd as u
+from paper_2509_15763_amd import synth
+from _parity import max_abs, rel_l2, to_np
+from test_gpu_attention import check
+from test_gpu_full_size import out_tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+def packed_inputs(Hq, Hkv, T, D, dtype, seed):
+    q, k, v, dout = synth.attn_inputs(1, Hq, Hkv, T, D, dtype=dtype, seed=seed)
+    return q[0], k[0], v[0], dout[0]
+
+
+def run_gpu(q, k, v, dout, r, W, cu):
+    qd, kd, vd, dod = (t.cuda() for t in (q, k, v, dout))
+    out, lse = u.attn_fwd_varlen(qd, kd, vd, r, W, cu)
+    dq, dk, dv = u.attn_bwd_varlen(qd, kd, vd, out, lse, dod, r, W, cu)
+    torch.cuda.synchronize()
+    return out, lse, dq, dk, dv
+
+
+def oracle_packed(q, k, v, dout, r, W, cu):
+    qn, kn, vn, don = (to_np(t)[None] for t in (q, k, v, dout))
+    out, lse = oracle.attn_fwd(qn, kn, vn, r, W, cu=cu)
+    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W, cu=cu)
+    return out[0], lse[0], dq[0], dk[0], dv[0]
+
+
+# Hq, Hkv, D, r, W, document lengths
+SMALL = [
+    (1, 1, 64, 4, 128, [300, 500, 224]),              # multiples of nothing in particular
+    (4, 2, 64, 4, 40, [1, 2, 130, 0, 64, 136]),        # one-token documents, an empty one, tile-sized ones
+    (4, 1, 128, 8, 100, [257, 443]),                   # D = 128, group of 4
+    (2, 2, 128, 2, 1, [90, 90, 77]),                   # W = 1
+    (2, 1, 64, 4, 10**6, [200, 184]),                  # window >= L: causal inside each document
+    (2, 1, 128, 2**31 - 2, 33, [150, 150]),            # no gists
+    (8, 8, 64, 16, 64, [100, 100]),                    # 8 kv heads
+    (2, 2, 128, 4, 16, [700]),                         # one document == the plain entry point's case
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("Hq,Hkv,D,r,W,lens", SMALL)
+def test_small_packs_match_oracle(Hq, Hkv, D, r, W, lens, dtype):
+    cu = [0] + np.cumsum(lens).tolist()
+    case = f"Hq{Hq} Hkv{Hkv} D{D} r{r} W{W} docs{lens} {dtype}"
+    print("case", case, flush=True)
+    q, k, v, dout = packed_inputs(Hq, Hkv, cu[-1], D, dtype, seed=31)
+    got = run_gpu(q, k, v, dout, r, W, cu)
+    check(case, got, oracle_packed(q, k, v, dout, r, W, cu), dtype)
+
+
+def test_mid_pack_matches_oracle():
+    # documents longer than 4096 (several dK/dV segments) next to short ones, ragged everywhere
+    lens = [4500, 37, 3000, 1463]
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = packed_inputs(4, 1, cu[-1], 128, torch.bfloat16, seed=32)
+    got = run_gpu(q, k, v, dout, 4, 300, cu)
+    check(f"docs{lens}", got, oracle_packed(q, k, v, dout, 4, 300, cu), torch.bfloat16)
+
+
+def test_single_document_is_the_plain_entry_point():
+    q, k, v, dout = packed_inputs(4, 2, 700, 128, torch.bfloat16, seed=3)
+    a = run_gpu(q, k, v, dout, 4, 64, [0, 700])
+    qd, kd, vd, dod = (t[None].cuda() for t in (q, k, v, dout))
+    out, lse = u.attn_fwd(qd, kd, vd, 4, 64)
+    b = (out, lse) + tuple(u.attn_bwd(qd, kd, vd, out, lse, dod, 4, 64))
+    for x, y in zip(a, b):
+        assert torch.equal(x, y[0])
+
+
+def test_documents_do_not_see_each_other():
+    # changing one document's keys, values and upstream gradients leaves every other document's results bit-identical
+    lens = [200, 333, 150]
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = packed_inputs(2, 1, cu[-1], 64, torch.bfloat16, seed=33)
+    a = run_gpu(q, k, v, dout, 4, 50, cu)
+    k2, v2, d2 = k.clone(), v.clone(), dout.clone()
+    k2[:, cu[1]:cu[2]] += 1.0
+    v2[:, cu[1]:cu[2]] -= 2.0
+    d2[:, cu[1]:cu[2]] *= 3.0
+    b = run_gpu(q, k2, v2, d2, 4, 50, cu)
+    for x, y in zip(a, b):
+        for lo, hi in ((cu[0], cu[1]), (cu[2], cu[3])):
+            assert torch.equal(x[:, lo:hi], y[:, lo:hi])
+        assert not torch.equal(x[:, cu[1]:cu[2]], y[:, cu[1]:cu[2]])
+
+
+def test_full_length_pack_sampled_rows_and_columns():
+    # the 32K training shape as a pack of five documents (each padded to a multiple of r as in App. B):
+    # sampled rows and key columns of two documents against the oracle on those documents alone
+    w = synth.WORKLOADS["cfg2_llama8b_32k"]
+    Hq, Hkv, T, D, r, W = w["Hq"], w["Hkv"], w["L"], w["D"], w["r"], w["W"]
+    lens = [8192, 4100, 12288, 1020, 7168]
+    assert sum(lens) == T
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = packed_inputs(Hq, Hkv, T, D, torch.bfloat16, seed=34)
+    out, lse, dq, dk, dv = run_gpu(q, k, v, dout, r, W, cu)
+    rng = np.random.default_rng(1)
+    G = Hq // Hkv
+    for d in (1, 2):
+        a, b = cu[d], cu[d + 1]
+        n = b - a
+        rows = np.unique(np.concatenate([[0, 1, 4, W - 1, W, W + 1, n - 1], rng.integers(0, n, 24)]))
+        cols = np.unique(np.concatenate([[0, 4, 9, n - 1, n - 2], rng.integers(0, n, 12)]))
+        for h in (3, 30):
+            hk = h // G
+            qn, kn, vn, don = (to_np(t[h_, a:b]) for t, h_ in ((q, h), (k, hk), (v, hk), (dout, h)))
+            o, l = oracle.attn_fwd_rows(qn, kn, vn, rows, r, W)
+            assert (np.abs(to_np(out[h, a:b])[rows] - o) <= out_tolerance(o)).all(), (d, h)
+            assert max_abs(to_np(lse[h, a:b])[rows], l) <= 1e-2
+            assert rel_l2(to_np(dq[h, a:b])[rows], oracle.attn_dq_rows(qn, kn, vn, don, rows, r, W)) <= 2e-2
+        hk = 6
+        gk = np.zeros((len(cols), D))
+        gv = np.zeros((len(cols), D))
+        for g in range(G):
+            x, y = oracle.attn_dkdv_cols(to_np(q[hk * G + g, a:b]), to_np(k[hk, a:b]), to_np(v[hk, a:b]),
+                                         to_np(dout[hk * G + g, a:b]), cols, r, W)
+            gk += x
+            gv += y
+        assert rel_l2(to_np(dk[hk, a:b])[cols], gk) <= 2e-2
+        assert rel_l2(to_np(dv[hk, a:b])[cols], gv) <= 2e-2
