@@ -18,3 +18,4 @@ from .binding import (  # noqa: F401
     attn_fwd_varlen, attn_bwd_varlen,
     attn_fwd, attn_bwd, decode, n_vis, KVCache, prefill_chunk,
 )
+from .autograd import gist_attention, gist_attention_varlen  # noqa: F401,E402
