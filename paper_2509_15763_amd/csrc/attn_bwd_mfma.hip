@@ -247,14 +247,13 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     // They are recomputed from the lane id at every use: kept in registers across the step they would be
     // spilled, and a reload from scratch waits on the same counter as the direct loads still in flight.
     constexpr int NLP = RPI >= 8 ? 1 : 8 / RPI;
-    auto issue = [&](int step, int buf) __attribute__((always_inline)) {
+    auto issue = [&](int g, int cc, int buf) __attribute__((always_inline)) {
         int ln = lane;
         asm volatile("" : "+v"(ln));  // opaque: keeps the address arithmetic below inside this call
         const int lrow_ = ln / CH;
         int lanepart[NLP];
 #pragma unroll
         for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz<CH>(i * RPI + lrow_)) << 4);
-        const int g = step / nch, cc = c_lo + step % nch;
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform; dense workspace rows
         const size_t hg = ((size_t)b * s.Hq + hk * G + g) * s.qhs;       // the head in the caller's tensors
         const char* qh = (const char*)(q + hg * D);
@@ -293,11 +292,10 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     const int toff0 = tr_lane_off<CH>(0);
 
     // one step on LDS stage BUF (a compile-time constant: LDS addresses = lane register + immediate)
-    auto do_step = [&](auto bufc, int step) __attribute__((always_inline)) {
+    auto do_step = [&](auto bufc, int cc) __attribute__((always_inline)) {
         constexpr int BUF = decltype(bufc)::value;
         const char* qt = sm.q[BUF];
         const char* gt = sm.g[BUF];
-        const int cc = c_lo + step % nch;
         const int q0 = cc * MQ;
 
         int nfar = 0;
@@ -405,17 +403,39 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         }
     };
 
-    issue(0, 0);
+    // Step t handles query chunk c_lo + t % nch of query head t / nch of the group; both walks (the chunk being
+    // computed, the chunk being fetched one step ahead) are kept as (head, chunk) counters instead of dividing.
+    int gi = 0, ci = c_lo;  // what the next issue() fetches
+    int cs = c_lo;          // what the next do_step() computes
+    auto next_issue = [&]() __attribute__((always_inline)) {
+        if (++ci > c_hi) {
+            ci = c_lo;
+            ++gi;
+        }
+    };
+    auto next_step = [&]() __attribute__((always_inline)) {
+        if (++cs > c_hi) cs = c_lo;
+    };
+    issue(gi, ci, 0);
+    next_issue();
     for (int step = 0; step < nsteps; step += 2) {
         wait_vmem();
         __syncthreads();
-        if (step + 1 < nsteps) issue(step + 1, 1);
-        do_step(std::integral_constant<int, 0>{}, step);
+        if (step + 1 < nsteps) {
+            issue(gi, ci, 1);
+            next_issue();
+        }
+        do_step(std::integral_constant<int, 0>{}, cs);
+        next_step();
         if (step + 1 < nsteps) {
             wait_vmem();
             __syncthreads();
-            if (step + 2 < nsteps) issue(step + 2, 0);
-            do_step(std::integral_constant<int, 1>{}, step + 1);
+            if (step + 2 < nsteps) {
+                issue(gi, ci, 0);
+                next_issue();
+            }
+            do_step(std::integral_constant<int, 1>{}, cs);
+            next_step();
         }
     }
 
