@@ -301,7 +301,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         int nfar = 0;
         if (GIST) nfar = nfar_of_chunk(s, cc);  // compact entries visible to this chunk: index < nfar
 
-#pragma unroll 1
+#pragma unroll
         for (int qb = 0; qb < MQ / 32; ++qb) {
             const int qb0 = q0 + 32 * qb;  // first query row of the block
             if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
