@@ -280,19 +280,19 @@ def attn_dkdv_cols(q, k, v, dout, cols, r, W, row_lo=0, row_hi=None, block=512, 
 # --------------------------------------------------------------------------
 # decode over the compressed cache (Sec. 4.3)
 # --------------------------------------------------------------------------
-def compressed_cache_positions(t, r, W):
-    """Positions a cache holds when position t is the query (Fig. 4): every gist
+def compressed_cache_positions(t, r, W, **mask):
+    """Positions a cache holds when position t is the query (Fig. 4): every sink and gist
     up to t plus the raw tokens still inside t's window.  Ascending order."""
     j = np.arange(t + 1, dtype=np.int64)
-    return j[visible(np.int64(t), j, r, W)]
+    return j[visible(np.int64(t), j, r, W, **mask)]
 
 
-def cache_positions(s, t, r):
-    """Positions a compressed cache in state (s, t) holds, in row order (Sec. 4.3, Fig. 4): the gists
-    that lie left of position s, then every position s .. t.  With s = max(0, t - W + 1) this is the
-    visible set of query t."""
+def cache_positions(s, t, r, sinks=0):
+    """Positions a compressed cache in state (s, t) holds, in row order (Sec. 4.3, Fig. 4): the sinks and
+    gists that lie left of position s, then every position s .. t.  With s the first position of query
+    t's window this is the visible set of query t."""
     j = np.arange(t + 1, dtype=np.int64)
-    keep = (j >= s) | is_gist(j, r)
+    keep = (j >= s) | (j < sinks) | is_gist(j, r, sinks)
     return j[keep]
 
 

@@ -161,3 +161,19 @@ def test_packed_mask_is_block_diagonal_of_the_single_document_masks(cu, r, W):
     # one document is the plain mask; every query sees itself
     assert np.array_equal(oracle.mask_rows(np.arange(T), T, r, W, cu=[0, T]), oracle.mask_rows(np.arange(T), T, r, W))
     assert M.diagonal().all()
+
+
+def test_cache_state_with_sinks_and_unit_windows():
+    # the worked example with 2 sinks and unit windows (tests/golden/visible_sets_L14_r2_sinks2_units1.txt):
+    # query 12 sees 0 1 4 7 8 9 10 11 12; its window starts at position 8, so state (8, 12) holds exactly that
+    assert oracle.cache_positions(8, 12, 2, sinks=2).tolist() == [0, 1, 4, 7, 8, 9, 10, 11, 12]
+    assert oracle.compressed_cache_positions(12, 2, 1, sinks=2, units=True).tolist() == [0, 1, 4, 7, 8, 9, 10, 11, 12]
+    for r, k, sinks in [(2, 1, 2), (4, 3, 5), (3, 2, 0), (4, 1, 40)]:
+        for t in (0, 1, sinks, sinks + 1, 30, 77):
+            vis = oracle.compressed_cache_positions(t, r, k, sinks=sinks, units=True)
+            s = t if t < sinks else sinks + max(0, (t - sinks) // (r + 1) - k) * (r + 1)   # first position of t's window
+            assert np.array_equal(oracle.cache_positions(s, t, r, sinks=sinks), vis)
+            # starting the window region earlier only adds raw tokens
+            wide = oracle.cache_positions(max(0, s - 4), t, r, sinks=sinks)
+            extra = np.setdiff1d(wide, vis)
+            assert not (oracle.is_gist(extra, r, sinks) | (extra < sinks)).any()
