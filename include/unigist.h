@@ -211,6 +211,23 @@ unigist_status unigist_prefill_chunk(const void* q, const void* kc, const void* 
                                      int p0, int s, int cap, unigist_dtype dt, void* hip_stream);
 
 /*
+ * The same three calls for the layout of unigist_attn_fwd_ex (Sec. 4.1: `sinks` sink tokens in front, window
+ * counted per `window_mode`).  The compact front of the cache then holds the sinks followed by the gists at
+ * positions < s, and a query at position i needs s <= the first position of its window (for UNITS: the
+ * first position of the unit W units before the one holding i; a sink query needs s <= i).  sinks = 0 with
+ * SLIDING gives the calls above.
+ */
+int unigist_cache_rows_ex(int s, int t, int r, int sinks);
+unigist_status unigist_cache_update_ex(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
+                                       const void* k_new, const void* v_new, int n_new, int new_rows,
+                                       void* kc_out, void* vc_out, int s_new, int cap_out,
+                                       int B, int Hkv, int D, int r, int sinks, unigist_dtype dt, void* hip_stream);
+unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                        int B, int Hq, int Hkv, int C, int D, int r, int W, int sinks,
+                                        int window_mode, int p0, int s, int cap, unigist_dtype dt,
+                                        void* hip_stream);
+
+/*
  * Block map (Sec. 4.2: with a fixed compression ratio the visible blocks are known in
  * closed form and need not be stored; this builder materialises them on the HOST for
  * tests and for the live-tile report).  The sequence is cut into query tiles of Bm rows

@@ -25,6 +25,7 @@ EXPORTS = [
     "unigist_tile_sizes", "unigist_cache_rows", "unigist_cache_update", "unigist_prefill_chunk",
     "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
+    "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
 ]
 
 
@@ -89,6 +90,12 @@ def load():
     lib.unigist_blockmap_build.argtypes = [ip] * 5 + [C.POINTER(C.POINTER(_BlockMap))]
     lib.unigist_blockmap_free.restype = None
     lib.unigist_blockmap_free.argtypes = [C.POINTER(_BlockMap)]
+    lib.unigist_cache_rows_ex.restype = ip
+    lib.unigist_cache_rows_ex.argtypes = [ip, ip, ip, ip]
+    lib.unigist_cache_update_ex.restype = ip
+    lib.unigist_cache_update_ex.argtypes = [vp, vp, ip, ip, ip, vp, vp, ip, ip, vp, vp, ip, ip, ip, ip, ip, ip, ip, ip, vp]
+    lib.unigist_prefill_chunk_ex.restype = ip
+    lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
     lib.unigist_cache_rows.restype = ip
     lib.unigist_cache_rows.argtypes = [ip, ip, ip]
     lib.unigist_cache_update.restype = ip
@@ -207,6 +214,22 @@ def unigist_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new
                          cap_out, B, Hkv, D, r, dt, stream=None) -> int:
     return load().unigist_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                        vc_out, s_new, cap_out, B, Hkv, D, r, dt, stream)
+
+
+def unigist_cache_rows_ex(s, t, r, sinks) -> int:
+    return load().unigist_cache_rows_ex(s, t, r, sinks)
+
+
+def unigist_cache_update_ex(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out, vc_out, s_new,
+                            cap_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
+    return load().unigist_cache_update_ex(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
+                                          vc_out, s_new, cap_out, B, Hkv, D, r, sinks, dt, stream)
+
+
+def unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s, cap, dt,
+                             stream=None) -> int:
+    return load().unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s,
+                                           cap, dt, stream)
 
 
 def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream=None) -> int:
@@ -365,15 +388,15 @@ class KVCache:
     """Two ping-pong [B, Hkv, cap, D] buffers and the state (s, t) of the compressed cache; thin host-side
     bookkeeping around unigist_cache_update (no arithmetic)."""
 
-    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda"):
-        self.B, self.Hkv, self.cap, self.D, self.r = B, Hkv, cap, D, int(r)
+    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda", sinks=0):
+        self.B, self.Hkv, self.cap, self.D, self.r, self.sinks = B, Hkv, cap, D, int(r), int(sinks)
         self.k = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
         self.v = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
         self.cur, self.s, self.t = 0, 0, -1
 
     @property
     def rows(self) -> int:
-        return unigist_cache_rows(self.s, self.t, self.r)
+        return unigist_cache_rows_ex(self.s, self.t, self.r, self.sinks)
 
     @property
     def kc(self):
@@ -390,20 +413,22 @@ class KVCache:
             _dev(k_new, v_new)
         s_new = self.s if s_new is None else int(s_new)
         nxt = 1 - self.cur
-        _check(unigist_cache_update(self.k[self.cur].data_ptr(), self.v[self.cur].data_ptr(), self.s, self.t, self.cap,
-                                    k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
-                                    self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), s_new, self.cap,
-                                    self.B, self.Hkv, self.D, self.r, _dt(self.k[0]), _stream()), "unigist_cache_update")
+        _check(unigist_cache_update_ex(self.k[self.cur].data_ptr(), self.v[self.cur].data_ptr(), self.s, self.t,
+                                       self.cap, k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
+                                       self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), s_new, self.cap,
+                                       self.B, self.Hkv, self.D, self.r, self.sinks, _dt(self.k[0]), _stream()),
+               "unigist_cache_update_ex")
         self.cur, self.s, self.t = nxt, s_new, self.t + n
 
 
-def prefill_chunk(q, cache: "KVCache", r, W, p0):
+def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING):
     """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse."""
     _dev(q)
     B, Hq, C, D = q.shape
     out = torch.empty_like(q)
     lse = torch.empty(B, Hq, C, device=q.device, dtype=torch.float32)
-    _check(unigist_prefill_chunk(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                                 B, Hq, cache.Hkv, C, D, int(r), int(W), int(p0), cache.s, cache.cap, _dt(q), _stream()),
-           "unigist_prefill_chunk")
+    _check(unigist_prefill_chunk_ex(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(),
+                                    lse.data_ptr(), B, Hq, cache.Hkv, C, D, int(r), int(W), cache.sinks,
+                                    int(window_mode), int(p0), cache.s, cache.cap, _dt(q), _stream()),
+           "unigist_prefill_chunk_ex")
     return out, lse

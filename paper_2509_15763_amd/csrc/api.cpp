@@ -172,16 +172,28 @@ extern "C" unigist_status unigist_decode(const void* q, const void* kcache, cons
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
-extern "C" int unigist_cache_rows(int s, int t, int r) {
-    if (s < 0 || r < 1 || t < s - 1) return -1;
-    return (int)((long long)s / ((long long)r + 1)) + (t - s + 1);
+extern "C" int unigist_cache_rows(int s, int t, int r) { return unigist_cache_rows_ex(s, t, r, 0); }
+
+extern "C" int unigist_cache_rows_ex(int s, int t, int r, int sinks) {
+    if (s < 0 || r < 1 || sinks < 0 || t < s - 1) return -1;
+    const long long na = s <= sinks ? s : sinks + ((long long)s - sinks) / ((long long)r + 1);
+    return (int)na + (t - s + 1);
 }
 
 extern "C" unigist_status unigist_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
                                                const void* k_new, const void* v_new, int n_new, int new_rows,
                                                void* kc_out, void* vc_out, int s_new, int cap_out, int B, int Hkv,
                                                int D, int r, unigist_dtype dt, void* hip_stream) {
-    if (B < 1 || Hkv < 1 || D < 1 || r < 1 || n_new < 0 || new_rows < n_new || cap_in < 0 || cap_out < 1)
+    return unigist_cache_update_ex(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out, vc_out,
+                                   s_new, cap_out, B, Hkv, D, r, 0, dt, hip_stream);
+}
+
+extern "C" unigist_status unigist_cache_update_ex(const void* kc_in, const void* vc_in, int s_old, int t_old,
+                                                  int cap_in, const void* k_new, const void* v_new, int n_new,
+                                                  int new_rows, void* kc_out, void* vc_out, int s_new, int cap_out,
+                                                  int B, int Hkv, int D, int r, int sinks, unigist_dtype dt,
+                                                  void* hip_stream) {
+    if (B < 1 || Hkv < 1 || D < 1 || r < 1 || sinks < 0 || n_new < 0 || new_rows < n_new || cap_in < 0 || cap_out < 1)
         return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
     if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
@@ -189,41 +201,48 @@ extern "C" unigist_status unigist_cache_update(const void* kc_in, const void* vc
     const long long t_new = (long long)t_old + n_new;
     if (t_new > kMaxL || s_new > t_new + 1) return UNIGIST_EINVAL;
     if ((long long)B * Hkv > 65535) return UNIGIST_EUNSUPPORTED;
-    const int rows_in = unigist_cache_rows(s_old, t_old, r);
-    const int rows_out = unigist_cache_rows(s_new, (int)t_new, r);
+    const int rows_in = unigist_cache_rows_ex(s_old, t_old, r, sinks);
+    const int rows_out = unigist_cache_rows_ex(s_new, (int)t_new, r, sinks);
     if (rows_in > cap_in || rows_out > cap_out) return UNIGIST_EINVAL;
     if (!kc_out || !vc_out) return UNIGIST_EINVAL;
     if (rows_in > 0 && (!kc_in || !vc_in)) return UNIGIST_EINVAL;
     if (n_new > 0 && (!k_new || !v_new)) return UNIGIST_EINVAL;
     const int rp1 = r >= kMaxL ? kMaxL + 1 : r + 1;
     hipError_t e = launch_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
-                                       vc_out, s_new, cap_out, B * Hkv, D, rp1, dt == UNIGIST_BF16 ? 2 : 4,
-                                       (hipStream_t)hip_stream);
+                                       vc_out, s_new, cap_out, B * Hkv, D, rp1, sinks > kMaxL ? kMaxL : sinks,
+                                       dt == UNIGIST_BF16 ? 2 : 4, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
 extern "C" unigist_status unigist_prefill_chunk(const void* q, const void* kc, const void* vc, void* out, float* lse,
                                                 int B, int Hq, int Hkv, int C, int D, int r, int W, int p0, int s,
                                                 int cap, unigist_dtype dt, void* hip_stream) {
+    return unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, 0, UNIGIST_WINDOW_SLIDING, p0, s, cap,
+                                    dt, hip_stream);
+}
+
+extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc, const void* vc, void* out,
+                                                   float* lse, int B, int Hq, int Hkv, int C, int D, int r, int W,
+                                                   int sinks, int window_mode, int p0, int s, int cap,
+                                                   unigist_dtype dt, void* hip_stream) {
     if (C < 1 || p0 < 0 || s < 0 || cap < 1) return UNIGIST_EINVAL;
     const long long Ltot = (long long)p0 + C;
     if (Ltot > kMaxL) return UNIGIST_EUNSUPPORTED;
-    unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, dt);
+    unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, dt, sinks, window_mode);
     if (st != UNIGIST_OK) return st;
     if (dt != UNIGIST_BF16) return UNIGIST_EUNSUPPORTED;
     if (!q || !kc || !vc || !out || !lse) return UNIGIST_EINVAL;
-    AttnShape sh = make_shape(B, Hq, Hkv, (int)Ltot, D, r, W);
+    AttnShape sh = make_shape(B, Hq, Hkv, (int)Ltot, D, r, W, sinks, window_mode);
     // every raw token the first query may see must still be cached
-    const int need = p0 - sh.W + 1 > 0 ? p0 - sh.W + 1 : 0;
-    if (s > need) return UNIGIST_EINVAL;
-    const int rows = unigist_cache_rows(s, (int)Ltot - 1, r);
+    if (s > win_lo(sh, p0)) return UNIGIST_EINVAL;
+    const int rows = unigist_cache_rows_ex(s, (int)Ltot - 1, r, sinks);
     if (rows < 0 || rows > cap) return UNIGIST_EINVAL;
     sh.Lq = C;
     sh.qhs = C;
     sh.qpos0 = p0;
     sh.kv_rows = cap;
     sh.s0 = s;
-    sh.ngb = s / sh.rp1;
+    sh.ngb = count_always(sh, s);
     hipError_t e = launch_fwd_mfma(q, kc, vc, out, lse, sh, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }

@@ -2,9 +2,10 @@
 // window are never attended to again and are dropped; gists are kept for ever.
 //
 // Cache layout per (batch, kv head): `cap` rows of D elements.  For a state (s, t) the first
-// ng(s) = floor(s / (r+1)) rows hold the gists at positions < s, compact and in order (gist g in row g);
-// the following t - s + 1 rows hold the positions s .. t (raw tokens and gists alike).  Every query at a
-// position >= t whose window starts at or after s sees exactly these rows.
+// na(s) rows hold the always-visible positions < s -- the sinks, then the gists -- compact and in order
+// (na(s) = floor(s / (r+1)) without sinks); the following t - s + 1 rows hold the positions s .. t (raw
+// tokens and gists alike).  Every query at a position >= t whose window starts at or after s sees exactly
+// these rows.
 //
 // cache_update builds the state (s_new, t_old + n_new) from the state (s_old, t_old) plus n_new freshly
 // computed rows (positions t_old+1 ..): a pure gather, one 16-byte chunk per lane, HBM bound
@@ -18,15 +19,16 @@ __global__ __launch_bounds__(256) void cache_update_kernel(const char* __restric
                                                           const char* __restrict__ k_new, const char* __restrict__ v_new,
                                                           char* __restrict__ kc_out, char* __restrict__ vc_out,
                                                           int s_old, int t_old, int cap_in, int new_rows, int s_new,
-                                                          int cap_out, int rows_out, int rp1, int row_bytes) {
+                                                          int cap_out, int rows_out, AttnShape lay, int row_bytes) {
     const int cpr = row_bytes / 16;                 // 16-byte chunks per row
     const int bh = blockIdx.y;
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const int n = (int)(idx / cpr), ch = (int)(idx % cpr);
     if (n >= rows_out) return;
-    const int ng_old = s_old / rp1, ng_new = s_new / rp1;
+    // `lay` carries the layout only (sink count and gist period)
+    const int ng_old = count_always(lay, s_old), ng_new = count_always(lay, s_new);
     // position held by output row n
-    const int pos = n < ng_new ? n * rp1 + rp1 - 1 : s_new + (n - ng_new);
+    const int pos = n < ng_new ? pos_of_always(lay, n) : s_new + (n - ng_new);
     const char *ks, *vs;
     size_t off;
     if (pos > t_old) {                              // one of the new rows
@@ -34,7 +36,7 @@ __global__ __launch_bounds__(256) void cache_update_kernel(const char* __restric
         ks = k_new;
         vs = v_new;
     } else {                                        // already cached: compact gist or window region
-        const int row = pos < s_old ? n /* gist n < ng_old keeps its row */ : ng_old + (pos - s_old);
+        const int row = pos < s_old ? n /* compact entry n < ng_old keeps its row */ : ng_old + (pos - s_old);
         off = ((size_t)bh * cap_in + row) * row_bytes;
         ks = kc_in;
         vs = vc_in;
@@ -48,17 +50,20 @@ __global__ __launch_bounds__(256) void cache_update_kernel(const char* __restric
 
 hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
                                const void* k_new, const void* v_new, int n_new, int new_rows, void* kc_out,
-                               void* vc_out, int s_new, int cap_out, int BH, int D, int rp1, int elem_bytes,
+                               void* vc_out, int s_new, int cap_out, int BH, int D, int rp1, int sinks, int elem_bytes,
                                hipStream_t st) {
+    AttnShape lay{};
+    lay.rp1 = rp1;
+    lay.S = sinks;
     const int t_new = t_old + n_new;
-    const int rows_out = s_new / rp1 + (t_new - s_new + 1);
+    const int rows_out = count_always(lay, s_new) + (t_new - s_new + 1);
     if (rows_out <= 0) return hipSuccess;
     const int row_bytes = D * elem_bytes;
     const long items = (long)rows_out * (row_bytes / 16);
     dim3 grid((unsigned)((items + 255) / 256), BH);
     cache_update_kernel<<<grid, 256, 0, st>>>((const char*)kc_in, (const char*)vc_in, (const char*)k_new,
                                               (const char*)v_new, (char*)kc_out, (char*)vc_out, s_old, t_old, cap_in,
-                                              new_rows, s_new, cap_out, rows_out, rp1, row_bytes);
+                                              new_rows, s_new, cap_out, rows_out, lay, row_bytes);
     return hipGetLastError();
 }
 

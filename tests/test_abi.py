@@ -96,6 +96,25 @@ def test_varlen_argument_validation():
         u.unigist_attn_bwd_workspace(1, 4, 2, 5000, 64, 4, 8, 0)
 
 
+def test_cache_ex_argument_validation():
+    assert u.unigist_cache_rows_ex(8, 12, 2, 2) == 9        # sinks 0 1, gists 4 7, positions 8 .. 12
+    assert u.unigist_cache_rows_ex(1, 5, 2, 4) == 6         # window start inside the sinks: everything is kept
+    assert u.unigist_cache_rows_ex(8, 12, 2, -1) == -1
+    assert u.unigist_cache_rows_ex(3, 5, 4, 0) == u.unigist_cache_rows(3, 5, 4)
+    ok = dict(kc_in=FAKE, vc_in=FAKE, s_old=0, t_old=9, cap_in=64, k_new=FAKE, v_new=FAKE, n_new=4, new_rows=4,
+              kc_out=FAKE, vc_out=FAKE, s_new=6, cap_out=64, B=1, Hkv=2, D=64, r=4, sinks=3, dt=0)
+    bad = dict(ok, sinks=-1)
+    assert u.unigist_cache_update_ex(*bad.values()) == 1
+    bad = dict(ok, cap_out=5)                                # 3 sinks + gist 7? no: always < 6 = 0 1 2; rows 3 + 8 > 5
+    assert u.unigist_cache_update_ex(*bad.values()) == 1
+    # prefill: unknown window mode, negative sinks, cache start right of the first query's window
+    pre = lambda **kw: u.unigist_prefill_chunk_ex(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 2, 64, 64, 4, 2,
+                                                  kw.get("sinks", 3), kw.get("mode", 1), 500, kw.get("s", 0), 4096, 0)
+    assert pre(mode=2) == 1 and pre(sinks=-1) == 1
+    # query 500 with 3 sinks, r = 4: unit (500 - 3) // 5 = 99, window starts at unit 97 = position 488
+    assert pre(s=489) == 1
+
+
 def test_decode_argument_validation():
     ok = dict(B=2, Hq=4, Hkv=2, Lk=100, D=128, dt=0)
     ws = u.unigist_decode_workspace(*ok.values())

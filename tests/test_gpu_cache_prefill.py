@@ -82,6 +82,71 @@ def test_chunkwise_prefill_equals_one_pass(B, Hq, Hkv, L, D, r, W, C):
     assert max_abs(to_np(o2), to_np(full_out[:, :, t])) <= 1.6e-2
 
 
+def _window_start(i, r, W, sinks, units):
+    if not units:
+        return max(0, i - W + 1)
+    if i < sinks:
+        return i
+    return sinks + max(0, (i - sinks) // (r + 1) - W) * (r + 1)
+
+
+@pytest.mark.parametrize("B,Hkv,D,r,L,sinks", [(2, 2, 128, 4, 700, 5), (1, 3, 64, 8, 513, 128), (1, 1, 128, 1, 64, 70)])
+def test_cache_updates_with_sinks_are_exact_gathers(B, Hkv, D, r, L, sinks):
+    _, k, v, _ = synth.attn_inputs(B, Hkv, Hkv, L, D, seed=23)
+    kd, vd = k.cuda(), v.cuda()
+    cache = u.KVCache(B, Hkv, L, D, r, sinks=sinks)
+    rng = np.random.default_rng(6)
+    while cache.t < L - 1:
+        n = int(min(L - 1 - cache.t, rng.choice([0, 1, 3, 64, 200])))
+        s_new = int(rng.integers(cache.s, cache.t + n + 2))
+        lo, hi = cache.t + 1, cache.t + 1 + n
+        cache.update(kd[:, :, lo:hi].contiguous() if n else None, vd[:, :, lo:hi].contiguous() if n else None, s_new)
+        pos = torch.from_numpy(oracle.cache_positions(cache.s, cache.t, r, sinks=sinks))
+        assert cache.rows == len(pos)
+        assert torch.equal(cache.kc[:, :, :cache.rows].cpu(), k[:, :, pos])
+        assert torch.equal(cache.vc[:, :, :cache.rows].cpu(), v[:, :, pos])
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,D,r,W,C,sinks,units", [
+    (1, 4, 1, 3000, 128, 4, 25, 512, 128, True),     # the paper's setting in small: 128 sinks, window of 25 units
+    (2, 4, 2, 2500, 128, 8, 110, 1000, 7, True),     # window longer than a chunk
+    (1, 2, 2, 1100, 64, 4, 100, 300, 33, False),     # sinks with the sliding window, D = 64
+    (1, 2, 1, 900, 128, 4, 3, 256, 300, True),       # the first chunk lies inside the sinks
+])
+def test_chunkwise_prefill_with_sinks_equals_one_pass(B, Hq, Hkv, L, D, r, W, C, sinks, units):
+    case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} C{C} sinks{sinks} units{int(units)}"
+    print("case", case, flush=True)
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=24)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    cache = u.KVCache(B, Hkv, L, D, r, sinks=sinks)
+    outs, lses = [], []
+    for p0 in range(0, L, C):
+        n = min(C, L - p0)
+        cache.update(kd[:, :, p0:p0 + n].contiguous(), vd[:, :, p0:p0 + n].contiguous(), _window_start(p0, r, W, sinks, units))
+        o, l = u.prefill_chunk(qd[:, :, p0:p0 + n].contiguous(), cache, r, W, p0, window_mode=int(units))
+        outs.append(o)
+        lses.append(l)
+    out, lse = torch.cat(outs, dim=2), torch.cat(lses, dim=2)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, sinks - 1, sinks, C - 1, C, min(L - 1, C + 1), L - 1],
+                                     np.random.default_rng(2).integers(0, L, 24)]))
+    for b, h in [(0, 0), (B - 1, Hq - 1)]:
+        g = h // (Hq // Hkv)
+        o, l = oracle.attn_fwd_rows(to_np(q[b, h]), to_np(k[b, g]), to_np(v[b, g]), rows, r, W, sinks=sinks, units=units)
+        assert max_abs(to_np(out[b, h])[rows], o) <= TOL_OUT_BF16, case
+        assert max_abs(to_np(lse[b, h])[rows], l) <= TOL_LSE_BF16, case
+    # decode the last position on the cache evicted down to its visible set
+    t = L - 1
+    cache.update(None, None, _window_start(t, r, W, sinks, units))
+    assert cache.rows == len(oracle.compressed_cache_positions(t, r, W, sinks=sinks, units=units))
+    sl = torch.full((B,), cache.rows, dtype=torch.int32, device="cuda")
+    o2, l2 = u.decode(qd[:, :, t].contiguous(), cache.kc, cache.vc, sl)
+    for b, h in [(0, 0), (B - 1, Hq - 1)]:
+        g = h // (Hq // Hkv)
+        o, l = oracle.attn_fwd_rows(to_np(q[b, h]), to_np(k[b, g]), to_np(v[b, g]), [t], r, W, sinks=sinks, units=units)
+        assert max_abs(to_np(o2[b, h]), o[0]) <= TOL_OUT_BF16 and abs(float(l2[b, h]) - l[0]) <= TOL_LSE_BF16
+
+
 def test_prefill_rejects_a_cache_that_dropped_too_much():
     B, Hq, Hkv, D, r, W, C, p0 = 1, 2, 1, 128, 4, 100, 64, 500
     cap = 1024
