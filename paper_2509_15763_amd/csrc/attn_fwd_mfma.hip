@@ -27,6 +27,7 @@ constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 32;   // keys per step
 constexpr int NT = 256;  // threads
 constexpr float kLazy = 8.f;  // slack of the softmax reference, in exp2 units
+constexpr float kBigSum = 16384.f;  // a partial row sum above this sends the step through the maximum search
 
 template <int D>
 struct FwdSmem {
@@ -103,6 +104,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 #pragma unroll
     for (int db = 0; db < DB; ++db) o[db] = zero16();
     float m = -INFINITY, l = 0.f;
+    bool need_max = true;  // until every row of the wave has a finite reference
     const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
 
     // ---- tile walk
@@ -212,43 +214,56 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
                     if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[kb2][i] = -INFINITY;
         }
 
-        // ---- online softmax (per query column = per lane, halves exchange once)
-        float mx = sa[0][0];
-#pragma unroll
-        for (int kb2 = 0; kb2 < NKB; ++kb2)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[kb2][i]);
-        mx = fmaxf(mx, other_half(mx));
-        // The reference m of the exponent only has to bound the scores from above within a fixed margin, not be
-        // their exact maximum: it is raised (and O, l rescaled) only when a row's maximum exceeds it by more than
-        // kLazy in exp2 units, so P <= 2^kLazy and, after the first tiles, almost no step rescales.  The result
-        // is the same quotient O / l.  A row that has seen nothing yet has m = -inf and grows on its first score;
-        // -inf - (-inf) is NaN and compares false.
-        const bool grow = (mx - m) * c > kLazy;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-            const float m_new = grow ? mx : m;
-            const float alpha = grow ? __builtin_amdgcn_exp2f((m - m_new) * c) : 1.f;  // m = -inf gives 0
-            l *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-            m = m_new;
-        }
-        const float mc = (m == -INFINITY ? 0.f : m) * c;  // rows with nothing visible so far: every P is exp2(-inf) = 0
-
-        // P = exp2(c S - c m): summed in fp32 for the row sum (lse stays fp32-accurate), rounded to bf16
-        // for the second MFMA
+        // ---- online softmax (per query column = per lane).  P = exp2(c S - c m) is summed in fp32 for the row
+        // sum (lse stays fp32-accurate) and rounded to bf16 for the second MFMA.  The reference m only has to
+        // bound the scores from above within a margin, not be their exact maximum, so the common step does not
+        // look for the maximum at all: it exponentiates against the current reference and only if a partial row
+        // sum comes out above 2^kBig (or not finite) -- some score exceeded the reference by a lot -- falls back
+        // to the step with the maximum.  The quotient O / l is the same either way.
         u32x4 pk[NKB][2];
+        float ls;
+        auto exps = [&](float mc) __attribute__((always_inline)) {
+            ls = 0.f;
 #pragma unroll
-        for (int kb2 = 0; kb2 < NKB; ++kb2)
+            for (int kb2 = 0; kb2 < NKB; ++kb2)
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
-                l += p0 + p1;
-                pk[kb2][i / 8][(i / 2) % 4] = pack_bf16x2(p0, p1);
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
+                    ls += p0 + p1;
+                    pk[kb2][i / 8][(i / 2) % 4] = pack_bf16x2(p0, p1);
+                }
+        };
+        bool with_max = need_max;  // wave-uniform: some row of the wave has no reference yet
+        if (!with_max) {
+            exps(m * c);
+            with_max = __builtin_amdgcn_ballot_w64(!(ls <= kBigSum)) != 0ull;
+        }
+        if (with_max) {
+            float mx = sa[0][0];
+#pragma unroll
+            for (int kb2 = 0; kb2 < NKB; ++kb2)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[kb2][i]);
+            mx = fmaxf(mx, other_half(mx));
+            // the reference is raised (and O, l rescaled) only when a row's maximum exceeds it by more than kLazy
+            // in exp2 units, so P <= 2^kLazy here.  A row that has seen nothing yet has m = -inf and grows on its
+            // first score; -inf - (-inf) is NaN and compares false.
+            const bool grow = (mx - m) * c > kLazy;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+                const float m_new = grow ? mx : m;
+                const float alpha = grow ? __builtin_amdgcn_exp2f((m - m_new) * c) : 1.f;  // m = -inf gives 0
+                l *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+                m = m_new;
             }
+            exps((m == -INFINITY ? 0.f : m) * c);  // rows with nothing visible so far: every P is exp2(-inf) = 0
+            need_max = __builtin_amdgcn_ballot_w64(m == -INFINITY) != 0ull;
+        }
+        l += ls;
 
         // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
 #pragma unroll
