@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1038159917, "dkdv_gist": 2315305902, "dkdv_window": 1536651994, "dq": 1395925855,
-                 "decode": 4567961286}
+TRAFFIC_BYTES = {"fwd": 1015236142, "dkdv_gist": 2318166520, "dkdv_window": 1526655975, "dq": 1397198270,
+                 "decode": 4567961701}
 
 
 def pair_counts(L, r, W):
