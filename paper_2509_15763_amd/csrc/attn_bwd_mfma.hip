@@ -500,16 +500,17 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict__ part, float* __restrict__ comp,
                                                         int n_gt, int nseg, int segc, int NC, AttnShape s,
                                                         int per_tile) {
-    // grid: x = slices of a tile's 2*D*BNK floats, y = tile, z = (b, hk)
+    // grid: x = slices of a tile's 2*D*BNK floats (four per thread, per_tile is a multiple of 4), y = tile,
+    // z = (b, hk).  The segments are added in ascending order, so the result does not depend on the launch.
     const int gt = blockIdx.y;
     const size_t t = (size_t)blockIdx.z * n_gt + gt;
-    const int idx = blockIdx.x * NT + threadIdx.x;
+    const int idx = 4 * (blockIdx.x * NT + threadIdx.x);
     if (idx >= per_tile) return;
     const int cf = first_chunk_with_more_far(s, NC, gt * BNK);
-    float acc = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if (cf < NC)
-        for (int sg = cf / segc; sg < nseg; ++sg) acc += part[(t * nseg + sg) * per_tile + idx];
-    comp[t * per_tile + idx] = acc;
+        for (int sg = cf / segc; sg < nseg; ++sg) acc += *(const f32x4*)(part + (t * nseg + sg) * per_tile + idx);
+    *(f32x4*)(comp + t * per_tile + idx) = acc;
 }
 
 // ------------------------------------------------------------------ 5. dQ
@@ -756,7 +757,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_GIST_REDUCE)) {
         const int per_tile = 2 * D * BNK;
-        gist_reduce_kernel<<<dim3((per_tile + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
+        gist_reduce_kernel<<<dim3((per_tile / 4 + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
             part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s, per_tile);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
