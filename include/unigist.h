@@ -15,7 +15,8 @@
  *
  * Conventions common to every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
- *     allocates and frees no device memory, keeps no state, does not synchronise:
+ *     allocates and frees no device memory, keeps no state (one exception: the
+ *     helper streams of the *_varlen calls, see there), does not synchronise:
  *     work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns at once.
  *   - Tensors are contiguous, head-major: q, out, dout, dq are [B, Hq, L, D];
@@ -146,8 +147,12 @@ size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r
  * document everything is as in unigist_attn_fwd / unigist_attn_bwd with L = its length: the gist period and
  * the window restart at the document's first token.  cu_seqlens is a HOST array of ndocs + 1 ints,
  * non-decreasing, cu_seqlens[0] = 0, cu_seqlens[ndocs] = T (UNIGIST_EINVAL otherwise); it is read before the
- * call returns.  Empty documents are allowed.  The documents are processed one after the other on the stream
- * and share the workspace (size from unigist_attn_bwd_varlen_workspace, 256-byte aligned).
+ * call returns.  Empty documents are allowed.  The documents are independent.  The forward launches one kernel
+ * per document on hip_stream.  The backward spreads the documents' kernel sequences over hip_stream and a few
+ * helper streams that the library creates once per device (default priority, kept until the process ends --
+ * the one piece of state this library holds); the helpers start after everything already enqueued on
+ * hip_stream and hip_stream continues after them, so the call behaves like work enqueued on hip_stream.
+ * workspace: size from unigist_attn_bwd_varlen_workspace (one slice per stream), 256-byte aligned.
  */
 unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
                                        int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,

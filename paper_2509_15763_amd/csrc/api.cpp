@@ -4,6 +4,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+#include <mutex>
+#include <vector>
+
 #include "common.h"
 
 using namespace unigist;
@@ -269,6 +273,83 @@ AttnShape doc_shape(int Hq, int Hkv, int T, int D, int r, int W, int len) {
 
 size_t elem_bytes(unigist_dtype dt) { return dt == UNIGIST_BF16 ? 2 : 4; }
 
+// The documents of a pack are independent, and a short document's kernels leave most of the chip idle.  Their
+// launch sequences are therefore spread over kLanes streams: lane 0 is the caller's stream, the others are
+// helper streams (default priority) created once per device and kept for the life of the process -- the only
+// state this library holds.  The helpers wait for the caller's stream before their first kernel and the
+// caller's stream waits for them after their last one, so to the caller the call still behaves like work
+// enqueued on its stream.  If the helpers cannot be created everything goes to the caller's stream.
+constexpr int kLanes = 4;
+
+struct Lanes {
+    bool tried = false, ok = false;
+    hipStream_t st[kLanes - 1];
+    hipEvent_t fork, join[kLanes - 1];
+};
+std::mutex g_lanes_mutex, g_enqueue_mutex;
+Lanes g_lanes[16];  // per device ordinal
+
+Lanes* helper_lanes() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    std::lock_guard<std::mutex> lock(g_lanes_mutex);
+    Lanes& l = g_lanes[dev];
+    if (!l.tried) {
+        l.tried = true;
+        bool ok = hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < kLanes - 1; ++i)
+            ok = hipStreamCreateWithFlags(&l.st[i], hipStreamNonBlocking) == hipSuccess &&
+                 hipEventCreateWithFlags(&l.join[i], hipEventDisableTiming) == hipSuccess;
+        l.ok = ok;
+        if (!ok) (void)hipGetLastError();  // fall back to the caller's stream alone
+    }
+    return l.ok ? &l : nullptr;
+}
+
+// documents in descending length, dealt round-robin to the lanes: lane_of[d], or -1 for an empty document
+int assign_lanes(const int* cu, int ndocs, int nlanes, std::vector<int>& order, std::vector<int>& lane_of) {
+    order.clear();
+    lane_of.assign(ndocs, -1);
+    for (int d = 0; d < ndocs; ++d)
+        if (cu[d + 1] > cu[d]) order.push_back(d);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+    const int used = (int)order.size() < nlanes ? (int)order.size() : nlanes;
+    for (size_t i = 0; i < order.size(); ++i) lane_of[order[i]] = (int)(i % (size_t)nlanes);
+    return used;
+}
+
+// run launch(d, stream, lane) for every non-empty document, longest first; with `spread` over the lanes, joined
+// back into `stream`, else all on `stream`
+template <typename F>
+unigist_status for_each_doc(const int* cu, int ndocs, hipStream_t stream, bool spread, F&& launch) {
+    std::vector<int> order, lane_of;
+    Lanes* l = spread ? helper_lanes() : nullptr;
+    const int nlanes = l ? kLanes : 1;
+    const int used = assign_lanes(cu, ndocs, nlanes, order, lane_of);
+    // the fork and join events are shared by all calls on a device: one host thread at a time enqueues
+    std::unique_lock<std::mutex> enqueue(g_enqueue_mutex, std::defer_lock);
+    if (used > 1) enqueue.lock();
+    if (used > 1) {
+        if (hipEventRecord(l->fork, stream) != hipSuccess) return UNIGIST_ELAUNCH;
+        for (int i = 1; i < used; ++i)
+            if (hipStreamWaitEvent(l->st[i - 1], l->fork, 0) != hipSuccess) return UNIGIST_ELAUNCH;
+    }
+    unigist_status rc = UNIGIST_OK;
+    for (int d : order) {
+        const int lane = lane_of[d];
+        if (launch(d, lane == 0 ? stream : l->st[lane - 1], lane) != hipSuccess) {
+            rc = UNIGIST_ELAUNCH;
+            break;
+        }
+    }
+    for (int i = 1; i < used; ++i)  // always join, also after a failed launch
+        if (hipEventRecord(l->join[i - 1], l->st[i - 1]) != hipSuccess ||
+            hipStreamWaitEvent(stream, l->join[i - 1], 0) != hipSuccess)
+            rc = UNIGIST_ELAUNCH;
+    return rc;
+}
+
 }  // namespace
 
 extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
@@ -277,28 +358,24 @@ extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, 
     unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
-    hipStream_t stream = (hipStream_t)hip_stream;
     const size_t eb = elem_bytes(dt);
-    for (int d = 0; d < ndocs; ++d) {
+    // one kernel per document, each of hundreds of workgroups whose tails overlap on one stream: measured faster
+    // than spreading them over streams
+    return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, false, [&](int d, hipStream_t stream, int) {
         const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
-        if (len == 0) continue;
         const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
         const size_t ro = (size_t)c0 * D * eb;  // byte offset of the document's first row inside a head
         const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
         char* od = (char*)out + ro;
-        hipError_t e;
-        if (dt == UNIGIST_BF16 && !plain_alu_forced())
-            e = launch_fwd_mfma(qd, kd, vd, od, lse + c0, s, stream);
-        else
-            e = launch_fwd_simple(qd, kd, vd, od, lse + c0, s, dt, stream);
-        if (e != hipSuccess) return UNIGIST_ELAUNCH;
-    }
-    return UNIGIST_OK;
+        if (dt == UNIGIST_BF16 && !plain_alu_forced()) return launch_fwd_mfma(qd, kd, vd, od, lse + c0, s, stream);
+        return launch_fwd_simple(qd, kd, vd, od, lse + c0, s, dt, stream);
+    });
 }
 
 extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                     int ndocs, unigist_dtype dt) {
     if (check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt) != UNIGIST_OK) return 0;
+    // one slice per lane, each large enough for the longest document that lane may get
     size_t need = 256;
     for (int d = 0; d < ndocs; ++d) {
         const int len = cu_seqlens[d + 1] - cu_seqlens[d];
@@ -306,7 +383,7 @@ extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int 
         const size_t n = unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt);
         if (n > need) need = n;
     }
-    return need;
+    return align256(need) * kLanes;
 }
 
 extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out,
@@ -317,26 +394,22 @@ extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, 
     unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
-    if (workspace_bytes < unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt))
-        return UNIGIST_EINVAL;
+    const size_t need = unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    if (workspace_bytes < need) return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
-    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t slice = need / kLanes;
     const size_t eb = elem_bytes(dt);
-    for (int d = 0; d < ndocs; ++d) {
+    // the documents of one lane run one after the other on its stream and share that lane's workspace slice
+    return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, true, [&](int d, hipStream_t stream, int lane) {
         const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
-        if (len == 0) continue;
         const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
         const size_t ro = (size_t)c0 * D * eb;
         const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
         const char *od = (const char*)out + ro, *gd = (const char*)dout + ro;
         char *dqd = (char*)dq + ro, *dkd = (char*)dk + ro, *dvd = (char*)dv + ro;
-        hipError_t e;
-        // the documents run one after the other on the stream, so they can share the workspace
+        char* ws = (char*)workspace + slice * lane;
         if (dt == UNIGIST_BF16 && !plain_alu_forced())
-            e = launch_bwd_mfma(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, workspace, s, UNIGIST_BWD_ALL, stream);
-        else
-            e = launch_bwd_simple(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, (float*)workspace, s, dt, stream);
-        if (e != hipSuccess) return UNIGIST_ELAUNCH;
-    }
-    return UNIGIST_OK;
+            return launch_bwd_mfma(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, ws, s, UNIGIST_BWD_ALL, stream);
+        return launch_bwd_simple(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, (float*)ws, s, dt, stream);
+    });
 }

@@ -128,3 +128,26 @@ def test_full_length_pack_sampled_rows_and_columns():
             gv += y
         assert rel_l2(to_np(dk[hk, a:b])[cols], gk) <= 2e-2
         assert rel_l2(to_np(dv[hk, a:b])[cols], gv) <= 2e-2
+
+
+def test_back_to_back_backward_calls_share_a_workspace():
+    # two backward calls enqueued without a synchronisation between them, on one workspace buffer, with
+    # different packs (more documents than streams in the first, fewer in the second): the second call's
+    # kernels may not start before the first call's have finished with the workspace
+    Hq, Hkv, D, r, W = 4, 2, 128, 4, 48
+    packs = [[600, 90, 1300, 257, 33, 410, 5], [2000, 300]]
+    ins, fwd = [], []
+    for n, lens in enumerate(packs):
+        q, k, v, dout = packed_inputs(Hq, Hkv, sum(lens), D, torch.bfloat16, seed=40 + n)
+        ins.append((q, k, v, dout))
+        qd, kd, vd, dod = (t.cuda() for t in (q, k, v, dout))
+        cu = [0] + np.cumsum(lens).tolist()
+        fwd.append((qd, kd, vd, dod, cu) + tuple(u.attn_fwd_varlen(qd, kd, vd, r, W, cu)))
+    need = max(u.unigist_attn_bwd_varlen_workspace(Hq, Hkv, f[4][-1], D, r, W, f[4], 0) for f in fwd)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    grads = [u.attn_bwd_varlen(qd, kd, vd, out, lse, dod, r, W, cu, workspace=ws) for qd, kd, vd, dod, cu, out, lse in fwd]
+    torch.cuda.synchronize()
+    for (q, k, v, dout), f, g in zip(ins, fwd, grads):
+        want = oracle_packed(q, k, v, dout, r, W, f[4])
+        check(f"docs{np.diff(f[4]).tolist()}", (f[5], f[6]) + tuple(g), want, torch.bfloat16)
