@@ -164,6 +164,15 @@ def main():
                 "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom),
                 "avg_ms": ms[dom], "alg_flops_per_launch": alg[dom]}
 
+    # what the matrix cores sustain on register-resident operands, outside the timed region: the chip is
+    # power-limited, so the rate with operands like the workload's (random) is below the published peak
+    g = torch.Generator(device="cpu").manual_seed(0)
+    probe = {}
+    for name, ops in (("random_operands", torch.randn(16384, generator=g)), ("constant_operands", torch.ones(16384))):
+        tf, mhz = u.probe_mfma_rate(ops.to(torch.bfloat16).to(dev))
+        probe[name] = {"tflops": tf, "clock_mhz": mhz}
+    roofline["frac_of_sustained_random_operand_rate"] = achieved / probe["random_operands"]["tflops"]
+
     # decode on its own workload, its own timed region
     dc = synth.WORKLOADS["cfg5_decode"]
     dq_, dk_, dv_ = synth.decode_inputs(dc["B"], dc["Hq"], dc["Hkv"], dc["Lk"], dc["D"], seed=0, device=dev)
@@ -221,6 +230,7 @@ def main():
                 "stage_ms": {n: ms[n] for n in stage_names}},
         "wall_ms_per_step": wall_ms,
         "roofline": roofline,
+        "mfma_sustained": probe,
         "decode": {"workload": "cfg5_decode", "ms": dec_ms, "roofline": {
             "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
             "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes}},

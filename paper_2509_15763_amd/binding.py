@@ -26,6 +26,7 @@ EXPORTS = [
     "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
+    "unigist_probe_mfma_rate",
 ]
 
 
@@ -102,6 +103,8 @@ def load():
     lib.unigist_cache_update.argtypes = [vp, vp, ip, ip, ip, vp, vp, ip, ip, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
     lib.unigist_prefill_chunk.restype = ip
     lib.unigist_prefill_chunk.argtypes = [vp, vp, vp, vp, fp] + [ip] * 10 + [ip, vp]
+    lib.unigist_probe_mfma_rate.restype = ip
+    lib.unigist_probe_mfma_rate.argtypes = [vp, vp, vp, ip, ip, vp]
     lib.unigist_tile_sizes.restype = None
     lib.unigist_tile_sizes.argtypes = [ip, ip, C.POINTER(ip), C.POINTER(ip)]
     _LIB = lib
@@ -234,6 +237,30 @@ def unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks,
 
 def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream=None) -> int:
     return load().unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream)
+
+
+def unigist_probe_mfma_rate(operands, clocks, sink, blocks, iters, stream=None) -> int:
+    return load().unigist_probe_mfma_rate(operands, clocks, sink, blocks, iters, stream)
+
+
+def probe_mfma_rate(operands, blocks=512, iters=100000):
+    """operands: 32 KiB of bf16 on the GPU -> (TFLOP/s, clock in MHz) of a register-resident MFMA loop."""
+    _dev(operands)
+    if operands.dtype != torch.bfloat16 or operands.numel() != 16384 or not operands.is_contiguous():
+        raise UnigistError("operands must be 16384 contiguous bf16 values")
+    clocks = torch.zeros(2 * blocks, dtype=torch.int64, device=operands.device)
+    sink = torch.zeros(1, dtype=torch.float32, device=operands.device)
+    run = lambda: _check(unigist_probe_mfma_rate(operands.data_ptr(), clocks.data_ptr(), sink.data_ptr(), blocks, iters,
+                                                 _stream()), "unigist_probe_mfma_rate")
+    run()  # lets the clock settle under this load
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    run()
+    e1.record()
+    torch.cuda.synchronize()
+    flops = blocks * 4 * iters * 8 * 2.0 * 32 * 32 * 16
+    c = clocks.view(blocks, 2).sum(0).tolist()
+    return flops / e0.elapsed_time(e1) / 1e9, 100.0 * c[0] / max(c[1], 1)
 
 
 def unigist_tile_sizes(D, dt):

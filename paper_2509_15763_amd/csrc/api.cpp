@@ -75,6 +75,13 @@ extern "C" void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn) {
     if (Bn) *Bn = dt == UNIGIST_BF16 ? 32 : 1;
 }
 
+extern "C" unigist_status unigist_probe_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks,
+                                                  int iters, void* hip_stream) {
+    if (!operands || !clocks || !sink || blocks < 1 || blocks > 65536 || iters < 1) return UNIGIST_EINVAL;
+    return launch_mfma_rate(operands, clocks, sink, blocks, iters, (hipStream_t)hip_stream) == hipSuccess ? UNIGIST_OK
+                                                                                                          : UNIGIST_ELAUNCH;
+}
+
 extern "C" unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                                            int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
                                            void* hip_stream) {

@@ -114,5 +114,6 @@ hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, 
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
                          float* ws, hipStream_t st);
+hipError_t launch_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters, hipStream_t st);
 
 }  // namespace unigist

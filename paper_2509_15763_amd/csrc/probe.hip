@@ -1,0 +1,52 @@
+// Measurement aid: the matrix-core rate the chip sustains on register-resident operands.
+//
+// Every wave runs a loop of v_mfma_f32_32x32x16_bf16 on four independent accumulators with operands it loaded
+// once from `operands`, so nothing but the matrix pipe is busy.  The rate depends on the operand values: the
+// chip is power-limited, and operands that toggle many bits (random data) lower the clock it holds.  The bench
+// reports this rate next to the published peak so that a kernel's fraction of either can be read off.
+#include "mfma_common.h"
+
+namespace unigist {
+namespace {
+
+constexpr int kProbeOperands = 2048;  // bf16x8 fragments in `operands` (32 KiB)
+
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict__ operands, long long* __restrict__ clocks,
+                                                        float* __restrict__ sink, int iters) {
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = operands[(threadIdx.x + 256 * i) % kProbeOperands];
+        b[i] = operands[(threadIdx.x + 256 * i + kProbeOperands / 2) % kProbeOperands];
+    }
+    f32x16 c0 = zero16(), c1 = zero16(), c2 = zero16(), c3 = zero16();
+    const long long t0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+        c0 = mfma32(a[0], b[0], c0);
+        c1 = mfma32(a[1], b[1], c1);
+        c2 = mfma32(a[2], b[2], c2);
+        c3 = mfma32(a[3], b[3], c3);
+        c0 = mfma32(a[1], b[2], c0);
+        c1 = mfma32(a[2], b[3], c1);
+        c2 = mfma32(a[3], b[0], c2);
+        c3 = mfma32(a[0], b[1], c3);
+    }
+    const long long t1 = clock64(), r1 = wall_clock64();
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s == 12345.678f) sink[0] = s;  // keeps the loop alive
+    if (threadIdx.x == 0) {
+        clocks[2 * blockIdx.x] = t1 - t0;      // shader clock cycles
+        clocks[2 * blockIdx.x + 1] = r1 - r0;  // ticks of the constant-rate counter
+    }
+}
+
+}  // namespace
+
+hipError_t launch_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters, hipStream_t st) {
+    mfma_rate_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16x8*)operands, clocks, sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace unigist

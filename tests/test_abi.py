@@ -172,3 +172,12 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk(*p.values()) == 1
     p.update(cap=1024, q=None)
     assert u.unigist_prefill_chunk(*p.values()) == 1
+
+
+def test_probe_argument_validation():
+    assert u.unigist_probe_mfma_rate(None, FAKE, FAKE, 1, 1) == 1
+    assert u.unigist_probe_mfma_rate(FAKE, None, FAKE, 1, 1) == 1
+    assert u.unigist_probe_mfma_rate(FAKE, FAKE, None, 1, 1) == 1
+    assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 0, 1) == 1
+    assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 65537, 1) == 1
+    assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 1, 0) == 1
