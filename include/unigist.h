@@ -48,7 +48,13 @@ typedef enum {
     UNIGIST_ELAUNCH = 3       /* HIP reported an error at launch */
 } unigist_status;
 
-typedef enum { UNIGIST_BF16 = 0, UNIGIST_F32 = 1 } unigist_dtype;
+/*
+ * Element types.  UNIGIST_E4M3 (one byte: E4M3 of the OCP 8-bit floating point format, bias 7, no infinities,
+ * largest magnitude 448) is a storage type of the compressed cache only: unigist_cache_update(_ex) moves it,
+ * unigist_quantize_e4m3 produces it, unigist_decode_e4m3 reads it; every other call answers
+ * UNIGIST_EUNSUPPORTED to it.
+ */
+typedef enum { UNIGIST_BF16 = 0, UNIGIST_F32 = 1, UNIGIST_E4M3 = 2 } unigist_dtype;
 
 /*
  * How the local window of Eq. 3 is counted (the *_ex entry points):
@@ -184,6 +190,26 @@ unigist_status unigist_decode(const void* q, const void* kcache, const void* vca
 size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt);
 
 /*
+ * The compressed cache stored in 8 bits (an extension of the decode step of Sec. 4.3, which the paper leaves
+ * in the model's dtype; decode streams the cache once from HBM, so halving its bytes halves the time).
+ * Storage: E4M3 codes with one positive scale per kv head for K and one for V, element = code * scale.
+ *
+ * unigist_quantize_e4m3: x [B, H, n, D] (dt_in = bf16 or fp32, DEVICE, 16-byte aligned) -> y, uint8 codes of the
+ * same shape: x / scale[h] in binary32 (one correctly rounded division), clamped to [-448, 448], rounded to the
+ * nearest E4M3 value, ties to even.  scale: DEVICE, H floats.  n may be 0.
+ *
+ * unigist_decode_e4m3: unigist_decode with bf16 q and out and with kcache, vcache [B, Hkv, Lk_max, D] holding
+ * E4M3 codes (8-byte aligned), k_scale, v_scale: DEVICE, Hkv floats each.  Same workspace as unigist_decode
+ * for bf16.  The cache itself is maintained by unigist_cache_update(_ex) with dt = UNIGIST_E4M3 on quantised rows.
+ */
+unigist_status unigist_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
+                                     unigist_dtype dt_in, void* hip_stream);
+unigist_status unigist_decode_e4m3(const void* q, const void* kcache, const void* vcache, const float* k_scale,
+                                   const float* v_scale, void* out, float* lse, int B, int Hq, int Hkv, int Lk_max,
+                                   const int* seqlens, int D, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream);
+
+/*
  * Compressed KV cache (Sec. 4.3, Fig. 4: raw tokens outside the local window are never attended to again
  * and can be dropped, chunk by chunk while prefilling and token by token while decoding).
  *
@@ -196,7 +222,7 @@ size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigi
  * ([B, Hkv, new_rows, D], positions t_old+1 .. t_old+n_new, n_new <= new_rows) -> state
  * (s_new, t_old + n_new) in kc_out/vc_out.  Requires 0 <= s_old <= s_new <= t_old + n_new + 1, t_old >= s_old - 1,
  * enough capacity, and out buffers that do not overlap the inputs.  kc_in/vc_in may be NULL for the empty
- * cache, k_new/v_new when n_new == 0.  A gather: bit-exact copies, both dtypes.
+ * cache, k_new/v_new when n_new == 0.  A gather: bit-exact copies, any dtype (UNIGIST_E4M3 included).
  */
 int unigist_cache_rows(int s, int t, int r);
 unigist_status unigist_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,

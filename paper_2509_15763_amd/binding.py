@@ -12,6 +12,7 @@ UNIGIST_BF16 = 0
 UNIGIST_F32 = 1
 BWD_STAGES = {"delta": 1, "dkdv_gist": 2, "gist_reduce": 4, "dkdv_window": 8, "dq": 16}
 UNIGIST_BWD_ALL = 31
+UNIGIST_E4M3 = 2  # storage type of the compressed cache only (uint8 tensors here)
 UNIGIST_WINDOW_SLIDING = 0
 UNIGIST_WINDOW_UNITS = 1
 
@@ -26,7 +27,7 @@ EXPORTS = [
     "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
-    "unigist_probe_mfma_rate",
+    "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3",
 ]
 
 
@@ -85,6 +86,10 @@ def load():
     lib.unigist_attn_bwd_varlen_workspace.argtypes = [ip] * 6 + [cup, ip, ip]
     lib.unigist_decode.restype = ip
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
+    lib.unigist_quantize_e4m3.restype = ip
+    lib.unigist_quantize_e4m3.argtypes = [vp, vp, vp, ip, ip, ip, ip, ip, vp]
+    lib.unigist_decode_e4m3.restype = ip
+    lib.unigist_decode_e4m3.argtypes = [vp, vp, vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, vp, sz, vp]
     lib.unigist_decode_workspace.restype = sz
     lib.unigist_decode_workspace.argtypes = [ip] * 5 + [ip]
     lib.unigist_blockmap_build.restype = ip
@@ -203,6 +208,14 @@ def unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, dt) -> in
 
 def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream=None) -> int:
     return load().unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream)
+
+
+def unigist_quantize_e4m3(x, y, scale, B, H, n, D, dt_in, stream=None) -> int:
+    return load().unigist_quantize_e4m3(x, y, scale, B, H, n, D, dt_in, stream)
+
+
+def unigist_decode_e4m3(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, ws_bytes, stream=None) -> int:
+    return load().unigist_decode_e4m3(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, ws_bytes, stream)
 
 
 def unigist_decode_workspace(B, Hq, Hkv, Lk, D, dt) -> int:
@@ -411,12 +424,62 @@ def decode(q, kcache, vcache, seqlens=None, want_lse=True, workspace=None):
     return out, lse
 
 
+def _scales(t, H):
+    _dev(t)
+    if t.dtype != torch.float32 or t.shape != (H,):
+        raise UnigistError("scales must be float32 [H] on the GPU")
+
+
+def quantize_e4m3(x, scale):
+    """x [B,H,n,D] bf16/fp32, scale float32 [H] on the GPU -> uint8 E4M3 codes of x / scale[h], same shape."""
+    _dev(x)
+    B, H, n, D = x.shape
+    _scales(scale, H)
+    y = torch.empty(x.shape, device=x.device, dtype=torch.uint8)
+    _check(unigist_quantize_e4m3(x.data_ptr(), y.data_ptr(), scale.data_ptr(), B, H, n, D, _dt(x), _stream()),
+           "unigist_quantize_e4m3")
+    return y
+
+
+def decode_e4m3(q, kcache, vcache, k_scale, v_scale, seqlens=None, want_lse=True, workspace=None):
+    """decode() over a cache of E4M3 codes (uint8 [B,Hkv,Lk,D]) with per-kv-head scales; q and out bf16."""
+    _dev(q, kcache, vcache, seqlens)
+    B, Hq, D = q.shape
+    Hkv, Lk = kcache.shape[1], kcache.shape[2]
+    if q.dtype != torch.bfloat16 or kcache.dtype != torch.uint8 or vcache.dtype != torch.uint8:
+        raise UnigistError("decode_e4m3 takes bf16 queries and uint8 caches")
+    if kcache.shape != (B, Hkv, Lk, D) or vcache.shape != kcache.shape:
+        raise UnigistError("q/kcache/vcache shapes disagree")
+    if seqlens is not None and (seqlens.dtype != torch.int32 or seqlens.shape != (B,)):
+        raise UnigistError("seqlens must be int32 [B]")
+    _scales(k_scale, Hkv)
+    _scales(v_scale, Hkv)
+    need = unigist_decode_workspace(B, Hq, Hkv, Lk, D, UNIGIST_BF16)
+    if need == 0:
+        raise UnigistError("unigist_decode_workspace: invalid or unsupported shape")
+    if workspace is None:
+        workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, device=q.device, dtype=torch.float32) if want_lse else None
+    _check(unigist_decode_e4m3(q.data_ptr(), kcache.data_ptr(), vcache.data_ptr(), k_scale.data_ptr(), v_scale.data_ptr(),
+                               out.data_ptr(), lse.data_ptr() if want_lse else None, B, Hq, Hkv, Lk,
+                               seqlens.data_ptr() if seqlens is not None else None, D,
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
+           "unigist_decode_e4m3")
+    return out, lse
+
+
 class KVCache:
     """Two ping-pong [B, Hkv, cap, D] buffers and the state (s, t) of the compressed cache; thin host-side
-    bookkeeping around unigist_cache_update (no arithmetic)."""
+    bookkeeping around unigist_cache_update (no arithmetic).  With dtype=torch.uint8 the cache holds E4M3 codes:
+    k_scale / v_scale (float32 [Hkv] on the GPU) are then required and update() quantises the rows it is given."""
 
-    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda", sinks=0):
+    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda", sinks=0, k_scale=None, v_scale=None):
         self.B, self.Hkv, self.cap, self.D, self.r, self.sinks = B, Hkv, cap, D, int(r), int(sinks)
+        self.k_scale, self.v_scale = k_scale, v_scale
+        if dtype == torch.uint8:
+            _scales(k_scale, Hkv)
+            _scales(v_scale, Hkv)
         self.k = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
         self.v = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
         self.cur, self.s, self.t = 0, 0, -1
@@ -438,12 +501,15 @@ class KVCache:
         n = 0 if k_new is None else k_new.shape[2]
         if n:
             _dev(k_new, v_new)
+            if self.k[0].dtype == torch.uint8 and k_new.dtype != torch.uint8:
+                k_new, v_new = quantize_e4m3(k_new, self.k_scale), quantize_e4m3(v_new, self.v_scale)
         s_new = self.s if s_new is None else int(s_new)
         nxt = 1 - self.cur
         _check(unigist_cache_update_ex(self.k[self.cur].data_ptr(), self.v[self.cur].data_ptr(), self.s, self.t,
                                        self.cap, k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
                                        self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), s_new, self.cap,
-                                       self.B, self.Hkv, self.D, self.r, self.sinks, _dt(self.k[0]), _stream()),
+                                       self.B, self.Hkv, self.D, self.r, self.sinks,
+                                       UNIGIST_E4M3 if self.k[0].dtype == torch.uint8 else _dt(self.k[0]), _stream()),
                "unigist_cache_update_ex")
         self.cur, self.s, self.t = nxt, s_new, self.t + n
 

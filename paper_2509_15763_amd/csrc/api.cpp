@@ -183,6 +183,34 @@ extern "C" unigist_status unigist_decode(const void* q, const void* kcache, cons
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
+extern "C" unigist_status unigist_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
+                                                unigist_dtype dt_in, void* hip_stream) {
+    if (B < 1 || H < 1 || n < 0 || D < 1) return UNIGIST_EINVAL;
+    if (dt_in != UNIGIST_BF16 && dt_in != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
+    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!scale || (n > 0 && (!x || !y))) return UNIGIST_EINVAL;
+    if (((uintptr_t)x & 15) != 0 || ((uintptr_t)y & 15) != 0) return UNIGIST_EINVAL;
+    hipError_t e = launch_quantize_e4m3(x, y, scale, B, H, n, D, dt_in, (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" unigist_status unigist_decode_e4m3(const void* q, const void* kcache, const void* vcache,
+                                              const float* k_scale, const float* v_scale, void* out, float* lse, int B,
+                                              int Hq, int Hkv, int Lk_max, const int* seqlens, int D, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || D < 1) return UNIGIST_EINVAL;
+    if (Hq % Hkv != 0) return UNIGIST_EINVAL;
+    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
+    if (!q || !kcache || !vcache || !k_scale || !v_scale || !out || !workspace) return UNIGIST_EINVAL;
+    if (workspace_bytes < unigist_decode_workspace(B, Hq, Hkv, Lk_max, D, UNIGIST_BF16)) return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    if (((uintptr_t)kcache & 7) != 0 || ((uintptr_t)vcache & 7) != 0) return UNIGIST_EINVAL;
+    hipError_t e = launch_decode_fp8(q, kcache, vcache, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk_max, seqlens, D,
+                                     (float*)workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
 extern "C" int unigist_cache_rows(int s, int t, int r) { return unigist_cache_rows_ex(s, t, r, 0); }
 
 extern "C" int unigist_cache_rows_ex(int s, int t, int r, int sinks) {
@@ -206,7 +234,7 @@ extern "C" unigist_status unigist_cache_update_ex(const void* kc_in, const void*
                                                   void* hip_stream) {
     if (B < 1 || Hkv < 1 || D < 1 || r < 1 || sinks < 0 || n_new < 0 || new_rows < n_new || cap_in < 0 || cap_out < 1)
         return UNIGIST_EINVAL;
-    if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
+    if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
     if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
     if (s_old < 0 || t_old < s_old - 1 || s_new < s_old) return UNIGIST_EINVAL;
     const long long t_new = (long long)t_old + n_new;
@@ -221,7 +249,7 @@ extern "C" unigist_status unigist_cache_update_ex(const void* kc_in, const void*
     const int rp1 = r >= kMaxL ? kMaxL + 1 : r + 1;
     hipError_t e = launch_cache_update(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                        vc_out, s_new, cap_out, B * Hkv, D, rp1, sinks > kMaxL ? kMaxL : sinks,
-                                       dt == UNIGIST_BF16 ? 2 : 4, (hipStream_t)hip_stream);
+                                       dt == UNIGIST_E4M3 ? 1 : dt == UNIGIST_BF16 ? 2 : 4, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 

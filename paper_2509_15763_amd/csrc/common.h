@@ -7,6 +7,9 @@
 namespace unigist {
 
 typedef uint16_t bf16_t;  // raw bf16 bits
+struct fp8_t {            // one E4M3 code (OCP 8-bit floating point: bias 7, no infinities, max 448)
+    uint8_t bits;
+};
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -114,6 +117,13 @@ hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, 
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
                          float* ws, hipStream_t st);
+// bf16 queries over a cache of E4M3 codes with one scale per kv head (device arrays of Hkv floats)
+hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
+                             void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
+                             float* ws, hipStream_t st);
+// y = e4m3(x / scale[head]) for x [B, H, n, D] (bf16 or fp32), 16 elements per lane
+hipError_t launch_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
+                                unigist_dtype dt_in, hipStream_t st);
 hipError_t launch_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters, hipStream_t st);
 
 }  // namespace unigist

@@ -57,6 +57,29 @@ template <int E> struct RowChunk<float, E> {
     }
 };
 
+// E4M3 codes -> float, two per v_cvt_pk_f32_fp8
+template <int E> struct RowChunk<fp8_t, E> {
+    static __device__ __forceinline__ void load(const fp8_t* p, float (&x)[E]) {
+        uint32_t r[E / 4];
+        if constexpr (E == 8) {
+            u32x2 t = *(const u32x2*)p;
+            r[0] = t[0];
+            r[1] = t[1];
+        } else {
+            r[0] = *(const uint32_t*)p;
+        }
+#pragma unroll
+        for (int t = 0; t < E / 4; ++t) {
+            f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)r[t], false);
+            f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)r[t], true);
+            x[4 * t] = lo[0];
+            x[4 * t + 1] = lo[1];
+            x[4 * t + 2] = hi[0];
+            x[4 * t + 3] = hi[1];
+        }
+    }
+};
+
 // sum over the 16 lanes of a DPP row; every lane ends with the total
 __device__ __forceinline__ float row16_sum(float x) {
     x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
@@ -66,10 +89,15 @@ __device__ __forceinline__ float row16_sum(float x) {
     return x;
 }
 
-// workspace layout per (b, hq, split): [m, l, acc[D]] floats
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restrict__ q, const T* __restrict__ kc,
+// workspace layout per (b, hq, split): [m, l, acc[D]] floats.
+// TQ: type of the queries; T: type the cache is stored in.  A cache of E4M3 codes comes with one scale per kv
+// head for K and for V (element = code * scale): the K scale is folded into the query, the V scale into the
+// slice's partial result.
+template <typename TQ, typename T, int D, int G, int U>
+__global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __restrict__ q, const T* __restrict__ kc,
                                                                const T* __restrict__ vc, const int* __restrict__ seqlens,
+                                                               const float* __restrict__ k_scale,
+                                                               const float* __restrict__ v_scale,
                                                                float* __restrict__ ws, int Hq, int Hkv, int Lk,
                                                                int nsplit, float scale) {
     constexpr int E = D / kLanesPerRow;
@@ -86,9 +114,11 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restr
     const int k1 = min(n, k0 + per);
 
     float qr[G][E], acc[G][E], m[G], l[G];
+    if (k_scale) scale *= k_scale[hk];
+    const float vmul = v_scale ? v_scale[hk] : 1.f;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        RowChunk<T, E>::load(q + ((size_t)b * Hq + hq0 + g) * D + sub * E, qr[g]);
+        RowChunk<TQ, E>::load(q + ((size_t)b * Hq + hq0 + g) * D + sub * E, qr[g]);
         m[g] = -INFINITY;
         l[g] = 0.f;
 #pragma unroll
@@ -100,11 +130,11 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restr
     const T* kb = kc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
     const T* vb = vc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
 
-    for (int base = k0; base < k1; base += kRowsPerIter * kUnroll) {
-        float kx[kUnroll][E], vx[kUnroll][E];
-        bool ok[kUnroll];
+    for (int base = k0; base < k1; base += kRowsPerIter * U) {
+        float kx[U][E], vx[U][E];
+        bool ok[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < U; ++u) {
             int row = base + u * kRowsPerIter + grp;
             ok[u] = row < k1;
             int rr = ok[u] ? row : k0;  // k0 < k1 <= n whenever this loop runs: always in bounds
@@ -112,7 +142,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restr
             RowChunk<T, E>::load(vb + (size_t)rr * D, vx[u]);
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float s = 0.f;
@@ -169,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const T* __restr
             o[0] = mm;
             o[1] = ll;
         }
-        o[2 + d] = a;
+        o[2 + d] = a * vmul;
     }
 }
 
@@ -190,24 +220,26 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
     if (lse && d == 0) lse[bh] = mm + __logf(ll);
 }
 
-template <typename T, int D>
-hipError_t decode_launch(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
-                         int Hkv, int Lk, const int* seqlens, float* ws, hipStream_t st) {
+template <typename TQ, typename T, int D>
+hipError_t decode_launch(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
+                         void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, float* ws,
+                         hipStream_t st) {
+    constexpr int U = kUnroll;
     const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
     const float scale = 1.0f / sqrtf((float)D);
     const int G = Hq / Hkv;
     if (G == 4) {
         dim3 grid(nsplit, Hkv, B);
-        decode_split_kernel<T, D, 4><<<grid, kThreads, 0, st>>>((const T*)q, (const T*)kc, (const T*)vc, seqlens, ws,
-                                                                Hq, Hkv, Lk, nsplit, scale);
+        decode_split_kernel<TQ, T, D, 4, U><<<grid, kThreads, 0, st>>>((const TQ*)q, (const T*)kc, (const T*)vc, seqlens,
+                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
     } else {
         dim3 grid(nsplit, Hq, B);
-        decode_split_kernel<T, D, 1><<<grid, kThreads, 0, st>>>((const T*)q, (const T*)kc, (const T*)vc, seqlens, ws,
-                                                                Hq, Hkv, Lk, nsplit, scale);
+        decode_split_kernel<TQ, T, D, 1, U><<<grid, kThreads, 0, st>>>((const TQ*)q, (const T*)kc, (const T*)vc, seqlens,
+                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_combine_kernel<T, D><<<B * Hq, D, 0, st>>>(ws, (T*)out, lse, nsplit);
+    decode_combine_kernel<TQ, D><<<B * Hq, D, 0, st>>>(ws, (TQ*)out, lse, nsplit);
     return hipGetLastError();
 }
 
@@ -229,10 +261,64 @@ int decode_num_splits(int B, int Hq, int Hkv, int Lk) {
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
                          int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt, float* ws, hipStream_t st) {
     if (dt == UNIGIST_F32)
-        return D == 64 ? decode_launch<float, 64>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                       : decode_launch<float, 128>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
-    return D == 64 ? decode_launch<bf16_t, 64>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                   : decode_launch<bf16_t, 128>(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+        return D == 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                       : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+    return D == 64 ? decode_launch<bf16_t, bf16_t, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                   : decode_launch<bf16_t, bf16_t, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+}
+
+hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
+                             void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
+                             float* ws, hipStream_t st) {
+    return D == 64 ? decode_launch<bf16_t, fp8_t, 64>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                   : decode_launch<bf16_t, fp8_t, 128>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Quantisation of new cache rows: y = e4m3(clamp(x / scale[head], -448, 448)), one correctly rounded binary32
+// division per element, conversion by v_cvt_pk_fp8_f32 (round to nearest even).  16 elements per lane.
+namespace {
+template <typename T>
+__global__ __launch_bounds__(256) void quantize_e4m3_kernel(const T* __restrict__ x, uint8_t* __restrict__ y,
+                                                           const float* __restrict__ scale, int H, long per_head,
+                                                           long nchunks) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nchunks) return;
+    const long e0 = idx * 16;
+    const float c = scale[(e0 / per_head) % H];
+    float f[2][8];
+    RowChunk<T, 8>::load(x + e0, f[0]);
+    RowChunk<T, 8>::load(x + e0 + 8, f[1]);
+    u32x4 w;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        float g[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float q = __fdiv_rn(f[t / 2][4 * (t % 2) + i], c);
+            g[i] = q != q ? q : fminf(fmaxf(q, -448.f), 448.f);
+        }
+        int p = 0;
+        p = __builtin_amdgcn_cvt_pk_fp8_f32(g[0], g[1], p, false);
+        p = __builtin_amdgcn_cvt_pk_fp8_f32(g[2], g[3], p, true);
+        w[t] = (uint32_t)p;
+    }
+    *(u32x4*)(y + e0) = w;
+}
+}  // namespace
+
+hipError_t launch_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
+                                unigist_dtype dt_in, hipStream_t st) {
+    const long per_head = (long)n * D;
+    const long nchunks = (long)B * H * per_head / 16;
+    if (nchunks <= 0) return hipSuccess;
+    const long blocks = (nchunks + 255) / 256;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    if (dt_in == UNIGIST_F32)
+        quantize_e4m3_kernel<float><<<dim3((unsigned)blocks), 256, 0, st>>>((const float*)x, (uint8_t*)y, scale, H, per_head, nchunks);
+    else
+        quantize_e4m3_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16_t*)x, (uint8_t*)y, scale, H, per_head, nchunks);
+    return hipGetLastError();
 }
 
 }  // namespace unigist

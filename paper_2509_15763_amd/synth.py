@@ -61,3 +61,12 @@ def ragged_seqlens(B, Lk, seed=0):
         s[0] = Lk
         s[1] = 1
     return s
+
+
+def e4m3_scales(H, seed=0, device="cpu"):
+    """One positive scale per kv head for K and one for V (float32 [H] each): about amax / 448 of unit-variance
+    data, different per head and not powers of two, so that the division has to round."""
+    g = _gen(seed, "cpu")
+    ks = (0.0093 + 0.004 * torch.rand(H, generator=g)).to(torch.float32)
+    vs = (0.0107 + 0.004 * torch.rand(H, generator=g)).to(torch.float32)
+    return ks.to(device), vs.to(device)

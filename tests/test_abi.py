@@ -181,3 +181,23 @@ def test_probe_argument_validation():
     assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 0, 1) == 1
     assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 65537, 1) == 1
     assert u.unigist_probe_mfma_rate(FAKE, FAKE, FAKE, 1, 0) == 1
+
+
+def test_e4m3_argument_validation():
+    q = u.unigist_quantize_e4m3
+    assert q(FAKE, FAKE, None, 1, 2, 3, 128, 0) == 1
+    assert q(None, FAKE, FAKE, 1, 2, 3, 128, 0) == 1
+    assert q(FAKE, FAKE, FAKE, 0, 2, 3, 128, 0) == 1
+    assert q(FAKE, FAKE, FAKE, 1, 2, 3, 96, 0) == 2
+    assert q(FAKE, FAKE, FAKE, 1, 2, 3, 128, 2) == 2            # E4M3 is not an input type
+    assert q(FAKE + 8, FAKE, FAKE, 1, 2, 3, 128, 0) == 1        # 16-byte alignment
+    d = u.unigist_decode_e4m3
+    ws = u.unigist_decode_workspace(2, 8, 2, 100, 128, 0)
+    good = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=None, B=2, Hq=8, Hkv=2, Lk=100,
+                seqlens=None, D=128, ws=FAKE, ws_bytes=ws)
+    for name, val, want in [("k_scale", None, 1), ("v_scale", None, 1), ("kc", None, 1), ("Hkv", 3, 1), ("D", 96, 2),
+                            ("ws_bytes", ws - 1, 1), ("ws", FAKE + 64, 1), ("kc", FAKE + 4, 1), ("B", 0, 1)]:
+        assert d(**{**good, name: val}) == want, name
+    # the attention calls do not take the storage type
+    assert u.unigist_attn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 2, 64, 128, 4, 8, 2) == 2
+    assert u.unigist_decode(FAKE, FAKE, FAKE, FAKE, None, 2, 8, 2, 100, None, 128, 2, FAKE, ws) == 2
