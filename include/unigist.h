@@ -199,7 +199,7 @@ size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigi
  * nearest E4M3 value, ties to even.  scale: DEVICE, H floats.  n may be 0.
  *
  * unigist_decode_e4m3: unigist_decode with bf16 q and out and with kcache, vcache [B, Hkv, Lk_max, D] holding
- * E4M3 codes (8-byte aligned), k_scale, v_scale: DEVICE, Hkv floats each.  Same workspace as unigist_decode
+ * E4M3 codes (q, kcache, vcache 16-byte aligned), k_scale, v_scale: DEVICE, Hkv floats each.  Same workspace as unigist_decode
  * for bf16.  The cache itself is maintained by unigist_cache_update(_ex) with dt = UNIGIST_E4M3 on quantised rows.
  */
 unigist_status unigist_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,

@@ -205,7 +205,7 @@ extern "C" unigist_status unigist_decode_e4m3(const void* q, const void* kcache,
     if (!q || !kcache || !vcache || !k_scale || !v_scale || !out || !workspace) return UNIGIST_EINVAL;
     if (workspace_bytes < unigist_decode_workspace(B, Hq, Hkv, Lk_max, D, UNIGIST_BF16)) return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
-    if (((uintptr_t)kcache & 7) != 0 || ((uintptr_t)vcache & 7) != 0) return UNIGIST_EINVAL;
+    if (((uintptr_t)kcache & 15) != 0 || ((uintptr_t)vcache & 15) != 0 || ((uintptr_t)q & 15) != 0) return UNIGIST_EINVAL;
     hipError_t e = launch_decode_fp8(q, kcache, vcache, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk_max, seqlens, D,
                                      (float*)workspace, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;

@@ -220,6 +220,190 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
     if (lse && d == 0) lse[bh] = mm + __logf(ll);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same slice kernel for a cache of E4M3 codes and bf16 queries.  With one byte per element the generic
+// kernel above is bound by its vector arithmetic, not by HBM, so this one spends less of it per element:
+//   * a lane takes 16 codes (one 16-byte load), so D/16 lanes share a row and the per-row work that every
+//     lane of a row repeats (reduction, softmax) is spread over twice as many elements;
+//   * the scores come from v_dot2c_f32_bf16 on packed pairs -- E4M3 values are exact in bf16 and the query
+//     already is bf16, so the products are the same numbers as before, two per instruction; the softmax
+//     scale and the K scale multiply the finished dot product;
+//   * P stays fp32 and the V codes are widened to fp32 for the accumulation.
+// The 256 / (D/16) row groups of a workgroup are folded in halves through LDS down to 16, then merged as above.
+template <int D, int G>
+__global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_t* __restrict__ q,
+                                                                    const uint8_t* __restrict__ kc,
+                                                                    const uint8_t* __restrict__ vc,
+                                                                    const int* __restrict__ seqlens,
+                                                                    const float* __restrict__ k_scale,
+                                                                    const float* __restrict__ v_scale,
+                                                                    float* __restrict__ ws, int Hq, int Hkv, int Lk,
+                                                                    int nsplit, float scale) {
+    constexpr int LPR = D / 16;            // lanes per row
+    constexpr int RPI = kThreads / LPR;    // row groups = rows per iteration
+    constexpr int U = 4;
+    constexpr int E = 16;
+    const int tid = threadIdx.x;
+    const int sub = tid % LPR, grp = tid / LPR;
+    const int split = blockIdx.x, b = blockIdx.z;
+    const int hq0 = blockIdx.y * G;
+    const int hk = hq0 / (Hq / Hkv);
+    const int n = seqlens ? seqlens[b] : Lk;
+    const int per = (((n + nsplit - 1) / nsplit) + kRowsPerIter - 1) / kRowsPerIter * kRowsPerIter;
+    const int k0 = split * per;
+    const int k1 = min(n, k0 + per);
+    const float sc = scale * k_scale[hk];
+
+    uint32_t qp[G][E / 2];  // packed bf16 pairs (elements 2j, 2j+1 of this lane's chunk)
+    float acc[G][E], m[G], l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const u32x4* p = (const u32x4*)(q + ((size_t)b * Hq + hq0 + g) * D + sub * E);
+        const u32x4 a = p[0], c = p[1];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            qp[g][t] = a[t];
+            qp[g][4 + t] = c[t];
+        }
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
+    }
+    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
+    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
+
+    for (int base = k0; base < k1; base += RPI * U) {
+        u32x4 kw[U], vw[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = base + u * RPI + grp;
+            ok[u] = row < k1;
+            const int rr = ok[u] ? row : k0;  // k0 < k1 <= n whenever this loop runs: always in bounds
+            kw[u] = *(const u32x4*)(kb + (size_t)rr * D);
+            vw[u] = *(const u32x4*)(vb + (size_t)rr * D);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t kp[E / 2];
+            float vf[E];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const f32x2 klo = __builtin_amdgcn_cvt_pk_f32_fp8((int)kw[u][t], false);
+                const f32x2 khi = __builtin_amdgcn_cvt_pk_f32_fp8((int)kw[u][t], true);
+                kp[2 * t] = pack_bf16x2(klo[0], klo[1]);
+                kp[2 * t + 1] = pack_bf16x2(khi[0], khi[1]);
+                const f32x2 vlo = __builtin_amdgcn_cvt_pk_f32_fp8((int)vw[u][t], false);
+                const f32x2 vhi = __builtin_amdgcn_cvt_pk_f32_fp8((int)vw[u][t], true);
+                vf[4 * t] = vlo[0];
+                vf[4 * t + 1] = vlo[1];
+                vf[4 * t + 2] = vhi[0];
+                vf[4 * t + 3] = vhi[1];
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < E / 2; ++j)
+                    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[j]),
+                                                        __builtin_bit_cast(bf16x2, qp[g][j]), s, false);
+                // sum over the LPR lanes of the row (lanes of one quad, then the neighbouring quad)
+                s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0xB1, 0xf, 0xf, false));
+                s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x4E, 0xf, 0xf, false));
+                if constexpr (LPR == 8)
+                    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x141, 0xf, 0xf, false));
+                s *= sc;
+                if (ok[u]) {
+                    if (s > m[g]) {
+                        const float a = __expf(m[g] - s);
+                        l[g] *= a;
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[g][e] *= a;
+                        m[g] = s;
+                    }
+                    const float p = __expf(s - m[g]);
+                    l[g] += p;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[g][e] += p * vf[e];
+                }
+            }
+        }
+    }
+
+    // fold the row groups in halves down to 16 of them: the upper half parks its state in LDS, the lower half
+    // merges it into its own
+    constexpr int HMAX = RPI / 2;
+    __shared__ float fm[G][HMAX];
+    __shared__ float fl[G][HMAX];
+    __shared__ float facc[G][HMAX][D];
+#pragma unroll
+    for (int half = HMAX; half >= kRowsPerIter; half /= 2) {
+        if (grp >= half && grp < 2 * half) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (sub == 0) {
+                    fm[g][grp - half] = m[g];
+                    fl[g][grp - half] = l[g];
+                }
+#pragma unroll
+                for (int e = 0; e < E; ++e) facc[g][grp - half][sub * E + e] = acc[g][e];
+            }
+        }
+        __syncthreads();
+        if (grp < half) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float m2 = fm[g][grp], l2 = fl[g][grp];
+                const float mm = fmaxf(m[g], m2);
+                if (mm > -INFINITY) {
+                    const float w1 = __expf(m[g] - mm), w2 = __expf(m2 - mm);  // exp(-inf) = 0 for a side that saw no key
+                    l[g] = w1 * l[g] + w2 * l2;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[g][e] = w1 * acc[g][e] + w2 * facc[g][grp][sub * E + e];
+                    m[g] = mm;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // the 16 remaining groups: merged as in the generic kernel (their states reuse the fold buffers)
+    if (grp < kRowsPerIter) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (sub == 0) {
+                fm[g][grp] = m[g];
+                fl[g][grp] = l[g];
+            }
+#pragma unroll
+            for (int e = 0; e < E; ++e) facc[g][grp][sub * E + e] = acc[g][e];
+        }
+    }
+    __syncthreads();
+    const float vmul = v_scale[hk];
+    for (int idx = tid; idx < G * D; idx += kThreads) {
+        const int g = idx / D, d = idx % D;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kRowsPerIter; ++t) mm = fmaxf(mm, fm[g][t]);
+        float ll = 0.f, a = 0.f;
+        if (mm > -INFINITY) {
+#pragma unroll
+            for (int t = 0; t < kRowsPerIter; ++t) {
+                const float w = __expf(fm[g][t] - mm);
+                ll += w * fl[g][t];
+                a += w * facc[g][t][d];
+            }
+        }
+        float* o = ws + (((size_t)b * Hq + hq0 + g) * nsplit + split) * (D + 2);
+        if (d == 0) {
+            o[0] = mm;
+            o[1] = ll;
+        }
+        o[2 + d] = a * vmul;
+    }
+}
+
 template <typename TQ, typename T, int D>
 hipError_t decode_launch(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
                          void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, float* ws,
@@ -270,8 +454,21 @@ hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* ou
 hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
                              void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
                              float* ws, hipStream_t st) {
-    return D == 64 ? decode_launch<bf16_t, fp8_t, 64>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                   : decode_launch<bf16_t, fp8_t, 128>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
+    const float scale = 1.0f / sqrtf((float)D);
+    const int G = Hq / Hkv;
+    const dim3 grid(nsplit, G == 4 ? Hkv : Hq, B);
+    auto go = [&](auto kern) {
+        kern<<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc, seqlens, k_scale, v_scale,
+                                        ws, Hq, Hkv, Lk, nsplit, scale);
+    };
+    if (D == 64) G == 4 ? go(decode_split_e4m3_kernel<64, 4>) : go(decode_split_e4m3_kernel<64, 1>);
+    else G == 4 ? go(decode_split_e4m3_kernel<128, 4>) : go(decode_split_e4m3_kernel<128, 1>);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
+    else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------

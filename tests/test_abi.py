@@ -196,7 +196,7 @@ def test_e4m3_argument_validation():
     good = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=None, B=2, Hq=8, Hkv=2, Lk=100,
                 seqlens=None, D=128, ws=FAKE, ws_bytes=ws)
     for name, val, want in [("k_scale", None, 1), ("v_scale", None, 1), ("kc", None, 1), ("Hkv", 3, 1), ("D", 96, 2),
-                            ("ws_bytes", ws - 1, 1), ("ws", FAKE + 64, 1), ("kc", FAKE + 4, 1), ("B", 0, 1)]:
+                            ("ws_bytes", ws - 1, 1), ("ws", FAKE + 64, 1), ("kc", FAKE + 8, 1), ("q", FAKE + 8, 1), ("B", 0, 1)]:
         assert d(**{**good, name: val}) == want, name
     # the attention calls do not take the storage type
     assert u.unigist_attn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 2, 64, 128, 4, 8, 2) == 2
