@@ -21,7 +21,8 @@ SOURCES = ["api.cpp", "blockmap.cpp", "attn_simple.hip", "attn_fwd_mfma.hip", "a
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-    # packed fp32 VALU ops are kept off on purpose (see the build notes of this library)
+    # packed fp32 VALU ops (v_pk_add/mul/fma_f32) are kept off on purpose: some of their forms have given wrong
+    # results on this hardware now and then; -O3 would otherwise form them from ordinary float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # keep MFMA accumulators in ordinary VGPRs: the softmax works on them with VALU ops, and
     # the AGPR form costs a copy in each direction per element

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 
-# Tolerances (see the arithmetic notes in the design document):
+# Tolerances:
 #   bf16 inputs, fp32 accumulation: max-abs error on out <= 1e-2, relative L2 error on
 #   dq/dk/dv <= 2e-2; fp32 debug build: <= 1e-5 for all of them.
 TOL_OUT_BF16 = 1e-2
