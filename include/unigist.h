@@ -157,7 +157,9 @@ size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r
  * per document on hip_stream.  The backward spreads the documents' kernel sequences over hip_stream and a few
  * helper streams that the library creates once per device (default priority, kept until the process ends --
  * the one piece of state this library holds); the helpers start after everything already enqueued on
- * hip_stream and hip_stream continues after them, so the call behaves like work enqueued on hip_stream.
+ * hip_stream and hip_stream continues after them, so the call behaves like work enqueued on hip_stream
+ * (under stream capture the helpers join the capture through those events; the streams themselves are
+ * created by the first backward call on a device, which therefore has to happen outside a capture).
  * workspace: size from unigist_attn_bwd_varlen_workspace (one slice per stream), 256-byte aligned.
  */
 unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
