@@ -1,5 +1,6 @@
 // C ABI of libunigist: argument validation and dispatch.  No device memory is
-// allocated here and nothing synchronises; kernels are enqueued on the caller's stream.
+// allocated here and nothing synchronises; kernels are enqueued on the caller's stream
+// (the packed backward also uses helper streams ordered behind and before it, see for_each_doc).
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
