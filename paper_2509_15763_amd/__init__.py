@@ -18,6 +18,6 @@ from .binding import (  # noqa: F401
     unigist_attn_fwd_varlen, unigist_attn_bwd_varlen, unigist_attn_bwd_varlen_workspace,
     attn_fwd_varlen, attn_bwd_varlen,
     unigist_cache_rows_ex, unigist_cache_update_ex, unigist_prefill_chunk_ex,
-    attn_fwd, attn_bwd, decode, n_vis, KVCache, prefill_chunk,
+    attn_fwd, attn_bwd, decode, n_vis, KVCache, RaggedKVCache, prefill_chunk,
 )
 from .autograd import gist_attention, gist_attention_varlen  # noqa: F401,E402

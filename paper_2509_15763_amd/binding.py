@@ -514,6 +514,45 @@ class KVCache:
         self.cur, self.s, self.t = nxt, s_new, self.t + n
 
 
+class RaggedKVCache:
+    """A batch of compressed caches whose sequences are in different states (s_b, t_b): one [B, Hkv, cap, D] buffer
+    pair as unigist_decode wants it, maintained one sequence at a time with unigist_cache_update_ex on that
+    sequence's slab (B = 1).  Host-side bookkeeping only; `seqlens()` is the int32 device vector decode takes."""
+
+    def __init__(self, B, Hkv, cap, D, r, dtype=torch.bfloat16, device="cuda", sinks=0):
+        self.B, self.Hkv, self.cap, self.D, self.r, self.sinks = B, Hkv, cap, D, int(r), int(sinks)
+        self.k = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
+        self.v = [torch.empty(B, Hkv, cap, D, device=device, dtype=dtype) for _ in range(2)]
+        self.cur = [0] * B           # which of the two buffers holds sequence b
+        self.s, self.t = [0] * B, [-1] * B
+
+    def rows(self, b) -> int:
+        return unigist_cache_rows_ex(self.s[b], self.t[b], self.r, self.sinks)
+
+    def update(self, b, k_new=None, v_new=None, s_new=None):
+        """Sequence b: append k_new/v_new ([Hkv, n, D], its next n positions), move its window start to s_new."""
+        n = 0 if k_new is None else k_new.shape[1]
+        if n:
+            _dev(k_new, v_new)
+        s_new = self.s[b] if s_new is None else int(s_new)
+        cur, nxt = self.cur[b], 1 - self.cur[b]
+        _check(unigist_cache_update_ex(self.k[cur][b].data_ptr(), self.v[cur][b].data_ptr(), self.s[b], self.t[b], self.cap,
+                                       k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
+                                       self.k[nxt][b].data_ptr(), self.v[nxt][b].data_ptr(), s_new, self.cap,
+                                       1, self.Hkv, self.D, self.r, self.sinks, _dt(self.k[0]), _stream()),
+               "unigist_cache_update_ex")
+        self.cur[b], self.s[b], self.t[b] = nxt, s_new, self.t[b] + n
+
+    def gathered(self):
+        """-> kc, vc [B, Hkv, cap, D] with every sequence's current slab in one buffer (sequences sitting in the
+        other buffer are moved over with an empty update), and seqlens int32 [B] on the GPU."""
+        for b in range(self.B):
+            if self.cur[b] != 0:
+                self.update(b)
+        sl = torch.tensor([self.rows(b) for b in range(self.B)], dtype=torch.int32).to(self.k[0].device)
+        return self.k[0], self.v[0], sl
+
+
 def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING):
     """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse."""
     _dev(q)

@@ -157,3 +157,29 @@ def test_prefill_rejects_a_cache_that_dropped_too_much():
     assert u.unigist_prefill_chunk(*args(p0 - W + 1)) == 0
     assert u.unigist_prefill_chunk(*args(p0 - W + 2)) == 1      # first query would miss a raw token
     torch.cuda.synchronize()
+
+
+def test_ragged_batch_of_caches_then_decode():
+    # sequences of one batch at different lengths and window starts: each slab is an exact gather of its own
+    # positions, and one decode call over the batch equals the oracle sequence by sequence
+    B, Hq, Hkv, D, r, W = 4, 8, 2, 128, 4, 48
+    lens = [700, 33, 412, 1]
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, max(lens), D, seed=25)
+    kd, vd = k.cuda(), v.cuda()
+    cache = u.RaggedKVCache(B, Hkv, max(lens), D, r)
+    rng = np.random.default_rng(9)
+    for b, n_b in enumerate(lens):
+        while cache.t[b] < n_b - 1:
+            n = int(min(n_b - 1 - cache.t[b], rng.choice([1, 2, 50, 300])))
+            lo, hi = cache.t[b] + 1, cache.t[b] + 1 + n
+            cache.update(b, kd[b, :, lo:hi].contiguous(), vd[b, :, lo:hi].contiguous(), max(0, hi - 1 - W + 1))
+    kc, vc, sl = cache.gathered()
+    qt = torch.stack([q[b, :, n_b - 1] for b, n_b in enumerate(lens)]).contiguous()      # each sequence's last position
+    out, lse = u.decode(qt.cuda(), kc, vc, sl)
+    torch.cuda.synchronize()
+    for b, n_b in enumerate(lens):
+        pos = oracle.compressed_cache_positions(n_b - 1, r, W)
+        assert int(sl[b]) == len(pos)
+        assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
+        o, l = oracle.decode(to_np(qt[b:b + 1]), to_np(k[b:b + 1][:, :, pos]), to_np(v[b:b + 1][:, :, pos]))
+        assert max_abs(to_np(out[b]), o[0]) <= TOL_OUT_BF16 and max_abs(to_np(lse[b]), l[0]) <= TOL_LSE_BF16
