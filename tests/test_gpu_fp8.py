@@ -54,6 +54,7 @@ def test_quantiser_is_bit_exact_on_cache_rows(B, H, n, D, dtype):
 CASES = [
     (3, 8, 2, 1000, 128, False), (3, 8, 2, 1000, 128, True), (2, 4, 4, 257, 64, True), (1, 32, 8, 5000, 128, False),
     (2, 6, 2, 300, 128, True), (1, 1, 1, 1, 64, False), (5, 16, 2, 77, 64, True),
+    (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
 ]
 
 
