@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ ou
 #pragma unroll
     for (int off = 1; off < LPR; off <<= 1) acc += __shfl_xor(acc, off, 64);
     if (row < nrows && sub == 0) {
-        delta[row] = acc;
+        delta[row] = -acc;               // stored negated: the consumers add it (dK/dV: as the dP accumulator's start)
         lse2[row] = lse[grow] * kLog2e;  // the exponent base the dK/dV and dQ kernels subtract
     }
 }
@@ -314,7 +314,15 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             // The fragment reads are issued PF k-steps ahead of the MFMAs that consume them; the scheduling
             // barriers keep the compiler from sinking them back to just before their use, where every MFMA
             // would wait for a full LDS round trip.
-            f32x16 sa = zero16(), dp = zero16();
+            // dP starts from -delta of its rows (the prepass stores delta negated), so dS = P (dP - delta) needs no
+            // subtraction afterwards
+            f32x16 sa = zero16(), dp;
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 8 * i4 + 4 * h]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) dp[4 * i4 + t] = d4[t];
+            }
             {
                 constexpr int PF = 2;
                 bf16x8 fq[KS], fg[KS];
@@ -369,11 +377,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                     if (!((vis >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
             }
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 8 * i4 + 4 * h]);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) dp[4 * i4 + t] = sa[4 * i4 + t] * (dp[4 * i4 + t] - d4[t]);
-            }
+            for (int i = 0; i < 16; ++i) dp[i] *= sa[i];
             // ---- dV^T += dO^T P,  dK^T += Q^T dS   (16 queries per MFMA)
             bf16x8 pb[2], sb[2];
 #pragma unroll
@@ -574,7 +578,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         }
     }
     const float ls = lse2[wrow];
-    const float dl = delta[wrow];
+    const float dl = delta[wrow];  // -delta of this lane's row
 
     f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
 #pragma unroll
@@ -682,7 +686,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
                     if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] = sa[i] * (dp[i] - dl);
+            for (int i = 0; i < 16; ++i) dp[i] = sa[i] * (dp[i] + dl);
             // dQ^T += K^T dS^T
             {
                 constexpr int N = 2 * DB;  // (kk, db) pairs
