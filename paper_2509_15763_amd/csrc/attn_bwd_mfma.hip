@@ -136,12 +136,13 @@ __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ ou
 // ------------------------------------------------------------------ 2./4. dK, dV
 template <int D>
 struct DkdvSmem {
-    // two stages of a 64-row Q chunk and dO chunk (rows unpadded, 16-byte chunks swizzled), plus the
-    // rows' lse * log2(e) and delta
-    char q[2][MQ * D * 2];
-    char g[2][MQ * D * 2];
+    // the rows' lse * log2(e) and -delta first: with the two 64 KB of tiles in front of them their addresses would
+    // not fit the 16-bit offset field of the LDS instructions and cost a vector instruction per read
     float lse2[2][MQ];
     float delta[2][MQ];
+    // two stages of a 64-row Q chunk and dO chunk (rows unpadded, 16-byte chunks swizzled)
+    char q[2][MQ * D * 2];
+    char g[2][MQ * D * 2];
 };
 
 // GEN = false (here and in dq_kernel) is the layout without sinks and with the sliding window: the mask
