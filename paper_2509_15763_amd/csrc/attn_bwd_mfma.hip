@@ -579,7 +579,19 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         }
     }
     const float ls = lse2[wrow];
-    const float dl = delta[wrow];  // -delta of this lane's row
+    // -delta of this lane's row in all 16 registers of an accumulator: dP starts from it (the MFMA adds its C
+    // operand for free), so dS = P (dP - delta) needs no subtraction.  The registers are made opaque so that they
+    // stay 16 registers instead of being rebuilt from one value at every use.
+    f32x16 ndl;
+    {
+        const float dl = delta[wrow];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float x = dl;
+            asm volatile("" : "+v"(x));
+            ndl[i] = x;
+        }
+    }
 
     f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
 #pragma unroll
@@ -659,7 +671,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             // S^T, dP^T for 32 keys: register i is key j0 + 32 kb2 + 8 (i/4) + 4h + i%4, lane = query
             // (fragment reads run PFS k-steps ahead of their MFMAs; the scheduling barriers keep them there)
-            f32x16 sa = zero16(), dp = zero16();
+            f32x16 sa = zero16(), dp = ndl;
             {
                 bf16x8 fk[KS], fv[KS];
 #pragma unroll
@@ -687,7 +699,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
                     if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] = sa[i] * (dp[i] + dl);
+            for (int i = 0; i < 16; ++i) dp[i] *= sa[i];
             // dQ^T += K^T dS^T
             {
                 constexpr int N = 2 * DB;  // (kk, db) pairs
