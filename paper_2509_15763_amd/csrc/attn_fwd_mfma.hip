@@ -9,19 +9,34 @@
 //   2. the contiguous key tiles from the window's first tile to the diagonal, where the
 //      full predicate is applied only on tiles that can contain an invisible pair.
 //
-// Work split: one workgroup = 128 query rows of one head, 4 waves x 32 rows; 64 keys
-// per step.  Scores are computed transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16,
-// so that one lane owns one query column: row max and row sum are in-lane reductions
-// plus one exchange between the wave's halves, and the accumulator registers of S^T are
-// already the B operand of O^T += V^T P^T.  V^T fragments come straight out of the
-// row-major V tile in LDS through ds_read_b64_tr_b16.  K/V tiles are staged with direct
-// global->LDS loads into two LDS stages (one barrier per step), 16-byte chunks swizzled.
+// Work split: one workgroup = 128 query rows of one head, 4 waves x 32 rows; 32 keys per step.
+// The matrix instruction is v_mfma_f32_16x16x32_bf16 (D = A * B + C, A 16 x 32, B 32 x 16).  With r16 = lane % 16
+// and g4 = lane / 16:
+//   A: lane holds A[r16][8 g4 .. 8 g4 + 7]      B: lane holds B[8 g4 .. 8 g4 + 7][r16]
+//   C/D: register i holds D[4 g4 + i][r16]
+// On random operands the chip, which is power-limited, sustains about 11 % more flops with this shape than with
+// 32x32x16; its A and B operands are half as large per flop, so every K and V fragment read from LDS is used
+// for the wave's two 16-row query blocks, which keeps the LDS and staging traffic per flop where it was.
+// Scores are computed transposed, S^T = K Q^T (A = K rows from LDS, B = Q in registers): a query is a column,
+// spread over the four lanes r16 + 16 g4, each of which holds 4 of every 16 keys; the running reference of the
+// softmax is kept identical on those four lanes and the row sum is a per-lane partial until the epilogue.  The
+// accumulator registers of S^T for two 16-key blocks are, after exponentiation and rounding, already the B
+// operand of O^T += V^T P^T with the contraction slot 8 g4 + 4 kb + i standing for key 16 kb + 4 g4 + i; the
+// matching A operand V^T comes straight out of the row-major V tile in LDS through two ds_read_b64_tr_b16 (rows
+// 4 g4 .. 4 g4 + 3 of either 16-key block).  K/V tiles are staged with direct global->LDS loads into two LDS
+// stages (one barrier per step), 16-byte chunks swizzled with a period of 16 rows.
 #include <type_traits>
 
 #include "mfma_common.h"
 
 namespace unigist {
 namespace {
+
+// Chunk swizzle of the K and V tiles: chunk ch of tile row r is stored at chunk position ch ^ swz16(r).  Its period
+// of 16 rows puts the 16 rows of a row-wise fragment read and the 4 rows of a transposing read on distinct banks;
+// the two transposing reads of a fragment lie 16 rows apart and so share one address register.
+template <int CH>
+__device__ __forceinline__ int swz16(int r) { return CH == 16 ? (r & 15) : ((r >> 1) & 7); }
 
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 32;   // keys per step
@@ -31,7 +46,7 @@ constexpr float kBigSum = 16384.f;  // a partial row sum above this sends the st
 
 template <int D>
 struct FwdSmem {
-    // two stages of a K tile and a V tile, rows unpadded, 16-byte chunks swizzled (see swz())
+    // two stages of a K tile and a V tile, rows unpadded, 16-byte chunks swizzled (see swz16())
     char k[2][BN * D * 2];
     char v[2][BN * D * 2];
 };
@@ -47,8 +62,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         s.S = 0;
         s.umode = 0;
     }
-    constexpr int KS = D / 16;            // k-steps of the score MFMA
-    constexpr int DB = D / 32;            // 32-row blocks of O^T
+    constexpr int KS = D / 32;            // k-steps of the score MFMA
+    constexpr int DB = D / 16;            // 16-row blocks of O^T
     constexpr int CH = D / 8;             // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // tile rows covered by one direct-load instruction
     constexpr int IPW = BN / RPI / 4;     // such instructions per wave, per matrix, per tile
@@ -57,7 +72,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
-    const int c32 = lane & 31, h = lane >> 5;
+    const int r16 = lane & 15, g4 = lane >> 4;  // MFMA 16x16x32: lane = (row or column r16, k-group g4)
 
     // ---- which (batch, head, query tile): heads of one kv group stay on one XCD, long tiles first
     const int G = s.Hq / s.Hkv;
@@ -85,25 +100,31 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const int qpos0 = s.qpos0, s0 = s.s0, ngb = s.ngb;
     const int i0 = qpos0 + qt * BM;
     const int i1 = min(L, i0 + BM) - 1;
-    const int qrow = i0 + 32 * w + c32;      // this lane's query row
-    const int qrow_ld = min(qrow, L - 1);    // rows past the end shadow the last row and are never stored
     const int wrow0 = i0 + 32 * w;           // first row of the wave
+    int qrow[2], qrow_ld[2];                 // this lane's two query rows (16-row blocks qb = 0, 1)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        qrow[qb] = wrow0 + 16 * qb + r16;
+        qrow_ld[qb] = min(qrow[qb], L - 1);  // rows past the end shadow the last row and are never stored
+    }
 
     const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
     const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
 
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow][16 ks + 8 h .. +7]
-    bf16x8 qf[KS];
-    {
-        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld - qpos0)) * D + 8 * h;
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow[qb]][32 ks + 8 g4 .. +7]
+    bf16x8 qf[2][KS];
+    f32x4 o[DB][2];   // O^T blocks: register i of o[db][qb] is d = 16 db + 4 g4 + i, column = query qrow[qb]
+    float m[2], l[2];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + 16 * ks);
+    for (int qb = 0; qb < 2; ++qb) {
+        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld[qb] - qpos0)) * D + 8 * g4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m[qb] = -INFINITY;
+        l[qb] = 0.f;
     }
-
-    f32x16 o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) o[db] = zero16();
-    float m = -INFINITY, l = 0.f;
     bool need_max = true;  // until every row of the wave has a finite reference
     const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
 
@@ -112,7 +133,9 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const int wstart = max((lo / BN) * BN, s0);  // first position of the window phase
     const int nfar = count_always(s, wstart);     // sinks and gists strictly left of the window phase
     const int ngt = (nfar + BN - 1) / BN;
-    const int span_q = qrow - win_lo(s, qrow);    // this lane's window reaches span_q positions back
+    int span_q[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) span_q[qb] = qrow[qb] - win_lo(s, qrow[qb]);  // the window reaches this far back
     const int lo_wlast = win_lo(s, wrow0 + 31);   // window start of the wave's last row
     const int nwin = (i1 - wstart) / BN + 1;
     const int ntiles = ngt + nwin;
@@ -122,7 +145,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const int wv = __builtin_amdgcn_readfirstlane(w);
     int choff[IPW];  // byte offset of the lane's (swizzled) chunk inside its row, per load slot
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow)) * 16;
     const int S = s.S;
     const char* kbytes = (const char*)kb;
     const char* vbytes = (const char*)vb;
@@ -150,131 +173,153 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     };
 
     // per-lane LDS offsets that do not depend on the tile
-    int koff[KS];  // row-wise read of K row c32 (+32), chunk 2 ks + h
+    int koff[KS];  // row-wise read of K row r16 (+16 kb), chunk 4 ks + g4
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = swz_off<CH>(c32, 2 * ks + h);
-    int voff[DB];  // transposing read of V, 32-column block db
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = r16 * (CH * 16) + (((4 * ks + g4) ^ swz16<CH>(r16)) << 4);
+    // transposing read of V: the 16 lanes of group g4 fetch the 4 x 16 block rows 4 g4 .. +3, columns 16 db .. +15:
+    // lane p passes the address of V[4 g4 + p/4][16 db + 4 (p%4)] and receives V[4 g4 .. +3][16 db + p]
+    int voff[DB];
 #pragma unroll
-    for (int db = 0; db < DB; ++db) voff[db] = tr_lane_off<CH>(db);
+    for (int db = 0; db < DB; ++db) {
+        const int rl = 4 * g4 + (r16 >> 2);
+        const int ch = 2 * db + ((r16 & 3) >> 1);
+        voff[db] = rl * (CH * 16) + ((ch ^ swz16<CH>(rl)) << 4) + (r16 & 1) * 8;
+    }
 
-    // one step of the walk on LDS stage BUF (a compile-time constant, so that every LDS address is a
-    // per-lane register plus an immediate)
     auto tile_step = [&](auto bufc, int it) {
         constexpr int BUF = decltype(bufc)::value;
         const char* kt = sm.k[BUF];
         const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
         const int j0 = gist_tile ? it * BN : wstart + (it - ngt) * BN;  // compact index or position
-        // a window tile entirely right of this wave's rows contributes nothing
         if (!gist_tile && j0 > wrow0 + 31) return;
 
-        // ---- S^T = K Q^T : two 32-key blocks
-        f32x16 sa[NKB];
+        // ---- S^T = K Q^T : sa[kb][qb] register i is key j0 + 16 kb + 4 g4 + i, column = query qrow[qb].
+        // The K fragments are read PFK groups ahead of the MFMAs that use them (each feeds both query blocks).
+        f32x4 sa[2][2];
+        {
+            constexpr int N = 2 * KS, PFK = 2;  // group n: key block n / KS, k-step n % KS
+            bf16x8 fk[N];
+            auto fetch = [&](int n) __attribute__((always_inline)) {
+                fk[n] = *(const bf16x8*)(kt + (n / KS) * 16 * CH * 16 + koff[n % KS]);
+            };
 #pragma unroll
-        for (int kb2 = 0; kb2 < NKB; ++kb2) {
-            sa[kb2] = zero16();
+            for (int n = 0; n < PFK; ++n) fetch(n);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 a = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + koff[ks]);
-                sa[kb2] = mfma32(a, qf[ks], sa[kb2]);
+            for (int n = 0; n < N; ++n) {
+                if (n + PFK < N) fetch(n + PFK);
+                const int kb = n / KS, ks = n % KS;
+                if (ks == 0) {
+                    sa[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk[n], qf[0][ks], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                    sa[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk[n], qf[1][ks], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                } else {
+                    sa[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk[n], qf[0][ks], sa[kb][0], 0, 0, 0);
+                    sa[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk[n], qf[1][ks], sa[kb][1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 
-        // ---- mask.  Accumulator element i of block kb2 is key  j0 + 32 kb2 + 8 (i/4) + 4 h + i%4; bit
-        // 8 (i/4) + i%4 of vis[kb2] says whether this lane's query sees it.  Visible sets are bit ranges
-        // (the tail of the compact list; the window) plus, in the window phase, the sinks and gists.
+        // ---- mask.  Bit t of vis[qb]: does query qrow[qb] see the key at offset t from j0?  This lane holds the
+        // offsets 16 kb + 4 g4 + i.
         bool masked;
-        unsigned vis[NKB];
-        auto below = [](int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; };  // bits 0 .. n-1
-        if (gist_tile) {
-            masked = j0 + BN > nfar;  // tail of the compact list
+        if (gist_tile) masked = j0 + BN > nfar;
+        else masked = !(j0 + BN - 1 <= wrow0 && j0 >= lo_wlast);
+        if (masked) {
+            auto below = [](int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; };  // bits 0 .. n-1
+            unsigned gm = 0u;
+            if (!gist_tile) gm = (unsigned)__builtin_amdgcn_ballot_w64(lane < BN && is_always(s, j0 + lane));
 #pragma unroll
-            for (int kb2 = 0; kb2 < NKB; ++kb2) vis[kb2] = below(nfar - j0 - 4 * h - 32 * kb2);
-        } else {
-            // unmasked iff all keys are causal for the wave's first row and in the window of its last row
-            masked = !(j0 + BN - 1 <= wrow0 && j0 >= lo_wlast);
-            if (masked) {
-                // bit t of gm: key j0 + 4h + t holds a sink or a gist.  One modulo per lane, shared by ballot.
-                const unsigned long long gbits = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
-                const unsigned long long gm = gbits >> (4 * h);
-                const int d0 = qrow - (j0 + 4 * h);  // distance to the lane's first key
-#pragma unroll
-                for (int kb2 = 0; kb2 < NKB; ++kb2) {
-                    const int d = d0 - 32 * kb2;  // offsets d - span_q .. d are in the window, offsets <= d causal
-                    const unsigned causal = below(d + 1);
-                    vis[kb2] = (causal & ~below(d - span_q)) | (causal & (unsigned)(gm >> (32 * kb2)));
+            for (int qb = 0; qb < 2; ++qb) {
+                unsigned vis;
+                if (gist_tile) {
+                    vis = below(nfar - j0);
+                } else {
+                    const int d0 = qrow[qb] - j0;  // offsets d0 - span_q .. d0 are in the window, offsets <= d0 causal
+                    vis = below(d0 + 1) & (~below(d0 - span_q[qb]) | gm);
                 }
+                vis >>= 4 * g4;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (!((vis >> (16 * kb + i)) & 1u)) sa[kb][qb][i] = -INFINITY;
             }
         }
-        if (masked) {
-#pragma unroll
-            for (int kb2 = 0; kb2 < NKB; ++kb2)
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[kb2][i] = -INFINITY;
-        }
 
-        // ---- online softmax (per query column = per lane).  P = exp2(c S - c m) is summed in fp32 for the row
-        // sum (lse stays fp32-accurate) and rounded to bf16 for the second MFMA.  The reference m only has to
-        // bound the scores from above within a margin, not be their exact maximum, so the common step does not
-        // look for the maximum at all: it exponentiates against the current reference and only if a partial row
-        // sum comes out above 2^kBig (or not finite) -- some score exceeded the reference by a lot -- falls back
-        // to the step with the maximum.  The quotient O / l is the same either way.
-        u32x4 pk[NKB][2];
-        float ls;
-        auto exps = [&](float mc) __attribute__((always_inline)) {
-            ls = 0.f;
+        // ---- online softmax: a query row is spread over the 4 lanes r16 + 16 g4 (4 keys of every 16 each), so the
+        // reference m[qb] is kept identical on those lanes and the row sum l[qb] is a per-lane partial
+        u32x4 pk[2];
+        float ls[2];
+        auto exps = [&](int qb, float mc) __attribute__((always_inline)) {
+            float p[8];
 #pragma unroll
-            for (int kb2 = 0; kb2 < NKB; ++kb2)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i + 1], c, -mc));
-                    ls += p0 + p1;
-                    pk[kb2][i / 8][(i / 2) % 4] = pack_bf16x2(p0, p1);
-                }
+                for (int i = 0; i < 4; ++i) p[4 * kb + i] = __builtin_amdgcn_exp2f(fmaf(sa[kb][qb][i], c, -mc));
+            ls[qb] = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+#pragma unroll
+            for (int t = 0; t < 4; ++t) pk[qb][t] = pack_bf16x2(p[2 * t], p[2 * t + 1]);
         };
-        bool with_max = need_max;  // wave-uniform: some row of the wave has no reference yet
+        bool with_max = need_max;
         if (!with_max) {
-            exps(m * c);
-            with_max = __builtin_amdgcn_ballot_w64(!(ls <= kBigSum)) != 0ull;
+            exps(0, m[0] * c);
+            exps(1, m[1] * c);
+            with_max = __builtin_amdgcn_ballot_w64(!(ls[0] <= kBigSum) || !(ls[1] <= kBigSum)) != 0ull;
         }
         if (with_max) {
-            float mx = sa[0][0];
+            bool any_inf = false;
 #pragma unroll
-            for (int kb2 = 0; kb2 < NKB; ++kb2)
+            for (int qb = 0; qb < 2; ++qb) {
+                float mx = sa[0][qb][0];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sa[kb2][i]);
-            mx = fmaxf(mx, other_half(mx));
-            // the reference is raised (and O, l rescaled) only when a row's maximum exceeds it by more than kLazy
-            // in exp2 units, so P <= 2^kLazy here.  A row that has seen nothing yet has m = -inf and grows on its
-            // first score; -inf - (-inf) is NaN and compares false.
-            const bool grow = (mx - m) * c > kLazy;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-                const float m_new = grow ? mx : m;
-                const float alpha = grow ? __builtin_amdgcn_exp2f((m - m_new) * c) : 1.f;  // m = -inf gives 0
-                l *= alpha;
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sa[kb][qb][i]);
+                mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const bool grow = (mx - m[qb]) * c > kLazy;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+                    const float m_new = grow ? mx : m[qb];
+                    const float alpha = grow ? __builtin_amdgcn_exp2f((m[qb] - m_new) * c) : 1.f;  // m = -inf gives 0
+                    l[qb] *= alpha;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-                m = m_new;
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[db][qb][i] *= alpha;
+                    m[qb] = m_new;
+                }
+                exps(qb, (m[qb] == -INFINITY ? 0.f : m[qb]) * c);
+                any_inf = any_inf || m[qb] == -INFINITY;
             }
-            exps((m == -INFINITY ? 0.f : m) * c);  // rows with nothing visible so far: every P is exp2(-inf) = 0
-            need_max = __builtin_amdgcn_ballot_w64(m == -INFINITY) != 0ull;
+            need_max = __builtin_amdgcn_ballot_w64(any_inf) != 0ull;
         }
-        l += ls;
+        l[0] += ls[0];
+        l[1] += ls[1];
 
-        // ---- O^T += V^T P^T : 16 keys per MFMA, A operand by transposing LDS reads
+        // ---- O^T += V^T P^T : contraction slot 8 g4 + 4 kb + i is key 16 kb + 4 g4 + i, on both operands.
+        // The V^T fragments (two transposing reads each) run PFV blocks ahead of their MFMAs.
+        {
+            constexpr int PFV = 2;
+            s16x4 lo[DB], hi[DB];
+            auto fetch = [&](int db) __attribute__((always_inline)) {
+                const char* a = vt + voff[db];
+                lo[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)a);
+                hi[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 16 * CH * 16));
+            };
 #pragma unroll
-        for (int kb2 = 0; kb2 < NKB; ++kb2)
+            for (int db = 0; db < PFV; ++db) fetch(db);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[kb2][kk]);
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    o[db] = mfma32(tr16_frag_at<CH>(vt + voff[db], 32 * kb2 + 16 * kk), pb, o[db]);
+            for (int db = 0; db < DB; ++db) {
+                if (db + PFV < DB) fetch(db + PFV);
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[db], hi[db], 0, 1, 2, 3, 4, 5, 6, 7));
+                o[db][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, __builtin_bit_cast(bf16x8, pk[0]), o[db][0], 0, 0, 0);
+                o[db][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, __builtin_bit_cast(bf16x8, pk[1]), o[db][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
     };
 
     issue(0, 0);
@@ -291,22 +336,25 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         }
     }
 
-    // ---- epilogue: normalise, store O (row qrow, d = 32 db + 8 (i/4) + 4 h + i%4) and LSE
-    const float lt = l + other_half(l);
-    const float inv = 1.f / lt;
-    if (qrow < L) {
-        const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow - qpos0);
-        bf16_t* op = out + orow * D + 4 * h;
+    // ---- epilogue: the row sums are spread over the 4 lanes of a query; normalise, store O and LSE
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < 2; ++qb) {
+        float lt = l[qb];
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        const float inv = 1.f / lt;
+        if (qrow[qb] < L) {
+            const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow[qb] - qpos0);
+            bf16_t* op = out + orow * D + 4 * g4;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
+            for (int db = 0; db < DB; ++db) {
                 u32x2 w2;
-                w2[0] = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-                w2[1] = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-                *(u32x2*)(op + 32 * db + 8 * i4) = w2;
+                w2[0] = pack_bf16x2(o[db][qb][0] * inv, o[db][qb][1] * inv);
+                w2[1] = pack_bf16x2(o[db][qb][2] * inv, o[db][qb][3] * inv);
+                *(u32x2*)(op + 16 * db) = w2;
             }
-        if (h == 0) lse[orow] = m * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
+            if (g4 == 0) lse[orow] = m[qb] * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
+        }
     }
 }
 
