@@ -33,7 +33,7 @@ constexpr int BNK = 128;  // keys per dkdv workgroup
 constexpr int MQ = 64;    // query rows per dkdv step
 constexpr int BMQ = 128;  // query rows per dq workgroup
 constexpr int BNQ = 64;   // keys per dq step
-constexpr int PFS = 2, PFT = 3;  // dq: LDS fragment reads issued this many MFMA groups ahead (S/dP phase, dQ phase)
+constexpr int PFS = 2, PFT = 2;  // dq: LDS fragment reads issued this many MFMA groups ahead (S/dP phase, dQ phase)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // bits 0 .. n-1 set (none for n <= 0, all for n >= 32)
@@ -536,13 +536,13 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         s.S = 0;
         s.umode = 0;
     }
-    constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
+    constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // 16x16x32 MFMA: k-steps of 32, 16-row blocks of dQ^T
     constexpr int RPI = 64 / CH;
     constexpr int IPW = BNQ / RPI / 4;
     __shared__ __attribute__((aligned(1024))) DqSmem<D> sm;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int c32 = lane & 31, h = lane >> 5;
+    const int g4 = lane >> 4;  // with r16 = lane % 16: the lane's place in a 16x16x32 operand
     const int G = s.Hq / s.Hkv, NP = s.B * s.Hkv;
     int n = blockIdx.x, g, pr, qt;
     if ((NP & 7) == 0) {
@@ -561,41 +561,46 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int b = pr / s.Hkv, hk = pr % s.Hkv, hq = hk * G + g;
     const int L = s.L, rp1 = s.rp1;
     const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
-    const int qrow = i0 + 32 * w + c32, qrow_ld = min(qrow, L - 1), wrow0 = i0 + 32 * w;
+    const int wrow0 = i0 + 32 * w;  // first row of the wave; the lane's two rows are wrow0 + 16 qb + r16
     const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
     const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
     const float c = s.scale * kLog2e;
 
-    bf16x8 qf[KS], gf[KS];
-    const size_t rowoff = ((size_t)b * s.Hq + hq) * s.qhs + qrow_ld;  // in the caller's tensors
-    const size_t wrow = ((size_t)b * s.Hq + hq) * L + qrow_ld;        // in the dense workspace
-    {
-        const bf16_t* qp = q + rowoff * D + 8 * h;
-        const bf16_t* gp = dout + rowoff * D + 8 * h;
+    // B operands Q and dO of this lane's two query rows, their lse * log2(e), and -delta in the 4 registers of an
+    // accumulator: dP starts from it (the MFMA adds its C operand for free), so dS = P (dP - delta) needs no
+    // subtraction.  The registers are made opaque so that they stay 4 registers instead of being rebuilt from one
+    // value at every use.
+    int qrow[2], span_q[2];
+    size_t rowoff[2];
+    bf16x8 qf[2][KS], gf[2][KS];
+    float ls[2];
+    f32x4 ndl[2];
+    f32x4 acc[DB][2];  // dQ^T: register i of acc[db][qb] is d = 16 db + 4 g4 + i, column = query qrow[qb]
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        qrow[qb] = wrow0 + 16 * qb + (lane & 15);
+        const int qrow_ld = min(qrow[qb], L - 1);
+        span_q[qb] = qrow[qb] - win_lo(s, qrow[qb]);  // this row's window reaches span_q positions back
+        rowoff[qb] = ((size_t)b * s.Hq + hq) * s.qhs + qrow_ld;           // in the caller's tensors
+        const size_t wrow = ((size_t)b * s.Hq + hq) * L + qrow_ld;        // in the dense workspace
+        const bf16_t* qp = q + rowoff[qb] * D + 8 * g4;
+        const bf16_t* gp = dout + rowoff[qb] * D + 8 * g4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            qf[ks] = *(const bf16x8*)(qp + 16 * ks);
-            gf[ks] = *(const bf16x8*)(gp + 16 * ks);
+            qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
+            gf[qb][ks] = *(const bf16x8*)(gp + 32 * ks);
         }
-    }
-    const float ls = lse2[wrow];
-    // -delta of this lane's row in all 16 registers of an accumulator: dP starts from it (the MFMA adds its C
-    // operand for free), so dS = P (dP - delta) needs no subtraction.  The registers are made opaque so that they
-    // stay 16 registers instead of being rebuilt from one value at every use.
-    f32x16 ndl;
-    {
+        ls[qb] = lse2[wrow];
         const float dl = delta[wrow];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 4; ++i) {
             float x = dl;
             asm volatile("" : "+v"(x));
-            ndl[i] = x;
+            ndl[qb][i] = x;
         }
-    }
-
-    f32x16 acc[DB];  // dQ^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4, lane = query
 #pragma unroll
-    for (int db = 0; db < DB; ++db) acc[db] = zero16();
+        for (int db = 0; db < DB; ++db) acc[db][qb] = zero4();
+    }
 
     const int lo = win_lo(s, i0);
     const int wstart = (lo / BNQ) * BNQ;          // first position of the window phase
@@ -603,7 +608,6 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int ngt = (nfar + BNQ - 1) / BNQ;
     const int nwin = (i1 - wstart) / BNQ + 1;
     const int ntiles = ngt + nwin;
-    const int span_q = qrow - win_lo(s, qrow);     // this lane's window reaches span_q positions back
     const int lo_wlast = win_lo(s, wrow0 + 31);    // window start of the wave's last row
     const int S = s.S;
 
@@ -612,7 +616,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int wv = __builtin_amdgcn_readfirstlane(w);
     int choff[IPW];
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow)) * 16;
     auto issue = [&](int it, int buf) {
         const bool gphase = it < ngt;
 #pragma unroll
@@ -630,12 +634,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
         }
     };
-    int roff[KS];  // row-wise read of tile row c32 (+32), chunk 2 ks + h
+    int roff[KS];  // row-wise read of tile row r16 (+16, +32, +48), chunk 4 ks + g4
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) roff[ks] = swz_off<CH>(c32, 2 * ks + h);
-    int toff[DB];  // transposing read of K, 32-column block db
+    for (int ks = 0; ks < KS; ++ks) roff[ks] = row16_lane_off<CH>(ks);
+    int toff[DB];  // transposing read of K, 16-column block db
 #pragma unroll
-    for (int db = 0; db < DB; ++db) toff[db] = tr_lane_off<CH>(db);
+    for (int db = 0; db < DB; ++db) toff[db] = tr16_lane_off16<CH>(db);
 
     auto tile_step = [&](auto bufc, int it) {
         constexpr int BUF = decltype(bufc)::value;
@@ -645,75 +649,86 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const int j0 = gist_tile ? it * BNQ : wstart + (it - ngt) * BNQ;
         if (!gist_tile && j0 > wrow0 + 31) return;
 
-        // bit 8 (i/4) + i%4 of vis[kb2]: does this lane's query see key j0 + 32 kb2 + 4h + 8 (i/4) + i%4?  Visible
-        // sets are bit ranges (the tail of the compact list; the window) plus, in the window phase, sinks and gists.
         bool masked;
-        unsigned vis[2] = {~0u, ~0u};
+        unsigned long long gm = 0ull;  // bit t: the key at offset t from j0 holds a sink or a gist
         if (gist_tile) {
             masked = j0 + BNQ > nfar;
-#pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2) vis[kb2] = below_bits(nfar - j0 - 4 * h - 32 * kb2);
         } else {
             masked = !(j0 + BNQ - 1 <= wrow0 && j0 >= lo_wlast);
-            if (masked) {
-                const unsigned long long gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane)) >> (4 * h);
-                const int d0 = qrow - (j0 + 4 * h);
-#pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2) {
-                    const int d = d0 - 32 * kb2;  // offsets d - span_q .. d are in the window, offsets <= d causal
-                    const unsigned causal = below_bits(d + 1);
-                    vis[kb2] = causal & (~below_bits(d - span_q) | (unsigned)(gm >> (32 * kb2)));
-                }
-            }
+            if (masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
         }
 
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
-            // S^T, dP^T for 32 keys: register i is key j0 + 32 kb2 + 8 (i/4) + 4h + i%4, lane = query
-            // (fragment reads run PFS k-steps ahead of their MFMAs; the scheduling barriers keep them there)
-            f32x16 sa = zero16(), dp = ndl;
+            // S^T, dP^T for 32 keys: register i of sa[kb][qb] is key j0 + 32 kb2 + 16 kb + 4 g4 + i, column = query
+            // qrow[qb].  Every K and V fragment serves both query blocks; the reads run PFS groups ahead of their
+            // MFMAs and the scheduling barriers keep them there.
+            f32x4 sa[2][2], dp[2][2];
             {
-                bf16x8 fk[KS], fv[KS];
+                constexpr int N = 2 * KS;  // group n: key block n / KS, k-step n % KS
+                bf16x8 fk[N], fv[N];
+                auto fetch = [&](int n) __attribute__((always_inline)) {
+                    const int o = (32 * kb2 + 16 * (n / KS)) * CH * 16 + roff[n % KS];
+                    fk[n] = *(const bf16x8*)(kt + o);
+                    fv[n] = *(const bf16x8*)(vt + o);
+                };
 #pragma unroll
-                for (int ks = 0; ks < PFS; ++ks) {
-                    fk[ks] = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks]);
-                    fv[ks] = *(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks]);
-                }
+                for (int n = 0; n < PFS; ++n) fetch(n);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    if (ks + PFS < KS) {
-                        fk[ks + PFS] = *(const bf16x8*)(kt + kb2 * 32 * CH * 16 + roff[ks + PFS]);
-                        fv[ks + PFS] = *(const bf16x8*)(vt + kb2 * 32 * CH * 16 + roff[ks + PFS]);
+                for (int n = 0; n < N; ++n) {
+                    if (n + PFS < N) fetch(n + PFS);
+                    const int kb = n / KS, ks = n % KS;
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb) {
+                        sa[kb][qb] = mfma16(fk[n], qf[qb][ks], ks == 0 ? zero4() : sa[kb][qb]);
+                        dp[kb][qb] = mfma16(fv[n], gf[qb][ks], ks == 0 ? ndl[qb] : dp[kb][qb]);
                     }
-                    sa = mfma32(fk[ks], qf[ks], sa);
-                    dp = mfma32(fv[ks], gf[ks], dp);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sa[i] = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -ls));
-            if (masked) {
+            for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (!((vis[kb2] >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) sa[kb][qb][i] = __builtin_amdgcn_exp2f(fmaf(sa[kb][qb][i], c, -ls[qb]));
+                if (masked) {
+                    // bit t of vis: does query qrow[qb] see the key at offset t of this 32-key block?  Visible sets
+                    // are bit ranges (the tail of the compact list; the window) plus, in the window phase, the sinks
+                    // and gists.  This lane holds the offsets 16 kb + 4 g4 + i.
+                    unsigned vis;
+                    if (gist_tile) {
+                        vis = below_bits(nfar - j0 - 32 * kb2);
+                    } else {
+                        const int d0 = qrow[qb] - (j0 + 32 * kb2);  // offsets d0 - span_q .. d0: window; <= d0: causal
+                        vis = below_bits(d0 + 1) & (~below_bits(d0 - span_q[qb]) | (unsigned)(gm >> (32 * kb2)));
+                    }
+                    vis >>= 4 * g4;
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (!((vis >> (16 * kb + i)) & 1u)) sa[kb][qb][i] = 0.f;
+                }
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) dp[kb][qb][i] *= sa[kb][qb][i];
             }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] *= sa[i];
-            // dQ^T += K^T dS^T
+            // dQ^T += K^T dS^T : contraction slot 8 g4 + 4 kb + i is key 16 kb + 4 g4 + i of the block, on both operands
             {
-                constexpr int N = 2 * DB;  // (kk, db) pairs
-                bf16x8 sb[2], ft[N];
+                bf16x8 sb[2], ft[DB];
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk) sb[kk] = pack8(dp, 8 * kk);
+                for (int qb = 0; qb < 2; ++qb) sb[qb] = pack44(dp[0][qb], dp[1][qb]);
 #pragma unroll
-                for (int n = 0; n < PFT; ++n) ft[n] = tr16_frag_at<CH>(kt + toff[n % DB], 32 * kb2 + 16 * (n / DB));
+                for (int db = 0; db < PFT; ++db) ft[db] = tr16_frag16<CH>(kt + toff[db], 32 * kb2);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int n = 0; n < N; ++n) {
-                    if (n + PFT < N)
-                        ft[n + PFT] = tr16_frag_at<CH>(kt + toff[(n + PFT) % DB], 32 * kb2 + 16 * ((n + PFT) / DB));
-                    acc[n % DB] = mfma32(ft[n], sb[n / DB], acc[n % DB]);
+                for (int db = 0; db < DB; ++db) {
+                    if (db + PFT < DB) ft[db + PFT] = tr16_frag16<CH>(kt + toff[db + PFT], 32 * kb2);
+                    acc[db][0] = mfma16(ft[db], sb[0], acc[db][0]);
+                    acc[db][1] = mfma16(ft[db], sb[1], acc[db][1]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -734,18 +749,18 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         }
     }
 
-    if (qrow < L) {
-        bf16_t* op = dq + rowoff * D + 4 * h;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < 2; ++qb)
+        if (qrow[qb] < L) {
+            bf16_t* op = dq + rowoff[qb] * D + 4 * g4;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
+            for (int db = 0; db < DB; ++db) {
                 u32x2 w2;
-                w2[0] = pack_bf16x2(acc[db][4 * i4] * s.scale, acc[db][4 * i4 + 1] * s.scale);
-                w2[1] = pack_bf16x2(acc[db][4 * i4 + 2] * s.scale, acc[db][4 * i4 + 3] * s.scale);
-                *(u32x2*)(op + 32 * db + 8 * i4) = w2;
+                w2[0] = pack_bf16x2(acc[db][qb][0] * s.scale, acc[db][qb][1] * s.scale);
+                w2[1] = pack_bf16x2(acc[db][qb][2] * s.scale, acc[db][qb][3] * s.scale);
+                *(u32x2*)(op + 16 * db) = w2;
             }
-    }
+        }
 }
 
 template <int D>

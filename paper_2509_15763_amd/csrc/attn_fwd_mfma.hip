@@ -32,12 +32,6 @@
 namespace unigist {
 namespace {
 
-// Chunk swizzle of the K and V tiles: chunk ch of tile row r is stored at chunk position ch ^ swz16(r).  Its period
-// of 16 rows puts the 16 rows of a row-wise fragment read and the 4 rows of a transposing read on distinct banks;
-// the two transposing reads of a fragment lie 16 rows apart and so share one address register.
-template <int CH>
-__device__ __forceinline__ int swz16(int r) { return CH == 16 ? (r & 15) : ((r >> 1) & 7); }
-
 constexpr int BM = 128;  // query rows per workgroup
 constexpr int BN = 32;   // keys per step
 constexpr int NT = 256;  // threads
