@@ -159,7 +159,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         s.S = 0;
         s.umode = 0;
     }
-    constexpr int KS = D / 16, DB = D / 32, CH = D / 8;
+    constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // 16x16x32 MFMA: k-steps of 32, 16-row blocks of dK^T / dV^T
     constexpr int RPI = 64 / CH;        // chunk rows covered by one direct-load instruction
     constexpr int IPW = MQ / RPI / 4;   // such instructions per wave, per matrix, per step
     constexpr int ROWB = CH * 16;       // bytes per row
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c32 = lane & 31, h = lane >> 5;
+    const int r16 = lane & 15, g4 = lane >> 4;  // the lane's place in a 16x16x32 operand
     const int L = s.L;
     const int G = s.Hq / s.Hkv;
     const float c = s.scale * kLog2e;
@@ -206,55 +206,59 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         c_hi = last_chunk_with_far_le(s, pl.NC, c_lo, j0);
     }
     const int key0 = tile * BNK + 32 * w;      // first key (position, or compact gist index) of the wave
-    const int key = key0 + c32;                // this lane's key
-    int krow;                                  // row of K/V holding it
-    if (GIST) {
-        const int atot = count_always(s, L);   // sinks + gists, >= 1 whenever a gist workgroup exists
-        krow = pos_of_always(s, min(key, atot - 1));
-    } else {
-        krow = min(key, L - 1);
+    // The wave's 32 keys are two 16-key blocks kb = 0, 1; this lane's keys are key0 + 16 kb + r16.
+    // K, V fragments (B operands): lane holds K[key[kb]][32 ks + 8 g4 .. +7].
+    int key[2], span_j[2];
+    bool gist_lane[2];
+    bf16x8 kf[2][KS], vf[2][KS];
+    f32x4 akT[DB][2], avT[DB][2];  // dK^T, dV^T: register i of [db][kb] is d = 16 db + 4 g4 + i, column = key[kb]
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        key[kb] = key0 + 16 * kb + r16;
+        int krow;                              // row of K/V holding it
+        if (GIST) {
+            const int atot = count_always(s, L);  // sinks + gists, >= 1 whenever a gist workgroup exists
+            krow = pos_of_always(s, min(key[kb], atot - 1));
+        } else {
+            krow = min(key[kb], L - 1);
+        }
+        gist_lane[kb] = GIST ? true : is_always(s, key[kb]);  // a sink or a gist: visible to every later row
+        // the key stays in the window for span_j more rows (W - 1 for every key in the sliding mode)
+        span_j[kb] = 0;
+        if constexpr (!GIST && GEN) span_j[kb] = key[kb] < L ? win_hi(s, key[kb]) - key[kb] : 0;
+        const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + krow) * D + 8 * g4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[kb][ks] = *(const bf16x8*)(k + base + 32 * ks);
+            vf[kb][ks] = *(const bf16x8*)(v + base + 32 * ks);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            akT[db][kb] = zero4();
+            avT[db][kb] = zero4();
+        }
     }
-    const bool gist_lane = GIST ? true : is_always(s, key);       // a sink or a gist: visible to every later row
-    // the key stays in the window for span_j more rows (W - 1 for every key in the sliding mode)
-    int span_j = 0;
-    if constexpr (!GIST && GEN) span_j = key < L ? win_hi(s, key) - key : 0;
     // last row that has the wave's first key in its window (rows >= L are excluded separately)
     int hi_w0 = 0;
     if constexpr (!GIST && GEN) hi_w0 = win_hi(s, min(key0, L - 1));
 
-    // ---- K, V fragments (B operands): lane holds K[key][16 ks + 8h .. +7]
-    bf16x8 kf[KS], vf[KS];
-    {
-        const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + krow) * D + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = *(const bf16x8*)(k + base + 16 * ks);
-            vf[ks] = *(const bf16x8*)(v + base + 16 * ks);
-        }
-    }
-    f32x16 akT[DB], avT[DB];  // dK^T, dV^T: register i of block db is d = 32 db + 8 (i/4) + 4h + i%4
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-        akT[db] = zero16();
-        avT[db] = zero16();
-    }
-
     // ---- staging of the Q / dO chunk: direct global->LDS loads
     const int nch = c_hi - c_lo + 1;
     const int nsteps = nch * G;
-    // Load slot i of wave w covers the chunk rows (w * IPW + i) * RPI + lane / CH.  The swizzle repeats every 8 rows and
-    // w * IPW * RPI is a multiple of 8, so the lane's byte offset inside the slot's rows takes only NLP different
+    // Load slot i of wave w covers the chunk rows (w * IPW + i) * RPI + lane / CH.  The swizzle repeats every 16 rows and
+    // w * IPW * RPI is a multiple of 16, so the lane's byte offset inside the slot's rows takes only NLP different
     // values; everything else of the address is wave-uniform or an immediate.
     // They are recomputed from the lane id at every use: kept in registers across the step they would be
     // spilled, and a reload from scratch waits on the same counter as the direct loads still in flight.
-    constexpr int NLP = RPI >= 8 ? 1 : 8 / RPI;
+    constexpr int NLP = 16 / RPI;
+    static_assert(IPW * RPI == 16 && NLP == IPW, "a wave stages 16 rows per matrix and step");
     auto issue = [&](int g, int cc, int buf) __attribute__((always_inline)) {
         int ln = lane;
         asm volatile("" : "+v"(ln));  // opaque: keeps the address arithmetic below inside this call
         const int lrow_ = ln / CH;
         int lanepart[NLP];
 #pragma unroll
-        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz<CH>(i * RPI + lrow_)) << 4);
+        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz16<CH>(i * RPI + lrow_)) << 4);
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform; dense workspace rows
         const size_t hg = ((size_t)b * s.Hq + hk * G + g) * s.qhs;       // the head in the caller's tensors
         const char* qh = (const char*)(q + hg * D);
@@ -285,12 +289,12 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                                              (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
         }
     };
-    // Per-lane LDS offsets.  Row-wise read of chunk row c32 (+32 qb), 16-byte chunk 2 ks + h: the swizzle XORs
-    // the chunk bits, so the offset for k-step ks is roff0 ^ (ks << 5); likewise the transposing read of the
-    // 32-column block db sits at toff0 ^ (db << 6).  Only the two bases stay live across the kernel (registers
+    // Per-lane LDS offsets.  Row-wise read of chunk row r16 (+16 qs + 32 qb), 16-byte chunk 4 ks + g4: the swizzle
+    // XORs the chunk bits, so the offset for k-step ks is roff0 ^ (ks << 6); likewise the transposing read of the
+    // 16-column block db sits at toff0 ^ (db << 5).  Only the two bases stay live across the kernel (registers
     // are what this kernel is short of); the XORs are redone per query block.
-    const int roff0 = swz_off<CH>(c32, h);
-    const int toff0 = tr_lane_off<CH>(0);
+    const int roff0 = row16_lane_off<CH>(0);
+    const int toff0 = tr16_lane_off16<CH>(0);
 
     // one step on LDS stage BUF (a compile-time constant: LDS addresses = lane register + immediate)
     auto do_step = [&](auto bufc, int cc) __attribute__((always_inline)) {
@@ -311,38 +315,40 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             int rb = roff0 + 32 * qb * ROWB, tb = toff0 + 32 * qb * ROWB;
             asm volatile("" : "+v"(rb), "+v"(tb));  // opaque: the derived offsets are not hoisted out of the loop
 
-            // ---- S = Q K^T, dP = dO V^T  (register i: query qb0 + 8 (i/4) + 4h + i%4, lane: key)
-            // The fragment reads are issued PF k-steps ahead of the MFMAs that consume them; the scheduling
-            // barriers keep the compiler from sinking them back to just before their use, where every MFMA
-            // would wait for a full LDS round trip.
+            // ---- S = Q K^T, dP = dO V^T for the two 16-row halves qs of the block and the two 16-key blocks kb:
+            // register i of sa[qs][kb] is query qb0 + 16 qs + 4 g4 + i, column = key[kb].  Every Q and dO fragment
+            // serves both key blocks.  The fragment reads are issued PF groups ahead of the MFMAs that consume them;
+            // the scheduling barriers keep the compiler from sinking them back to just before their use, where every
+            // MFMA would wait for a full LDS round trip.
             // dP starts from -delta of its rows (the prepass stores delta negated), so dS = P (dP - delta) needs no
-            // subtraction afterwards
-            f32x16 sa = zero16(), dp;
+            // subtraction afterwards.
+            f32x4 sa[2][2], dp[2][2];
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 8 * i4 + 4 * h]);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) dp[4 * i4 + t] = d4[t];
+            for (int qs = 0; qs < 2; ++qs) {
+                const f32x4 d4 = *(const f32x4*)(&sm.delta[BUF][32 * qb + 16 * qs + 4 * g4]);
+                dp[qs][0] = d4;
+                dp[qs][1] = d4;
             }
             {
-                constexpr int PF = 2;
-                bf16x8 fq[KS], fg[KS];
+                constexpr int N = 2 * KS, PF = 1;  // group n: half n / KS, k-step n % KS
+                bf16x8 fq[N], fg[N];
+                auto fetch = [&](int n) __attribute__((always_inline)) {
+                    const int ro = (rb ^ ((n % KS) << 6)) + 16 * (n / KS) * ROWB;
+                    fq[n] = *(const bf16x8*)(qt + ro);
+                    fg[n] = *(const bf16x8*)(gt + ro);
+                };
 #pragma unroll
-                for (int ks = 0; ks < PF; ++ks) {
-                    const int ro = rb ^ (ks << 5);
-                    fq[ks] = *(const bf16x8*)(qt + ro);
-                    fg[ks] = *(const bf16x8*)(gt + ro);
-                }
+                for (int n = 0; n < PF; ++n) fetch(n);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    if (ks + PF < KS) {
-                        const int ro = rb ^ ((ks + PF) << 5);
-                        fq[ks + PF] = *(const bf16x8*)(qt + ro);
-                        fg[ks + PF] = *(const bf16x8*)(gt + ro);
+                for (int n = 0; n < N; ++n) {
+                    if (n + PF < N) fetch(n + PF);
+                    const int qs = n / KS, ks = n % KS;
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb) {
+                        sa[qs][kb] = mfma16(fq[n], kf[kb][ks], ks == 0 ? zero4() : sa[qs][kb]);
+                        dp[qs][kb] = mfma16(fg[n], vf[kb][ks], dp[qs][kb]);
                     }
-                    sa = mfma32(fq[ks], kf[ks], sa);
-                    dp = mfma32(fg[ks], vf[ks], dp);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -351,57 +357,69 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             if (GIST) masked = key0 + 31 >= nfar || qb0 + 31 >= L;
             else if constexpr (GEN) masked = !(key0 + 31 <= qb0 && qb0 + 31 <= hi_w0 && qb0 + 31 < L);
             else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < s.W && qb0 + 31 < L);
-            // bit 8 (i/4) + i%4 of vis: does query qb0 + 4h + 8 (i/4) + i%4 see this lane's key?  The visible
-            // queries are a range of offsets (those inside the sequence; for a raw key those that still have it
-            // in their window), cut at the diagonal.
-            unsigned vis = ~0u;
-            if (masked) {
-                const unsigned inside = below_bits(L - qb0 - 4 * h);
-                if (GIST) {
-                    vis = key < nfar ? inside : 0u;
-                } else {
-                    const int d0 = qb0 + 4 * h - key;  // distance i - j of the lane's first query to its key
-                    const int span = GEN ? span_j : s.W - 1;
-                    const unsigned win = gist_lane ? ~0u : below_bits(span - d0 + 1);
-                    vis = inside & win & ~below_bits(-d0);
+            f32x4 l4[2];
+#pragma unroll
+            for (int qs = 0; qs < 2; ++qs) l4[qs] = *(const f32x4*)(&sm.lse2[BUF][32 * qb + 16 * qs + 4 * g4]);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        sa[qs][kb][i] = __builtin_amdgcn_exp2f(fmaf(sa[qs][kb][i], c, -l4[qs][i]));
+                if (masked) {
+                    // bit t of vis: does query qb0 + t see this lane's key[kb]?  The visible queries are a range of
+                    // offsets (those inside the sequence; for a raw key those that still have it in their window),
+                    // cut at the diagonal.  This lane holds the offsets 16 qs + 4 g4 + i.
+                    unsigned vis;
+                    const unsigned inside = below_bits(L - qb0);
+                    if (GIST) {
+                        vis = key[kb] < nfar ? inside : 0u;
+                    } else {
+                        const int d0 = qb0 - key[kb];  // distance i - j of the block's first query to the key
+                        const int span = GEN ? span_j[kb] : s.W - 1;
+                        const unsigned win = gist_lane[kb] ? ~0u : below_bits(span - d0 + 1);
+                        vis = inside & win & ~below_bits(-d0);
+                    }
+                    vis >>= 4 * g4;
+#pragma unroll
+                    for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (!((vis >> (16 * qs + i)) & 1u)) sa[qs][kb][i] = 0.f;
                 }
+#pragma unroll
+                for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) dp[qs][kb][i] *= sa[qs][kb][i];
             }
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 l4 = *(const f32x4*)(&sm.lse2[BUF][32 * qb + 8 * i4 + 4 * h]);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) sa[4 * i4 + t] = __builtin_amdgcn_exp2f(fmaf(sa[4 * i4 + t], c, -l4[t]));
-            }
-            if (masked) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (!((vis >> (8 * (i / 4) + (i % 4))) & 1u)) sa[i] = 0.f;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] *= sa[i];
-            // ---- dV^T += dO^T P,  dK^T += Q^T dS   (16 queries per MFMA)
+            // ---- dV^T += dO^T P,  dK^T += Q^T dS : contraction slot 8 g4 + 4 qs + i is query 16 qs + 4 g4 + i of the
+            // block, on both operands; every dO^T and Q^T fragment serves both key blocks
             bf16x8 pb[2], sb[2];
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                pb[kk] = pack8(sa, 8 * kk);
-                sb[kk] = pack8(dp, 8 * kk);
+            for (int kb = 0; kb < 2; ++kb) {
+                pb[kb] = pack44(sa[0][kb], sa[1][kb]);
+                sb[kb] = pack44(dp[0][kb], dp[1][kb]);
             }
             {
-                constexpr int N = 2 * DB, PF = 3;  // N (kk, db) pairs, each one dO^T and one Q^T fragment
-                bf16x8 fg[N], fq[N];
-                auto fetch = [&](int n) __attribute__((always_inline)) {
-                    const int to = tb ^ ((n % DB) << 6);
-                    fg[n] = tr16_frag_at<CH>(gt + to, 16 * (n / DB));
-                    fq[n] = tr16_frag_at<CH>(qt + to, 16 * (n / DB));
+                constexpr int PF = 2;
+                bf16x8 fg[DB], fq[DB];
+                auto fetch = [&](int db) __attribute__((always_inline)) {
+                    const int to = tb ^ (db << 5);
+                    fg[db] = tr16_frag16<CH>(gt + to, 0);
+                    fq[db] = tr16_frag16<CH>(qt + to, 0);
                 };
 #pragma unroll
-                for (int n = 0; n < PF; ++n) fetch(n);
+                for (int db = 0; db < PF; ++db) fetch(db);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int n = 0; n < N; ++n) {
-                    if (n + PF < N) fetch(n + PF);
-                    avT[n % DB] = mfma32(fg[n], pb[n / DB], avT[n % DB]);
-                    akT[n % DB] = mfma32(fq[n], sb[n / DB], akT[n % DB]);
+                for (int db = 0; db < DB; ++db) {
+                    if (db + PF < DB) fetch(db + PF);
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb) {
+                        avT[db][kb] = mfma16(fg[db], pb[kb], avT[db][kb]);
+                        akT[db][kb] = mfma16(fq[db], sb[kb], akT[db][kb]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -444,59 +462,62 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         }
     }
 
-    // ---- epilogue
+    // ---- epilogue: register i of [db][kb] is d = 16 db + 4 g4 + i of key[kb]
     if (GIST) {
         // fp32 partials, transposed: [dK^T | dV^T][d][BNK keys]
-        float* o = part + ((((size_t)b * s.Hkv + hk) * pl.n_gt + tile) * pl.nseg + seg) * (2 * D * BNK) + 32 * w + c32;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int d = 32 * db + 8 * (i / 4) + 4 * h + (i % 4);
-                o[(size_t)d * BNK] = akT[db][i] * s.scale;
-                o[(size_t)(D + d) * BNK] = avT[db][i];
-            }
-    } else {
-        if (gist_lane && pl.n_gt > 0) {
-            // add what the gist phase collected for this row (zero if no chunk saw it from afar)
-            const int gi = count_always(s, key);  // its index in the compact list of sinks and gists
-            const int gt = gi / BNK;
-            if (gt < pl.n_gt && key < L) {
-                const float* cp = comp + (((size_t)b * s.Hkv + hk) * pl.n_gt + gt) * (2 * D * BNK) + gi % BNK;
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int d = 32 * db + 8 * (i / 4) + 4 * h + (i % 4);
-                        akT[db][i] = akT[db][i] * s.scale + cp[(size_t)d * BNK];
-                        avT[db][i] += cp[(size_t)(D + d) * BNK];
-                    }
-            } else {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) akT[db][i] *= s.scale;
-            }
-        } else {
+        for (int kb = 0; kb < 2; ++kb) {
+            float* o = part + ((((size_t)b * s.Hkv + hk) * pl.n_gt + tile) * pl.nseg + seg) * (2 * D * BNK) + 32 * w +
+                       16 * kb + r16;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) akT[db][i] *= s.scale;
-        }
-        if (key < L) {
-            const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + key) * D + 4 * h;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    u32x2 a, bb;
-                    a[0] = pack_bf16x2(akT[db][4 * i4], akT[db][4 * i4 + 1]);
-                    a[1] = pack_bf16x2(akT[db][4 * i4 + 2], akT[db][4 * i4 + 3]);
-                    bb[0] = pack_bf16x2(avT[db][4 * i4], avT[db][4 * i4 + 1]);
-                    bb[1] = pack_bf16x2(avT[db][4 * i4 + 2], avT[db][4 * i4 + 3]);
-                    *(u32x2*)(dk + base + 32 * db + 8 * i4) = a;
-                    *(u32x2*)(dv + base + 32 * db + 8 * i4) = bb;
+                for (int i = 0; i < 4; ++i) {
+                    const int d = 16 * db + 4 * g4 + i;
+                    o[(size_t)d * BNK] = akT[db][kb][i] * s.scale;
+                    o[(size_t)(D + d) * BNK] = avT[db][kb][i];
                 }
+        }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            bool added = false;
+            if (gist_lane[kb] && pl.n_gt > 0) {
+                // add what the gist phase collected for this row (zero if no chunk saw it from afar)
+                const int gi = count_always(s, key[kb]);  // its index in the compact list of sinks and gists
+                const int gt = gi / BNK;
+                if (gt < pl.n_gt && key[kb] < L) {
+                    const float* cp = comp + (((size_t)b * s.Hkv + hk) * pl.n_gt + gt) * (2 * D * BNK) + gi % BNK;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int d = 16 * db + 4 * g4 + i;
+                            akT[db][kb][i] = akT[db][kb][i] * s.scale + cp[(size_t)d * BNK];
+                            avT[db][kb][i] += cp[(size_t)(D + d) * BNK];
+                        }
+                    added = true;
+                }
+            }
+            if (!added) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) akT[db][kb][i] *= s.scale;
+            }
+            if (key[kb] < L) {
+                const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + key[kb]) * D + 4 * g4;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    u32x2 a, bb;
+                    a[0] = pack_bf16x2(akT[db][kb][0], akT[db][kb][1]);
+                    a[1] = pack_bf16x2(akT[db][kb][2], akT[db][kb][3]);
+                    bb[0] = pack_bf16x2(avT[db][kb][0], avT[db][kb][1]);
+                    bb[1] = pack_bf16x2(avT[db][kb][2], avT[db][kb][3]);
+                    *(u32x2*)(dk + base + 16 * db) = a;
+                    *(u32x2*)(dv + base + 16 * db) = bb;
+                }
+            }
         }
     }
 }
