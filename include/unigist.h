@@ -312,8 +312,8 @@ void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn);
 /*
  * Measurement aid, not part of the method: the bf16 matrix-core rate the chip sustains on register-resident
  * operands, against which the attention kernels' rates can be read.  `blocks` workgroups of 4 waves each run
- * `iters` rounds of 8 v_mfma_f32_32x32x16_bf16 (2 * 32 * 32 * 16 flops each, so blocks * 4 * iters * 8 of them in
- * all) on operands read once from `operands` (DEVICE, 32 KiB, any bf16 values: the chip is power-limited and the
+ * `iters` rounds of 16 v_mfma_f32_16x16x32_bf16, the shape the attention kernels use (2 * 16 * 16 * 32 flops
+ * each, so blocks * 4 * iters * 16 of them in all) on operands read once from `operands` (DEVICE, 32 KiB, any bf16 values: the chip is power-limited and the
  * rate depends on how many bits the operands toggle -- ones and random values give different answers).
  * clocks (DEVICE, 2 * blocks int64): per workgroup the shader-clock cycles and the ticks of the constant-rate
  * (100 MHz) counter the loop took; their ratio is the clock the chip held.  sink (DEVICE, one float) is never

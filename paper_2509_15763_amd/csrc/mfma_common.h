@@ -1,12 +1,4 @@
 // Device helpers shared by the MFMA kernels (gfx950 only).
-//
-// Fragment layouts of v_mfma_f32_32x32x16_bf16 (D = A * B + C, A is 32 x 16, B is 16 x 32), with
-// c32 = lane % 32 and h = lane / 32:
-//   A: lane holds A[c32][8h .. 8h+7]          B: lane holds B[8h .. 8h+7][c32]
-//   C/D: register i holds D[8 (i/4) + 4h + i%4][c32]
-// Since the contraction index can be permuted freely as long as A and B agree, the 8 C registers
-// 8t .. 8t+7 of a lane, read as a B operand, stand for the contraction slots (8 (2t) + 4h + 0..3) and
-// (8 (2t+1) + 4h + 0..3); tr16_frag() below fetches the matching A operand from a row-major tile.
 #pragma once
 #include "common.h"
 
@@ -15,40 +7,11 @@ namespace unigist {
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ f32x16 zero16() {
-    f32x16 z;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) z[i] = 0.f;
-    return z;
-}
-
-// value held by lane ^ 32
-__device__ __forceinline__ float other_half(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false,
-                                              false);
-    // lanes < 32 find the partner's value in r[1], lanes >= 32 in r[0]; the other slot is their own
-    float a = __builtin_bit_cast(float, (unsigned)r[0]);
-    float b = __builtin_bit_cast(float, (unsigned)r[1]);
-    return (threadIdx.x & 32) ? a : b;
-}
-
 // ---------------------------------------------------------------------------------------------
 // Tiles staged with direct global->LDS loads (global_load_lds_dwordx4).
 // One such instruction makes a wave write 64 x 16 B = 1 KB of consecutive LDS, so rows cannot be
-// padded; bank conflicts are avoided by permuting the 16-byte chunks of each row instead: chunk
-// ch of tile row r is stored at chunk position ch ^ swz(r).  With swz even and periodic in 8 rows
-// (of 256 B) the 8 lanes of a row-wise 16-byte read and the 4 rows of a transposing read each fall
-// on distinct banks.  CH = chunks per row (D / 8).
-template <int CH>
-__device__ __forceinline__ int swz(int r) { return 2 * ((r * CH / 16) % (CH / 2)); }
-
-// byte offset of (row r, chunk ch) inside a swizzled tile
-template <int CH>
-__device__ __forceinline__ int swz_off(int r, int ch) { return r * (CH * 16) + ((ch ^ swz<CH>(r)) << 4); }
+// padded; bank conflicts are avoided by permuting the 16-byte chunks of each row instead (swz16 below).
+// CH = chunks per row (D / 8).
 
 // issue one 1 KB direct load: lane `lane` fetches 16 bytes from `src` into lds_base + 16 * lane
 __device__ __forceinline__ void g2l16(const void* src, void* lds_base_uniform) {
@@ -58,44 +21,6 @@ __device__ __forceinline__ void g2l16(const void* src, void* lds_base_uniform) {
 
 // wait until this wave's outstanding vector-memory operations (direct loads included) are done
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-template <int CH>
-__device__ __forceinline__ int tr_lane_row() {
-    const int lane = threadIdx.x & 63;
-    return 4 * (lane >> 5) + ((lane & 15) >> 2);
-}
-// A operand X^T from a swizzled row-major LDS tile X[row][col]: the lane gets, for column col0 + lane % 32,
-// the 8 rows row0 + 4h + {0,1,2,3} and row0 + 8 + 4h + {0,1,2,3} (row0 a multiple of 8, col0 = 32 db) with two
-// ds_read_b64_tr_b16: within each 16-lane group, lane p passes the address of X[r + p/4][c + 4 (p%4)] and
-// receives X[r .. r+3][c + p].  The address is split into a per-lane register tr_lane_off<CH>(db),
-// computed once per kernel, and compile-time parts (rows, LDS stage) that become immediates.
-template <int CH>
-__device__ __forceinline__ int tr_lane_off(int db) {
-    const int lane = threadIdx.x & 63;
-    const int p16 = lane & 15, gi2 = (lane >> 4) & 1;
-    const int rl = tr_lane_row<CH>();
-    const int ch = 4 * db + 2 * gi2 + ((p16 & 3) >> 1);
-    return rl * (CH * 16) + ((ch ^ swz<CH>(rl)) << 4) + (p16 & 1) * 8;
-}
-template <int CH>
-__device__ __forceinline__ bf16x8 tr16_frag_at(const char* tile_plus_lane_off, int row0) {
-    const char* a = tile_plus_lane_off + row0 * (CH * 16);
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)a);
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 8 * CH * 16));
-    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, r);
-}
-
-// 8 consecutive C registers (starting at i0) -> bf16 B operand
-__device__ __forceinline__ bf16x8 pack8(const f32x16& x, int i0) {
-    u32x4 r;
-    r[0] = pack_bf16x2(x[i0], x[i0 + 1]);
-    r[1] = pack_bf16x2(x[i0 + 2], x[i0 + 3]);
-    r[2] = pack_bf16x2(x[i0 + 4], x[i0 + 5]);
-    r[3] = pack_bf16x2(x[i0 + 6], x[i0 + 7]);
-    return __builtin_bit_cast(bf16x8, r);
-}
-
 
 // ---------------------------------------------------------------------------------------------
 // v_mfma_f32_16x16x32_bf16 (D = A * B + C, A 16 x 32, B 32 x 16).  With r16 = lane % 16 and g4 = lane / 16:

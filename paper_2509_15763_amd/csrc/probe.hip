@@ -1,7 +1,7 @@
 // Measurement aid: the matrix-core rate the chip sustains on register-resident operands.
 //
-// Every wave runs a loop of v_mfma_f32_32x32x16_bf16 on four independent accumulators with operands it loaded
-// once from `operands`, so nothing but the matrix pipe is busy.  The rate depends on the operand values: the
+// Every wave runs a loop of v_mfma_f32_16x16x32_bf16 (the shape the attention kernels use) on eight independent
+// accumulators with operands it loaded once from `operands`, so nothing but the matrix pipe is busy.  The rate depends on the operand values: the
 // chip is power-limited, and operands that toggle many bits (random data) lower the clock it holds.  The bench
 // reports this rate next to the published peak so that a kernel's fraction of either can be read off.
 #include "mfma_common.h"
@@ -19,22 +19,18 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict
         a[i] = operands[(threadIdx.x + 256 * i) % kProbeOperands];
         b[i] = operands[(threadIdx.x + 256 * i + kProbeOperands / 2) % kProbeOperands];
     }
-    f32x16 c0 = zero16(), c1 = zero16(), c2 = zero16(), c3 = zero16();
+    f32x4 c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = zero4();
     const long long t0 = clock64(), r0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
-        c0 = mfma32(a[0], b[0], c0);
-        c1 = mfma32(a[1], b[1], c1);
-        c2 = mfma32(a[2], b[2], c2);
-        c3 = mfma32(a[3], b[3], c3);
-        c0 = mfma32(a[1], b[2], c0);
-        c1 = mfma32(a[2], b[3], c1);
-        c2 = mfma32(a[3], b[0], c2);
-        c3 = mfma32(a[0], b[1], c3);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) c[u % 8] = mfma16(a[u % 4], b[(u + u / 4) % 4], c[u % 8]);
     }
     const long long t1 = clock64(), r1 = wall_clock64();
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    for (int i = 0; i < 8; ++i) s += c[i][0] + c[i][1] + c[i][2] + c[i][3];
     if (s == 12345.678f) sink[0] = s;  // keeps the loop alive
     if (threadIdx.x == 0) {
         clocks[2 * blockIdx.x] = t1 - t0;      // shader clock cycles
