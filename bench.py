@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1014532165, "dkdv_gist": 2358822488, "dkdv_window": 1498441656, "dq": 1399469975,
-                 "decode": 4567945116, "decode_e4m3": 2287379682}
+TRAFFIC_BYTES = {"fwd": 1039538988, "dkdv_gist": 2414710159, "dkdv_window": 1476173131, "dq": 1401891691,
+                 "decode": 4567944164, "decode_e4m3": 2287378804}
 
 
 def pair_counts(L, r, W):
