@@ -17,10 +17,13 @@
 // the sinks and gists at positions < far(c) = floor(win_lo(64c) / 128) * 128 in the gist phase (win_lo = first
 // position of a row's local window) and every key >= far(c) in the window phase.
 //
-// dkdv: a wave owns 32 keys (one lane = one key), K and V fragments stay in registers, Q / dO chunks are
-// staged in LDS and read both row-wise (S = Q K^T, dP = dO V^T) and through transposing LDS reads
-// (dV^T += dO^T P, dK^T += Q^T dS); the S/dP accumulators are already the B operands of the last two.
-// dq: forward-shaped; S^T = K Q^T and dP^T = V dO^T per lane-owned query, dQ^T += K^T dS^T.
+// All contractions run on v_mfma_f32_16x16x32_bf16 (operand layouts in mfma_common.h); a wave always works on
+// two 16-wide blocks at once so that every fragment read from LDS feeds two MFMAs.
+// dkdv: a wave owns 32 keys as two 16-key blocks (a key is a column, spread over four lanes), K and V fragments
+// stay in registers, Q / dO chunks are staged in LDS and read both row-wise (S = Q K^T, dP = dO V^T) and through
+// transposing LDS reads (dV^T += dO^T P, dK^T += Q^T dS); the S/dP accumulators of the two 16-row halves of a
+// query block are already the B operands of the last two.
+// dq: forward-shaped; S^T = K Q^T and dP^T = V dO^T for the wave's two 16-row query blocks, dQ^T += K^T dS^T.
 #include <type_traits>
 
 #include "mfma_common.h"
