@@ -61,7 +61,6 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     constexpr int CH = D / 8;             // 16-byte chunks per row
     constexpr int RPI = 64 / CH;          // tile rows covered by one direct-load instruction
     constexpr int IPW = BN / RPI / 4;     // such instructions per wave, per matrix, per tile
-    constexpr int NKB = BN / 32;          // 32-key blocks per step
     __shared__ __attribute__((aligned(1024))) FwdSmem<D> sm;
 
     const int tid = threadIdx.x;
