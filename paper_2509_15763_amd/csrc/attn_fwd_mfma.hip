@@ -15,8 +15,8 @@
 //   A: lane holds A[r16][8 g4 .. 8 g4 + 7]      B: lane holds B[8 g4 .. 8 g4 + 7][r16]
 //   C/D: register i holds D[4 g4 + i][r16]
 // On random operands the chip, which is power-limited, sustains about 11 % more flops with this shape than with
-// 32x32x16; its A and B operands are half as large per flop, so every K and V fragment read from LDS is used
-// for the wave's two 16-row query blocks, which keeps the LDS and staging traffic per flop where it was.
+// 32x32x16; an operand of the same size feeds half as many flops, so every K and V fragment read from LDS is
+// used for the wave's two 16-row query blocks, which keeps the LDS and staging traffic per flop where it was.
 // Scores are computed transposed, S^T = K Q^T (A = K rows from LDS, B = Q in registers): a query is a column,
 // spread over the four lanes r16 + 16 g4, each of which holds 4 of every 16 keys; the running reference of the
 // softmax is kept identical on those four lanes and the row sum is a per-lane partial until the epilogue.  The
