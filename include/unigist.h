@@ -233,6 +233,21 @@ unigist_status unigist_cache_update(const void* kc_in, const void* vc_in, int s_
                                     int B, int Hkv, int D, int r, unigist_dtype dt, void* hip_stream);
 
 /*
+ * unigist_cache_update_ex for a batch whose sequences are in different states: s_old, t_old, n_new, s_new are
+ * DEVICE arrays of B ints (sequence b goes from state (s_old[b], t_old[b]) to (s_new[b], t_old[b] + n_new[b]),
+ * taking its first n_new[b] <= new_rows rows of k_new/v_new [B, Hkv, new_rows, D]), so that a serving loop never
+ * has to bring the states to the host.  rows_out (DEVICE, B ints, out) receives the rows in use afterwards -- the
+ * `seqlens` unigist_decode takes -- or -1 for a sequence whose state violates the conditions of
+ * unigist_cache_update or does not fit cap_in / cap_out; such a sequence's output rows are left untouched.  The
+ * host checks only what it can see (shapes, pointers, dtype).
+ */
+unigist_status unigist_cache_update_ragged(const void* kc_in, const void* vc_in, const int* s_old, const int* t_old,
+                                           int cap_in, const void* k_new, const void* v_new, const int* n_new,
+                                           int new_rows, void* kc_out, void* vc_out, const int* s_new, int cap_out,
+                                           int* rows_out, int B, int Hkv, int D, int r, int sinks, unigist_dtype dt,
+                                           void* hip_stream);
+
+/*
  * Chunk-wise prefill (Sec. 4.3: the prompt is encoded chunk by chunk with the training kernel, dropping
  * the invisible tokens after each chunk).  q holds the C query rows at positions p0 .. p0+C-1, [B, Hq, C, D];
  * kc/vc are caches in state (s, p0+C-1), i.e. already updated with the chunk's own keys, with

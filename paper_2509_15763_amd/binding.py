@@ -27,7 +27,7 @@ EXPORTS = [
     "unigist_attn_fwd_ex", "unigist_attn_bwd_ex", "unigist_attn_bwd_workspace_ex", "unigist_blockmap_build_ex",
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
-    "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3",
+    "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
 ]
 
 
@@ -100,6 +100,8 @@ def load():
     lib.unigist_cache_rows_ex.argtypes = [ip, ip, ip, ip]
     lib.unigist_cache_update_ex.restype = ip
     lib.unigist_cache_update_ex.argtypes = [vp, vp, ip, ip, ip, vp, vp, ip, ip, vp, vp, ip, ip, ip, ip, ip, ip, ip, ip, vp]
+    lib.unigist_cache_update_ragged.restype = ip
+    lib.unigist_cache_update_ragged.argtypes = [vp, vp, vp, vp, ip, vp, vp, vp, ip, vp, vp, vp, ip, vp] + [ip] * 6 + [vp]
     lib.unigist_prefill_chunk_ex.restype = ip
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
     lib.unigist_cache_rows.restype = ip
@@ -246,6 +248,12 @@ def unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks,
                              stream=None) -> int:
     return load().unigist_prefill_chunk_ex(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s,
                                            cap, dt, stream)
+
+
+def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out, vc_out, s_new,
+                                cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
+    return load().unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
+                                              vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
 
 
 def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream=None) -> int:
@@ -542,6 +550,35 @@ class RaggedKVCache:
                                        1, self.Hkv, self.D, self.r, self.sinks, _dt(self.k[0]), _stream()),
                "unigist_cache_update_ex")
         self.cur[b], self.s[b], self.t[b] = nxt, s_new, self.t[b] + n
+
+    def update_batch(self, k_new, v_new, n_new, s_new):
+        """All sequences in one launch (unigist_cache_update_ragged): k_new/v_new [B, Hkv, new_rows, D] (sequence b
+        uses its first n_new[b] rows), n_new and s_new sequences of B ints.  -> rows in use per sequence, int32 [B] on
+        the GPU (-1 where a state was invalid).  Every sequence must currently sit in the same buffer."""
+        if len(set(self.cur)) != 1:
+            raise UnigistError("update_batch needs all sequences in the same buffer: call gathered() first")
+        _dev(k_new, v_new)
+        dev = self.k[0].device
+        as_dev = lambda x: torch.tensor([int(v) for v in x], dtype=torch.int32).to(dev)
+        so, to, nn, sn = as_dev(self.s), as_dev(self.t), as_dev(n_new), as_dev(s_new)
+        rows = torch.empty(self.B, dtype=torch.int32, device=dev)
+        cur, nxt = self.cur[0], 1 - self.cur[0]
+        _check(unigist_cache_update_ragged(self.k[cur].data_ptr(), self.v[cur].data_ptr(), so.data_ptr(), to.data_ptr(),
+                                           self.cap, k_new.data_ptr(), v_new.data_ptr(), nn.data_ptr(), k_new.shape[2],
+                                           self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), sn.data_ptr(), self.cap,
+                                           rows.data_ptr(), self.B, self.Hkv, self.D, self.r, self.sinks,
+                                           UNIGIST_E4M3 if self.k[0].dtype == torch.uint8 else _dt(self.k[0]), _stream()),
+               "unigist_cache_update_ragged")
+        self.cur = [nxt] * self.B
+        self.s = [int(v) for v in s_new]
+        self.t = [t + int(n) for t, n in zip(self.t, n_new)]
+        return rows
+
+    def current(self):
+        """-> kc, vc of the buffer all sequences sit in (after update_batch)."""
+        if len(set(self.cur)) != 1:
+            raise UnigistError("sequences sit in different buffers: call gathered()")
+        return self.k[self.cur[0]], self.v[self.cur[0]]
 
     def gathered(self):
         """-> kc, vc [B, Hkv, cap, D] with every sequence's current slab in one buffer (sequences sitting in the

@@ -254,6 +254,28 @@ extern "C" unigist_status unigist_cache_update_ex(const void* kc_in, const void*
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
+extern "C" unigist_status unigist_cache_update_ragged(const void* kc_in, const void* vc_in, const int* s_old,
+                                                      const int* t_old, int cap_in, const void* k_new,
+                                                      const void* v_new, const int* n_new, int new_rows, void* kc_out,
+                                                      void* vc_out, const int* s_new, int cap_out, int* rows_out, int B,
+                                                      int Hkv, int D, int r, int sinks, unigist_dtype dt,
+                                                      void* hip_stream) {
+    if (B < 1 || Hkv < 1 || D < 1 || r < 1 || sinks < 0 || new_rows < 0 || cap_in < 0 || cap_out < 1) return UNIGIST_EINVAL;
+    if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
+    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (B > 65535 || Hkv > 65535) return UNIGIST_EUNSUPPORTED;
+    if (!kc_out || !vc_out || !s_old || !t_old || !n_new || !s_new || !rows_out) return UNIGIST_EINVAL;
+    if (cap_in > 0 && (!kc_in || !vc_in)) return UNIGIST_EINVAL;
+    if (new_rows > 0 && (!k_new || !v_new)) return UNIGIST_EINVAL;
+    const int rp1 = r >= kMaxL ? kMaxL + 1 : r + 1;
+    hipError_t e = launch_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
+                                              vc_out, s_new, cap_out, rows_out, B, Hkv, D, rp1,
+                                              sinks > kMaxL ? kMaxL : sinks,
+                                              dt == UNIGIST_E4M3 ? 1 : dt == UNIGIST_BF16 ? 2 : 4, kMaxL,
+                                              (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
 extern "C" unigist_status unigist_prefill_chunk(const void* q, const void* kc, const void* vc, void* out, float* lse,
                                                 int B, int Hq, int Hkv, int C, int D, int r, int W, int p0, int s,
                                                 int cap, unigist_dtype dt, void* hip_stream) {

@@ -46,7 +46,71 @@ __global__ __launch_bounds__(256) void cache_update_kernel(const char* __restric
     *(u32x4*)(vc_out + o) = *(const u32x4*)(vs + off + ch * 16);
 }
 
+// The same gather with one state per sequence, read from device memory (a serving loop whose sequences are at
+// different lengths never has to bring them to the host).  A sequence whose state is inconsistent or does not fit
+// the buffers is left alone and reported as -1 rows.
+__global__ __launch_bounds__(256) void cache_update_ragged_kernel(
+    const char* __restrict__ kc_in, const char* __restrict__ vc_in, const int* __restrict__ s_old_v,
+    const int* __restrict__ t_old_v, int cap_in, const char* __restrict__ k_new, const char* __restrict__ v_new,
+    const int* __restrict__ n_new_v, int new_rows, char* __restrict__ kc_out, char* __restrict__ vc_out,
+    const int* __restrict__ s_new_v, int cap_out, int* __restrict__ rows_out_v, int Hkv, AttnShape lay, int row_bytes,
+    int max_pos) {
+    const int b = blockIdx.z, bh = b * Hkv + blockIdx.y;
+    const int s_old = s_old_v[b], t_old = t_old_v[b], n_new = n_new_v[b], s_new = s_new_v[b];
+    bool ok = s_old >= 0 && t_old >= s_old - 1 && n_new >= 0 && n_new <= new_rows && s_new >= s_old &&
+              t_old <= max_pos - n_new && s_new <= t_old + n_new + 1;
+    int rows_out = -1;
+    if (ok) {
+        const int rows_in = count_always(lay, s_old) + (t_old - s_old + 1);
+        rows_out = count_always(lay, s_new) + (t_old + n_new - s_new + 1);
+        if (rows_in > cap_in || rows_out > cap_out) {
+            ok = false;
+            rows_out = -1;
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rows_out_v[b] = rows_out;
+    if (!ok) return;
+    const int cpr = row_bytes / 16;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = (int)(idx / cpr), ch = (int)(idx % cpr);
+    if (n >= rows_out) return;
+    const int ng_old = count_always(lay, s_old), ng_new = count_always(lay, s_new);
+    const int pos = n < ng_new ? pos_of_always(lay, n) : s_new + (n - ng_new);
+    const char *ks, *vs;
+    size_t off;
+    if (pos > t_old) {
+        off = ((size_t)bh * new_rows + (pos - t_old - 1)) * row_bytes;
+        ks = k_new;
+        vs = v_new;
+    } else {
+        const int row = pos < s_old ? n : ng_old + (pos - s_old);
+        off = ((size_t)bh * cap_in + row) * row_bytes;
+        ks = kc_in;
+        vs = vc_in;
+    }
+    const size_t o = ((size_t)bh * cap_out + n) * row_bytes + ch * 16;
+    *(u32x4*)(kc_out + o) = *(const u32x4*)(ks + off + ch * 16);
+    *(u32x4*)(vc_out + o) = *(const u32x4*)(vs + off + ch * 16);
+}
+
 }  // namespace
+
+hipError_t launch_cache_update_ragged(const void* kc_in, const void* vc_in, const int* s_old, const int* t_old, int cap_in,
+                                      const void* k_new, const void* v_new, const int* n_new, int new_rows,
+                                      void* kc_out, void* vc_out, const int* s_new, int cap_out, int* rows_out, int B,
+                                      int Hkv, int D, int rp1, int sinks, int elem_bytes, int max_pos, hipStream_t st) {
+    AttnShape lay{};
+    lay.rp1 = rp1;
+    lay.S = sinks;
+    const int row_bytes = D * elem_bytes;
+    const long items = (long)cap_out * (row_bytes / 16);
+    dim3 grid((unsigned)((items + 255) / 256), Hkv, B);
+    cache_update_ragged_kernel<<<grid, 256, 0, st>>>((const char*)kc_in, (const char*)vc_in, s_old, t_old, cap_in,
+                                                     (const char*)k_new, (const char*)v_new, n_new, new_rows,
+                                                     (char*)kc_out, (char*)vc_out, s_new, cap_out, rows_out, Hkv, lay,
+                                                     row_bytes, max_pos);
+    return hipGetLastError();
+}
 
 hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
                                const void* k_new, const void* v_new, int n_new, int new_rows, void* kc_out,

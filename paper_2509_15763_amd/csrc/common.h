@@ -114,6 +114,10 @@ hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, 
                                const void* k_new, const void* v_new, int n_new, int new_rows,
                                void* kc_out, void* vc_out, int s_new, int cap_out,
                                int BH, int D, int rp1, int sinks, int elem_bytes, hipStream_t st);
+hipError_t launch_cache_update_ragged(const void* kc_in, const void* vc_in, const int* s_old, const int* t_old, int cap_in,
+                                      const void* k_new, const void* v_new, const int* n_new, int new_rows,
+                                      void* kc_out, void* vc_out, const int* s_new, int cap_out, int* rows_out, int B,
+                                      int Hkv, int D, int rp1, int sinks, int elem_bytes, int max_pos, hipStream_t st);
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
                          float* ws, hipStream_t st);

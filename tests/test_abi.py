@@ -201,3 +201,13 @@ def test_e4m3_argument_validation():
     # the attention calls do not take the storage type
     assert u.unigist_attn_fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 2, 64, 128, 4, 8, 2) == 2
     assert u.unigist_decode(FAKE, FAKE, FAKE, FAKE, None, 2, 8, 2, 100, None, 128, 2, FAKE, ws) == 2
+
+
+def test_ragged_cache_update_argument_validation():
+    f = u.unigist_cache_update_ragged
+    good = dict(kc_in=FAKE, vc_in=FAKE, s_old=FAKE, t_old=FAKE, cap_in=64, k_new=FAKE, v_new=FAKE, n_new=FAKE, new_rows=8,
+                kc_out=FAKE, vc_out=FAKE, s_new=FAKE, cap_out=64, rows_out=FAKE, B=2, Hkv=2, D=128, r=4, sinks=0, dt=0)
+    for name, val, want in [("s_old", None, 1), ("t_old", None, 1), ("n_new", None, 1), ("s_new", None, 1), ("rows_out", None, 1),
+                            ("kc_out", None, 1), ("kc_in", None, 1), ("k_new", None, 1), ("cap_out", 0, 1), ("r", 0, 1),
+                            ("D", 96, 2), ("dt", 7, 2), ("B", 0, 1), ("new_rows", -1, 1)]:
+        assert f(**{**good, name: val}) == want, name

@@ -183,3 +183,70 @@ def test_ragged_batch_of_caches_then_decode():
         assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
         o, l = oracle.decode(to_np(qt[b:b + 1]), to_np(k[b:b + 1][:, :, pos]), to_np(v[b:b + 1][:, :, pos]))
         assert max_abs(to_np(out[b]), o[0]) <= TOL_OUT_BF16 and max_abs(to_np(lse[b]), l[0]) <= TOL_LSE_BF16
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.uint8], ids=["bf16", "e4m3"])
+def test_batched_ragged_updates_then_decode(dtype):
+    # one launch per step for the whole batch, states read from device memory: every sequence appends and evicts
+    # at its own pace; a sequence given an impossible state is reported as -1 and left alone
+    B, Hq, Hkv, D, r, W = 5, 8, 2, 128, 4, 40
+    lens = [300, 33, 212, 1, 150]
+    Lmax = max(lens)
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, Lmax, D, seed=26)
+    ks, vs = synth.e4m3_scales(Hkv, seed=9)
+    if dtype == torch.uint8:
+        kq = torch.from_numpy(oracle.quantize_e4m3(k.to(torch.float32).numpy(), ks.numpy()))
+        vq = torch.from_numpy(oracle.quantize_e4m3(v.to(torch.float32).numpy(), vs.numpy()))
+    else:
+        kq, vq = k, v
+    kd, vd = kq.cuda(), vq.cuda()
+    cache = u.RaggedKVCache(B, Hkv, Lmax, D, r, dtype=dtype)
+    rng = np.random.default_rng(10)
+    step = 0
+    while any(cache.t[b] < lens[b] - 1 for b in range(B)):
+        n_new = [int(min(lens[b] - 1 - cache.t[b], rng.choice([0, 1, 7, 64]))) for b in range(B)]
+        nmax = max(max(n_new), 1)
+        kn = torch.zeros(B, Hkv, nmax, D, dtype=kd.dtype, device="cuda")
+        vn = torch.zeros_like(kn)
+        for b in range(B):
+            lo = cache.t[b] + 1
+            kn[b, :, :n_new[b]] = kd[b, :, lo:lo + n_new[b]]
+            vn[b, :, :n_new[b]] = vd[b, :, lo:lo + n_new[b]]
+        s_new = [max(cache.s[b], cache.t[b] + n_new[b] - W + 1, 0) for b in range(B)]
+        rows = cache.update_batch(kn, vn, n_new, s_new).cpu().tolist()
+        kc, vc = cache.current()
+        for b in range(B):
+            pos = oracle.cache_positions(cache.s[b], cache.t[b], r)
+            assert rows[b] == len(pos), (step, b)
+            assert torch.equal(kc[b, :, :len(pos)].cpu(), kq[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), vq[b][:, pos])
+        step += 1
+    assert step > 3
+    kc, vc = cache.current()
+    sl = torch.tensor([cache.rows(b) for b in range(B)], dtype=torch.int32, device="cuda")
+    qt = torch.stack([q[b, :, n_b - 1] for b, n_b in enumerate(lens)]).contiguous()
+    if dtype == torch.uint8:
+        out, lse = u.decode_e4m3(qt.cuda(), kc, vc, ks.cuda(), vs.cuda(), sl)
+    else:
+        out, lse = u.decode(qt.cuda(), kc, vc, sl)
+    for b, n_b in enumerate(lens):
+        pos = oracle.compressed_cache_positions(n_b - 1, r, W)
+        assert int(sl[b]) == len(pos)
+        if dtype == torch.uint8:
+            o, l = oracle.decode_e4m3(to_np(qt[b:b + 1]), kq[b:b + 1][:, :, pos].numpy(), vq[b:b + 1][:, :, pos].numpy(), ks.numpy(), vs.numpy())
+        else:
+            o, l = oracle.decode(to_np(qt[b:b + 1]), to_np(k[b:b + 1][:, :, pos]), to_np(v[b:b + 1][:, :, pos]))
+        assert max_abs(to_np(out[b]), o[0]) <= TOL_OUT_BF16 and max_abs(to_np(lse[b]), l[0]) <= TOL_LSE_BF16
+    # an impossible request (window start behind the old one for sequence 1, too many rows for sequence 2)
+    before_k = cache.current()[0].clone()
+    s_bad = list(cache.s)
+    s_bad[1] = cache.s[1] - 1 if cache.s[1] > 0 else cache.t[1] + 5
+    n_bad = [0] * B
+    n_bad[2] = 3                      # more than the new_rows of the call below
+    kn = torch.zeros(B, Hkv, 1, D, dtype=kd.dtype, device="cuda")
+    saved = (list(cache.s), list(cache.t), list(cache.cur))
+    rows = cache.update_batch(kn, kn, n_bad, s_bad).cpu().tolist()
+    assert rows[1] == -1 and rows[2] == -1 and all(rows[b] >= 0 for b in (0, 3, 4))
+    kc2 = cache.current()[0]
+    for b in (0, 3, 4):
+        n = rows[b]
+        assert torch.equal(kc2[b, :, :n], before_k[b, :, :n])
