@@ -14,7 +14,7 @@
 //   groups of a workgroup are merged through LDS and the slice's partial result goes
 //   to the workspace as (m, l, acc[D]).  A second kernel merges the slices:
 //   lse = ln sum_s l_s e^{m_s}, out = sum_s e^{m_s - m} acc_s / sum_s e^{m_s - m} l_s.
-#include "common.h"
+#include "mfma_common.h"
 
 namespace unigist {
 namespace {
@@ -404,6 +404,201 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// E4M3 cache, query groups of 2 .. 8 heads per kv head: the contractions go to the matrix cores
+// (v_mfma_f32_16x16x32_bf16; operand layouts in mfma_common.h), which are idle in this bandwidth-bound op, and the
+// vector pipe is left with widening the codes (E4M3 values are exact in bf16) and a softmax over 16-key columns.
+// A wave takes 32 keys per iteration, the workgroup's four waves 128:
+//   S^T = K Q^T   A = K: lane (key r16, g4) loads the D/4 codes [D/4 g4, D/4 (g4+1)) of its key's row, k-step ks uses
+//                 the eight at offset 8 ks (the contraction order is free as long as Q uses the same one);
+//                 B = Q^T: column = query head of the group (columns >= G are zero), in registers;
+//   softmax       a head is a column spread over four lanes, each holding 4 of every 16 keys; its running
+//                 reference is kept identical on the four lanes and raised lazily, the row sum is a per-lane partial;
+//   O^T += V^T P^T  P in place as the B operand (slot 8 g4 + 4 kb + i = key 16 kb + 4 g4 + i); V^T through LDS: the
+//                 wave widens its 32 V rows to bf16 into a private swizzled tile and reads it back transposed.
+// The four waves' partial (m, l, O) are merged through LDS and written to the workspace like the other kernels'.
+template <int D, int G>
+__global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const bf16_t* __restrict__ q,
+                                                                         const uint8_t* __restrict__ kc,
+                                                                         const uint8_t* __restrict__ vc,
+                                                                         const int* __restrict__ seqlens,
+                                                                         const float* __restrict__ k_scale,
+                                                                         const float* __restrict__ v_scale,
+                                                                         float* __restrict__ ws, int Hq, int Hkv, int Lk,
+                                                                         int nsplit, float scale) {
+    constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // k-steps, 16-row blocks of O^T, 16-byte chunks per bf16 row
+    constexpr int BPL = D / 4;                           // K codes per lane and key
+    constexpr int NLV = 32 * D / 1024;                   // 16-byte loads per lane for the wave's 32 V rows
+    constexpr int LPR = D / 16;                          // lanes per V row
+    constexpr float kLog2e = 1.4426950408889634f;
+    constexpr float kSlack = 8.f;                        // the reference is raised when a score exceeds it by 2^kSlack
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 32 * D * 2];  // per wave: 32 rows of D bf16
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r16 = lane & 15, g4 = lane >> 4;
+    const int split = blockIdx.x, b = blockIdx.z, hk = blockIdx.y, hq0 = hk * G;
+    const int n = seqlens ? seqlens[b] : Lk;
+    const int per = (((n + nsplit - 1) / nsplit) + 127) / 128 * 128;
+    const int k0 = split * per;
+    const int k1 = min(n, k0 + per);
+    const float c = scale * k_scale[hk] * kLog2e;        // exp(x) = exp2(x log2 e); the K scale rides along
+
+    // B operand Q^T: lane (column r16 = head of the group, g4) holds Q[head][BPL g4 + 8 ks .. +7]
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (r16 < G) z = *(const u32x4*)(q + ((size_t)b * Hq + hq0 + r16) * D + BPL * g4 + 8 * ks);
+        qf[ks] = __builtin_bit_cast(bf16x8, z);
+    }
+    f32x4 o[DB];  // O^T: register i of o[db] is d = 16 db + 4 g4 + i, column = head r16
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o[db] = zero4();
+    float m = -INFINITY, l = 0.f;
+
+    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * D;
+    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * D;
+    char* vt = smem + w * (32 * D * 2);
+    int toff[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) toff[db] = tr16_lane_off16<CH>(db);
+    // where this lane's V loads go in the tile: load j covers row (64 / LPR) j + lane / LPR, codes 16 (lane % LPR) .. +15,
+    // i.e. the bf16 chunks 2 (lane % LPR) and 2 (lane % LPR) + 1 of that row
+    int vwoff[NLV][2];
+#pragma unroll
+    for (int j = 0; j < NLV; ++j) {
+        const int row = (64 / LPR) * j + lane / LPR;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) vwoff[j][t] = row * (CH * 16) + (((2 * (lane % LPR) + t) ^ swz16<CH>(row)) << 4);
+    }
+
+    for (int base = k0 + 32 * w; base < k1; base += 128) {
+        // ---- loads: K rows base + 16 kb + r16 (clamped into the slice: clamped keys are masked below), V rows likewise
+        u32x4 kw[2][BPL / 16], vw[NLV];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            const int row = min(base + 16 * kb2 + r16, k1 - 1);
+#pragma unroll
+            for (int t = 0; t < BPL / 16; ++t) kw[kb2][t] = *(const u32x4*)(kb + (size_t)row * D + BPL * g4 + 16 * t);
+        }
+#pragma unroll
+        for (int j = 0; j < NLV; ++j) {
+            const int row = min(base + (64 / LPR) * j + lane / LPR, k1 - 1);
+            vw[j] = *(const u32x4*)(vb + (size_t)row * D + 16 * (lane % LPR));
+        }
+        // ---- S^T = K Q^T
+        f32x4 sa[2];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            sa[kb2] = zero4();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint32_t w0 = kw[kb2][ks / 2][2 * (ks % 2)], w1 = kw[kb2][ks / 2][2 * (ks % 2) + 1];
+                const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+                const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+                u32x4 kf;
+                kf[0] = pack_bf16x2(a0[0], a0[1]);
+                kf[1] = pack_bf16x2(a1[0], a1[1]);
+                kf[2] = pack_bf16x2(a2[0], a2[1]);
+                kf[3] = pack_bf16x2(a3[0], a3[1]);
+                sa[kb2] = mfma16(__builtin_bit_cast(bf16x8, kf), qf[ks], sa[kb2]);
+            }
+        }
+        // ---- V rows widened to bf16 into the wave's tile
+#pragma unroll
+        for (int j = 0; j < NLV; ++j) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t w0 = vw[j][2 * t], w1 = vw[j][2 * t + 1];
+                const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+                const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+                u32x4 x;
+                x[0] = pack_bf16x2(a0[0], a0[1]);
+                x[1] = pack_bf16x2(a1[0], a1[1]);
+                x[2] = pack_bf16x2(a2[0], a2[1]);
+                x[3] = pack_bf16x2(a3[0], a3[1]);
+                *(u32x4*)(vt + vwoff[j][t]) = x;
+            }
+        }
+        // ---- softmax over the 32 keys; keys past the slice are masked
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (base + 16 * kb2 + 4 * g4 + i >= k1) sa[kb2][i] = -INFINITY;
+        float mx = fmaxf(fmaxf(fmaxf(sa[0][0], sa[0][1]), fmaxf(sa[0][2], sa[0][3])),
+                         fmaxf(fmaxf(sa[1][0], sa[1][1]), fmaxf(sa[1][2], sa[1][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if ((mx - m) * c > kSlack || m == -INFINITY) {  // same decision on the four lanes of a head (same mx, same m)
+            if (mx > m) {
+                const float alpha = __builtin_amdgcn_exp2f((m - mx) * c);  // m = -inf gives 0
+                l *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[db][i] *= alpha;
+                m = mx;
+            }
+        }
+        const float mc = (m == -INFINITY ? 0.f : m) * c;
+        float p[8];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p[4 * kb2 + i] = __builtin_amdgcn_exp2f(fmaf(sa[kb2][i], c, -mc));
+        l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        u32x4 pk;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) pk[t] = pack_bf16x2(p[2 * t], p[2 * t + 1]);
+        // ---- O^T += V^T P^T (the tile writes above are this wave's own: LDS operations of a wave complete in order)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db] = mfma16(tr16_frag16<CH>(vt + toff[db], 0), __builtin_bit_cast(bf16x8, pk), o[db]);
+    }
+
+    // ---- merge the four waves (the tiles are dead: their memory takes the partials)
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    __syncthreads();
+    float* pm = (float*)smem;              // [4 waves][G]
+    float* pl = pm + 4 * G;                // [4 waves][G]
+    float* po = pl + 4 * G;                // [4 waves][G][D]
+    if (r16 < G) {
+        if (g4 == 0) {
+            pm[w * G + r16] = m;
+            pl[w * G + r16] = l;
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) po[((size_t)w * G + r16) * D + 16 * db + 4 * g4 + i] = o[db][i];
+    }
+    __syncthreads();
+    const float vmul = v_scale[hk];
+    const float ln2 = 0.6931471805599453f;
+    for (int idx = tid; idx < G * D; idx += kThreads) {
+        const int g = idx / D, d = idx % D;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) mm = fmaxf(mm, pm[t * G + g]);
+        float ll = 0.f, a = 0.f;
+        if (mm > -INFINITY) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float wgt = __builtin_amdgcn_exp2f((pm[t * G + g] - mm) * c);  // exp2(-inf) = 0 for a wave that saw no key
+                ll += wgt * pl[t * G + g];
+                a += wgt * po[((size_t)t * G + g) * D + d];
+            }
+        }
+        float* outp = ws + (((size_t)b * Hq + hq0 + g) * nsplit + split) * (D + 2);
+        if (d == 0) {
+            outp[0] = mm * c * ln2;  // the other kernels keep m in natural-log units of the scaled score
+            outp[1] = ll;
+        }
+        outp[2 + d] = a * vmul;
+    }
+}
+
 template <typename TQ, typename T, int D>
 hipError_t decode_launch(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
                          void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, float* ws,
@@ -457,13 +652,23 @@ hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, cons
     const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
     const float scale = 1.0f / sqrtf((float)D);
     const int G = Hq / Hkv;
-    const dim3 grid(nsplit, G == 4 ? Hkv : Hq, B);
+    const bool grouped = G == 2 || G == 4 || G == 8;  // one workgroup serves the whole group from the same K/V bytes
+    const dim3 grid(nsplit, grouped ? Hkv : Hq, B);
     auto go = [&](auto kern) {
         kern<<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc, seqlens, k_scale, v_scale,
                                         ws, Hq, Hkv, Lk, nsplit, scale);
     };
-    if (D == 64) G == 4 ? go(decode_split_e4m3_kernel<64, 4>) : go(decode_split_e4m3_kernel<64, 1>);
-    else G == 4 ? go(decode_split_e4m3_kernel<128, 4>) : go(decode_split_e4m3_kernel<128, 1>);
+    if (D == 64) {
+        if (G == 2) go(decode_split_e4m3_mfma_kernel<64, 2>);
+        else if (G == 4) go(decode_split_e4m3_mfma_kernel<64, 4>);
+        else if (G == 8) go(decode_split_e4m3_mfma_kernel<64, 8>);
+        else go(decode_split_e4m3_kernel<64, 1>);
+    } else {
+        if (G == 2) go(decode_split_e4m3_mfma_kernel<128, 2>);
+        else if (G == 4) go(decode_split_e4m3_mfma_kernel<128, 4>);
+        else if (G == 8) go(decode_split_e4m3_mfma_kernel<128, 8>);
+        else go(decode_split_e4m3_kernel<128, 1>);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);

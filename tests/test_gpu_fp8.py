@@ -55,6 +55,7 @@ CASES = [
     (3, 8, 2, 1000, 128, False), (3, 8, 2, 1000, 128, True), (2, 4, 4, 257, 64, True), (1, 32, 8, 5000, 128, False),
     (2, 6, 2, 300, 128, True), (1, 1, 1, 1, 64, False), (5, 16, 2, 77, 64, True),
     (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
+    (2, 4, 2, 500, 128, True), (1, 8, 1, 700, 128, False), (3, 16, 2, 129, 64, True), (1, 32, 1, 300, 128, False),
 ]
 
 
@@ -73,7 +74,11 @@ def test_decode_over_codes_matches_oracle(B, Hq, Hkv, Lk, D, ragged):
     o, l = oracle.decode_e4m3(to_np(q), kq, vq, ks.numpy(), vs.numpy(), None if sl is None else sl.numpy())
     eo, el = max_abs(to_np(out), o), max_abs(to_np(lse), l)
     print(f"  out {eo:.3e} lse {el:.3e}", flush=True)
-    assert eo <= TOL_OUT_BF16 and el <= TOL_LSE_BF16
+    # `out` is stored as bf16: a sequence of a few keys returns values of v themselves (up to 448 * scale, about 4.8),
+    # where the rounding of the stored result alone is 2^(e-8) for |out| in [2^e, 2^(e+1)); allowed on top from 2 on
+    w = np.abs(o)
+    half_ulp = np.where(w >= 2.0, 2.0 ** (np.floor(np.log2(np.maximum(w, 1e-30))) - 8), 0.0)
+    assert (np.abs(to_np(out) - o) <= TOL_OUT_BF16 + half_ulp).all() and el <= TOL_LSE_BF16
 
 
 def test_quantised_cache_through_updates_then_decode():
