@@ -3,7 +3,12 @@
 // key; the paper notes this is compatible with FlashDecoding-style split-K).
 //
 // The op streams K and V once from HBM: 4 flops per byte, so it is bandwidth bound.
-// Layout of the work:
+// Three slice kernels share the workspace format and the combine kernel:
+//   decode_split_mfma_kernel      bf16 queries, bf16 or E4M3 cache, query groups of 2, 4 or 8 heads: contractions on
+//                                 the matrix cores (described at the kernel);
+//   decode_split_kernel           any dtype (the fp32 debug build) and any group size, plain vector arithmetic;
+//   decode_split_e4m3_kernel      E4M3 cache for the remaining group sizes, vector arithmetic.
+// Layout of the work of the vector kernels:
 //   grid = (splits, kv heads or q heads, B), 256 threads.
 //   A workgroup owns one contiguous slice of one sequence's keys for one kv head and
 //   serves all G = Hq/Hkv query heads of that group from the same K/V bytes.
@@ -405,11 +410,12 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_
 }
 
 // ---------------------------------------------------------------------------------------------
-// E4M3 cache, query groups of 2 .. 8 heads per kv head: the contractions go to the matrix cores
+// bf16 queries, cache in bf16 or as E4M3 codes, query groups of 2, 4 or 8 heads per kv head: the contractions go to the matrix cores
 // (v_mfma_f32_16x16x32_bf16; operand layouts in mfma_common.h), which are idle in this bandwidth-bound op, and the
-// vector pipe is left with widening the codes (E4M3 values are exact in bf16) and a softmax over 16-key columns.
+// vector pipe is left with widening the codes (E4M3 values are exact in bf16; nothing to do for a bf16 cache) and a
+// softmax over 16-key columns.
 // A wave takes 32 keys per iteration, the workgroup's four waves 128:
-//   S^T = K Q^T   A = K: lane (key r16, g4) loads the D/4 codes [D/4 g4, D/4 (g4+1)) of its key's row, k-step ks uses
+//   S^T = K Q^T   A = K: lane (key r16, g4) loads the D/4 elements [D/4 g4, D/4 (g4+1)) of its key's row, k-step ks uses
 //                 the eight at offset 8 ks (the contraction order is free as long as Q uses the same one);
 //                 B = Q^T: column = query head of the group (columns >= G are zero), in registers;
 //   softmax       a head is a column spread over four lanes, each holding 4 of every 16 keys; its running
@@ -417,8 +423,8 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_
 //   O^T += V^T P^T  P in place as the B operand (slot 8 g4 + 4 kb + i = key 16 kb + 4 g4 + i); V^T through LDS: the
 //                 wave widens its 32 V rows to bf16 into a private swizzled tile and reads it back transposed.
 // The four waves' partial (m, l, O) are merged through LDS and written to the workspace like the other kernels'.
-template <int D, int G>
-__global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const bf16_t* __restrict__ q,
+template <int D, int G, bool E4M3>
+__global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_t* __restrict__ q,
                                                                          const uint8_t* __restrict__ kc,
                                                                          const uint8_t* __restrict__ vc,
                                                                          const int* __restrict__ seqlens,
@@ -427,9 +433,11 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const 
                                                                          float* __restrict__ ws, int Hq, int Hkv, int Lk,
                                                                          int nsplit, float scale) {
     constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // k-steps, 16-row blocks of O^T, 16-byte chunks per bf16 row
-    constexpr int BPL = D / 4;                           // K codes per lane and key
-    constexpr int NLV = 32 * D / 1024;                   // 16-byte loads per lane for the wave's 32 V rows
-    constexpr int LPR = D / 16;                          // lanes per V row
+    constexpr int EB = E4M3 ? 1 : 2;                     // bytes per cache element
+    constexpr int BPL = D / 4;                           // K elements per lane and key
+    constexpr int NKL = BPL * EB / 16;                   // 16-byte loads per lane and key for them
+    constexpr int NLV = 32 * D * EB / 1024;              // 16-byte loads per lane for the wave's 32 V rows
+    constexpr int LPR = D * EB / 16;                     // lanes per V row
     constexpr float kLog2e = 1.4426950408889634f;
     constexpr float kSlack = 8.f;                        // the reference is raised when a score exceeds it by 2^kSlack
     __shared__ __attribute__((aligned(1024))) char smem[4 * 32 * D * 2];  // per wave: 32 rows of D bf16
@@ -441,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const 
     const int per = (((n + nsplit - 1) / nsplit) + 127) / 128 * 128;
     const int k0 = split * per;
     const int k1 = min(n, k0 + per);
-    const float c = scale * k_scale[hk] * kLog2e;        // exp(x) = exp2(x log2 e); the K scale rides along
+    const float c = scale * (E4M3 ? k_scale[hk] : 1.f) * kLog2e;  // exp(x) = exp2(x log2 e); the K scale rides along
 
     // B operand Q^T: lane (column r16 = head of the group, g4) holds Q[head][BPL g4 + 8 ks .. +7]
     bf16x8 qf[KS];
@@ -456,35 +464,38 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const 
     for (int db = 0; db < DB; ++db) o[db] = zero4();
     float m = -INFINITY, l = 0.f;
 
-    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * D;
-    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * D;
+    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * (D * EB);
+    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * (D * EB);
     char* vt = smem + w * (32 * D * 2);
     int toff[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) toff[db] = tr16_lane_off16<CH>(db);
-    // where this lane's V loads go in the tile: load j covers row (64 / LPR) j + lane / LPR, codes 16 (lane % LPR) .. +15,
-    // i.e. the bf16 chunks 2 (lane % LPR) and 2 (lane % LPR) + 1 of that row
-    int vwoff[NLV][2];
+    // where this lane's V loads go in the tile: load j covers row (64 / LPR) j + lane / LPR and 16 bytes of it -- 16
+    // codes, i.e. the bf16 chunks 2 (lane % LPR) and 2 (lane % LPR) + 1 of that row, or the bf16 chunk lane % LPR itself
+    constexpr int NVW = E4M3 ? 2 : 1;
+    int vwoff[NLV][NVW];
 #pragma unroll
     for (int j = 0; j < NLV; ++j) {
         const int row = (64 / LPR) * j + lane / LPR;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) vwoff[j][t] = row * (CH * 16) + (((2 * (lane % LPR) + t) ^ swz16<CH>(row)) << 4);
+        for (int t = 0; t < NVW; ++t)
+            vwoff[j][t] = row * (CH * 16) + (((NVW * (lane % LPR) + t) ^ swz16<CH>(row)) << 4);
     }
 
     for (int base = k0 + 32 * w; base < k1; base += 128) {
         // ---- loads: K rows base + 16 kb + r16 (clamped into the slice: clamped keys are masked below), V rows likewise
-        u32x4 kw[2][BPL / 16], vw[NLV];
+        u32x4 kw[2][NKL], vw[NLV];
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             const int row = min(base + 16 * kb2 + r16, k1 - 1);
 #pragma unroll
-            for (int t = 0; t < BPL / 16; ++t) kw[kb2][t] = *(const u32x4*)(kb + (size_t)row * D + BPL * g4 + 16 * t);
+            for (int t = 0; t < NKL; ++t)
+                kw[kb2][t] = *(const u32x4*)(kb + (size_t)row * (D * EB) + BPL * EB * g4 + 16 * t);
         }
 #pragma unroll
         for (int j = 0; j < NLV; ++j) {
             const int row = min(base + (64 / LPR) * j + lane / LPR, k1 - 1);
-            vw[j] = *(const u32x4*)(vb + (size_t)row * D + 16 * (lane % LPR));
+            vw[j] = *(const u32x4*)(vb + (size_t)row * (D * EB) + 16 * (lane % LPR));
         }
         // ---- S^T = K Q^T
         f32x4 sa[2];
@@ -493,22 +504,30 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const 
             sa[kb2] = zero4();
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const uint32_t w0 = kw[kb2][ks / 2][2 * (ks % 2)], w1 = kw[kb2][ks / 2][2 * (ks % 2) + 1];
-                const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
-                const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
                 u32x4 kf;
-                kf[0] = pack_bf16x2(a0[0], a0[1]);
-                kf[1] = pack_bf16x2(a1[0], a1[1]);
-                kf[2] = pack_bf16x2(a2[0], a2[1]);
-                kf[3] = pack_bf16x2(a3[0], a3[1]);
+                if constexpr (E4M3) {
+                    const uint32_t w0 = kw[kb2][ks / 2][2 * (ks % 2)], w1 = kw[kb2][ks / 2][2 * (ks % 2) + 1];
+                    const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+                    const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+                    kf[0] = pack_bf16x2(a0[0], a0[1]);
+                    kf[1] = pack_bf16x2(a1[0], a1[1]);
+                    kf[2] = pack_bf16x2(a2[0], a2[1]);
+                    kf[3] = pack_bf16x2(a3[0], a3[1]);
+                } else {
+                    kf = kw[kb2][ks];
+                }
                 sa[kb2] = mfma16(__builtin_bit_cast(bf16x8, kf), qf[ks], sa[kb2]);
             }
         }
-        // ---- V rows widened to bf16 into the wave's tile
+        // ---- V rows (widened to bf16) into the wave's tile
 #pragma unroll
         for (int j = 0; j < NLV; ++j) {
+            if constexpr (!E4M3) {
+                *(u32x4*)(vt + vwoff[j][0]) = vw[j];
+                continue;
+            }
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < NVW; ++t) {
                 const uint32_t w0 = vw[j][2 * t], w1 = vw[j][2 * t + 1];
                 const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
                 const f32x2 a2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), a3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
@@ -574,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_mfma_kernel(const 
             for (int i = 0; i < 4; ++i) po[((size_t)w * G + r16) * D + 16 * db + 4 * g4 + i] = o[db][i];
     }
     __syncthreads();
-    const float vmul = v_scale[hk];
+    const float vmul = E4M3 ? v_scale[hk] : 1.f;
     const float ln2 = 0.6931471805599453f;
     for (int idx = tid; idx < G * D; idx += kThreads) {
         const int g = idx / D, d = idx % D;
@@ -642,6 +661,24 @@ hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* ou
     if (dt == UNIGIST_F32)
         return D == 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
                        : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+    const int G = Hq / Hkv;
+    if (G == 2 || G == 4 || G == 8) {
+        // the matrix-core kernel: one workgroup per kv head serves the whole group from the same K/V bytes
+        const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
+        const float scale = 1.0f / sqrtf((float)D);
+        const dim3 grid(nsplit, Hkv, B);
+        auto go = [&](auto kern) {
+            kern<<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc, seqlens, nullptr, nullptr,
+                                            ws, Hq, Hkv, Lk, nsplit, scale);
+        };
+        if (D == 64) G == 2 ? go(decode_split_mfma_kernel<64, 2, false>) : G == 4 ? go(decode_split_mfma_kernel<64, 4, false>) : go(decode_split_mfma_kernel<64, 8, false>);
+        else G == 2 ? go(decode_split_mfma_kernel<128, 2, false>) : G == 4 ? go(decode_split_mfma_kernel<128, 4, false>) : go(decode_split_mfma_kernel<128, 8, false>);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
+        else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
+        return hipGetLastError();
+    }
     return D == 64 ? decode_launch<bf16_t, bf16_t, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
                    : decode_launch<bf16_t, bf16_t, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
 }
@@ -659,14 +696,14 @@ hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, cons
                                         ws, Hq, Hkv, Lk, nsplit, scale);
     };
     if (D == 64) {
-        if (G == 2) go(decode_split_e4m3_mfma_kernel<64, 2>);
-        else if (G == 4) go(decode_split_e4m3_mfma_kernel<64, 4>);
-        else if (G == 8) go(decode_split_e4m3_mfma_kernel<64, 8>);
+        if (G == 2) go(decode_split_mfma_kernel<64, 2, true>);
+        else if (G == 4) go(decode_split_mfma_kernel<64, 4, true>);
+        else if (G == 8) go(decode_split_mfma_kernel<64, 8, true>);
         else go(decode_split_e4m3_kernel<64, 1>);
     } else {
-        if (G == 2) go(decode_split_e4m3_mfma_kernel<128, 2>);
-        else if (G == 4) go(decode_split_e4m3_mfma_kernel<128, 4>);
-        else if (G == 8) go(decode_split_e4m3_mfma_kernel<128, 8>);
+        if (G == 2) go(decode_split_mfma_kernel<128, 2, true>);
+        else if (G == 4) go(decode_split_mfma_kernel<128, 4, true>);
+        else if (G == 8) go(decode_split_mfma_kernel<128, 8, true>);
         else go(decode_split_e4m3_kernel<128, 1>);
     }
     hipError_t e = hipGetLastError();

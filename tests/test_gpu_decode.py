@@ -15,6 +15,7 @@ CASES = [
     (3, 8, 2, 1000, 128, False), (3, 8, 2, 1000, 128, True), (2, 4, 4, 257, 64, True), (1, 32, 8, 5000, 128, False),
     (2, 6, 2, 300, 128, True), (1, 1, 1, 1, 64, False), (5, 16, 2, 77, 64, True),
     (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
+    (2, 4, 2, 500, 128, True), (1, 8, 1, 700, 128, False), (3, 16, 2, 129, 64, True), (1, 32, 1, 300, 128, False),
 ]
 
 
@@ -32,7 +33,11 @@ def test_decode_matches_oracle(B, Hq, Hkv, Lk, D, ragged, dtype):
     if dtype == torch.float32:
         assert eo <= TOL_F32 and el <= TOL_F32
     else:
-        assert eo <= TOL_OUT_BF16 and el <= TOL_LSE_BF16
+        # `out` is stored as bf16: from |out| >= 2 on (sequences of a few keys) the rounding of the stored result alone,
+        # 2^(e-8) for |out| in [2^e, 2^(e+1)), is allowed on top
+        w = np.abs(o)
+        half_ulp = np.where(w >= 2.0, 2.0 ** (np.floor(np.log2(np.maximum(w, 1e-30))) - 8), 0.0)
+        assert (np.abs(to_np(out) - o) <= TOL_OUT_BF16 + half_ulp).all() and el <= TOL_LSE_BF16
 
 
 def test_decode_equals_last_row_of_the_training_kernel():
