@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1039538988, "dkdv_gist": 2414710159, "dkdv_window": 1476173131, "dq": 1401891691,
-                 "decode": 4567944164, "decode_e4m3": 2287378804}
+TRAFFIC_BYTES = {"fwd": 1041487893, "dkdv_gist": 2401463265, "dkdv_window": 1481242740, "dq": 1401412280,
+                 "decode": 4637786785, "decode_e4m3": 2288772555}
 
 
 def pair_counts(L, r, W):
