@@ -163,7 +163,7 @@ extern "C" unigist_status unigist_attn_bwd(const void* q, const void* k, const v
 extern "C" size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt) {
     if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || Hq % Hkv != 0) return 0;
     if ((D != 64 && D != 128) || (dt != UNIGIST_BF16 && dt != UNIGIST_F32)) return 0;
-    const int ns = decode_num_splits(B, Hq, Hkv, Lk_max);
+    const int ns = decode_num_splits(B, Hq, Hkv, Lk_max, dt);
     return align256((size_t)B * Hq * ns * (D + 2) * sizeof(float));
 }
 

@@ -109,7 +109,8 @@ size_t bwd_mfma_workspace(const AttnShape& s);
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws,
                            const AttnShape& s, unsigned stages, hipStream_t st);
-int decode_num_splits(int B, int Hq, int Hkv, int Lk);
+bool decode_grouped(int Hq, int Hkv, unigist_dtype dt);
+int decode_num_splits(int B, int Hq, int Hkv, int Lk, unigist_dtype dt);
 hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
                                const void* k_new, const void* v_new, int n_new, int new_rows,
                                void* kc_out, void* vc_out, int s_new, int cap_out,

@@ -4,11 +4,10 @@
 //
 // The op streams K and V once from HBM: 4 flops per byte, so it is bandwidth bound.
 // Three slice kernels share the workspace format and the combine kernel:
-//   decode_split_mfma_kernel      bf16 queries, bf16 or E4M3 cache, query groups of 2, 4 or 8 heads: contractions on
+//   decode_split_mfma_kernel      bf16 queries, bf16 or E4M3 cache, query groups of up to 15 heads: contractions on
 //                                 the matrix cores (described at the kernel);
-//   decode_split_kernel           any dtype (the fp32 debug build) and any group size, plain vector arithmetic;
-//   decode_split_e4m3_kernel      E4M3 cache for the remaining group sizes, vector arithmetic.
-// Layout of the work of the vector kernels:
+//   decode_split_kernel           any dtype (the fp32 debug build) and any group size, plain vector arithmetic.
+// Layout of the work of the vector kernel:
 //   grid = (splits, kv heads or q heads, B), 256 threads.
 //   A workgroup owns one contiguous slice of one sequence's keys for one kv head and
 //   serves all G = Hq/Hkv query heads of that group from the same K/V bytes.
@@ -19,6 +18,8 @@
 //   groups of a workgroup are merged through LDS and the slice's partial result goes
 //   to the workspace as (m, l, acc[D]).  A second kernel merges the slices:
 //   lse = ln sum_s l_s e^{m_s}, out = sum_s e^{m_s - m} acc_s / sum_s e^{m_s - m} l_s.
+#include <type_traits>
+
 #include "mfma_common.h"
 
 namespace unigist {
@@ -226,191 +227,7 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same slice kernel for a cache of E4M3 codes and bf16 queries.  With one byte per element the generic
-// kernel above is bound by its vector arithmetic, not by HBM, so this one spends less of it per element:
-//   * a lane takes 16 codes (one 16-byte load), so D/16 lanes share a row and the per-row work that every
-//     lane of a row repeats (reduction, softmax) is spread over twice as many elements;
-//   * the scores come from v_dot2c_f32_bf16 on packed pairs -- E4M3 values are exact in bf16 and the query
-//     already is bf16, so the products are the same numbers as before, two per instruction; the softmax
-//     scale and the K scale multiply the finished dot product;
-//   * P stays fp32 and the V codes are widened to fp32 for the accumulation.
-// The 256 / (D/16) row groups of a workgroup are folded in halves through LDS down to 16, then merged as above.
-template <int D, int G>
-__global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_t* __restrict__ q,
-                                                                    const uint8_t* __restrict__ kc,
-                                                                    const uint8_t* __restrict__ vc,
-                                                                    const int* __restrict__ seqlens,
-                                                                    const float* __restrict__ k_scale,
-                                                                    const float* __restrict__ v_scale,
-                                                                    float* __restrict__ ws, int Hq, int Hkv, int Lk,
-                                                                    int nsplit, float scale) {
-    constexpr int LPR = D / 16;            // lanes per row
-    constexpr int RPI = kThreads / LPR;    // row groups = rows per iteration
-    constexpr int U = 4;
-    constexpr int E = 16;
-    const int tid = threadIdx.x;
-    const int sub = tid % LPR, grp = tid / LPR;
-    const int split = blockIdx.x, b = blockIdx.z;
-    const int hq0 = blockIdx.y * G;
-    const int hk = hq0 / (Hq / Hkv);
-    const int n = seqlens ? seqlens[b] : Lk;
-    const int per = (((n + nsplit - 1) / nsplit) + kRowsPerIter - 1) / kRowsPerIter * kRowsPerIter;
-    const int k0 = split * per;
-    const int k1 = min(n, k0 + per);
-    const float sc = scale * k_scale[hk];
-
-    uint32_t qp[G][E / 2];  // packed bf16 pairs (elements 2j, 2j+1 of this lane's chunk)
-    float acc[G][E], m[G], l[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const u32x4* p = (const u32x4*)(q + ((size_t)b * Hq + hq0 + g) * D + sub * E);
-        const u32x4 a = p[0], c = p[1];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            qp[g][t] = a[t];
-            qp[g][4 + t] = c[t];
-        }
-        m[g] = -INFINITY;
-        l[g] = 0.f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
-    }
-    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
-    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
-
-    for (int base = k0; base < k1; base += RPI * U) {
-        u32x4 kw[U], vw[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = base + u * RPI + grp;
-            ok[u] = row < k1;
-            const int rr = ok[u] ? row : k0;  // k0 < k1 <= n whenever this loop runs: always in bounds
-            kw[u] = *(const u32x4*)(kb + (size_t)rr * D);
-            vw[u] = *(const u32x4*)(vb + (size_t)rr * D);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t kp[E / 2];
-            float vf[E];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const f32x2 klo = __builtin_amdgcn_cvt_pk_f32_fp8((int)kw[u][t], false);
-                const f32x2 khi = __builtin_amdgcn_cvt_pk_f32_fp8((int)kw[u][t], true);
-                kp[2 * t] = pack_bf16x2(klo[0], klo[1]);
-                kp[2 * t + 1] = pack_bf16x2(khi[0], khi[1]);
-                const f32x2 vlo = __builtin_amdgcn_cvt_pk_f32_fp8((int)vw[u][t], false);
-                const f32x2 vhi = __builtin_amdgcn_cvt_pk_f32_fp8((int)vw[u][t], true);
-                vf[4 * t] = vlo[0];
-                vf[4 * t + 1] = vlo[1];
-                vf[4 * t + 2] = vhi[0];
-                vf[4 * t + 3] = vhi[1];
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float s = 0.f;
-#pragma unroll
-                for (int j = 0; j < E / 2; ++j)
-                    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kp[j]),
-                                                        __builtin_bit_cast(bf16x2, qp[g][j]), s, false);
-                // sum over the LPR lanes of the row (lanes of one quad, then the neighbouring quad)
-                s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0xB1, 0xf, 0xf, false));
-                s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x4E, 0xf, 0xf, false));
-                if constexpr (LPR == 8)
-                    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x141, 0xf, 0xf, false));
-                s *= sc;
-                if (ok[u]) {
-                    if (s > m[g]) {
-                        const float a = __expf(m[g] - s);
-                        l[g] *= a;
-#pragma unroll
-                        for (int e = 0; e < E; ++e) acc[g][e] *= a;
-                        m[g] = s;
-                    }
-                    const float p = __expf(s - m[g]);
-                    l[g] += p;
-#pragma unroll
-                    for (int e = 0; e < E; ++e) acc[g][e] += p * vf[e];
-                }
-            }
-        }
-    }
-
-    // fold the row groups in halves down to 16 of them: the upper half parks its state in LDS, the lower half
-    // merges it into its own
-    constexpr int HMAX = RPI / 2;
-    __shared__ float fm[G][HMAX];
-    __shared__ float fl[G][HMAX];
-    __shared__ float facc[G][HMAX][D];
-#pragma unroll
-    for (int half = HMAX; half >= kRowsPerIter; half /= 2) {
-        if (grp >= half && grp < 2 * half) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (sub == 0) {
-                    fm[g][grp - half] = m[g];
-                    fl[g][grp - half] = l[g];
-                }
-#pragma unroll
-                for (int e = 0; e < E; ++e) facc[g][grp - half][sub * E + e] = acc[g][e];
-            }
-        }
-        __syncthreads();
-        if (grp < half) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float m2 = fm[g][grp], l2 = fl[g][grp];
-                const float mm = fmaxf(m[g], m2);
-                if (mm > -INFINITY) {
-                    const float w1 = __expf(m[g] - mm), w2 = __expf(m2 - mm);  // exp(-inf) = 0 for a side that saw no key
-                    l[g] = w1 * l[g] + w2 * l2;
-#pragma unroll
-                    for (int e = 0; e < E; ++e) acc[g][e] = w1 * acc[g][e] + w2 * facc[g][grp][sub * E + e];
-                    m[g] = mm;
-                }
-            }
-        }
-        __syncthreads();
-    }
-    // the 16 remaining groups: merged as in the generic kernel (their states reuse the fold buffers)
-    if (grp < kRowsPerIter) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (sub == 0) {
-                fm[g][grp] = m[g];
-                fl[g][grp] = l[g];
-            }
-#pragma unroll
-            for (int e = 0; e < E; ++e) facc[g][grp][sub * E + e] = acc[g][e];
-        }
-    }
-    __syncthreads();
-    const float vmul = v_scale[hk];
-    for (int idx = tid; idx < G * D; idx += kThreads) {
-        const int g = idx / D, d = idx % D;
-        float mm = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < kRowsPerIter; ++t) mm = fmaxf(mm, fm[g][t]);
-        float ll = 0.f, a = 0.f;
-        if (mm > -INFINITY) {
-#pragma unroll
-            for (int t = 0; t < kRowsPerIter; ++t) {
-                const float w = __expf(fm[g][t] - mm);
-                ll += w * fl[g][t];
-                a += w * facc[g][t][d];
-            }
-        }
-        float* o = ws + (((size_t)b * Hq + hq0 + g) * nsplit + split) * (D + 2);
-        if (d == 0) {
-            o[0] = mm;
-            o[1] = ll;
-        }
-        o[2 + d] = a * vmul;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// bf16 queries, cache in bf16 or as E4M3 codes, query groups of 2, 4 or 8 heads per kv head: the contractions go to the matrix cores
+// bf16 queries, cache in bf16 or as E4M3 codes, query groups of up to 15 heads per kv head: the contractions go to the matrix cores
 // (v_mfma_f32_16x16x32_bf16; operand layouts in mfma_common.h), which are idle in this bandwidth-bound op, and the
 // vector pipe is left with widening the codes (E4M3 values are exact in bf16; nothing to do for a bf16 cache) and a
 // softmax over 16-key columns.
@@ -423,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_e4m3_kernel(const bf16_
 //   O^T += V^T P^T  P in place as the B operand (slot 8 g4 + 4 kb + i = key 16 kb + 4 g4 + i); V^T through LDS: the
 //                 wave widens its 32 V rows to bf16 into a private swizzled tile and reads it back transposed.
 // The four waves' partial (m, l, O) are merged through LDS and written to the workspace like the other kernels'.
-template <int D, int G, bool E4M3>
+template <int D, bool E4M3>
 __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_t* __restrict__ q,
                                                                          const uint8_t* __restrict__ kc,
                                                                          const uint8_t* __restrict__ vc,
@@ -444,6 +261,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g4 = lane >> 4;
+    const int G = Hq / Hkv;  // <= 15: the merge buffer below holds 4 G (D + 2) floats
     const int split = blockIdx.x, b = blockIdx.z, hk = blockIdx.y, hq0 = hk * G;
     const int n = seqlens ? seqlens[b] : Lk;
     const int per = (((n + nsplit - 1) / nsplit) + 127) / 128 * 128;
@@ -623,10 +441,10 @@ hipError_t decode_launch(const void* q, const void* kc, const void* vc, const fl
                          void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, float* ws,
                          hipStream_t st) {
     constexpr int U = kUnroll;
-    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
+    constexpr unigist_dtype dt = std::is_same<TQ, float>::value ? UNIGIST_F32 : UNIGIST_BF16;
+    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk, dt);
     const float scale = 1.0f / sqrtf((float)D);
-    const int G = Hq / Hkv;
-    if (G == 4) {
+    if (decode_grouped(Hq, Hkv, dt) && Hq / Hkv == 4) {
         dim3 grid(nsplit, Hkv, B);
         decode_split_kernel<TQ, T, D, 4, U><<<grid, kThreads, 0, st>>>((const TQ*)q, (const T*)kc, (const T*)vc, seqlens,
                                                                        k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
@@ -645,9 +463,15 @@ hipError_t decode_launch(const void* q, const void* kc, const void* vc, const fl
 
 // Enough slices to put several workgroups on each of the 256 CUs, but never slices
 // shorter than 256 keys.
-int decode_num_splits(int B, int Hq, int Hkv, int Lk) {
+// Does one workgroup serve all query heads of a kv head?  The matrix-core kernel takes groups of up to 15 heads
+// (bf16 queries); the vector kernel, which the fp32 build uses, shares the K/V bytes for groups of 4 only.
+bool decode_grouped(int Hq, int Hkv, unigist_dtype dt) {
     const int G = Hq / Hkv;
-    const long units = (long)B * (G == 4 ? Hkv : Hq);
+    return dt == UNIGIST_F32 ? G == 4 : G <= 15;
+}
+
+int decode_num_splits(int B, int Hq, int Hkv, int Lk, unigist_dtype dt) {
+    const long units = (long)B * (decode_grouped(Hq, Hkv, dt) ? Hkv : Hq);
     long want = (2048 + units - 1) / units;
     long cap = (Lk + 255) / 256;
     long n = want < cap ? want : cap;
@@ -656,61 +480,46 @@ int decode_num_splits(int B, int Hq, int Hkv, int Lk) {
     return (int)n;
 }
 
-hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
-                         int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt, float* ws, hipStream_t st) {
-    if (dt == UNIGIST_F32)
-        return D == 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                       : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
-    const int G = Hq / Hkv;
-    if (G == 2 || G == 4 || G == 8) {
-        // the matrix-core kernel: one workgroup per kv head serves the whole group from the same K/V bytes
-        const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
-        const float scale = 1.0f / sqrtf((float)D);
-        const dim3 grid(nsplit, Hkv, B);
-        auto go = [&](auto kern) {
-            kern<<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc, seqlens, nullptr, nullptr,
-                                            ws, Hq, Hkv, Lk, nsplit, scale);
-        };
-        if (D == 64) G == 2 ? go(decode_split_mfma_kernel<64, 2, false>) : G == 4 ? go(decode_split_mfma_kernel<64, 4, false>) : go(decode_split_mfma_kernel<64, 8, false>);
-        else G == 2 ? go(decode_split_mfma_kernel<128, 2, false>) : G == 4 ? go(decode_split_mfma_kernel<128, 4, false>) : go(decode_split_mfma_kernel<128, 8, false>);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
-        else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
-        return hipGetLastError();
+namespace {
+// bf16 queries over a bf16 or E4M3 cache: the matrix-core kernel when the group fits its columns, else one
+// workgroup per query head with the vector kernel
+template <bool E4M3>
+hipError_t decode_bf16q(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale, void* out,
+                        float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, float* ws, hipStream_t st) {
+    if (!decode_grouped(Hq, Hkv, UNIGIST_BF16)) {
+        using T = std::conditional_t<E4M3, fp8_t, bf16_t>;
+        return D == 64 ? decode_launch<bf16_t, T, 64>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                       : decode_launch<bf16_t, T, 128>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
     }
-    return D == 64 ? decode_launch<bf16_t, bf16_t, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                   : decode_launch<bf16_t, bf16_t, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
-}
-
-hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
-                             void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
-                             float* ws, hipStream_t st) {
-    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk);
+    const int nsplit = decode_num_splits(B, Hq, Hkv, Lk, UNIGIST_BF16);
     const float scale = 1.0f / sqrtf((float)D);
-    const int G = Hq / Hkv;
-    const bool grouped = G == 2 || G == 4 || G == 8;  // one workgroup serves the whole group from the same K/V bytes
-    const dim3 grid(nsplit, grouped ? Hkv : Hq, B);
-    auto go = [&](auto kern) {
-        kern<<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc, seqlens, k_scale, v_scale,
-                                        ws, Hq, Hkv, Lk, nsplit, scale);
-    };
-    if (D == 64) {
-        if (G == 2) go(decode_split_mfma_kernel<64, 2, true>);
-        else if (G == 4) go(decode_split_mfma_kernel<64, 4, true>);
-        else if (G == 8) go(decode_split_mfma_kernel<64, 8, true>);
-        else go(decode_split_e4m3_kernel<64, 1>);
-    } else {
-        if (G == 2) go(decode_split_mfma_kernel<128, 2, true>);
-        else if (G == 4) go(decode_split_mfma_kernel<128, 4, true>);
-        else if (G == 8) go(decode_split_mfma_kernel<128, 8, true>);
-        else go(decode_split_e4m3_kernel<128, 1>);
-    }
+    const dim3 grid(nsplit, Hkv, B);
+    if (D == 64)
+        decode_split_mfma_kernel<64, E4M3><<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc,
+                                                                      seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
+    else
+        decode_split_mfma_kernel<128, E4M3><<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc,
+                                                                       seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
     else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
+                         int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt, float* ws, hipStream_t st) {
+    if (dt == UNIGIST_F32)
+        return D == 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
+                       : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+    return decode_bf16q<false>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st);
+}
+
+hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
+                             void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
+                             float* ws, hipStream_t st) {
+    return decode_bf16q<true>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -16,6 +16,7 @@ CASES = [
     (2, 6, 2, 300, 128, True), (1, 1, 1, 1, 64, False), (5, 16, 2, 77, 64, True),
     (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
     (2, 4, 2, 500, 128, True), (1, 8, 1, 700, 128, False), (3, 16, 2, 129, 64, True), (1, 32, 1, 300, 128, False),
+    (2, 16, 1, 200, 64, True), (2, 15, 1, 333, 128, True), (1, 12, 4, 1000, 128, False),
 ]
 
 
