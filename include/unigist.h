@@ -179,7 +179,8 @@ size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, i
  * visible; the order of the keys in the cache is irrelevant.
  *   q [B,Hq,D]; kcache, vcache [B,Hkv,Lk_max,D] (dt): in.
  *   seqlens: device int32 [B], number of valid keys per sequence (each in
- *            [1, Lk_max]); NULL means Lk_max for all.
+ *            [1, Lk_max]; a sequence given 0 keys gets out = 0 and lse = -inf);
+ *            NULL means Lk_max for all.
  *   out [B,Hq,D] (dt): out.  lse [B,Hq] float: out, may be NULL.
  * Split-K over the keys with a log-sum-exp combine (FlashDecoding style).
  * workspace: at least unigist_decode_workspace(...) bytes, 256-byte aligned.

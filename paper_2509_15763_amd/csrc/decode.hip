@@ -216,6 +216,11 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
     const float* p = ws + (size_t)bh * nsplit * (D + 2);
     float mm = -INFINITY;
     for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, p[s * (D + 2)]);
+    if (mm == -INFINITY) {  // a sequence of zero keys (outside the contract): the empty sum, not NaN
+        Elem<T>::store(out + (size_t)bh * D + d, 0.f);
+        if (lse && d == 0) lse[bh] = -INFINITY;
+        return;
+    }
     float ll = 0.f, a = 0.f;
     for (int s = 0; s < nsplit; ++s) {
         float w = __expf(p[s * (D + 2)] - mm);
@@ -461,8 +466,6 @@ hipError_t decode_launch(const void* q, const void* kc, const void* vc, const fl
 
 }  // namespace
 
-// Enough slices to put several workgroups on each of the 256 CUs, but never slices
-// shorter than 256 keys.
 // Does one workgroup serve all query heads of a kv head?  The matrix-core kernel takes groups of up to 15 heads
 // (bf16 queries); the vector kernel, which the fp32 build uses, shares the K/V bytes for groups of 4 only.
 bool decode_grouped(int Hq, int Hkv, unigist_dtype dt) {
@@ -470,6 +473,7 @@ bool decode_grouped(int Hq, int Hkv, unigist_dtype dt) {
     return dt == UNIGIST_F32 ? G == 4 : G <= 15;
 }
 
+// Enough slices to put several workgroups on each of the 256 CUs, but never slices shorter than 256 keys.
 int decode_num_splits(int B, int Hq, int Hkv, int Lk, unigist_dtype dt) {
     const long units = (long)B * (decode_grouped(Hq, Hkv, dt) ? Hkv : Hq);
     long want = (2048 + units - 1) / units;

@@ -52,3 +52,16 @@ def test_decode_equals_last_row_of_the_training_kernel():
     o2, l2 = u.decode(q[:, :, t].contiguous().cuda(), kc.cuda(), vc.cuda())
     assert max_abs(to_np(o2), to_np(out[:, :, t])) <= 1e-2
     assert max_abs(to_np(l2), to_np(lse[:, :, t])) <= 1e-3
+
+
+def test_a_sequence_of_zero_keys_gives_the_empty_sum():
+    # outside the contract (seqlens are >= 1), but it must not poison the batch with NaN
+    B, Hq, Hkv, Lk, D = 3, 8, 2, 300, 128
+    q, kc, vc = synth.decode_inputs(B, Hq, Hkv, Lk, D, seed=5)
+    sl = torch.tensor([300, 0, 17], dtype=torch.int32)
+    out, lse = u.decode(q.cuda(), kc.cuda(), vc.cuda(), sl.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(out[1].cpu(), torch.zeros_like(out[1].cpu())) and torch.isinf(lse[1]).all() and (lse[1] < 0).all()
+    keep = [0, 2]
+    o, l = oracle.decode(to_np(q[keep]), to_np(kc[keep]), to_np(vc[keep]), sl[keep].numpy())
+    assert max_abs(to_np(out[keep]), o) <= 2e-2 and max_abs(to_np(lse[keep]), l) <= TOL_LSE_BF16
