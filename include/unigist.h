@@ -153,14 +153,20 @@ size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r
  * document everything is as in unigist_attn_fwd / unigist_attn_bwd with L = its length: the gist period and
  * the window restart at the document's first token.  cu_seqlens is a HOST array of ndocs + 1 ints,
  * non-decreasing, cu_seqlens[0] = 0, cu_seqlens[ndocs] = T (UNIGIST_EINVAL otherwise); it is read before the
- * call returns.  Empty documents are allowed.  The documents are independent.  The forward launches one kernel
- * per document on hip_stream.  The backward spreads the documents' kernel sequences over hip_stream and a few
- * helper streams that the library creates once per device (default priority, kept until the process ends --
- * the one piece of state this library holds); the helpers start after everything already enqueued on
- * hip_stream and hip_stream continues after them, so the call behaves like work enqueued on hip_stream
- * (under stream capture the helpers join the capture through those events; the streams themselves are
- * created by the first backward call on a device, which therefore has to happen outside a capture).
- * workspace: size from unigist_attn_bwd_varlen_workspace (one slice per stream), 256-byte aligned.
+ * call returns.  Empty documents are allowed.  The documents are independent.
+ * bf16: every kernel is launched once for up to 64 documents (the document boundaries travel as a kernel
+ * argument and each workgroup looks up the document it belongs to), everything on hip_stream; longer lists of
+ * documents take one launch per 64.
+ * fp32 (the plain-ALU debug kernels) and bf16 under UNIGIST_DEBUG_PLAIN_ALU=1: one launch sequence per document;
+ * the backward spreads the documents over hip_stream and a few helper streams that the library creates once per
+ * device (default priority, kept until the process ends -- the one piece of state this library holds); the
+ * helpers start after everything already enqueued on hip_stream and hip_stream continues after them, so the
+ * call behaves like work enqueued on hip_stream (under stream capture the helpers join the capture through
+ * those events; the streams themselves are created by the first such backward call on a device, which therefore
+ * has to happen outside a capture).
+ * workspace: size from unigist_attn_bwd_varlen_workspace, 256-byte aligned.  bf16: two floats per (head, token)
+ * plus the gist-phase partial sums of every document; fp32: one slice per stream, each sized for the longest
+ * document.
  */
 unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
                                        int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,

@@ -1,6 +1,7 @@
 // C ABI of libunigist: argument validation and dispatch.  No device memory is
 // allocated here and nothing synchronises; kernels are enqueued on the caller's stream
-// (the packed backward also uses helper streams ordered behind and before it, see for_each_doc).
+// (the document-by-document packed backward of the fp32 kernels also uses helper streams ordered behind and
+// before it, see for_each_doc).
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -331,8 +332,9 @@ AttnShape doc_shape(int Hq, int Hkv, int T, int D, int r, int W, int len) {
 
 size_t elem_bytes(unigist_dtype dt) { return dt == UNIGIST_BF16 ? 2 : 4; }
 
-// The documents of a pack are independent, and a short document's kernels leave most of the chip idle.  Their
-// launch sequences are therefore spread over kLanes streams: lane 0 is the caller's stream, the others are
+// The bf16 kernels take a whole pack in one launch (launch_*_mfma_pack).  The fp32 kernels run document by
+// document: the documents are independent, and a short document's kernels leave most of the chip idle, so their
+// launch sequences are spread over kLanes streams: lane 0 is the caller's stream, the others are
 // helper streams (default priority) created once per device and kept for the life of the process -- the only
 // state this library holds.  The helpers wait for the caller's stream before their first kernel and the
 // caller's stream waits for them after their last one, so to the caller the call still behaves like work
@@ -417,15 +419,18 @@ extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, 
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
     const size_t eb = elem_bytes(dt);
-    // one kernel per document, each of hundreds of workgroups whose tails overlap on one stream: measured faster
-    // than spreading them over streams
+    if (dt == UNIGIST_BF16 && !plain_alu_forced()) {  // one launch, the workgroups look their document up
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, T);
+        return launch_fwd_mfma_pack(q, k, v, out, lse, s, cu_seqlens, ndocs, (hipStream_t)hip_stream) == hipSuccess
+                   ? UNIGIST_OK
+                   : UNIGIST_ELAUNCH;
+    }
     return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, false, [&](int d, hipStream_t stream, int) {
         const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
         const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
         const size_t ro = (size_t)c0 * D * eb;  // byte offset of the document's first row inside a head
         const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
         char* od = (char*)out + ro;
-        if (dt == UNIGIST_BF16 && !plain_alu_forced()) return launch_fwd_mfma(qd, kd, vd, od, lse + c0, s, stream);
         return launch_fwd_simple(qd, kd, vd, od, lse + c0, s, dt, stream);
     });
 }
@@ -433,7 +438,7 @@ extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, 
 extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                     int ndocs, unigist_dtype dt) {
     if (check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt) != UNIGIST_OK) return 0;
-    // one slice per lane, each large enough for the longest document that lane may get
+    // document-by-document path: one slice per lane, each large enough for the longest document that lane may get
     size_t need = 256;
     for (int d = 0; d < ndocs; ++d) {
         const int len = cu_seqlens[d + 1] - cu_seqlens[d];
@@ -441,7 +446,15 @@ extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int 
         const size_t n = unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt);
         if (n > need) need = n;
     }
-    return align256(need) * kLanes;
+    need = align256(need) * kLanes;
+    if (dt == UNIGIST_BF16) {
+        // single-launch path: delta and lse2 of the whole pack plus every document's gist partial sums.  The larger
+        // of the two is asked for, so that the debug switch to the plain-ALU kernels needs no other buffer.
+        const size_t pack = bwd_mfma_pack_workspace(doc_shape(Hq, Hkv, T, D, r, W, T), cu_seqlens, ndocs);
+        if (pack == 0) return 0;
+        need = std::max(need, pack);
+    }
+    return need;
 }
 
 extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out,
@@ -455,7 +468,18 @@ extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, 
     const size_t need = unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
     if (workspace_bytes < need) return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
-    const size_t slice = need / kLanes;
+    if (dt == UNIGIST_BF16 && !plain_alu_forced()) {  // one launch per kernel, the workgroups look their document up
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, T);
+        return launch_bwd_mfma_pack(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, cu_seqlens, ndocs,
+                                    (hipStream_t)hip_stream) == hipSuccess
+                   ? UNIGIST_OK
+                   : UNIGIST_ELAUNCH;
+    }
+    size_t slice = 256;
+    for (int d = 0; d < ndocs; ++d) {
+        const int len = cu_seqlens[d + 1] - cu_seqlens[d];
+        if (len > 0) slice = std::max(slice, align256(unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt)));
+    }
     const size_t eb = elem_bytes(dt);
     // the documents of one lane run one after the other on its stream and share that lane's workspace slice
     return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, true, [&](int d, hipStream_t stream, int lane) {
@@ -466,8 +490,6 @@ extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, 
         const char *od = (const char*)out + ro, *gd = (const char*)dout + ro;
         char *dqd = (char*)dq + ro, *dkd = (char*)dk + ro, *dvd = (char*)dv + ro;
         char* ws = (char*)workspace + slice * lane;
-        if (dt == UNIGIST_BF16 && !plain_alu_forced())
-            return launch_bwd_mfma(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, ws, s, UNIGIST_BWD_ALL, stream);
         return launch_bwd_simple(qd, kd, vd, od, lse + c0, gd, dqd, dkd, dvd, (float*)ws, s, dt, stream);
     });
 }

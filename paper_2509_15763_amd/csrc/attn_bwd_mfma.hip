@@ -24,7 +24,11 @@
 // transposing LDS reads (dV^T += dO^T P, dK^T += Q^T dS); the S/dP accumulators of the two 16-row halves of a
 // query block are already the B operands of the last two.
 // dq: forward-shaped; S^T = K Q^T and dP^T = V dO^T for the wave's two 16-row query blocks, dQ^T += K^T dS^T.
+#include <string.h>
+
+#include <algorithm>
 #include <type_traits>
+#include <vector>
 
 #include "mfma_common.h"
 
@@ -87,14 +91,19 @@ __host__ __device__ inline int last_chunk_with_far_le(const AttnShape& s, int NC
     return lo;
 }
 
-BwdPlan make_plan(const AttnShape& s) {
-    BwdPlan p;
+// the counts of a plan (the workgroups of a packed launch recompute them for their document)
+__host__ __device__ inline void plan_counts(const AttnShape& s, BwdPlan& p) {
     p.NC = (s.L + MQ - 1) / MQ;
     const int nfar_max = nfar_of_chunk(s, p.NC - 1);
     p.n_gt = (nfar_max + BNK - 1) / BNK;
     p.segc = 32;  // 32 chunks x Hq/Hkv heads = 128 steps per workgroup: short enough to balance the last round
     while ((p.NC + p.segc - 1) / p.segc > 32) p.segc *= 2;
     p.nseg = (p.NC + p.segc - 1) / p.segc;
+}
+
+BwdPlan make_plan(const AttnShape& s) {
+    BwdPlan p;
+    plan_counts(s, p);
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_lse2 = off;  // lse * log2(e), written by the delta pass
@@ -150,17 +159,39 @@ struct DkdvSmem {
 
 // GEN = false (here and in dq_kernel) is the layout without sinks and with the sliding window: the mask
 // helpers then fold to their short forms at compile time.
-template <int D, bool GIST, bool GEN>
+// PACK = true (here and in dq_kernel): the launch covers the documents of a packed buffer (docs), s_arg is the shape
+// of the whole pack, delta and lse2 have the layout of the caller's lse ([Hq, T]), and every document has its
+// own run of slots in part and comp.
+template <int D, bool GIST, bool GEN, bool PACK>
 __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                     const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                     const bf16_t* __restrict__ dout, const float* __restrict__ delta,
                                                     bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
                                                     float* __restrict__ part, const float* __restrict__ comp,
-                                                    AttnShape s_arg, BwdPlan pl) {
+                                                    AttnShape s_arg, BwdPlan pl,
+                                                    std::conditional_t<PACK, DocTab, NoDocs> docs) {
     AttnShape s = s_arg;
     if constexpr (!GEN) {
         s.S = 0;
         s.umode = 0;
+    }
+    int n = blockIdx.x;
+    if constexpr (PACK) {  // the document becomes the whole problem
+        const int d = doc_of_block(docs, n);
+        n -= docs.blk0[d];
+        s = doc_view(s, docs.len[d]);
+        plan_counts(s, pl);
+        const size_t ro = (size_t)docs.c0[d] * D;
+        q += ro;
+        k += ro;
+        v += ro;
+        dout += ro;
+        dk += ro;
+        dv += ro;
+        lse2 += docs.c0[d];
+        delta += docs.c0[d];
+        part += (size_t)docs.part0[d] * (2 * D * BNK);
+        comp += (size_t)docs.comp0[d] * (2 * D * BNK);
     }
     constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // 16x16x32 MFMA: k-steps of 32, 16-row blocks of dK^T / dV^T
     constexpr int RPI = 64 / CH;        // chunk rows covered by one direct-load instruction
@@ -179,7 +210,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     // XCDs, so with id % 8 selecting the (batch, kv head) pair every XCD gets the same amount of work
     // and one head's Q/dO stream stays in one XCD's L2.
     const int NP = s.B * s.Hkv;
-    int n = blockIdx.x, pr, unit;
+    int pr, unit;
     if ((NP & 7) == 0) {
         const int mm = n >> 3;
         pr = (n & 7) + 8 * (mm % (NP >> 3));
@@ -262,7 +293,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         int lanepart[NLP];
 #pragma unroll
         for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz16<CH>(i * RPI + lrow_)) << 4);
-        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * L;           // wave-uniform; dense workspace rows
+        const size_t hb = ((size_t)b * s.Hq + hk * G + g) * (PACK ? s.qhs : L);  // wave-uniform; workspace rows
         const size_t hg = ((size_t)b * s.Hq + hk * G + g) * s.qhs;       // the head in the caller's tensors
         const char* qh = (const char*)(q + hg * D);
         const char* gh = (const char*)(dout + hg * D);
@@ -542,6 +573,29 @@ __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict
     *(f32x4*)(comp + t * per_tile + idx) = acc;
 }
 
+// The same for a packed launch.  grid: x = slot of comp (a document's slots are its (kv head, gist tile) pairs,
+// docs.blk0 holds the first slot of each document), y = slice of the slot's 2*D*BNK floats.
+__global__ __launch_bounds__(NT) void gist_reduce_pack_kernel(const float* __restrict__ part, float* __restrict__ comp,
+                                                             AttnShape s_arg, int per_tile, DocTab docs) {
+    const int idx = 4 * (blockIdx.y * NT + threadIdx.x);
+    if (idx >= per_tile) return;
+    const int d = doc_of_block(docs, blockIdx.x);
+    const int t = blockIdx.x - docs.blk0[d];  // (kv head) * n_gt + gist tile
+    AttnShape s = doc_view(s_arg, docs.len[d]);
+    s.S = 0;
+    s.umode = 0;
+    BwdPlan pl;
+    plan_counts(s, pl);
+    const int gt = t % pl.n_gt;
+    const int cf = first_chunk_with_more_far(s, pl.NC, gt * BNK);
+    const float* pp = part + (size_t)docs.part0[d] * per_tile;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (cf < pl.NC)
+        for (int sg = cf / pl.segc; sg < pl.nseg; ++sg)
+            acc += *(const f32x4*)(pp + ((size_t)t * pl.nseg + sg) * per_tile + idx);
+    *(f32x4*)(comp + ((size_t)docs.comp0[d] + t) * per_tile + idx) = acc;
+}
+
 // ------------------------------------------------------------------ 5. dQ
 template <int D>
 struct DqSmem {
@@ -550,15 +604,31 @@ struct DqSmem {
     char v[2][BNQ * D * 2];
 };
 
-template <int D, bool GEN>
+template <int D, bool GEN, bool PACK>
 __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                   const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ delta,
-                                                  bf16_t* __restrict__ dq, AttnShape s_arg, int nq) {
+                                                  bf16_t* __restrict__ dq, AttnShape s_arg, int nq,
+                                                  std::conditional_t<PACK, DocTab, NoDocs> docs) {
     AttnShape s = s_arg;
     if constexpr (!GEN) {
         s.S = 0;
         s.umode = 0;
+    }
+    int n = blockIdx.x;
+    if constexpr (PACK) {
+        const int d = doc_of_block(docs, n);
+        n -= docs.blk0[d];
+        s = doc_view(s, docs.len[d]);
+        nq = (s.L + BMQ - 1) / BMQ;
+        const size_t ro = (size_t)docs.c0[d] * D;
+        q += ro;
+        k += ro;
+        v += ro;
+        dout += ro;
+        dq += ro;
+        lse2 += docs.c0[d];
+        delta += docs.c0[d];
     }
     constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // 16x16x32 MFMA: k-steps of 32, 16-row blocks of dQ^T
     constexpr int RPI = 64 / CH;
@@ -568,7 +638,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int g4 = lane >> 4;  // with r16 = lane % 16: the lane's place in a 16x16x32 operand
     const int G = s.Hq / s.Hkv, NP = s.B * s.Hkv;
-    int n = blockIdx.x, g, pr, qt;
+    int g, pr, qt;
     if ((NP & 7) == 0) {
         const int xcd = n & 7, mm = n >> 3;
         g = mm % G;
@@ -606,7 +676,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const int qrow_ld = min(qrow[qb], L - 1);
         span_q[qb] = qrow[qb] - win_lo(s, qrow[qb]);  // this row's window reaches span_q positions back
         rowoff[qb] = ((size_t)b * s.Hq + hq) * s.qhs + qrow_ld;           // in the caller's tensors
-        const size_t wrow = ((size_t)b * s.Hq + hq) * L + qrow_ld;        // in the dense workspace
+        const size_t wrow = ((size_t)b * s.Hq + hq) * (PACK ? s.qhs : L) + qrow_ld;  // in the workspace
         const bf16_t* qp = q + rowoff[qb] * D + 8 * g4;
         const bf16_t* gp = dout + rowoff[qb] * D + 8 * g4;
 #pragma unroll
@@ -807,8 +877,8 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
         const dim3 grid((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B));
-        if (gen) dkdv_kernel<D, true, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
-        else dkdv_kernel<D, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
+        if (gen) dkdv_kernel<D, true, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        else dkdv_kernel<D, true, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_GIST_REDUCE)) {
@@ -819,22 +889,145 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     }
     if (stages & UNIGIST_BWD_DKDV_WINDOW) {
         const dim3 grid((unsigned)((long)((s.L + BNK - 1) / BNK) * s.Hkv * s.B));
-        if (gen) dkdv_kernel<D, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
-        else dkdv_kernel<D, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl);
+        if (gen) dkdv_kernel<D, false, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        else dkdv_kernel<D, false, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (!(stages & UNIGIST_BWD_DQ)) return hipSuccess;
     const int nq = (s.L + BMQ - 1) / BMQ;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
-    if (gen) dq_kernel<D, true><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
-    else dq_kernel<D, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq);
+    if (gen) dq_kernel<D, true, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
+    else dq_kernel<D, false, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
     return hipGetLastError();
+}
+
+// ---- packed documents: the non-empty documents, longest first (their long tiles should not start last), and
+// the slots each of them gets in the partial-sum arrays
+struct PackPlan {
+    std::vector<int> c0, len, part0, comp0;  // per document, in launch order
+    size_t off_lse2, off_part, off_comp, total;
+};
+
+PackPlan make_pack_plan(const AttnShape& s, const int* cu, int ndocs) {
+    PackPlan pp;
+    std::vector<int> order;
+    for (int d = 0; d < ndocs; ++d)
+        if (cu[d + 1] > cu[d]) order.push_back(d);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+    size_t nslot_part = 0, nslot_comp = 0;
+    for (int d : order) {
+        BwdPlan pl;
+        plan_counts(doc_view(s, cu[d + 1] - cu[d]), pl);
+        pp.c0.push_back(cu[d]);
+        pp.len.push_back(cu[d + 1] - cu[d]);
+        pp.part0.push_back((int)nslot_part);
+        pp.comp0.push_back((int)nslot_comp);
+        nslot_part += (size_t)s.Hkv * pl.n_gt * pl.nseg;
+        nslot_comp += (size_t)s.Hkv * pl.n_gt;
+    }
+    const size_t a = 255, per_tile = (size_t)2 * s.D * BNK * sizeof(float);
+    size_t off = ((size_t)s.Hq * s.L * sizeof(float) + a) & ~a;  // delta, [Hq, T] like the caller's lse
+    pp.off_lse2 = off;
+    off += ((size_t)s.Hq * s.L * sizeof(float) + a) & ~a;
+    pp.off_part = off;
+    off += nslot_part * per_tile;
+    pp.off_comp = off;
+    off += nslot_comp * per_tile;
+    pp.total = (off + a) & ~a;
+    if (nslot_part > 0x7fffffffUL) pp.total = 0;  // slot numbers are kept in 32 bits
+    return pp;
+}
+
+template <int D>
+hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* out, const float* lse,
+                           const bf16_t* dout, bf16_t* dq, bf16_t* dk, bf16_t* dv, char* ws, const AttnShape& s,
+                           const int* cu, int ndocs, hipStream_t st) {
+    const PackPlan pp = make_pack_plan(s, cu, ndocs);
+    if (pp.total == 0) return hipErrorInvalidValue;
+    float* delta = (float*)ws;
+    float* lse2 = (float*)(ws + pp.off_lse2);
+    float* part = (float*)(ws + pp.off_part);
+    float* comp = (float*)(ws + pp.off_comp);
+    hipError_t e;
+    {  // delta and lse2 of every row of the pack (a row's delta does not depend on its document)
+        constexpr int rows_per_blk = NT / (D / 8);
+        const long nrows = (long)s.Hq * s.L;
+        delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    const int nd = (int)pp.len.size();
+    // one launch of each kernel per kMaxDocs documents; blocks(i) = workgroups (or slots) of document i
+    auto for_chunks = [&](auto&& blocks, auto&& launch) -> hipError_t {
+        for (int at = 0; at < nd; at += kMaxDocs) {
+            DocTab t;
+            memset(&t, 0, sizeof t);
+            t.n = std::min(kMaxDocs, nd - at);
+            long nblk = 0;
+            for (int i = 0; i < t.n; ++i) {
+                t.c0[i] = pp.c0[at + i];
+                t.len[i] = pp.len[at + i];
+                t.part0[i] = pp.part0[at + i];
+                t.comp0[i] = pp.comp0[at + i];
+                t.blk0[i] = (int)nblk;
+                nblk += blocks(pp.len[at + i]);
+                if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
+            }
+            t.blk0[t.n] = (int)nblk;
+            if (nblk == 0) continue;
+            launch(t, (unsigned)nblk);
+            const hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return err;
+        }
+        return hipSuccess;
+    };
+    auto counts = [&](int len) {
+        BwdPlan pl;
+        plan_counts(doc_view(s, len), pl);
+        return pl;
+    };
+    const BwdPlan none = {};
+    e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.n_gt * pl.nseg * s.Hkv; },
+                   [&](const DocTab& t, unsigned nblk) {
+                       dkdv_kernel<D, true, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                  part, comp, s, none, t);
+                   });
+    if (e != hipSuccess) return e;
+    constexpr int per_tile = 2 * D * BNK;
+    e = for_chunks([&](int len) { return (long)counts(len).n_gt * s.Hkv; },
+                   [&](const DocTab& t, unsigned nblk) {
+                       gist_reduce_pack_kernel<<<dim3(nblk, (per_tile / 4 + NT - 1) / NT), NT, 0, st>>>(part, comp, s,
+                                                                                                       per_tile, t);
+                   });
+    if (e != hipSuccess) return e;
+    e = for_chunks([&](int len) { return (long)((len + BNK - 1) / BNK) * s.Hkv; },
+                   [&](const DocTab& t, unsigned nblk) {
+                       dkdv_kernel<D, false, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                   part, comp, s, none, t);
+                   });
+    if (e != hipSuccess) return e;
+    return for_chunks([&](int len) { return (long)((len + BMQ - 1) / BMQ) * s.Hq; },
+                      [&](const DocTab& t, unsigned nblk) {
+                          dq_kernel<D, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
+                      });
 }
 
 }  // namespace
 
 size_t bwd_mfma_workspace(const AttnShape& s) { return make_plan(s).total; }
+
+size_t bwd_mfma_pack_workspace(const AttnShape& s, const int* cu, int ndocs) { return make_pack_plan(s, cu, ndocs).total; }
+
+hipError_t launch_bwd_mfma_pack(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                                const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
+                                const int* cu, int ndocs, hipStream_t st) {
+    if (s.D == 64)
+        return bwd_launch_pack<64>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
+                                   (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, cu, ndocs, st);
+    return bwd_launch_pack<128>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
+                                (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, cu, ndocs, st);
+}
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,

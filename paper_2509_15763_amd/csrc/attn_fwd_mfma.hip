@@ -25,7 +25,11 @@
 // matching A operand V^T comes straight out of the row-major V tile in LDS through two ds_read_b64_tr_b16 (rows
 // 4 g4 .. 4 g4 + 3 of either 16-key block).  K/V tiles are staged with direct global->LDS loads into two LDS
 // stages (one barrier per step), 16-byte chunks swizzled with a period of 16 rows.
+#include <string.h>
+
+#include <algorithm>
 #include <type_traits>
+#include <vector>
 
 #include "mfma_common.h"
 
@@ -47,14 +51,29 @@ struct FwdSmem {
 
 // GEN = false is the layout without sinks and with the sliding window: the mask helpers then fold to their
 // short forms at compile time.
-template <int D, bool GEN>
+// PACK = true: the launch covers the documents of a packed buffer (docs), s_arg is the shape of the whole pack.
+template <int D, bool GEN, bool PACK>
 __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
-                                                        float* __restrict__ lse, AttnShape s_arg, int nq) {
+                                                        float* __restrict__ lse, AttnShape s_arg, int nq,
+                                                        std::conditional_t<PACK, DocTab, NoDocs> docs) {
     AttnShape s = s_arg;
     if constexpr (!GEN) {
         s.S = 0;
         s.umode = 0;
+    }
+    int n = blockIdx.x;
+    if constexpr (PACK) {  // the document becomes the whole problem: its rows, its tiles, its workgroup ids
+        const int d = doc_of_block(docs, n);
+        n -= docs.blk0[d];
+        s = doc_view(s, docs.len[d]);
+        nq = (s.L + BM - 1) / BM;
+        const size_t ro = (size_t)docs.c0[d] * D;
+        q += ro;
+        k += ro;
+        v += ro;
+        out += ro;
+        lse += docs.c0[d];
     }
     constexpr int KS = D / 32;            // k-steps of the score MFMA
     constexpr int DB = D / 16;            // 16-row blocks of O^T
@@ -70,7 +89,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     // ---- which (batch, head, query tile): heads of one kv group stay on one XCD, long tiles first
     const int G = s.Hq / s.Hkv;
     const int NP = s.B * s.Hkv;
-    int n = blockIdx.x, g, pr, qt;
+    int g, pr, qt;
     if ((NP & 7) == 0) {
         const int xcd = n & 7, mm = n >> 3;
         g = mm % G;
@@ -361,11 +380,44 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
     const bool gen = s.S != 0 || s.umode != 0;
     auto go = [&](auto kern) {
         kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
-                                                  s, nq);
+                                                  s, nq, NoDocs{});
     };
-    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true>) : go(fwd_mfma_kernel<64, false>);
-    else gen ? go(fwd_mfma_kernel<128, true>) : go(fwd_mfma_kernel<128, false>);
+    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, false>) : go(fwd_mfma_kernel<64, false, false>);
+    else gen ? go(fwd_mfma_kernel<128, true, false>) : go(fwd_mfma_kernel<128, false, false>);
     return hipGetLastError();
+}
+
+hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
+                                const int* cu, int ndocs, hipStream_t st) {
+    // long documents first: their long tiles are the ones that should not start last
+    std::vector<int> order;
+    for (int d = 0; d < ndocs; ++d)
+        if (cu[d + 1] > cu[d]) order.push_back(d);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+    for (size_t at = 0; at < order.size(); at += kMaxDocs) {
+        DocTab t;
+        memset(&t, 0, sizeof t);
+        t.n = (int)std::min<size_t>(kMaxDocs, order.size() - at);
+        long nblk = 0;
+        for (int i = 0; i < t.n; ++i) {
+            const int d = order[at + i];
+            t.c0[i] = cu[d];
+            t.len[i] = cu[d + 1] - cu[d];
+            t.blk0[i] = (int)nblk;
+            nblk += (long)((t.len[i] + BM - 1) / BM) * s.Hq;
+        }
+        if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
+        t.blk0[t.n] = (int)nblk;
+        auto go = [&](auto kern) {
+            kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out,
+                                                      lse, s, 0, t);
+        };
+        if (s.D == 64) go(fwd_mfma_kernel<64, false, true>);
+        else go(fwd_mfma_kernel<128, false, true>);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace unigist

@@ -97,6 +97,38 @@ __host__ __device__ inline int pos_of_always(const AttnShape& s, int c) {
     return c < s.S ? c : s.S + (c - s.S) * s.rp1 + s.rp1 - 1;
 }
 
+// ---- packed documents: one launch covers up to kMaxDocs documents of a [H, T, D] buffer, each an independent
+// sequence (its gist period and window restart at its first row).  The table travels as a kernel argument and is
+// read with scalar loads; a workgroup finds its document from its id.
+constexpr int kMaxDocs = 64;
+struct DocTab {
+    int n;                   // documents in this launch (>= 1), none of them empty
+    int c0[kMaxDocs];        // first row of the document inside a head of the packed buffers
+    int len[kMaxDocs];       // its rows
+    int blk0[kMaxDocs + 1];  // first workgroup id of the document in this launch; blk0[n] = grid size
+    int part0[kMaxDocs];     // backward: the document's first slot in the array of per-segment gist partials
+    int comp0[kMaxDocs];     // backward: the document's first slot in the array of reduced gist sums
+};
+struct NoDocs {};
+// document owning workgroup blk: the last d with blk0[d] <= blk
+__device__ __forceinline__ int doc_of_block(const DocTab& t, int blk) {
+    int lo = 0, hi = t.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (t.blk0[mid] <= blk) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+// the shape of one document of len rows, given the shape of the whole pack (B = 1, L = T, strides T)
+__host__ __device__ inline AttnShape doc_view(AttnShape s, int len) {
+    s.rp1 = s.rp1 - 1 >= len ? len + 1 : s.rp1;
+    s.W = s.W > len ? len : s.W;
+    s.L = len;
+    s.Lq = len;
+    return s;
+}
+
 // --- launchers implemented in the .hip files (all enqueue on `st`, return hipGetLastError) ---
 hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,
                              const AttnShape& s, unigist_dtype dt, hipStream_t st);
@@ -105,10 +137,19 @@ hipError_t launch_bwd_simple(const void* q, const void* k, const void* v, const 
                              const AttnShape& s, unigist_dtype dt, hipStream_t st);
 hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
                            const AttnShape& s, hipStream_t st);
+// the same over the documents [cu[d], cu[d+1]) of a packed buffer (s: the shape of the whole pack, no sinks,
+// sliding window), one launch per kMaxDocs documents
+hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, void* out, float* lse,
+                                const AttnShape& s, const int* cu, int ndocs, hipStream_t st);
 size_t bwd_mfma_workspace(const AttnShape& s);
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws,
                            const AttnShape& s, unsigned stages, hipStream_t st);
+// packed documents (see launch_fwd_mfma_pack); ws: bwd_mfma_pack_workspace bytes (0: the pack is too large)
+size_t bwd_mfma_pack_workspace(const AttnShape& s, const int* cu, int ndocs);
+hipError_t launch_bwd_mfma_pack(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                                const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
+                                const int* cu, int ndocs, hipStream_t st);
 bool decode_grouped(int Hq, int Hkv, unigist_dtype dt);
 int decode_num_splits(int B, int Hq, int Hkv, int Lk, unigist_dtype dt);
 hipError_t launch_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,

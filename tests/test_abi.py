@@ -91,9 +91,17 @@ def test_varlen_argument_validation():
         assert u.unigist_attn_bwd_varlen_workspace(*args, bad, 0) == 0
         assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, bad, 0, FAKE, 1 << 40) == 1
     assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, cu, 0, FAKE, 16) == 1                # workspace too small
-    # one slice per stream the documents are spread over, each sized for the longest document
+    # fp32 runs document by document: one slice per stream the documents are spread over, each sized for the
+    # longest document
+    one = u.unigist_attn_bwd_workspace(1, 4, 2, 5000, 64, 4, 8, 1)
+    assert u.unigist_attn_bwd_varlen_workspace(4, 2, 6000, 64, 4, 8, [0, 5000, 6000], 1) == 4 * ((one + 255) // 256 * 256)
+    # bf16 runs the whole pack in one launch per kernel: two fp32 values per (head, row) plus the gist partial sums
+    # of every document (5000 rows with r = 4: 1000 gists, 8 tiles of 128 per kv head, one segment each, reduced
+    # once more); never less than the document-by-document need, which the debug switch falls back to
+    pack = u.unigist_attn_bwd_varlen_workspace(4, 2, 6000, 64, 4, 8, [0, 5000, 6000], 0)
     one = u.unigist_attn_bwd_workspace(1, 4, 2, 5000, 64, 4, 8, 0)
-    assert u.unigist_attn_bwd_varlen_workspace(4, 2, 6000, 64, 4, 8, [0, 5000, 6000], 0) == 4 * ((one + 255) // 256 * 256)
+    assert pack >= 4 * ((one + 255) // 256 * 256)
+    assert pack >= 2 * 4 * 6000 * 4 + 2 * (2 * 7) * (2 * 64 * 128 * 4)
 
 
 def test_cache_ex_argument_validation():

@@ -67,6 +67,19 @@ def test_mid_pack_matches_oracle():
     check(f"docs{lens}", got, oracle_packed(q, k, v, dout, 4, 300, cu), torch.bfloat16)
 
 
+def test_more_documents_than_one_launch_holds():
+    # The bf16 kernels cover 64 documents per launch: 150 documents (empty ones among them) need three launches
+    # of every kernel.  Two documents are long enough to have gists left of their window (gist-phase partial
+    # sums, which each document keeps in slots of its own), and the longest ones do not come first.
+    rng = np.random.default_rng(5)
+    lens = rng.integers(0, 40, size=150).tolist()
+    lens[3], lens[77], lens[140] = 700, 0, 900
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = packed_inputs(4, 2, cu[-1], 64, torch.bfloat16, seed=33)
+    got = run_gpu(q, k, v, dout, 2, 24, cu)
+    check(f"{len(lens)} docs", got, oracle_packed(q, k, v, dout, 2, 24, cu), torch.bfloat16)
+
+
 def test_single_document_is_the_plain_entry_point():
     q, k, v, dout = packed_inputs(4, 2, 700, 128, torch.bfloat16, seed=3)
     a = run_gpu(q, k, v, dout, 4, 64, [0, 700])
