@@ -283,6 +283,22 @@ unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc, const voi
                                         void* hip_stream);
 
 /*
+ * unigist_prefill_chunk_ex for a batch whose sequences are in different states (Sec. 4.3, one launch for all of
+ * them): p0, n and s are DEVICE arrays of B ints.  Sequence b has n[b] <= C query rows at positions
+ * p0[b] .. p0[b]+n[b]-1, the first n[b] rows of its slab of q [B, Hq, C, D]; its slab of kc/vc [B, Hkv, cap, D] is
+ * in state (s[b], p0[b]+n[b]-1), e.g. after unigist_cache_update_ragged.  The first n[b] rows of its slab of out
+ * and lse are written, the others are left alone.  rows_out (DEVICE, B ints, out) receives the cache rows in use
+ * -- what unigist_decode takes as seqlens -- or -1 for a sequence whose state is impossible (negative values,
+ * n[b] > C, a window start s[b] right of the first position the first query sees, more rows than cap, more than
+ * 2^23 positions); nothing else is written for such a sequence.  n[b] = 0 is allowed.  The host checks only what
+ * it can see (shapes, pointers, dtype); bf16 only.
+ */
+unigist_status unigist_prefill_chunk_ragged(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                            int B, int Hq, int Hkv, int C, int D, int r, int W, int sinks,
+                                            int window_mode, const int* p0, const int* n, const int* s, int cap,
+                                            int* rows_out, unigist_dtype dt, void* hip_stream);
+
+/*
  * Block map (Sec. 4.2: with a fixed compression ratio the visible blocks are known in
  * closed form and need not be stored; this builder materialises them on the HOST for
  * tests and for the live-tile report).  The sequence is cut into query tiles of Bm rows

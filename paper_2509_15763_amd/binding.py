@@ -28,6 +28,7 @@ EXPORTS = [
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
+    "unigist_prefill_chunk_ragged",
 ]
 
 
@@ -104,6 +105,8 @@ def load():
     lib.unigist_cache_update_ragged.argtypes = [vp, vp, vp, vp, ip, vp, vp, vp, ip, vp, vp, vp, ip, vp] + [ip] * 6 + [vp]
     lib.unigist_prefill_chunk_ex.restype = ip
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
+    lib.unigist_prefill_chunk_ragged.restype = ip
+    lib.unigist_prefill_chunk_ragged.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [vp, vp, vp, ip, vp, ip, vp]
     lib.unigist_cache_rows.restype = ip
     lib.unigist_cache_rows.argtypes = [ip, ip, ip]
     lib.unigist_cache_update.restype = ip
@@ -254,6 +257,12 @@ def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new
                                 cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
     return load().unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                               vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
+
+
+def unigist_prefill_chunk_ragged(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, n, s, cap,
+                                 rows_out, dt, stream=None) -> int:
+    return load().unigist_prefill_chunk_ragged(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, n,
+                                               s, cap, rows_out, dt, stream)
 
 
 def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, cap, dt, stream=None) -> int:
@@ -573,6 +582,27 @@ class RaggedKVCache:
         self.s = [int(v) for v in s_new]
         self.t = [t + int(n) for t, n in zip(self.t, n_new)]
         return rows
+
+    def prefill_batch(self, q, n, W, window_mode=UNIGIST_WINDOW_SLIDING, out=None, lse=None):
+        """All sequences in one launch (unigist_prefill_chunk_ragged), after update_batch appended the chunk's keys:
+        q [B, Hq, C, D], sequence b's queries are its first n[b] rows, at the last n[b] positions of its cache.
+        -> out, lse (rows past n[b] untouched) and the rows in use per sequence, int32 [B] on the GPU (-1 where a
+        state was invalid)."""
+        kc, vc = self.current()
+        _dev(q)
+        B, Hq, C, D = q.shape
+        dev = q.device
+        as_dev = lambda x: torch.tensor([int(v) for v in x], dtype=torch.int32).to(dev)
+        p0, nn, ss = as_dev([t + 1 - int(nb) for t, nb in zip(self.t, n)]), as_dev(n), as_dev(self.s)
+        out = torch.empty_like(q) if out is None else out
+        lse = torch.empty(B, Hq, C, device=dev, dtype=torch.float32) if lse is None else lse
+        rows = torch.empty(B, dtype=torch.int32, device=dev)
+        _check(unigist_prefill_chunk_ragged(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                            B, Hq, self.Hkv, C, D, self.r, int(W), self.sinks, int(window_mode),
+                                            p0.data_ptr(), nn.data_ptr(), ss.data_ptr(), self.cap,
+                                            rows.data_ptr(), _dt(q), _stream()),
+               "unigist_prefill_chunk_ragged")
+        return out, lse, rows
 
     def current(self):
         """-> kc, vc of the buffer all sequences sit in (after update_batch)."""

@@ -310,6 +310,31 @@ extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
+extern "C" unigist_status unigist_prefill_chunk_ragged(const void* q, const void* kc, const void* vc, void* out,
+                                                       float* lse, int B, int Hq, int Hkv, int C, int D, int r, int W,
+                                                       int sinks, int window_mode, const int* p0, const int* n,
+                                                       const int* s, int cap, int* rows_out, unigist_dtype dt,
+                                                       void* hip_stream) {
+    if (C < 1 || cap < 1) return UNIGIST_EINVAL;
+    unigist_status st = check_attn(B, Hq, Hkv, kMaxL, D, r, W, dt, sinks, window_mode);
+    if (st != UNIGIST_OK) return st;
+    if (dt != UNIGIST_BF16) return UNIGIST_EUNSUPPORTED;
+    if (C > kMaxL || cap > kMaxL) return UNIGIST_EUNSUPPORTED;
+    if (!q || !kc || !vc || !out || !lse || !p0 || !n || !s || !rows_out) return UNIGIST_EINVAL;
+    // the launch's shape: up to kMaxL positions per sequence; the kernel narrows it to each sequence's state
+    AttnShape sh = make_shape(B, Hq, Hkv, kMaxL, D, r, W, sinks, window_mode);
+    sh.Lq = C;
+    sh.qhs = C;
+    sh.kv_rows = cap;
+    RaggedSeqs seqs;
+    seqs.p0 = p0;
+    seqs.n = n;
+    seqs.s0 = s;
+    seqs.rows = rows_out;
+    hipError_t e = launch_fwd_mfma_ragged(q, kc, vc, out, lse, sh, seqs, (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
 // ---------------------------------------------------------------- packed documents
 namespace {
 

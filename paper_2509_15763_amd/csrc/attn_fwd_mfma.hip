@@ -51,29 +51,36 @@ struct FwdSmem {
 
 // GEN = false is the layout without sinks and with the sliding window: the mask helpers then fold to their
 // short forms at compile time.
-// PACK = true: the launch covers the documents of a packed buffer (docs), s_arg is the shape of the whole pack.
-template <int D, bool GEN, bool PACK>
+enum { PLAIN = 0, PACK = 1, RAGGED = 2 };
+template <int MODE> struct ModeArg { typedef NoDocs type; };
+template <> struct ModeArg<PACK> { typedef DocTab type; };
+template <> struct ModeArg<RAGGED> { typedef RaggedSeqs type; };
+
+// MODE = PACK: the launch covers the documents of a packed buffer (ext), s_arg is the shape of the whole pack.
+// MODE = RAGGED: chunk-wise prefill of a batch whose sequences are in different states (ext: device arrays);
+// s_arg is the launch's shape and each workgroup derives its sequence's (seq_view).
+template <int D, bool GEN, int MODE>
 __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
                                                         float* __restrict__ lse, AttnShape s_arg, int nq,
-                                                        std::conditional_t<PACK, DocTab, NoDocs> docs) {
+                                                        typename ModeArg<MODE>::type ext) {
     AttnShape s = s_arg;
     if constexpr (!GEN) {
         s.S = 0;
         s.umode = 0;
     }
     int n = blockIdx.x;
-    if constexpr (PACK) {  // the document becomes the whole problem: its rows, its tiles, its workgroup ids
-        const int d = doc_of_block(docs, n);
-        n -= docs.blk0[d];
-        s = doc_view(s, docs.len[d]);
+    if constexpr (MODE == PACK) {  // the document becomes the whole problem: its rows, its tiles, its workgroup ids
+        const int d = doc_of_block(ext, n);
+        n -= ext.blk0[d];
+        s = doc_view(s, ext.len[d]);
         nq = (s.L + BM - 1) / BM;
-        const size_t ro = (size_t)docs.c0[d] * D;
+        const size_t ro = (size_t)ext.c0[d] * D;
         q += ro;
         k += ro;
         v += ro;
         out += ro;
-        lse += docs.c0[d];
+        lse += ext.c0[d];
     }
     constexpr int KS = D / 32;            // k-steps of the score MFMA
     constexpr int DB = D / 16;            // 16-row blocks of O^T
@@ -105,6 +112,27 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     }
     const int b = pr / s.Hkv, hk = pr % s.Hkv;
     const int hq = hk * G + g;
+    if constexpr (MODE == RAGGED) {
+        // The sequence's state comes from device memory, so it is checked here: a workgroup of a sequence whose
+        // state is invalid, or whose tile lies past the sequence's rows, leaves (the whole workgroup, before any
+        // barrier); one workgroup per sequence reports the cache rows in use, or -1.
+        const int p0 = ext.p0[b], nb = ext.n[b], s0b = ext.s0[b];
+        int rows = -1;
+        if (p0 >= 0 && nb >= 0 && nb <= s.Lq && s0b >= 0 && (long long)p0 + nb <= s.L) {
+            if (nb == 0) {
+                if (s0b <= p0) rows = count_always(s, s0b) + (p0 - s0b);
+            } else {
+                const AttnShape sv = seq_view(s, p0, nb, s0b);
+                const int need = sv.ngb + (sv.L - s0b);
+                if (s0b <= win_lo(sv, p0) && need <= s.kv_rows) {  // every key the first query sees is cached
+                    rows = need;
+                    s = sv;
+                }
+            }
+        }
+        if (hq == 0 && qt == nq - 1 && threadIdx.x == 0) ext.rows[b] = rows;
+        if (rows < 0 || qt * BM >= nb) return;
+    }
 
     // Positions are absolute; q/out/lse hold the rows qpos0 .. L-1, K/V hold ngb compact gist rows followed
     // by the positions s0 .. L-1 (training: everything from position 0, no compact rows).
@@ -382,8 +410,23 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
         kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
                                                   s, nq, NoDocs{});
     };
-    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, false>) : go(fwd_mfma_kernel<64, false, false>);
-    else gen ? go(fwd_mfma_kernel<128, true, false>) : go(fwd_mfma_kernel<128, false, false>);
+    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, PLAIN>) : go(fwd_mfma_kernel<64, false, PLAIN>);
+    else gen ? go(fwd_mfma_kernel<128, true, PLAIN>) : go(fwd_mfma_kernel<128, false, PLAIN>);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_mfma_ragged(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
+                                  const RaggedSeqs& seqs, hipStream_t st) {
+    const int nq = (s.Lq + BM - 1) / BM;  // tiles of the longest possible chunk; shorter sequences skip theirs
+    const long nblk = (long)nq * s.Hq * s.B;
+    if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
+    const bool gen = s.S != 0 || s.umode != 0;
+    auto go = [&](auto kern) {
+        kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
+                                                  s, nq, seqs);
+    };
+    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, RAGGED>) : go(fwd_mfma_kernel<64, false, RAGGED>);
+    else gen ? go(fwd_mfma_kernel<128, true, RAGGED>) : go(fwd_mfma_kernel<128, false, RAGGED>);
     return hipGetLastError();
 }
 
@@ -412,8 +455,8 @@ hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, voi
             kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out,
                                                       lse, s, 0, t);
         };
-        if (s.D == 64) go(fwd_mfma_kernel<64, false, true>);
-        else go(fwd_mfma_kernel<128, false, true>);
+        if (s.D == 64) go(fwd_mfma_kernel<64, false, PACK>);
+        else go(fwd_mfma_kernel<128, false, PACK>);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -129,6 +129,28 @@ __host__ __device__ inline AttnShape doc_view(AttnShape s, int len) {
     return s;
 }
 
+// ---- chunk-wise prefill of a batch whose sequences are in different states (device arrays of B ints)
+struct RaggedSeqs {
+    const int* p0;  // position of the sequence's first query row
+    const int* n;   // its query rows in this chunk (the first n rows of its slab of q/out/lse)
+    const int* s0;  // first position stored in the window region of its cache
+    int* rows;      // out: cache rows in use, -1 if the state is invalid (then nothing else is written for it)
+};
+// The shape of one such sequence, given the launch's shape (L = the largest position count allowed, Lq = rows per
+// slab of q, kv_rows = cache capacity).  Needs n >= 1.
+__host__ __device__ inline AttnShape seq_view(AttnShape s, int p0, int n, int s0) {
+    const int L = p0 + n;
+    s.rp1 = s.rp1 - 1 >= L ? L + 1 : s.rp1;
+    s.W = s.W > L ? L : s.W;
+    s.S = s.S > L ? L : s.S;
+    s.L = L;
+    s.Lq = n;
+    s.qpos0 = p0;
+    s.s0 = s0;
+    s.ngb = count_always(s, s0);
+    return s;
+}
+
 // --- launchers implemented in the .hip files (all enqueue on `st`, return hipGetLastError) ---
 hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,
                              const AttnShape& s, unigist_dtype dt, hipStream_t st);
@@ -141,6 +163,9 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
 // sliding window), one launch per kMaxDocs documents
 hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, void* out, float* lse,
                                 const AttnShape& s, const int* cu, int ndocs, hipStream_t st);
+// chunk-wise prefill with per-sequence states (s: the launch's shape, see seq_view; cap = s.kv_rows)
+hipError_t launch_fwd_mfma_ragged(const void* q, const void* k, const void* v, void* out, float* lse,
+                                  const AttnShape& s, const RaggedSeqs& seqs, hipStream_t st);
 size_t bwd_mfma_workspace(const AttnShape& s);
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv, void* ws,

@@ -180,6 +180,14 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk(*p.values()) == 1
     p.update(cap=1024, q=None)
     assert u.unigist_prefill_chunk(*p.values()) == 1
+    # ragged prefill: the host checks what it can see (the per-sequence states live in device memory)
+    g = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=2, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
+             window_mode=0, p0=FAKE, n=FAKE, s=FAKE, cap=1024, rows_out=FAKE, dt=0)
+    bad = lambda **kw: u.unigist_prefill_chunk_ragged(*dict(g, **kw).values())
+    assert bad(dt=1) == 2 and bad(D=96) == 2
+    assert bad(C=0) == 1 and bad(cap=0) == 1 and bad(window_mode=2) == 1 and bad(sinks=-1) == 1 and bad(Hq=3, Hkv=2) == 1
+    for name in ("q", "kc", "vc", "out", "lse", "p0", "n", "s", "rows_out"):
+        assert bad(**{name: None}) == 1, name
 
 
 def test_probe_argument_validation():

@@ -250,3 +250,97 @@ def test_batched_ragged_updates_then_decode(dtype):
     for b in (0, 3, 4):
         n = rows[b]
         assert torch.equal(kc2[b, :, :n], before_k[b, :, :n])
+
+
+@pytest.mark.parametrize("sinks,units,W", [(0, False, 40), (9, True, 6)], ids=["sliding", "sinks_units"])
+def test_batched_ragged_prefill_equals_one_pass(sinks, units, W):
+    # One launch per step for the whole batch: every sequence is prefilled in chunks of its own sizes (none at
+    # all in some steps), the states are read from device memory.  Every row each sequence ever gets must equal
+    # that row of the one-pass attention over the sequence; rows past a sequence's chunk are left alone.
+    B, Hq, Hkv, D, r, C = 5, 8, 2, 128, 4, 200
+    lens = [700, 33, 412, 1, 150]
+    Lmax = max(lens)
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, Lmax, D, seed=27)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    cache = u.RaggedKVCache(B, Hkv, Lmax, D, r, sinks=sinks)
+    rng = np.random.default_rng(11)
+    got_o = [torch.zeros(Hq, n, D, dtype=torch.bfloat16) for n in lens]
+    got_l = [torch.zeros(Hq, n) for n in lens]
+    step = 0
+    while any(cache.t[b] < lens[b] - 1 for b in range(B)):
+        n_new = [int(min(lens[b] - 1 - cache.t[b], rng.choice([0, 1, 37, 130, C]))) for b in range(B)]
+        kn = torch.zeros(B, Hkv, C, D, dtype=kd.dtype, device="cuda")
+        vn = torch.zeros_like(kn)
+        qn = torch.zeros(B, Hq, C, D, dtype=qd.dtype, device="cuda")
+        for b in range(B):
+            lo = cache.t[b] + 1
+            kn[b, :, :n_new[b]] = kd[b, :, lo:lo + n_new[b]]
+            vn[b, :, :n_new[b]] = vd[b, :, lo:lo + n_new[b]]
+            qn[b, :, :n_new[b]] = qd[b, :, lo:lo + n_new[b]]
+        # window start: what the chunk's first query needs (an empty chunk keeps the old one)
+        s_new = [max(cache.s[b], _window_start(cache.t[b] + 1, r, W, sinks, units)) if n_new[b] else cache.s[b]
+                 for b in range(B)]
+        p0 = [cache.t[b] + 1 for b in range(B)]
+        rows_u = cache.update_batch(kn, vn, n_new, s_new).cpu().tolist()
+        out = torch.full((B, Hq, C, D), 7.0, dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((B, Hq, C), 7.0, device="cuda")
+        _, _, rows = cache.prefill_batch(qn, n_new, W, window_mode=int(units), out=out, lse=lse)
+        torch.cuda.synchronize()
+        assert rows.cpu().tolist() == rows_u, step
+        out, lse = out.cpu(), lse.cpu()
+        for b in range(B):
+            got_o[b][:, p0[b]:p0[b] + n_new[b]] = out[b, :, :n_new[b]]
+            got_l[b][:, p0[b]:p0[b] + n_new[b]] = lse[b, :, :n_new[b]]
+            assert bool((out[b, :, n_new[b]:] == 7.0).all()) and bool((lse[b, :, n_new[b]:] == 7.0).all()), (step, b)
+        step += 1
+    assert step > 3
+    for b, n_b in enumerate(lens):
+        rows = np.unique(np.concatenate([[0, n_b - 1, min(n_b - 1, sinks)], np.random.default_rng(b).integers(0, n_b, 12)]))
+        for h in (0, Hq - 1):
+            g = h // (Hq // Hkv)
+            o, l = oracle.attn_fwd_rows(to_np(q[b, h, :n_b]), to_np(k[b, g, :n_b]), to_np(v[b, g, :n_b]), rows, r, W,
+                                        sinks=sinks, units=units)
+            assert max_abs(to_np(got_o[b][h])[rows], o) <= TOL_OUT_BF16, (b, h)
+            assert max_abs(to_np(got_l[b][h])[rows], l) <= TOL_LSE_BF16, (b, h)
+
+
+def test_ragged_prefill_with_equal_states_is_the_plain_call_and_bad_states_are_reported():
+    B, Hq, Hkv, D, r, W, C, L = 3, 4, 2, 64, 4, 50, 300, 900
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=28)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    plain = u.KVCache(B, Hkv, L, D, r)
+    ragged = u.RaggedKVCache(B, Hkv, L, D, r)
+    for p0 in range(0, L, C):
+        kn, vn, qn = (t[:, :, p0:p0 + C].contiguous() for t in (kd, vd, qd))
+        s = max(0, p0 - W + 1)
+        plain.update(kn, vn, s)
+        a_o, a_l = u.prefill_chunk(qn, plain, r, W, p0)
+        ragged.update_batch(kn, vn, [C] * B, [s] * B)
+        b_o, b_l, rows = ragged.prefill_batch(qn, [C] * B, W)
+        assert torch.equal(a_o, b_o) and torch.equal(a_l, b_l)
+        assert rows.cpu().tolist() == [plain.rows] * B
+    # impossible states: a window start right of what the first query sees, more rows than the queries' slab, a
+    # negative position; the good sequence in between is still served, the others' outputs stay as they were
+    kc, vc = ragged.current()
+    qn = qd[:, :, L - C:].contiguous()
+    dev = lambda x: torch.tensor(x, dtype=torch.int32, device="cuda")
+    out = torch.full((B, Hq, C, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, C), 7.0, device="cuda")
+    rows = torch.zeros(B, dtype=torch.int32, device="cuda")
+    s_ok = L - C - W + 1
+    p0, n, s0 = dev([L - C, L - C, -5]), dev([C, C, C]), dev([s_ok + 1, s_ok, s_ok])  # kept alive across the call
+    st = u.unigist_prefill_chunk_ragged(qn.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                        B, Hq, Hkv, C, D, r, W, 0, 0, p0.data_ptr(), n.data_ptr(), s0.data_ptr(), L,
+                                        rows.data_ptr(), 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert st == 0
+    assert rows.cpu().tolist() == [-1, u.unigist_cache_rows(s_ok, L - 1, r), -1]
+    assert torch.equal(out[1], b_o[1]) and torch.equal(lse[1], b_l[1])
+    assert bool((out[0] == 7.0).all()) and bool((out[2] == 7.0).all()) and bool((lse[0] == 7.0).all())
+    # n > C and a cache too small for the state
+    p0, n, s0 = dev([L - C, 0, L - C]), dev([C + 1, 0, C]), dev([s_ok, 0, s_ok])
+    st = u.unigist_prefill_chunk_ragged(qn.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                        B, Hq, Hkv, C, D, r, W, 0, 0, p0.data_ptr(), n.data_ptr(), s0.data_ptr(), 100,
+                                        rows.data_ptr(), 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert st == 0 and rows.cpu().tolist() == [-1, 0, -1]
