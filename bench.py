@@ -98,8 +98,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-prefill", action="store_true",
-                    help="skip the chunk-wise prefill region (profiling runs: it launches the forward kernel under the "
-                         "same name at a smaller size)")
+                    help="skip the chunk-wise prefill region and the packed-documents region (profiling runs: the first "
+                         "launches the forward kernel under the same name at a smaller size)")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the matrix-core rate probe (profiling runs: its kernel would top the kernel statistics)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -236,6 +236,35 @@ def main():
 
     bm, bn = u.unigist_tile_sizes(D, u.UNIGIST_BF16)
     m = u.unigist_blockmap_build(L, r, W, bm, bn)
+    # the same 32K tokens as a pack of five documents (attention confined to each), own region
+    pack = None
+    if not args.no_prefill:
+        lens = [8192, 4100, 12288, 1020, 7168]
+        cu = [0]
+        for n in lens:
+            cu.append(cu[-1] + n)
+        q1, k1, v1, d1 = q[0], k[0], v[0], dout[0]
+        po, pl_ = u.attn_fwd_varlen(q1, k1, v1, r, W, cu)
+        pws = torch.empty(u.unigist_attn_bwd_varlen_workspace(Hq, Hkv, L, D, r, W, cu, u.UNIGIST_BF16), dtype=torch.uint8,
+                          device="cuda")
+        pack_nvis = sum(u.n_vis(n, r, W) for n in lens)
+        pack = {"workload": f"{WORKLOAD} as a pack of documents of {lens} tokens"}
+        for name, fn, fl in (("fwd", lambda: u.attn_fwd_varlen(q1, k1, v1, r, W, cu), 4.0),
+                             ("bwd", lambda: u.attn_bwd_varlen(q1, k1, v1, po, pl_, d1, r, W, cu, workspace=pws), 10.0)):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / 10
+            tf = fl * D * pack_nvis * Hq / t / 1e9
+            pack[name] = {"ms": t, "tflops": tf, "pct_of_peak": 100.0 * tf / PEAK_BF16_TFLOPS}
+        del po, pl_, pws
+
     value = (flops_fwd + flops_bwd) / step_ms / 1e9
     res = {
         "metric": "gist-attn fwd+bwd TFLOP/s (unmasked) @32K GQA; % of bf16 MFMA peak",
@@ -258,6 +287,8 @@ def main():
             "bound": "hbm", "achieved": dec8_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec8_gbs / PEAK_HBM_GBS,
             "traffic": TRAFFIC_BYTES.get("decode_e4m3"), "alg_bytes_per_launch": dec8_bytes}},
     }
+    if pack is not None:
+        res["packed_documents"] = pack
     if prefill_ms is not None:
         res["prefill"] = {"workload": f"{WORKLOAD} in {C}-token chunks through the compressed cache", "ms": prefill_ms,
                           "tflops": flops_fwd / prefill_ms / 1e9,
