@@ -283,6 +283,21 @@ unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc, const voi
                                         void* hip_stream);
 
 /*
+ * unigist_prefill_chunk_ex over a cache of E4M3 codes (as unigist_decode_e4m3 reads it: kc/vc uint8
+ * [B, Hkv, cap, D], 16-byte aligned, the value of an element is its code times k_scale / v_scale of its kv head,
+ * DEVICE arrays of Hkv positive floats).  q, out bf16.  The rows in use are first widened to bf16 in `workspace`
+ * (exact: every E4M3 value is a bf16 value; unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, t = p0+C-1, r,
+ * sinks) bytes, 256-byte aligned), then the forward kernel runs on them with the scales applied in fp32 to the
+ * scores and to the output -- the same arithmetic on the same values as unigist_decode_e4m3.  The result is the
+ * rows p0 .. p0+C-1 of attention over the dequantised keys and values.
+ */
+size_t unigist_prefill_chunk_e4m3_workspace(int B, int Hkv, int D, int s, int t, int r, int sinks);
+unigist_status unigist_prefill_chunk_e4m3(const void* q, const void* kc, const void* vc, const float* k_scale,
+                                          const float* v_scale, void* out, float* lse, int B, int Hq, int Hkv, int C,
+                                          int D, int r, int W, int sinks, int window_mode, int p0, int s, int cap,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * unigist_prefill_chunk_ex for a batch whose sequences are in different states (Sec. 4.3, one launch for all of
  * them): p0, n and s are DEVICE arrays of B ints.  Sequence b has n[b] <= C query rows at positions
  * p0[b] .. p0[b]+n[b]-1, the first n[b] rows of its slab of q [B, Hq, C, D]; its slab of kc/vc [B, Hkv, cap, D] is

@@ -28,7 +28,7 @@ EXPORTS = [
     "unigist_attn_fwd_varlen", "unigist_attn_bwd_varlen", "unigist_attn_bwd_varlen_workspace",
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
-    "unigist_prefill_chunk_ragged",
+    "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
 ]
 
 
@@ -107,6 +107,10 @@ def load():
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
     lib.unigist_prefill_chunk_ragged.restype = ip
     lib.unigist_prefill_chunk_ragged.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [vp, vp, vp, ip, vp, ip, vp]
+    lib.unigist_prefill_chunk_e4m3_workspace.restype = sz
+    lib.unigist_prefill_chunk_e4m3_workspace.argtypes = [ip] * 7
+    lib.unigist_prefill_chunk_e4m3.restype = ip
+    lib.unigist_prefill_chunk_e4m3.argtypes = [vp, vp, vp, vp, vp, vp, fp] + [ip] * 12 + [vp, sz, vp]
     lib.unigist_cache_rows.restype = ip
     lib.unigist_cache_rows.argtypes = [ip, ip, ip]
     lib.unigist_cache_update.restype = ip
@@ -257,6 +261,16 @@ def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new
                                 cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
     return load().unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                               vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
+
+
+def unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, t, r, sinks) -> int:
+    return load().unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, t, r, sinks)
+
+
+def unigist_prefill_chunk_e4m3(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s,
+                               cap, ws, ws_bytes, stream=None) -> int:
+    return load().unigist_prefill_chunk_e4m3(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, C, D, r, W, sinks,
+                                             window_mode, p0, s, cap, ws, ws_bytes, stream)
 
 
 def unigist_prefill_chunk_ragged(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, n, s, cap,
@@ -620,12 +634,24 @@ class RaggedKVCache:
         return self.k[0], self.v[0], sl
 
 
-def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING):
-    """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse."""
+def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING, workspace=None):
+    """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse.
+    A cache of E4M3 codes goes through unigist_prefill_chunk_e4m3 (workspace: a uint8 tensor to reuse, optional)."""
     _dev(q)
     B, Hq, C, D = q.shape
     out = torch.empty_like(q)
     lse = torch.empty(B, Hq, C, device=q.device, dtype=torch.float32)
+    if cache.kc.dtype == torch.uint8:
+        need = unigist_prefill_chunk_e4m3_workspace(B, cache.Hkv, D, cache.s, int(p0) + C - 1, int(r), cache.sinks)
+        if workspace is None or workspace.numel() < need:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        _check(unigist_prefill_chunk_e4m3(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(),
+                                          cache.k_scale.data_ptr(), cache.v_scale.data_ptr(), out.data_ptr(),
+                                          lse.data_ptr(), B, Hq, cache.Hkv, C, D, int(r), int(W), cache.sinks,
+                                          int(window_mode), int(p0), cache.s, cache.cap, workspace.data_ptr(),
+                                          workspace.numel(), _stream()),
+               "unigist_prefill_chunk_e4m3")
+        return out, lse
     _check(unigist_prefill_chunk_ex(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(),
                                     lse.data_ptr(), B, Hq, cache.Hkv, C, D, int(r), int(W), cache.sinks,
                                     int(window_mode), int(p0), cache.s, cache.cap, _dt(q), _stream()),

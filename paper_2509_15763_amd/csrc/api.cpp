@@ -54,6 +54,8 @@ AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sin
     s.kv_rows = L;
     s.s0 = 0;
     s.ngb = 0;
+    s.kscale = nullptr;
+    s.vscale = nullptr;
     return s;
 }
 
@@ -307,6 +309,48 @@ extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc
     sh.s0 = s;
     sh.ngb = count_always(sh, s);
     hipError_t e = launch_fwd_mfma(q, kc, vc, out, lse, sh, (hipStream_t)hip_stream);
+    return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" size_t unigist_prefill_chunk_e4m3_workspace(int B, int Hkv, int D, int s, int t, int r, int sinks) {
+    const int rows = unigist_cache_rows_ex(s, t, r, sinks);
+    if (B < 1 || Hkv < 1 || D < 1 || rows < 0) return 0;
+    return 2 * align256((size_t)B * Hkv * rows * D * 2);  // the rows in use of K and of V, widened to bf16
+}
+
+extern "C" unigist_status unigist_prefill_chunk_e4m3(const void* q, const void* kc, const void* vc,
+                                                     const float* k_scale, const float* v_scale, void* out, float* lse,
+                                                     int B, int Hq, int Hkv, int C, int D, int r, int W, int sinks,
+                                                     int window_mode, int p0, int s, int cap, void* workspace,
+                                                     size_t workspace_bytes, void* hip_stream) {
+    if (C < 1 || p0 < 0 || s < 0 || cap < 1) return UNIGIST_EINVAL;
+    const long long Ltot = (long long)p0 + C;
+    if (Ltot > kMaxL) return UNIGIST_EUNSUPPORTED;
+    unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, UNIGIST_BF16, sinks, window_mode);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !kc || !vc || !k_scale || !v_scale || !out || !lse || !workspace) return UNIGIST_EINVAL;
+    if (((uintptr_t)kc & 15) != 0 || ((uintptr_t)vc & 15) != 0 || ((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    AttnShape sh = make_shape(B, Hq, Hkv, (int)Ltot, D, r, W, sinks, window_mode);
+    if (s > win_lo(sh, p0)) return UNIGIST_EINVAL;  // every raw token the first query may see must still be cached
+    const int rows = unigist_cache_rows_ex(s, (int)Ltot - 1, r, sinks);
+    if (rows < 0 || rows > cap) return UNIGIST_EINVAL;
+    const size_t need = unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, (int)Ltot - 1, r, sinks);
+    if (workspace_bytes < need) return UNIGIST_EINVAL;
+    // the rows in use, widened (exactly) to bf16, slabs of `rows` rows; the scales go to the kernel
+    char* kw = (char*)workspace;
+    char* vw = kw + need / 2;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (launch_widen_e4m3(kc, kw, B * Hkv, cap, rows, D, stream) != hipSuccess) return UNIGIST_ELAUNCH;
+    if (launch_widen_e4m3(vc, vw, B * Hkv, cap, rows, D, stream) != hipSuccess) return UNIGIST_ELAUNCH;
+    sh.Lq = C;
+    sh.qhs = C;
+    sh.qpos0 = p0;
+    sh.kv_rows = rows;
+    sh.s0 = s;
+    sh.ngb = count_always(sh, s);
+    sh.kscale = k_scale;
+    sh.vscale = v_scale;
+    hipError_t e = launch_fwd_mfma(q, kw, vw, out, lse, sh, stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 

@@ -166,7 +166,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         l[qb] = 0.f;
     }
     bool need_max = true;  // until every row of the wave has a finite reference
-    const float c = s.scale * 1.4426950408889634f;  // exp(x * scale) = exp2(x * c)
+    const float sc = s.kscale ? s.scale * s.kscale[hk] : s.scale;  // softmax scale times the scale of the stored keys
+    const float c = sc * 1.4426950408889634f;                       // exp(x * sc) = exp2(x * c)
 
     // ---- tile walk
     const int lo = win_lo(s, i0);                 // leftmost position inside any window of the tile
@@ -382,7 +383,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         float lt = l[qb];
         lt += __shfl_xor(lt, 16, 64);
         lt += __shfl_xor(lt, 32, 64);
-        const float inv = 1.f / lt;
+        float inv = 1.f / lt;
+        if (s.vscale) inv *= s.vscale[hk];  // the stored values stand for V * vscale
         if (qrow[qb] < L) {
             const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow[qb] - qpos0);
             bf16_t* op = out + orow * D + 4 * g4;
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
                 w2[1] = pack_bf16x2(o[db][qb][2] * inv, o[db][qb][3] * inv);
                 *(u32x2*)(op + 16 * db) = w2;
             }
-            if (g4 == 0) lse[orow] = m[qb] * s.scale + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
+            if (g4 == 0) lse[orow] = m[qb] * sc + __builtin_amdgcn_logf(lt) * 0.6931471805599453f;
         }
     }
 }

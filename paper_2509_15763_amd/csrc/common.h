@@ -67,6 +67,10 @@ struct AttnShape {
     int kv_rows;  // rows per head in the K/V buffers
     int s0;       // first position stored in the window region of K/V
     int ngb;      // rows in front of it: the gists at positions < s0, compact (gist g in row g)
+    // Forward only: K and V stand for K * kscale[kv head] and V * vscale[kv head] (device arrays of Hkv floats; null
+    // = 1).  The scales are applied in fp32 to the scores and to the output, never to the bf16 operands.
+    const float* kscale;
+    const float* vscale;
 };
 
 // ---- the visibility rule of Sec. 4.1 (Eq. 3) in the closed forms the kernels use.  A key j <= i is visible
@@ -192,6 +196,8 @@ hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* ou
 hipError_t launch_decode_fp8(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
                              void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D,
                              float* ws, hipStream_t st);
+// the first `rows` rows of every [cap, D] slab of E4M3 codes -> bf16 (exact), slabs of `rows` rows; BH slabs
+hipError_t launch_widen_e4m3(const void* codes, void* y, int BH, int cap, int rows, int D, hipStream_t st);
 // y = e4m3(x / scale[head]) for x [B, H, n, D] (bf16 or fp32), 16 elements per lane
 hipError_t launch_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
                                 unigist_dtype dt_in, hipStream_t st);

@@ -557,7 +557,42 @@ __global__ __launch_bounds__(256) void quantize_e4m3_kernel(const T* __restrict_
     }
     *(u32x4*)(y + e0) = w;
 }
+// E4M3 codes -> the same values in bf16 (exact: 3 mantissa bits, exponents well inside bf16's), 16 per lane.
+// Lane idx covers the elements 16 idx .. 16 idx + 15 of the output, whose slabs hold `rows` of the input slab's `cap` rows.
+__global__ __launch_bounds__(256) void widen_e4m3_kernel(const uint8_t* __restrict__ x, bf16_t* __restrict__ y,
+                                                        long per_slab_out, long per_slab_in, long nchunks) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nchunks) return;
+    const long e0 = idx * 16;
+    const long slab = e0 / per_slab_out, within = e0 % per_slab_out;
+    const u32x4 w = *(const u32x4*)(x + slab * per_slab_in + within);
+    u32x4 lo, hi;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[t], false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[t], true);
+        const uint32_t p0 = pack_bf16x2(a[0], a[1]), p1 = pack_bf16x2(b[0], b[1]);
+        if (t < 2) {
+            lo[2 * t] = p0;
+            lo[2 * t + 1] = p1;
+        } else {
+            hi[2 * (t - 2)] = p0;
+            hi[2 * (t - 2) + 1] = p1;
+        }
+    }
+    *(u32x4*)(y + e0) = lo;
+    *(u32x4*)(y + e0 + 8) = hi;
+}
 }  // namespace
+
+hipError_t launch_widen_e4m3(const void* codes, void* y, int BH, int cap, int rows, int D, hipStream_t st) {
+    const long per_out = (long)rows * D, per_in = (long)cap * D;
+    const long nchunks = (long)BH * per_out / 16;
+    if (nchunks <= 0) return hipSuccess;
+    const long blocks = (nchunks + 255) / 256;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    widen_e4m3_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((const uint8_t*)codes, (bf16_t*)y, per_out, per_in, nchunks);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
                                 unigist_dtype dt_in, hipStream_t st) {

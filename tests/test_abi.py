@@ -180,6 +180,17 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk(*p.values()) == 1
     p.update(cap=1024, q=None)
     assert u.unigist_prefill_chunk(*p.values()) == 1
+    # prefill over a cache of codes: the same checks plus scales, alignment and workspace
+    e = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128,
+             r=4, W=100, sinks=0, window_mode=0, p0=500, s=401, cap=1024, ws=FAKE, ws_bytes=1 << 30)
+    bad = lambda **kw: u.unigist_prefill_chunk_e4m3(*dict(e, **kw).values())
+    need = u.unigist_prefill_chunk_e4m3_workspace(1, 1, 128, 401, 563, 4, 0)
+    assert need == 2 * (80 + 163) * 128 * 2                  # 80 gists left of 401, positions 401 .. 563, K and V
+    assert u.unigist_prefill_chunk_e4m3_workspace(1, 1, 128, 401, 399, 4, 0) == 0
+    assert bad(s=402) == 1 and bad(cap=100) == 1 and bad(ws_bytes=need - 1) == 1 and bad(D=96) == 2
+    assert bad(kc=FAKE + 8) == 1 and bad(ws=FAKE + 16) == 1
+    for name in ("q", "kc", "vc", "k_scale", "v_scale", "out", "lse", "ws"):
+        assert bad(**{name: None}) == 1, name
     # ragged prefill: the host checks what it can see (the per-sequence states live in device memory)
     g = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=2, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
              window_mode=0, p0=FAKE, n=FAKE, s=FAKE, cap=1024, rows_out=FAKE, dt=0)

@@ -112,6 +112,50 @@ def test_quantised_cache_through_updates_then_decode():
     assert max_abs(o, o16) < 0.05
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,L,C,r,W,sinks,units", [
+    (8, 2, 128, 1500, 400, 4, 64, 0, False),
+    (4, 1, 64, 900, 256, 4, 5, 40, True),       # sinks and a window of whole units, D = 64, ragged last chunk
+])
+def test_chunkwise_prefill_over_codes(Hq, Hkv, D, L, C, r, W, sinks, units):
+    # the prompt goes through a cache of one-byte rows chunk by chunk: every chunk's rows equal attention over the
+    # dequantised keys and values (the oracle's codes times the scales, in fp64), and the last row agrees with decode
+    B = 2
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=54)
+    ks, vs = synth.e4m3_scales(Hkv, seed=8)
+    kq = oracle.quantize_e4m3(k.to(torch.float32).numpy(), ks.numpy())
+    vq = oracle.quantize_e4m3(v.to(torch.float32).numpy(), vs.numpy())
+    kdq, vdq = oracle.dequantize_e4m3(kq, ks.numpy()), oracle.dequantize_e4m3(vq, vs.numpy())
+    cache = u.KVCache(B, Hkv, L, D, r, dtype=torch.uint8, k_scale=ks.cuda(), v_scale=vs.cuda(), sinks=sinks)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+
+    def wstart(i):
+        if not units:
+            return max(0, i - W + 1)
+        return i if i < sinks else sinks + max(0, (i - sinks) // (r + 1) - W) * (r + 1)
+
+    outs, lses = [], []
+    for p0 in range(0, L, C):
+        n = min(C, L - p0)
+        cache.update(kd[:, :, p0:p0 + n].contiguous(), vd[:, :, p0:p0 + n].contiguous(), wstart(p0))
+        o, l = u.prefill_chunk(qd[:, :, p0:p0 + n].contiguous(), cache, r, W, p0, window_mode=int(units))
+        outs.append(o)
+        lses.append(l)
+    out, lse = torch.cat(outs, dim=2), torch.cat(lses, dim=2)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, max(sinks - 1, 0), sinks, C - 1, C, L - 1], np.random.default_rng(3).integers(0, L, 20)]))
+    for b, h in [(0, 0), (B - 1, Hq - 1)]:
+        g = h // (Hq // Hkv)
+        o, l = oracle.attn_fwd_rows(to_np(q[b, h]), kdq[b, g], vdq[b, g], rows, r, W, sinks=sinks, units=units)
+        assert max_abs(to_np(out[b, h])[rows], o) <= TOL_OUT_BF16, (b, h)
+        assert max_abs(to_np(lse[b, h])[rows], l) <= TOL_LSE_BF16, (b, h)
+    t = L - 1
+    cache.update(None, None, wstart(t))
+    sl = torch.full((B,), cache.rows, dtype=torch.int32, device="cuda")
+    o2, l2 = u.decode_e4m3(qd[:, :, t].contiguous(), cache.kc, cache.vc, cache.k_scale, cache.v_scale, sl)
+    assert max_abs(to_np(o2), to_np(out[:, :, t])) <= 2 * TOL_OUT_BF16
+    assert max_abs(to_np(l2), to_np(lse[:, :, t])) <= 2 * TOL_LSE_BF16
+
+
 def test_full_size_decode_over_codes_sampled():
     # the serving shape, cache bytes halved: sampled (batch, head) pairs against the oracle on the same codes
     w = synth.WORKLOADS["cfg5_decode"]
