@@ -180,6 +180,22 @@ size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, i
                                          int ndocs, unigist_dtype dt);
 
 /*
+ * The same for the layout of unigist_attn_fwd_ex inside every document (Sec. 4.1 with the cross-document masking
+ * of Sec. 5.1 -- the paper's training setting): each document starts with `sinks` sink tokens (a shorter document
+ * is all sinks) and its window is counted per `window_mode`.  (0, UNIGIST_WINDOW_SLIDING) gives the calls above.
+ */
+unigist_status unigist_attn_fwd_varlen_ex(const void* q, const void* k, const void* v, void* out, float* lse,
+                                          int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode,
+                                          const int* cu_seqlens, int ndocs, unigist_dtype dt, void* hip_stream);
+unigist_status unigist_attn_bwd_varlen_ex(const void* q, const void* k, const void* v, const void* out,
+                                          const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                          int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode,
+                                          const int* cu_seqlens, int ndocs, unigist_dtype dt, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream);
+size_t unigist_attn_bwd_varlen_workspace_ex(int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode,
+                                            const int* cu_seqlens, int ndocs, unigist_dtype dt);
+
+/*
  * Decode over the compressed KV cache (Sec. 4.3, Fig. 4): the raw tokens that have
  * left the window were physically removed, so every cached key of a sequence is
  * visible; the order of the keys in the cache is irrelevant.

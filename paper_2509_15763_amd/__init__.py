@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     UNIGIST_E4M3, unigist_quantize_e4m3, unigist_decode_e4m3, quantize_e4m3, decode_e4m3,
     unigist_cache_update_ragged, unigist_prefill_chunk_ragged,
     unigist_prefill_chunk_e4m3, unigist_prefill_chunk_e4m3_workspace,
+    unigist_attn_fwd_varlen_ex, unigist_attn_bwd_varlen_ex, unigist_attn_bwd_varlen_workspace_ex,
     unigist_cache_rows, unigist_cache_update, unigist_prefill_chunk,
     UNIGIST_WINDOW_SLIDING, UNIGIST_WINDOW_UNITS,
     unigist_attn_fwd_ex, unigist_attn_bwd_ex, unigist_attn_bwd_workspace_ex, unigist_blockmap_build_ex,

@@ -4,6 +4,7 @@ and the backward both run in the HIP kernels of libunigist).
     out = gist_attention(q, k, v, r, W)                         # [B,Hq,L,D], [B,Hkv,L,D] -> [B,Hq,L,D]
     out = gist_attention(q, k, v, r, W, sinks=128, window_mode=UNIGIST_WINDOW_UNITS)
     out = gist_attention_varlen(q, k, v, r, W, cu_seqlens)      # [Hq,T,D], [Hkv,T,D] -> [Hq,T,D]
+    out = gist_attention_varlen(q, k, v, r, W, cu_seqlens, sinks=128, window_mode=UNIGIST_WINDOW_UNITS)
 
 The backward of the attention needs q, k, v, out and the row-wise log-sum-exp, which the forward saves
 (Sec. 4.2: no attention matrix is ever materialised).
@@ -32,20 +33,21 @@ class _GistAttention(torch.autograd.Function):
 
 class _GistAttentionVarlen(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, k, v, r, W, cu_seqlens):
+    def forward(ctx, q, k, v, r, W, cu_seqlens, sinks, window_mode):
         q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
         cu = [int(x) for x in cu_seqlens]
-        out, lse = _b.attn_fwd_varlen(q, k, v, r, W, cu)
+        out, lse = _b.attn_fwd_varlen(q, k, v, r, W, cu, sinks=sinks, window_mode=window_mode)
         ctx.save_for_backward(q, k, v, out, lse)
-        ctx.mask = (int(r), int(W), cu)
+        ctx.mask = (int(r), int(W), cu, int(sinks), int(window_mode))
         return out
 
     @staticmethod
     def backward(ctx, dout):
         q, k, v, out, lse = ctx.saved_tensors
-        r, W, cu = ctx.mask
-        dq, dk, dv = _b.attn_bwd_varlen(q, k, v, out, lse, dout.contiguous(), r, W, cu)
-        return dq, dk, dv, None, None, None
+        r, W, cu, sinks, window_mode = ctx.mask
+        dq, dk, dv = _b.attn_bwd_varlen(q, k, v, out, lse, dout.contiguous(), r, W, cu, sinks=sinks,
+                                        window_mode=window_mode)
+        return dq, dk, dv, None, None, None, None, None
 
 
 def gist_attention(q, k, v, r, W, sinks=0, window_mode=_b.UNIGIST_WINDOW_SLIDING):
@@ -53,6 +55,6 @@ def gist_attention(q, k, v, r, W, sinks=0, window_mode=_b.UNIGIST_WINDOW_SLIDING
     return _GistAttention.apply(q, k, v, r, W, sinks, window_mode)
 
 
-def gist_attention_varlen(q, k, v, r, W, cu_seqlens):
+def gist_attention_varlen(q, k, v, r, W, cu_seqlens, sinks=0, window_mode=_b.UNIGIST_WINDOW_SLIDING):
     """The same for documents packed along the token axis; cu_seqlens is a host sequence of boundaries."""
-    return _GistAttentionVarlen.apply(q, k, v, r, W, cu_seqlens)
+    return _GistAttentionVarlen.apply(q, k, v, r, W, cu_seqlens, sinks, window_mode)

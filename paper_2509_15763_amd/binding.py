@@ -29,6 +29,7 @@ EXPORTS = [
     "unigist_cache_rows_ex", "unigist_cache_update_ex", "unigist_prefill_chunk_ex",
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
+    "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
 ]
 
 
@@ -85,6 +86,12 @@ def load():
     lib.unigist_attn_bwd_varlen.argtypes = [vp] * 9 + [ip] * 6 + [cup, ip, ip, vp, sz, vp]
     lib.unigist_attn_bwd_varlen_workspace.restype = sz
     lib.unigist_attn_bwd_varlen_workspace.argtypes = [ip] * 6 + [cup, ip, ip]
+    lib.unigist_attn_fwd_varlen_ex.restype = ip
+    lib.unigist_attn_fwd_varlen_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 8 + [cup, ip, ip, vp]
+    lib.unigist_attn_bwd_varlen_ex.restype = ip
+    lib.unigist_attn_bwd_varlen_ex.argtypes = [vp] * 9 + [ip] * 8 + [cup, ip, ip, vp, sz, vp]
+    lib.unigist_attn_bwd_varlen_workspace_ex.restype = sz
+    lib.unigist_attn_bwd_varlen_workspace_ex.argtypes = [ip] * 8 + [cup, ip, ip]
     lib.unigist_decode.restype = ip
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
     lib.unigist_quantize_e4m3.restype = ip
@@ -208,6 +215,24 @@ def unigist_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, 
     cu, nd = _cu(cu_seqlens)
     return load().unigist_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, cu, nd, dt, ws,
                                           ws_bytes, stream)
+
+
+def unigist_attn_fwd_varlen_ex(q, k, v, out, lse, Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, dt,
+                               stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_fwd_varlen_ex(q, k, v, out, lse, Hq, Hkv, T, D, r, W, sinks, window_mode, cu, nd, dt, stream)
+
+
+def unigist_attn_bwd_varlen_ex(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens,
+                               dt, ws, ws_bytes, stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_bwd_varlen_ex(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, sinks, window_mode,
+                                             cu, nd, dt, ws, ws_bytes, stream)
+
+
+def unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, dt) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, sinks, window_mode, cu, nd, dt)
 
 
 def unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, dt) -> int:
@@ -390,7 +415,7 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_A
     return dq, dk, dv
 
 
-def attn_fwd_varlen(q, k, v, r, W, cu_seqlens):
+def attn_fwd_varlen(q, k, v, r, W, cu_seqlens, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
     """Packed documents: q [Hq,T,D], k/v [Hkv,T,D] on the GPU, cu_seqlens a host sequence -> out, lse [Hq,T]."""
     _dev(q, k, v)
     Hq, T, D = q.shape
@@ -399,13 +424,15 @@ def attn_fwd_varlen(q, k, v, r, W, cu_seqlens):
         raise UnigistError("q/k/v shapes or dtypes disagree")
     out = torch.empty_like(q)
     lse = torch.empty(Hq, T, device=q.device, dtype=torch.float32)
-    _check(unigist_attn_fwd_varlen(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                                   Hq, Hkv, T, D, int(r), int(W), cu_seqlens, _dt(q), _stream()),
-           "unigist_attn_fwd_varlen")
+    _check(unigist_attn_fwd_varlen_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                      Hq, Hkv, T, D, int(r), int(W), int(sinks), int(window_mode), cu_seqlens, _dt(q),
+                                      _stream()),
+           "unigist_attn_fwd_varlen_ex")
     return out, lse
 
 
-def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None):
+def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None, sinks=0,
+                    window_mode=UNIGIST_WINDOW_SLIDING):
     """-> dq [Hq,T,D], dk, dv [Hkv,T,D] for packed documents."""
     _dev(q, k, v, out, lse, dout)
     Hq, T, D = q.shape
@@ -415,18 +442,18 @@ def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None):
         raise UnigistError("out/dout/lse shapes or dtypes disagree")
     if k.shape != (Hkv, T, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:
         raise UnigistError("q/k/v/out/dout shapes or dtypes disagree")
-    need = unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, int(r), int(W), cu_seqlens, dt)
+    need = unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, int(r), int(W), int(sinks), int(window_mode), cu_seqlens, dt)
     if need == 0:
         raise UnigistError("unigist_attn_bwd_varlen_workspace: invalid shape or document bounds")
     if workspace is None:
         workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
     # rows of no document (none when cu_seqlens covers 0 .. T) would stay unwritten: start from zero
     dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
-    _check(unigist_attn_bwd_varlen(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                                   dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D,
-                                   int(r), int(W), cu_seqlens, dt, workspace.data_ptr(),
-                                   workspace.numel() * workspace.element_size(), _stream()),
-           "unigist_attn_bwd_varlen")
+    _check(unigist_attn_bwd_varlen_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                      dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D,
+                                      int(r), int(W), int(sinks), int(window_mode), cu_seqlens, dt, workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream()),
+           "unigist_attn_bwd_varlen_ex")
     return dq, dk, dv
 
 

@@ -382,17 +382,18 @@ extern "C" unigist_status unigist_prefill_chunk_ragged(const void* q, const void
 // ---------------------------------------------------------------- packed documents
 namespace {
 
-unigist_status check_docs(int Hq, int Hkv, int T, int D, int r, int W, const int* cu, int ndocs, unigist_dtype dt) {
+unigist_status check_docs(int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode, const int* cu,
+                          int ndocs, unigist_dtype dt) {
     if (!cu || ndocs < 1 || T < 1) return UNIGIST_EINVAL;
     if (cu[0] != 0 || cu[ndocs] != T) return UNIGIST_EINVAL;
     for (int d = 0; d < ndocs; ++d)
         if (cu[d + 1] < cu[d]) return UNIGIST_EINVAL;
-    return check_attn(1, Hq, Hkv, T, D, r, W, dt);
+    return check_attn(1, Hq, Hkv, T, D, r, W, dt, sinks, window_mode);
 }
 
 // the document [c0, c0 + len) of a packed [H, T, D] buffer as a shape of its own
-AttnShape doc_shape(int Hq, int Hkv, int T, int D, int r, int W, int len) {
-    AttnShape s = make_shape(1, Hq, Hkv, len, D, r, W);
+AttnShape doc_shape(int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode, int len) {
+    AttnShape s = make_shape(1, Hq, Hkv, len, D, r, W, sinks, window_mode);
     s.qhs = T;
     s.kvhs = T;
     s.kv_rows = T;
@@ -484,19 +485,27 @@ unigist_status for_each_doc(const int* cu, int ndocs, hipStream_t stream, bool s
 extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
                                                   int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                   int ndocs, unigist_dtype dt, void* hip_stream) {
-    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    return unigist_attn_fwd_varlen_ex(q, k, v, out, lse, Hq, Hkv, T, D, r, W, 0, UNIGIST_WINDOW_SLIDING, cu_seqlens, ndocs,
+                                      dt, hip_stream);
+}
+
+extern "C" unigist_status unigist_attn_fwd_varlen_ex(const void* q, const void* k, const void* v, void* out,
+                                                     float* lse, int Hq, int Hkv, int T, int D, int r, int W, int sinks,
+                                                     int window_mode, const int* cu_seqlens, int ndocs,
+                                                     unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
     const size_t eb = elem_bytes(dt);
     if (dt == UNIGIST_BF16 && !plain_alu_forced()) {  // one launch, the workgroups look their document up
-        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, T);
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, T);
         return launch_fwd_mfma_pack(q, k, v, out, lse, s, cu_seqlens, ndocs, (hipStream_t)hip_stream) == hipSuccess
                    ? UNIGIST_OK
                    : UNIGIST_ELAUNCH;
     }
     return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, false, [&](int d, hipStream_t stream, int) {
         const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
-        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, len);
         const size_t ro = (size_t)c0 * D * eb;  // byte offset of the document's first row inside a head
         const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
         char* od = (char*)out + ro;
@@ -506,20 +515,26 @@ extern "C" unigist_status unigist_attn_fwd_varlen(const void* q, const void* k, 
 
 extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                     int ndocs, unigist_dtype dt) {
-    if (check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt) != UNIGIST_OK) return 0;
+    return unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, 0, UNIGIST_WINDOW_SLIDING, cu_seqlens, ndocs, dt);
+}
+
+extern "C" size_t unigist_attn_bwd_varlen_workspace_ex(int Hq, int Hkv, int T, int D, int r, int W, int sinks,
+                                                       int window_mode, const int* cu_seqlens, int ndocs,
+                                                       unigist_dtype dt) {
+    if (check_docs(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt) != UNIGIST_OK) return 0;
     // document-by-document path: one slice per lane, each large enough for the longest document that lane may get
     size_t need = 256;
     for (int d = 0; d < ndocs; ++d) {
         const int len = cu_seqlens[d + 1] - cu_seqlens[d];
         if (len == 0) continue;
-        const size_t n = unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt);
+        const size_t n = unigist_attn_bwd_workspace_ex(1, Hq, Hkv, len, D, r, W, sinks, window_mode, dt);
         if (n > need) need = n;
     }
     need = align256(need) * kLanes;
     if (dt == UNIGIST_BF16) {
         // single-launch path: delta and lse2 of the whole pack plus every document's gist partial sums.  The larger
         // of the two is asked for, so that the debug switch to the plain-ALU kernels needs no other buffer.
-        const size_t pack = bwd_mfma_pack_workspace(doc_shape(Hq, Hkv, T, D, r, W, T), cu_seqlens, ndocs);
+        const size_t pack = bwd_mfma_pack_workspace(doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, T), cu_seqlens, ndocs);
         if (pack == 0) return 0;
         need = std::max(need, pack);
     }
@@ -531,14 +546,24 @@ extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, 
                                                   int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                   int ndocs, unigist_dtype dt, void* workspace,
                                                   size_t workspace_bytes, void* hip_stream) {
-    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    return unigist_attn_bwd_varlen_ex(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, 0, UNIGIST_WINDOW_SLIDING,
+                                      cu_seqlens, ndocs, dt, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" unigist_status unigist_attn_bwd_varlen_ex(const void* q, const void* k, const void* v, const void* out,
+                                                     const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                                     int Hq, int Hkv, int T, int D, int r, int W, int sinks,
+                                                     int window_mode, const int* cu_seqlens, int ndocs,
+                                                     unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                                     void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
     if (st != UNIGIST_OK) return st;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
-    const size_t need = unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, ndocs, dt);
+    const size_t need = unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
     if (workspace_bytes < need) return UNIGIST_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
     if (dt == UNIGIST_BF16 && !plain_alu_forced()) {  // one launch per kernel, the workgroups look their document up
-        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, T);
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, T);
         return launch_bwd_mfma_pack(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, cu_seqlens, ndocs,
                                     (hipStream_t)hip_stream) == hipSuccess
                    ? UNIGIST_OK
@@ -547,13 +572,13 @@ extern "C" unigist_status unigist_attn_bwd_varlen(const void* q, const void* k, 
     size_t slice = 256;
     for (int d = 0; d < ndocs; ++d) {
         const int len = cu_seqlens[d + 1] - cu_seqlens[d];
-        if (len > 0) slice = std::max(slice, align256(unigist_attn_bwd_workspace(1, Hq, Hkv, len, D, r, W, dt)));
+        if (len > 0) slice = std::max(slice, align256(unigist_attn_bwd_workspace_ex(1, Hq, Hkv, len, D, r, W, sinks, window_mode, dt)));
     }
     const size_t eb = elem_bytes(dt);
     // the documents of one lane run one after the other on its stream and share that lane's workspace slice
     return for_each_doc(cu_seqlens, ndocs, (hipStream_t)hip_stream, true, [&](int d, hipStream_t stream, int lane) {
         const int c0 = cu_seqlens[d], len = cu_seqlens[d + 1] - c0;
-        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, len);
+        const AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, len);
         const size_t ro = (size_t)c0 * D * eb;
         const char *qd = (const char*)q + ro, *kd = (const char*)k + ro, *vd = (const char*)v + ro;
         const char *od = (const char*)out + ro, *gd = (const char*)dout + ro;

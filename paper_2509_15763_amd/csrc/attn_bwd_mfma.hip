@@ -581,9 +581,7 @@ __global__ __launch_bounds__(NT) void gist_reduce_pack_kernel(const float* __res
     if (idx >= per_tile) return;
     const int d = doc_of_block(docs, blockIdx.x);
     const int t = blockIdx.x - docs.blk0[d];  // (kv head) * n_gt + gist tile
-    AttnShape s = doc_view(s_arg, docs.len[d]);
-    s.S = 0;
-    s.umode = 0;
+    const AttnShape s = doc_view(s_arg, docs.len[d]);
     BwdPlan pl;
     plan_counts(s, pl);
     const int gt = t % pl.n_gt;
@@ -988,10 +986,15 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
         return pl;
     };
     const BwdPlan none = {};
+    const bool gen = s.S != 0 || s.umode != 0;
     e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.n_gt * pl.nseg * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
-                       dkdv_kernel<D, true, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                  part, comp, s, none, t);
+                       if (gen)
+                           dkdv_kernel<D, true, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                     part, comp, s, none, t);
+                       else
+                           dkdv_kernel<D, true, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                      part, comp, s, none, t);
                    });
     if (e != hipSuccess) return e;
     constexpr int per_tile = 2 * D * BNK;
@@ -1003,13 +1006,18 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     if (e != hipSuccess) return e;
     e = for_chunks([&](int len) { return (long)((len + BNK - 1) / BNK) * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
-                       dkdv_kernel<D, false, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                   part, comp, s, none, t);
+                       if (gen)
+                           dkdv_kernel<D, false, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                      part, comp, s, none, t);
+                       else
+                           dkdv_kernel<D, false, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
+                                                                                       part, comp, s, none, t);
                    });
     if (e != hipSuccess) return e;
     return for_chunks([&](int len) { return (long)((len + BMQ - 1) / BMQ) * s.Hq; },
                       [&](const DocTab& t, unsigned nblk) {
-                          dq_kernel<D, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
+                          if (gen) dq_kernel<D, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
+                          else dq_kernel<D, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
                       });
 }
 

@@ -435,6 +435,7 @@ hipError_t launch_fwd_mfma_ragged(const void* q, const void* k, const void* v, v
 hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, void* out, float* lse, const AttnShape& s,
                                 const int* cu, int ndocs, hipStream_t st) {
     // long documents first: their long tiles are the ones that should not start last
+    const bool gen = s.S != 0 || s.umode != 0;
     std::vector<int> order;
     for (int d = 0; d < ndocs; ++d)
         if (cu[d + 1] > cu[d]) order.push_back(d);
@@ -457,8 +458,8 @@ hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, voi
             kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out,
                                                       lse, s, 0, t);
         };
-        if (s.D == 64) go(fwd_mfma_kernel<64, false, PACK>);
-        else go(fwd_mfma_kernel<128, false, PACK>);
+        if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, PACK>) : go(fwd_mfma_kernel<64, false, PACK>);
+        else gen ? go(fwd_mfma_kernel<128, true, PACK>) : go(fwd_mfma_kernel<128, false, PACK>);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

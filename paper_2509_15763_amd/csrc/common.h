@@ -128,6 +128,7 @@ __device__ __forceinline__ int doc_of_block(const DocTab& t, int blk) {
 __host__ __device__ inline AttnShape doc_view(AttnShape s, int len) {
     s.rp1 = s.rp1 - 1 >= len ? len + 1 : s.rp1;
     s.W = s.W > len ? len : s.W;
+    s.S = s.S > len ? len : s.S;
     s.L = len;
     s.Lq = len;
     return s;
@@ -163,8 +164,8 @@ hipError_t launch_bwd_simple(const void* q, const void* k, const void* v, const 
                              const AttnShape& s, unigist_dtype dt, hipStream_t st);
 hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* out, float* lse,
                            const AttnShape& s, hipStream_t st);
-// the same over the documents [cu[d], cu[d+1]) of a packed buffer (s: the shape of the whole pack, no sinks,
-// sliding window), one launch per kMaxDocs documents
+// the same over the documents [cu[d], cu[d+1]) of a packed buffer (s: the shape of the whole pack), one launch
+// per kMaxDocs documents
 hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, void* out, float* lse,
                                 const AttnShape& s, const int* cu, int ndocs, hipStream_t st);
 // chunk-wise prefill with per-sequence states (s: the launch's shape, see seq_view; cap = s.kv_rows)

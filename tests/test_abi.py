@@ -91,6 +91,17 @@ def test_varlen_argument_validation():
         assert u.unigist_attn_bwd_varlen_workspace(*args, bad, 0) == 0
         assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, bad, 0, FAKE, 1 << 40) == 1
     assert u.unigist_attn_bwd_varlen(*([FAKE] * 9), *args, cu, 0, FAKE, 16) == 1                # workspace too small
+    # the layout with sinks and unit windows: the same checks plus the two extra arguments
+    ex = (4, 2, 100, 64, 4, 8)
+    assert u.unigist_attn_bwd_varlen_workspace_ex(*ex, 5, 1, cu, 0) > 0
+    assert u.unigist_attn_bwd_varlen_workspace_ex(*ex, -1, 1, cu, 0) == 0
+    assert u.unigist_attn_bwd_varlen_workspace_ex(*ex, 5, 2, cu, 0) == 0
+    assert u.unigist_attn_fwd_varlen_ex(FAKE, FAKE, FAKE, FAKE, FAKE, *ex, -1, 0, cu, 0) == 1
+    assert u.unigist_attn_fwd_varlen_ex(FAKE, FAKE, FAKE, FAKE, FAKE, *ex, 5, 2, cu, 0) == 1
+    assert u.unigist_attn_fwd_varlen_ex(None, FAKE, FAKE, FAKE, FAKE, *ex, 5, 1, cu, 0) == 1
+    assert u.unigist_attn_bwd_varlen_ex(*([FAKE] * 9), *ex, 5, 1, cu, 0, FAKE, 16) == 1         # workspace too small
+    assert u.unigist_attn_bwd_varlen_ex(*([FAKE] * 9), *ex, 5, 3, cu, 0, FAKE, 1 << 40) == 1
+    assert u.unigist_attn_bwd_varlen_workspace(*ex, cu, 0) == u.unigist_attn_bwd_varlen_workspace_ex(*ex, 0, 0, cu, 0)
     # fp32 runs document by document: one slice per stream the documents are spread over, each sized for the
     # longest document
     one = u.unigist_attn_bwd_workspace(1, 4, 2, 5000, 64, 4, 8, 1)

@@ -27,13 +27,14 @@ def test_backward_through_the_wrapper(mask):
         assert rel_l2(to_np(got), want) <= TOL_GRAD_BF16
 
 
-def test_backward_through_the_varlen_wrapper():
-    Hq, Hkv, D, r, W, cu = 4, 1, 64, 4, 40, [0, 130, 131, 500]
+@pytest.mark.parametrize("W,sinks,units", [(40, 0, False), (3, 20, True)], ids=["sliding", "sinks_units"])
+def test_backward_through_the_varlen_wrapper(W, sinks, units):
+    Hq, Hkv, D, r, cu = 4, 1, 64, 4, [0, 130, 131, 500]
     q, k, v, dout = synth.attn_inputs(1, Hq, Hkv, cu[-1], D, seed=42)
     qd, kd, vd = (t[0].cuda().requires_grad_(True) for t in (q, k, v))
-    out = u.gist_attention_varlen(qd, kd, vd, r, W, cu)
+    out = u.gist_attention_varlen(qd, kd, vd, r, W, cu, sinks=sinks, window_mode=int(units))
     (out.float() * dout[0].cuda().float()).sum().backward()
     qn, kn, vn, don = (to_np(t) for t in (q, k, v, dout))
-    g = oracle.attn_bwd(qn, kn, vn, don, r, W, cu=cu)
+    g = oracle.attn_bwd(qn, kn, vn, don, r, W, cu=cu, sinks=sinks, units=units)
     for got, want in zip((qd.grad, kd.grad, vd.grad), g):
         assert rel_l2(to_np(got), want[0]) <= TOL_GRAD_BF16

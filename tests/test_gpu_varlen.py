@@ -19,18 +19,18 @@ def packed_inputs(Hq, Hkv, T, D, dtype, seed):
     return q[0], k[0], v[0], dout[0]
 
 
-def run_gpu(q, k, v, dout, r, W, cu):
+def run_gpu(q, k, v, dout, r, W, cu, sinks=0, units=False):
     qd, kd, vd, dod = (t.cuda() for t in (q, k, v, dout))
-    out, lse = u.attn_fwd_varlen(qd, kd, vd, r, W, cu)
-    dq, dk, dv = u.attn_bwd_varlen(qd, kd, vd, out, lse, dod, r, W, cu)
+    out, lse = u.attn_fwd_varlen(qd, kd, vd, r, W, cu, sinks=sinks, window_mode=int(units))
+    dq, dk, dv = u.attn_bwd_varlen(qd, kd, vd, out, lse, dod, r, W, cu, sinks=sinks, window_mode=int(units))
     torch.cuda.synchronize()
     return out, lse, dq, dk, dv
 
 
-def oracle_packed(q, k, v, dout, r, W, cu):
+def oracle_packed(q, k, v, dout, r, W, cu, **mask):
     qn, kn, vn, don = (to_np(t)[None] for t in (q, k, v, dout))
-    out, lse = oracle.attn_fwd(qn, kn, vn, r, W, cu=cu)
-    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W, cu=cu)
+    out, lse = oracle.attn_fwd(qn, kn, vn, r, W, cu=cu, **mask)
+    dq, dk, dv = oracle.attn_bwd(qn, kn, vn, don, r, W, cu=cu, **mask)
     return out[0], lse[0], dq[0], dk[0], dv[0]
 
 
@@ -56,6 +56,37 @@ def test_small_packs_match_oracle(Hq, Hkv, D, r, W, lens, dtype):
     q, k, v, dout = packed_inputs(Hq, Hkv, cu[-1], D, dtype, seed=31)
     got = run_gpu(q, k, v, dout, r, W, cu)
     check(case, got, oracle_packed(q, k, v, dout, r, W, cu), dtype)
+
+
+# Hq, Hkv, D, r, W, sinks, unit windows, document lengths: the layout with sinks and unit-aligned windows
+# restarting in every document (the training setting of Sec. 5.1)
+SMALL_EX = [
+    (4, 2, 64, 4, 3, 10, True, [300, 7, 500, 10, 11, 224]),      # documents shorter than, equal to, one past the sinks
+    (4, 1, 128, 2, 6, 33, True, [257, 443, 1]),
+    (2, 2, 128, 4, 40, 5, False, [90, 190, 77]),                 # sinks with the sliding window
+    (2, 1, 64, 8, 1, 128, True, [129, 600, 128]),                # 128 sinks, window of one unit
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("Hq,Hkv,D,r,W,sinks,units,lens", SMALL_EX)
+def test_small_packs_with_sinks_and_unit_windows_match_oracle(Hq, Hkv, D, r, W, sinks, units, lens, dtype):
+    cu = [0] + np.cumsum(lens).tolist()
+    case = f"Hq{Hq} Hkv{Hkv} D{D} r{r} W{W} sinks{sinks} units{int(units)} docs{lens} {dtype}"
+    print("case", case, flush=True)
+    q, k, v, dout = packed_inputs(Hq, Hkv, cu[-1], D, dtype, seed=34)
+    got = run_gpu(q, k, v, dout, r, W, cu, sinks=sinks, units=units)
+    check(case, got, oracle_packed(q, k, v, dout, r, W, cu, sinks=sinks, units=units), dtype)
+
+
+def test_mid_pack_with_sinks_and_unit_windows_matches_oracle():
+    # the paper's proportions in small (r = 4, a window of 25 units, 128 sinks): documents long enough for gists
+    # left of the window (the gist phase and its per-document partial sums) next to short ones
+    lens = [4500, 37, 3000, 130, 1463]
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = packed_inputs(4, 1, cu[-1], 128, torch.bfloat16, seed=35)
+    got = run_gpu(q, k, v, dout, 4, 25, cu, sinks=128, units=True)
+    check(f"docs{lens}", got, oracle_packed(q, k, v, dout, 4, 25, cu, sinks=128, units=True), torch.bfloat16)
 
 
 def test_mid_pack_matches_oracle():

@@ -163,6 +163,27 @@ def test_packed_mask_is_block_diagonal_of_the_single_document_masks(cu, r, W):
     assert M.diagonal().all()
 
 
+@pytest.mark.parametrize("cu,r,W,sinks", [([0, 5, 5, 17, 18, 40], 3, 1, 2), ([0, 30, 61, 100], 4, 2, 7),
+                                           ([0, 3, 40], 2, 3, 5)])
+def test_packed_mask_with_sinks_and_unit_windows_restarts_in_every_document(cu, r, W, sinks):
+    # Sec. 4.1's layout inside every document of a pack (Sec. 5.1): each document has its own sinks (a document
+    # shorter than the sink prefix is all sinks, i.e. plain causal) and its own gist units
+    T = cu[-1]
+    M = oracle.mask_rows(np.arange(T), T, r, W, cu=cu, sinks=sinks, units=True)
+    want = np.zeros((T, T), dtype=bool)
+    for a, b in zip(cu[:-1], cu[1:]):
+        if b > a:
+            want[a:b, a:b] = oracle.mask_rows(np.arange(b - a), b - a, r, W, sinks=sinks, units=True)
+            if b - a <= sinks:
+                assert np.array_equal(want[a:b, a:b], np.tri(b - a, dtype=bool))
+    assert np.array_equal(M, want)
+    # the first `sinks` positions of a document are seen by all of its later queries and by no other document's
+    for a, b in zip(cu[:-1], cu[1:]):
+        n = min(sinks, b - a)
+        assert M[b - 1:b, a:a + n].all() if b > a else True
+        assert not M[b:, a:a + n].any()
+
+
 def test_cache_state_with_sinks_and_unit_windows():
     # the worked example with 2 sinks and unit windows (tests/golden/visible_sets_L14_r2_sinks2_units1.txt):
     # query 12 sees 0 1 4 7 8 9 10 11 12; its window starts at position 8, so state (8, 12) holds exactly that
