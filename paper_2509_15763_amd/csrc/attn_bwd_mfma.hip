@@ -91,19 +91,37 @@ __host__ __device__ inline int last_chunk_with_far_le(const AttnShape& s, int NC
     return lo;
 }
 
-// the counts of a plan (the workgroups of a packed launch recompute them for their document)
-__host__ __device__ inline void plan_counts(const AttnShape& s, BwdPlan& p) {
+// The counts of a plan, given the segment length the launch asks for (pick_segc; the workgroups of a packed
+// launch recompute the counts for their document).  No more than 32 segments per gist tile.
+__host__ __device__ inline void plan_counts(const AttnShape& s, BwdPlan& p, int segc) {
     p.NC = (s.L + MQ - 1) / MQ;
     const int nfar_max = nfar_of_chunk(s, p.NC - 1);
     p.n_gt = (nfar_max + BNK - 1) / BNK;
-    p.segc = 32;  // 32 chunks x Hq/Hkv heads = 128 steps per workgroup: short enough to balance the last round
+    p.segc = segc;
     while ((p.NC + p.segc - 1) / p.segc > 32) p.segc *= 2;
     p.nseg = (p.NC + p.segc - 1) / p.segc;
 }
 
+// chunk steps (per kv head) of the gist phase of one sequence: every gist tile is walked by the chunks from the
+// first one that has it left of its window phase to the last
+long gist_chunk_steps(const AttnShape& s) {
+    BwdPlan p;
+    plan_counts(s, p, 32);
+    long n = 0;
+    for (int t = 0; t < p.n_gt; ++t) n += p.NC - first_chunk_with_more_far(s, p.NC, t * BNK);
+    return n;
+}
+
+// Segment length (query chunks per gist-phase workgroup) for a launch with `steps` chunk steps in total over all
+// (batch, kv head) pairs: 32 chunks (x Hq/Hkv heads = 128 steps per workgroup) balance the last round of a 32K
+// sequence; a launch that could not give the 512 workgroup slots of the chip (2 per CU) about five such rounds
+// gets segments of 16 (one 8K sequence: 10 % faster, a 32K pack of five documents: 2 %; 8 and 4 were no better,
+// their partial sums cost what the balance gains).
+int pick_segc(long steps) { return steps / (512 * 5) >= 32 ? 32 : 16; }
+
 BwdPlan make_plan(const AttnShape& s) {
     BwdPlan p;
-    plan_counts(s, p);
+    plan_counts(s, p, pick_segc(gist_chunk_steps(s) * s.B * s.Hkv));
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_lse2 = off;  // lse * log2(e), written by the delta pass
@@ -180,7 +198,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         const int d = doc_of_block(docs, n);
         n -= docs.blk0[d];
         s = doc_view(s, docs.len[d]);
-        plan_counts(s, pl);
+        plan_counts(s, pl, pl.segc);  // pl arrives with the launch's segment length only
         const size_t ro = (size_t)docs.c0[d] * D;
         q += ro;
         k += ro;
@@ -576,14 +594,14 @@ __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict
 // The same for a packed launch.  grid: x = slot of comp (a document's slots are its (kv head, gist tile) pairs,
 // docs.blk0 holds the first slot of each document), y = slice of the slot's 2*D*BNK floats.
 __global__ __launch_bounds__(NT) void gist_reduce_pack_kernel(const float* __restrict__ part, float* __restrict__ comp,
-                                                             AttnShape s_arg, int per_tile, DocTab docs) {
+                                                             AttnShape s_arg, int per_tile, int segc, DocTab docs) {
     const int idx = 4 * (blockIdx.y * NT + threadIdx.x);
     if (idx >= per_tile) return;
     const int d = doc_of_block(docs, blockIdx.x);
     const int t = blockIdx.x - docs.blk0[d];  // (kv head) * n_gt + gist tile
     const AttnShape s = doc_view(s_arg, docs.len[d]);
     BwdPlan pl;
-    plan_counts(s, pl);
+    plan_counts(s, pl, segc);
     const int gt = t % pl.n_gt;
     const int cf = first_chunk_with_more_far(s, pl.NC, gt * BNK);
     const float* pp = part + (size_t)docs.part0[d] * per_tile;
@@ -904,6 +922,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
 // the slots each of them gets in the partial-sum arrays
 struct PackPlan {
     std::vector<int> c0, len, part0, comp0;  // per document, in launch order
+    int segc;                                // segment length asked of every document's plan
     size_t off_lse2, off_part, off_comp, total;
 };
 
@@ -913,10 +932,13 @@ PackPlan make_pack_plan(const AttnShape& s, const int* cu, int ndocs) {
     for (int d = 0; d < ndocs; ++d)
         if (cu[d + 1] > cu[d]) order.push_back(d);
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+    long steps = 0;
+    for (int d : order) steps += gist_chunk_steps(doc_view(s, cu[d + 1] - cu[d]));
+    pp.segc = pick_segc(steps * s.Hkv);
     size_t nslot_part = 0, nslot_comp = 0;
     for (int d : order) {
         BwdPlan pl;
-        plan_counts(doc_view(s, cu[d + 1] - cu[d]), pl);
+        plan_counts(doc_view(s, cu[d + 1] - cu[d]), pl, pp.segc);
         pp.c0.push_back(cu[d]);
         pp.len.push_back(cu[d + 1] - cu[d]);
         pp.part0.push_back((int)nslot_part);
@@ -982,10 +1004,11 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     };
     auto counts = [&](int len) {
         BwdPlan pl;
-        plan_counts(doc_view(s, len), pl);
+        plan_counts(doc_view(s, len), pl, pp.segc);
         return pl;
     };
-    const BwdPlan none = {};
+    BwdPlan none = {};
+    none.segc = pp.segc;
     const bool gen = s.S != 0 || s.umode != 0;
     e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.n_gt * pl.nseg * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
@@ -1000,8 +1023,8 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     constexpr int per_tile = 2 * D * BNK;
     e = for_chunks([&](int len) { return (long)counts(len).n_gt * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
-                       gist_reduce_pack_kernel<<<dim3(nblk, (per_tile / 4 + NT - 1) / NT), NT, 0, st>>>(part, comp, s,
-                                                                                                       per_tile, t);
+                       gist_reduce_pack_kernel<<<dim3(nblk, (per_tile / 4 + NT - 1) / NT), NT, 0, st>>>(
+                           part, comp, s, per_tile, pp.segc, t);
                    });
     if (e != hipSuccess) return e;
     e = for_chunks([&](int len) { return (long)((len + BNK - 1) / BNK) * s.Hkv; },
