@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1040370710, "dkdv_gist": 2422387586, "dkdv_window": 1468223284, "dq": 1401724071,
-                 "decode": 4637305841, "decode_e4m3": 2288785746}
+TRAFFIC_BYTES = {"fwd": 1038732724, "dkdv_gist": 2430265226, "dkdv_window": 1472433143, "dq": 1401825066,
+                 "decode": 4637469208, "decode_e4m3": 2288767345}
 
 
 def pair_counts(L, r, W):
