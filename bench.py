@@ -216,12 +216,13 @@ def main():
     # chunk-wise prefill of the same 32K sequence through the compressed cache (4096-token chunks), own region
     C = 4096
     cache = u.KVCache(B, Hkv, min(L, W + C) + L // (r + 1) + 8, D, r)
-    def prefill_pass():
+    pout, plse = torch.empty_like(q), torch.empty(B, Hq, L, device=dev, dtype=torch.float32)
+    def prefill_pass():  # the chunks are row slices of q, k, v, out and lse: nothing is copied out
         cache.cur, cache.s, cache.t = 0, 0, -1
         for p0 in range(0, L, C):
             n = min(C, L - p0)
-            cache.update(k[:, :, p0:p0 + n].contiguous(), v[:, :, p0:p0 + n].contiguous(), max(0, p0 - W + 1))
-            u.prefill_chunk(q[:, :, p0:p0 + n].contiguous(), cache, r, W, p0)
+            cache.update(k[:, :, p0:p0 + n], v[:, :, p0:p0 + n], max(0, p0 - W + 1))
+            u.prefill_chunk(q[:, :, p0:p0 + n], cache, r, W, p0, out=pout[:, :, p0:p0 + n], lse=plse[:, :, p0:p0 + n])
     prefill_ms = None
     if not args.no_prefill:
         prefill_pass()
@@ -292,7 +293,7 @@ def main():
     if prefill_ms is not None:
         res["prefill"] = {"workload": f"{WORKLOAD} in {C}-token chunks through the compressed cache", "ms": prefill_ms,
                           "tflops": flops_fwd / prefill_ms / 1e9,
-                          "note": "includes the slicing copies of q/k/v chunks and the cache updates"}
+                          "note": "includes the cache updates; the chunks are row slices, nothing is copied out"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))

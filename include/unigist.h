@@ -299,6 +299,18 @@ unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc, const voi
                                         void* hip_stream);
 
 /*
+ * unigist_prefill_chunk_ex on a slice of larger tensors, so that the chunks of a prompt need not be copied out:
+ * q and out point at the chunk's first row of every head inside tensors [B, Hq, q_rows, D] (lse: [B, Hq, q_rows]),
+ * i.e. consecutive heads are q_rows >= C rows apart; only the C rows of each head are read and written.
+ * q_rows = C is unigist_prefill_chunk_ex.  (The new keys of unigist_cache_update can be such a slice already:
+ * pass the pointer to the chunk's first row and new_rows = the rows per head of the tensor it lies in.)
+ */
+unigist_status unigist_prefill_chunk_view(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                          int B, int Hq, int Hkv, int C, int q_rows, int D, int r, int W, int sinks,
+                                          int window_mode, int p0, int s, int cap, unigist_dtype dt,
+                                          void* hip_stream);
+
+/*
  * unigist_prefill_chunk_ex over a cache of E4M3 codes (as unigist_decode_e4m3 reads it: kc/vc uint8
  * [B, Hkv, cap, D], 16-byte aligned, the value of an element is its code times k_scale / v_scale of its kv head,
  * DEVICE arrays of Hkv positive floats).  q, out bf16.  The rows in use are first widened to bf16 in `workspace`

@@ -30,6 +30,7 @@ EXPORTS = [
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
     "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
+    "unigist_prefill_chunk_view",
 ]
 
 
@@ -112,6 +113,8 @@ def load():
     lib.unigist_cache_update_ragged.argtypes = [vp, vp, vp, vp, ip, vp, vp, vp, ip, vp, vp, vp, ip, vp] + [ip] * 6 + [vp]
     lib.unigist_prefill_chunk_ex.restype = ip
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
+    lib.unigist_prefill_chunk_view.restype = ip
+    lib.unigist_prefill_chunk_view.argtypes = [vp, vp, vp, vp, fp] + [ip] * 14 + [vp]
     lib.unigist_prefill_chunk_ragged.restype = ip
     lib.unigist_prefill_chunk_ragged.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [vp, vp, vp, ip, vp, ip, vp]
     lib.unigist_prefill_chunk_e4m3_workspace.restype = sz
@@ -153,6 +156,22 @@ def _dev(*ts):
             raise UnigistError("libunigist takes device tensors only (no CPU path)")
         if not t.is_contiguous():
             raise UnigistError("tensors must be contiguous [B,H,L,D]")
+
+
+def _head_rows(t: torch.Tensor, lead: int) -> int:
+    """Rows between consecutive heads of t [..., H, n, D] (lead dims in front of H), which may be a slice along the
+    row axis of a larger contiguous tensor; raises for any other layout."""
+    if not t.is_cuda:
+        raise UnigistError("libunigist takes device tensors only (no CPU path)")
+    n, D = t.shape[-2], t.shape[-1]
+    st = t.stride()
+    rows = st[-3] // D if D and st[-3] % D == 0 else -1
+    ok = st[-1] == 1 and st[-2] == D and rows >= n
+    for i in range(lead):  # the dims in front of H must be laid out densely over heads of `rows` rows
+        ok = ok and (t.shape[i] == 1 or st[i] == st[i + 1] * t.shape[i + 1])
+    if not ok:
+        raise UnigistError("tensor must be contiguous or a slice along the row axis of a contiguous [.., H, rows, D] tensor")
+    return rows
 
 
 def _stream() -> int:
@@ -286,6 +305,12 @@ def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new
                                 cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
     return load().unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                               vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
+
+
+def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0, s, cap, dt,
+                               stream=None) -> int:
+    return load().unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0,
+                                             s, cap, dt, stream)
 
 
 def unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, t, r, sinks) -> int:
@@ -555,16 +580,21 @@ class KVCache:
         return self.v[self.cur]
 
     def update(self, k_new=None, v_new=None, s_new=None):
-        """Append k_new/v_new ([B, Hkv, n, D], the next n positions) and move the window start to s_new."""
+        """Append k_new/v_new ([B, Hkv, n, D], the next n positions; may be slices along the row axis of larger
+        tensors) and move the window start to s_new."""
         n = 0 if k_new is None else k_new.shape[2]
+        rows = n
         if n:
-            _dev(k_new, v_new)
             if self.k[0].dtype == torch.uint8 and k_new.dtype != torch.uint8:
+                k_new, v_new = k_new.contiguous(), v_new.contiguous()
                 k_new, v_new = quantize_e4m3(k_new, self.k_scale), quantize_e4m3(v_new, self.v_scale)
+            rows = _head_rows(k_new, 1)
+            if _head_rows(v_new, 1) != rows or v_new.shape != k_new.shape:
+                raise UnigistError("k_new and v_new must have the same shape and layout")
         s_new = self.s if s_new is None else int(s_new)
         nxt = 1 - self.cur
         _check(unigist_cache_update_ex(self.k[self.cur].data_ptr(), self.v[self.cur].data_ptr(), self.s, self.t,
-                                       self.cap, k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
+                                       self.cap, k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, rows,
                                        self.k[nxt].data_ptr(), self.v[nxt].data_ptr(), s_new, self.cap,
                                        self.B, self.Hkv, self.D, self.r, self.sinks,
                                        UNIGIST_E4M3 if self.k[0].dtype == torch.uint8 else _dt(self.k[0]), _stream()),
@@ -661,11 +691,26 @@ class RaggedKVCache:
         return self.k[0], self.v[0], sl
 
 
-def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING, workspace=None):
+def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING, workspace=None, out=None, lse=None):
     """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse.
-    A cache of E4M3 codes goes through unigist_prefill_chunk_e4m3 (workspace: a uint8 tensor to reuse, optional)."""
-    _dev(q)
+    A cache of E4M3 codes goes through unigist_prefill_chunk_e4m3 (workspace: a uint8 tensor to reuse, optional).
+    q may be a slice along the row axis of a [B, Hq, L, D] tensor if out and lse are given as the same slice of
+    tensors [B, Hq, L, D] and [B, Hq, L] (unigist_prefill_chunk_view: no copies of the chunk)."""
     B, Hq, C, D = q.shape
+    if out is not None or lse is not None or not q.is_contiguous():
+        if out is None or lse is None or cache.kc.dtype == torch.uint8:
+            raise UnigistError("a sliced q needs out= and lse= slices of the same layout (bf16 caches only)")
+        rows = _head_rows(q, 1)
+        lrows = lse.stride(1) if lse.dim() == 3 and lse.stride(2) == 1 and lse.is_cuda else -1
+        if _head_rows(out, 1) != rows or lrows != rows or out.shape != q.shape or lse.shape != (B, Hq, C) or \
+                (B > 1 and lse.stride(0) != Hq * rows) or out.dtype != q.dtype or lse.dtype != torch.float32:
+            raise UnigistError("q, out and lse must be the same row slice of tensors with equal rows per head")
+        _check(unigist_prefill_chunk_view(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(),
+                                          lse.data_ptr(), B, Hq, cache.Hkv, C, rows, D, int(r), int(W), cache.sinks,
+                                          int(window_mode), int(p0), cache.s, cache.cap, _dt(q), _stream()),
+               "unigist_prefill_chunk_view")
+        return out, lse
+    _dev(q)
     out = torch.empty_like(q)
     lse = torch.empty(B, Hq, C, device=q.device, dtype=torch.float32)
     if cache.kc.dtype == torch.uint8:

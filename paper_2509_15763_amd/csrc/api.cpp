@@ -290,7 +290,16 @@ extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc
                                                    float* lse, int B, int Hq, int Hkv, int C, int D, int r, int W,
                                                    int sinks, int window_mode, int p0, int s, int cap,
                                                    unigist_dtype dt, void* hip_stream) {
-    if (C < 1 || p0 < 0 || s < 0 || cap < 1) return UNIGIST_EINVAL;
+    return unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, C, D, r, W, sinks, window_mode, p0, s, cap, dt,
+                                      hip_stream);
+}
+
+extern "C" unigist_status unigist_prefill_chunk_view(const void* q, const void* kc, const void* vc, void* out,
+                                                     float* lse, int B, int Hq, int Hkv, int C, int q_rows, int D, int r,
+                                                     int W, int sinks, int window_mode, int p0, int s, int cap,
+                                                     unigist_dtype dt, void* hip_stream) {
+    if (C < 1 || p0 < 0 || s < 0 || cap < 1 || q_rows < C) return UNIGIST_EINVAL;
+    if (q_rows > kMaxL) return UNIGIST_EUNSUPPORTED;
     const long long Ltot = (long long)p0 + C;
     if (Ltot > kMaxL) return UNIGIST_EUNSUPPORTED;
     unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, dt, sinks, window_mode);
@@ -303,7 +312,7 @@ extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc
     const int rows = unigist_cache_rows_ex(s, (int)Ltot - 1, r, sinks);
     if (rows < 0 || rows > cap) return UNIGIST_EINVAL;
     sh.Lq = C;
-    sh.qhs = C;
+    sh.qhs = q_rows;
     sh.qpos0 = p0;
     sh.kv_rows = cap;
     sh.s0 = s;

@@ -191,6 +191,14 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk(*p.values()) == 1
     p.update(cap=1024, q=None)
     assert u.unigist_prefill_chunk(*p.values()) == 1
+    # prefill on a row slice: heads q_rows >= C rows apart
+    pv = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, q_rows=63, D=128, r=4, W=100, sinks=0,
+              window_mode=0, p0=500, s=401, cap=1024, dt=0)
+    assert u.unigist_prefill_chunk_view(*pv.values()) == 1
+    pv.update(q_rows=1 << 24)
+    assert u.unigist_prefill_chunk_view(*pv.values()) == 2
+    pv.update(q_rows=4096, s=402)
+    assert u.unigist_prefill_chunk_view(*pv.values()) == 1
     # prefill over a cache of codes: the same checks plus scales, alignment and workspace
     e = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128,
              r=4, W=100, sinks=0, window_mode=0, p0=500, s=401, cap=1024, ws=FAKE, ws_bytes=1 << 30)

@@ -344,3 +344,28 @@ def test_ragged_prefill_with_equal_states_is_the_plain_call_and_bad_states_are_r
                                         rows.data_ptr(), 0, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert st == 0 and rows.cpu().tolist() == [-1, 0, -1]
+
+
+def test_prefill_on_row_slices_equals_prefill_on_copies():
+    # chunks passed as slices along the row axis of the full tensors (no copies): same bits as with contiguous
+    # chunks, and nothing outside the chunk's rows is written
+    B, Hq, Hkv, D, r, W, C, L = 2, 4, 2, 128, 4, 60, 300, 1000
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=29)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    a, b = u.KVCache(B, Hkv, L, D, r), u.KVCache(B, Hkv, L, D, r)
+    out = torch.full((B, Hq, L, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, L), 7.0, device="cuda")
+    for p0 in range(0, L, C):
+        n = min(C, L - p0)
+        s = max(0, p0 - W + 1)
+        a.update(kd[:, :, p0:p0 + n].contiguous(), vd[:, :, p0:p0 + n].contiguous(), s)
+        b.update(kd[:, :, p0:p0 + n], vd[:, :, p0:p0 + n], s)
+        assert torch.equal(a.kc[:, :, :a.rows], b.kc[:, :, :b.rows]) and torch.equal(a.vc[:, :, :a.rows], b.vc[:, :, :b.rows])
+        o, l = u.prefill_chunk(qd[:, :, p0:p0 + n].contiguous(), a, r, W, p0)
+        u.prefill_chunk(qd[:, :, p0:p0 + n], b, r, W, p0, out=out[:, :, p0:p0 + n], lse=lse[:, :, p0:p0 + n])
+        assert torch.equal(out[:, :, p0:p0 + n], o) and torch.equal(lse[:, :, p0:p0 + n], l)
+        assert bool((out[:, :, p0 + n:] == 7.0).all()) and bool((lse[:, :, p0 + n:] == 7.0).all())
+    with pytest.raises(u.UnigistError):
+        u.prefill_chunk(qd[:, :, 0:C], b, r, W, 0)                                  # a slice without out= / lse=
+    with pytest.raises(u.UnigistError):
+        u.prefill_chunk(qd[:, :, 0:C], b, r, W, 0, out=out[:, :, 0:C].contiguous(), lse=lse[:, :, 0:C])
