@@ -138,36 +138,40 @@ def test_documents_do_not_see_each_other():
         assert not torch.equal(x[:, cu[1]:cu[2]], y[:, cu[1]:cu[2]])
 
 
-def test_full_length_pack_sampled_rows_and_columns():
-    # the 32K training shape as a pack of five documents (each padded to a multiple of r as in App. B):
+@pytest.mark.parametrize("Wm,sinks,units", [(None, 0, False), (25, 128, True)], ids=["sliding", "sinks_units"])
+def test_full_length_pack_sampled_rows_and_columns(Wm, sinks, units):
+    # the 32K training shape as a pack of five documents (each padded to a multiple of r as in App. B), with the
+    # sliding window of the benchmark and in the paper's layout (128 sinks, a window of 25 units):
     # sampled rows and key columns of two documents against the oracle on those documents alone
     w = synth.WORKLOADS["cfg2_llama8b_32k"]
     Hq, Hkv, T, D, r, W = w["Hq"], w["Hkv"], w["L"], w["D"], w["r"], w["W"]
+    W = W if Wm is None else Wm
+    mask = dict(sinks=sinks, units=units) if sinks or units else {}
     lens = [8192, 4100, 12288, 1020, 7168]
     assert sum(lens) == T
     cu = [0] + np.cumsum(lens).tolist()
     q, k, v, dout = packed_inputs(Hq, Hkv, T, D, torch.bfloat16, seed=34)
-    out, lse, dq, dk, dv = run_gpu(q, k, v, dout, r, W, cu)
+    out, lse, dq, dk, dv = run_gpu(q, k, v, dout, r, W, cu, sinks=sinks, units=units)
     rng = np.random.default_rng(1)
     G = Hq // Hkv
     for d in (1, 2):
         a, b = cu[d], cu[d + 1]
         n = b - a
-        rows = np.unique(np.concatenate([[0, 1, 4, W - 1, W, W + 1, n - 1], rng.integers(0, n, 24)]))
+        rows = np.unique(np.concatenate([[0, 1, 4, W - 1, W, W + 1, sinks, sinks + 1, n - 1], rng.integers(0, n, 24)]))
         cols = np.unique(np.concatenate([[0, 4, 9, n - 1, n - 2], rng.integers(0, n, 12)]))
         for h in (3, 30):
             hk = h // G
             qn, kn, vn, don = (to_np(t[h_, a:b]) for t, h_ in ((q, h), (k, hk), (v, hk), (dout, h)))
-            o, l = oracle.attn_fwd_rows(qn, kn, vn, rows, r, W)
+            o, l = oracle.attn_fwd_rows(qn, kn, vn, rows, r, W, **mask)
             assert (np.abs(to_np(out[h, a:b])[rows] - o) <= out_tolerance(o)).all(), (d, h)
             assert max_abs(to_np(lse[h, a:b])[rows], l) <= 1e-2
-            assert rel_l2(to_np(dq[h, a:b])[rows], oracle.attn_dq_rows(qn, kn, vn, don, rows, r, W)) <= 2e-2
+            assert rel_l2(to_np(dq[h, a:b])[rows], oracle.attn_dq_rows(qn, kn, vn, don, rows, r, W, **mask)) <= 2e-2
         hk = 6
         gk = np.zeros((len(cols), D))
         gv = np.zeros((len(cols), D))
         for g in range(G):
             x, y = oracle.attn_dkdv_cols(to_np(q[hk * G + g, a:b]), to_np(k[hk, a:b]), to_np(v[hk, a:b]),
-                                         to_np(dout[hk * G + g, a:b]), cols, r, W)
+                                         to_np(dout[hk * G + g, a:b]), cols, r, W, **mask)
             gk += x
             gv += y
         assert rel_l2(to_np(dk[hk, a:b])[cols], gk) <= 2e-2
