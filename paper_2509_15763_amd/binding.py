@@ -31,6 +31,7 @@ EXPORTS = [
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
     "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
     "unigist_prefill_chunk_view",
+    "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
 ]
 
 
@@ -113,6 +114,13 @@ def load():
     lib.unigist_cache_update_ragged.argtypes = [vp, vp, vp, vp, ip, vp, vp, vp, ip, vp, vp, vp, ip, vp] + [ip] * 6 + [vp]
     lib.unigist_prefill_chunk_ex.restype = ip
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
+    lib.unigist_cache_ring_rows.restype = ip
+    lib.unigist_cache_ring_rows.argtypes = [ip] * 4
+    for fn in (lib.unigist_cache_to_ring, lib.unigist_cache_from_ring):
+        fn.restype = ip
+        fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 7 + [vp]
+    lib.unigist_cache_ring_append.restype = ip
+    lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 7 + [vp]
     lib.unigist_prefill_chunk_view.restype = ip
     lib.unigist_prefill_chunk_view.argtypes = [vp, vp, vp, vp, fp] + [ip] * 14 + [vp]
     lib.unigist_prefill_chunk_ragged.restype = ip
@@ -305,6 +313,28 @@ def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new
                                 cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream=None) -> int:
     return load().unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new, n_new, new_rows, kc_out,
                                               vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
+
+
+def unigist_cache_ring_rows(t, r, W, sinks=0) -> int:
+    return load().unigist_cache_ring_rows(t, r, W, sinks)
+
+
+def unigist_cache_to_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
+                          stream=None) -> int:
+    return load().unigist_cache_to_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W,
+                                        sinks, dt, stream)
+
+
+def unigist_cache_from_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
+                            stream=None) -> int:
+    return load().unigist_cache_from_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W,
+                                          sinks, dt, stream)
+
+
+def unigist_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D, r, W, sinks, dt,
+                              stream=None) -> int:
+    return load().unigist_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D, r, W,
+                                            sinks, dt, stream)
 
 
 def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0, s, cap, dt,
@@ -689,6 +719,56 @@ class RaggedKVCache:
                 self.update(b)
         sl = torch.tensor([self.rows(b) for b in range(self.B)], dtype=torch.int32).to(self.k[0].device)
         return self.k[0], self.v[0], sl
+
+
+class RingKVCache:
+    """The cache of a batch in the ring layout for token-by-token decoding (sliding window of W positions): appending
+    a token writes one or two rows per (sequence, kv head) instead of gathering the cache.  Built from a
+    RaggedKVCache whose sequences have their window start at max(0, t - W + 1); `t` (int32 [B] on the GPU) is each
+    sequence's last position and `rows` the rows in use -- the seqlens of decode.  Bookkeeping only."""
+
+    def __init__(self, ragged: "RaggedKVCache", W):
+        kc, vc = ragged.current()
+        self.B, self.Hkv, self.cap, self.D, self.r, self.sinks, self.W = (ragged.B, ragged.Hkv, ragged.cap, ragged.D,
+                                                                         ragged.r, ragged.sinks, int(W))
+        dev = kc.device
+        self.dt = UNIGIST_E4M3 if kc.dtype == torch.uint8 else _dt(kc)
+        self.kc, self.vc = torch.empty_like(kc), torch.empty_like(vc)
+        self.t = torch.tensor(ragged.t, dtype=torch.int32).to(dev)
+        s = torch.tensor(ragged.s, dtype=torch.int32).to(dev)
+        self.rows = torch.empty(self.B, dtype=torch.int32, device=dev)
+        _check(unigist_cache_to_ring(kc.data_ptr(), vc.data_ptr(), s.data_ptr(), self.t.data_ptr(), self.cap,
+                                     self.kc.data_ptr(), self.vc.data_ptr(), self.cap, self.rows.data_ptr(), self.B,
+                                     self.Hkv, self.D, self.r, self.W, self.sinks, self.dt, _stream()),
+               "unigist_cache_to_ring")
+
+    def append(self, k_new, v_new, active=None):
+        """k_new/v_new [B, Hkv, 1, D]: the next position of every sequence (of those with active[b] = 1, int32 [B] on
+        the GPU).  -> rows in use per sequence (int32 [B] on the GPU, -1 for a sequence that does not fit)."""
+        _dev(k_new, v_new, active)
+        if active is None:
+            active = torch.ones(self.B, dtype=torch.int32, device=self.kc.device)
+        _check(unigist_cache_ring_append(self.kc.data_ptr(), self.vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                         k_new.shape[2], self.t.data_ptr(), active.data_ptr(), self.cap,
+                                         self.rows.data_ptr(), self.B, self.Hkv, self.D, self.r, self.W, self.sinks,
+                                         self.dt, _stream()),
+               "unigist_cache_ring_append")
+        self.t = self.t + active  # a new tensor: the kernel above still reads the old one
+        return self.rows
+
+    def to_ragged(self, ragged: "RaggedKVCache"):
+        """Back to the layout prefill wants, into `ragged`'s buffers: every sequence in state (max(0, t - W + 1), t)."""
+        t = self.t.cpu().tolist()
+        s = [max(0, x - self.W + 1) for x in t]
+        dev = self.kc.device
+        sd = torch.tensor(s, dtype=torch.int32).to(dev)
+        rows = torch.empty(self.B, dtype=torch.int32, device=dev)
+        _check(unigist_cache_from_ring(self.kc.data_ptr(), self.vc.data_ptr(), sd.data_ptr(), self.t.data_ptr(), self.cap,
+                                       ragged.k[0].data_ptr(), ragged.v[0].data_ptr(), ragged.cap, rows.data_ptr(),
+                                       self.B, self.Hkv, self.D, self.r, self.W, self.sinks, self.dt, _stream()),
+               "unigist_cache_from_ring")
+        ragged.cur, ragged.s, ragged.t = [0] * self.B, s, t
+        return rows
 
 
 def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLIDING, workspace=None, out=None, lse=None):
