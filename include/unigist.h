@@ -272,31 +272,38 @@ unigist_status unigist_cache_update_ragged(const void* kc_in, const void* vc_in,
 
 /*
  * Token-by-token decoding without re-gathering the cache (Sec. 4.3: at every step one token enters the window
- * and one leaves; unigist_decode attends to all rows of a slab in whatever order they lie).  Ring layout of a
- * slab, sliding window of W positions, `sinks` sink tokens: rows [0, W) hold the window, position p in row p % W;
- * rows [W, ..) hold the sinks and gists that have left the window, in order of position.  In ring state t (last
- * position held) a slab has unigist_cache_ring_rows(t, r, W, sinks) rows in use -- the seqlens of unigist_decode
- * for the query at position t.
- *   unigist_cache_to_ring / unigist_cache_from_ring convert between the state (s[b], t[b]) of the layout above and
- *     ring state t[b] (s, t: DEVICE arrays of B ints; s[b] must be the first position of the window of a query at
- *     t[b], max(0, t[b] - W + 1), so that both sides hold the same positions; out buffers must not overlap the
- *     inputs).  Use to_ring after the prompt's last prefill chunk and from_ring before prefilling again.
+ * and tokens leave it; unigist_decode attends to all rows of a slab in whatever order they lie).  In ring state t
+ * (the last position held) a slab holds exactly the positions visible to the query at t, in
+ * unigist_cache_ring_rows(t, r, W, sinks, window_mode) rows -- the seqlens of unigist_decode for that query.
+ * Layout of a slab:
+ *   SLIDING: rows [0, W) hold the window, position p in row p % W; rows [W, ..) hold the sinks and gists that
+ *     have left the window, in order of position.
+ *   UNITS (u = r + 1 positions per unit, after `sinks` sinks; kc = the unit of position t): while kc <= W the
+ *     positions 0 .. t in order; afterwards [sinks | W complete units, unit k in slot k % W, u rows each | the
+ *     gists of the units 0 .. kc-W-1 | the positions of unit kc present so far].
+ *   unigist_cache_to_ring / unigist_cache_from_ring convert between the ordered layout above in state (s[b], t[b])
+ *     and ring state t[b] (s, t: DEVICE arrays of B ints; s[b] must be the first position of the window of the
+ *     query at t[b], so that both sides hold the same positions; out buffers must not overlap the inputs).  Use
+ *     to_ring after the prompt's last prefill chunk and from_ring before prefilling again.
  *   unigist_cache_ring_append, in place: every sequence with n_new[b] = 1 appends row 0 of its slab of k_new/v_new
- *     ([B, Hkv, new_rows, D]) as position t_old[b] + 1 -- one row written, two when the position leaving the
- *     window is a sink or a gist (it moves to the far rows first); n_new[b] = 0 leaves the sequence alone.
+ *     ([B, Hkv, new_rows, D]) as position t_old[b] + 1.  SLIDING: one row written, two when the position leaving
+ *     the window is a sink or a gist (it moves to the far rows first).  UNITS: one row written; when a unit starts,
+ *     the r + 1 rows of the unit just completed first move into the slot of the unit that leaves (whose gist is
+ *     kept).  n_new[b] = 0 leaves the sequence alone.
  * rows_out (DEVICE, B ints, out): rows in use afterwards, or -1 for a sequence whose state is impossible or does
  * not fit (nothing is written for it).  Any dtype (rows are copied bit for bit).
  */
-int unigist_cache_ring_rows(int t, int r, int W, int sinks);
+int unigist_cache_ring_rows(int t, int r, int W, int sinks, int window_mode);
 unigist_status unigist_cache_to_ring(const void* kc_in, const void* vc_in, const int* s, const int* t, int cap_in,
                                      void* kc_out, void* vc_out, int cap_out, int* rows_out, int B, int Hkv, int D,
-                                     int r, int W, int sinks, unigist_dtype dt, void* hip_stream);
+                                     int r, int W, int sinks, int window_mode, unigist_dtype dt, void* hip_stream);
 unigist_status unigist_cache_from_ring(const void* kc_in, const void* vc_in, const int* s, const int* t, int cap_in,
                                        void* kc_out, void* vc_out, int cap_out, int* rows_out, int B, int Hkv, int D,
-                                       int r, int W, int sinks, unigist_dtype dt, void* hip_stream);
+                                       int r, int W, int sinks, int window_mode, unigist_dtype dt, void* hip_stream);
 unigist_status unigist_cache_ring_append(void* kc, void* vc, const void* k_new, const void* v_new, int new_rows,
                                          const int* t_old, const int* n_new, int cap, int* rows_out, int B, int Hkv,
-                                         int D, int r, int W, int sinks, unigist_dtype dt, void* hip_stream);
+                                         int D, int r, int W, int sinks, int window_mode, unigist_dtype dt,
+                                         void* hip_stream);
 
 /*
  * Chunk-wise prefill (Sec. 4.3: the prompt is encoded chunk by chunk with the training kernel, dropping

@@ -115,12 +115,12 @@ def load():
     lib.unigist_prefill_chunk_ex.restype = ip
     lib.unigist_prefill_chunk_ex.argtypes = [vp, vp, vp, vp, fp] + [ip] * 13 + [vp]
     lib.unigist_cache_ring_rows.restype = ip
-    lib.unigist_cache_ring_rows.argtypes = [ip] * 4
+    lib.unigist_cache_ring_rows.argtypes = [ip] * 5
     for fn in (lib.unigist_cache_to_ring, lib.unigist_cache_from_ring):
         fn.restype = ip
-        fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 7 + [vp]
+        fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
     lib.unigist_cache_ring_append.restype = ip
-    lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 7 + [vp]
+    lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
     lib.unigist_prefill_chunk_view.restype = ip
     lib.unigist_prefill_chunk_view.argtypes = [vp, vp, vp, vp, fp] + [ip] * 14 + [vp]
     lib.unigist_prefill_chunk_ragged.restype = ip
@@ -315,26 +315,26 @@ def unigist_cache_update_ragged(kc_in, vc_in, s_old, t_old, cap_in, k_new, v_new
                                               vc_out, s_new, cap_out, rows_out, B, Hkv, D, r, sinks, dt, stream)
 
 
-def unigist_cache_ring_rows(t, r, W, sinks=0) -> int:
-    return load().unigist_cache_ring_rows(t, r, W, sinks)
+def unigist_cache_ring_rows(t, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:
+    return load().unigist_cache_ring_rows(t, r, W, sinks, window_mode)
 
 
-def unigist_cache_to_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
-                          stream=None) -> int:
+def unigist_cache_to_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks,
+                          window_mode, dt, stream=None) -> int:
     return load().unigist_cache_to_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W,
-                                        sinks, dt, stream)
+                                        sinks, window_mode, dt, stream)
 
 
-def unigist_cache_from_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
-                            stream=None) -> int:
+def unigist_cache_from_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks,
+                            window_mode, dt, stream=None) -> int:
     return load().unigist_cache_from_ring(kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W,
-                                          sinks, dt, stream)
+                                          sinks, window_mode, dt, stream)
 
 
-def unigist_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D, r, W, sinks, dt,
-                              stream=None) -> int:
+def unigist_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D, r, W, sinks,
+                              window_mode, dt, stream=None) -> int:
     return load().unigist_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D, r, W,
-                                            sinks, dt, stream)
+                                            sinks, window_mode, dt, stream)
 
 
 def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0, s, cap, dt,
@@ -722,15 +722,16 @@ class RaggedKVCache:
 
 
 class RingKVCache:
-    """The cache of a batch in the ring layout for token-by-token decoding (sliding window of W positions): appending
-    a token writes one or two rows per (sequence, kv head) instead of gathering the cache.  Built from a
-    RaggedKVCache whose sequences have their window start at max(0, t - W + 1); `t` (int32 [B] on the GPU) is each
+    """The cache of a batch in the ring layout for token-by-token decoding: appending a token writes a row or two
+    per (sequence, kv head) instead of gathering the cache.  Built from a RaggedKVCache whose sequences have their
+    window start at the first position of the window of their last position t; `t` (int32 [B] on the GPU) is each
     sequence's last position and `rows` the rows in use -- the seqlens of decode.  Bookkeeping only."""
 
-    def __init__(self, ragged: "RaggedKVCache", W):
+    def __init__(self, ragged: "RaggedKVCache", W, window_mode=UNIGIST_WINDOW_SLIDING):
         kc, vc = ragged.current()
         self.B, self.Hkv, self.cap, self.D, self.r, self.sinks, self.W = (ragged.B, ragged.Hkv, ragged.cap, ragged.D,
                                                                          ragged.r, ragged.sinks, int(W))
+        self.mode = int(window_mode)
         dev = kc.device
         self.dt = UNIGIST_E4M3 if kc.dtype == torch.uint8 else _dt(kc)
         self.kc, self.vc = torch.empty_like(kc), torch.empty_like(vc)
@@ -739,7 +740,7 @@ class RingKVCache:
         self.rows = torch.empty(self.B, dtype=torch.int32, device=dev)
         _check(unigist_cache_to_ring(kc.data_ptr(), vc.data_ptr(), s.data_ptr(), self.t.data_ptr(), self.cap,
                                      self.kc.data_ptr(), self.vc.data_ptr(), self.cap, self.rows.data_ptr(), self.B,
-                                     self.Hkv, self.D, self.r, self.W, self.sinks, self.dt, _stream()),
+                                     self.Hkv, self.D, self.r, self.W, self.sinks, self.mode, self.dt, _stream()),
                "unigist_cache_to_ring")
 
     def append(self, k_new, v_new, active=None):
@@ -751,21 +752,26 @@ class RingKVCache:
         _check(unigist_cache_ring_append(self.kc.data_ptr(), self.vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
                                          k_new.shape[2], self.t.data_ptr(), active.data_ptr(), self.cap,
                                          self.rows.data_ptr(), self.B, self.Hkv, self.D, self.r, self.W, self.sinks,
-                                         self.dt, _stream()),
+                                         self.mode, self.dt, _stream()),
                "unigist_cache_ring_append")
         self.t = self.t + active  # a new tensor: the kernel above still reads the old one
         return self.rows
 
     def to_ragged(self, ragged: "RaggedKVCache"):
-        """Back to the layout prefill wants, into `ragged`'s buffers: every sequence in state (max(0, t - W + 1), t)."""
+        """Back to the layout prefill wants, into `ragged`'s buffers: every sequence in state (first position of the
+        window of t, t)."""
         t = self.t.cpu().tolist()
-        s = [max(0, x - self.W + 1) for x in t]
+        u = self.r + 1
+        if self.mode == UNIGIST_WINDOW_SLIDING:
+            s = [max(0, x - self.W + 1) for x in t]
+        else:
+            s = [x if x < self.sinks else self.sinks + max(0, (x - self.sinks) // u - self.W) * u for x in t]
         dev = self.kc.device
         sd = torch.tensor(s, dtype=torch.int32).to(dev)
         rows = torch.empty(self.B, dtype=torch.int32, device=dev)
         _check(unigist_cache_from_ring(self.kc.data_ptr(), self.vc.data_ptr(), sd.data_ptr(), self.t.data_ptr(), self.cap,
                                        ragged.k[0].data_ptr(), ragged.v[0].data_ptr(), ragged.cap, rows.data_ptr(),
-                                       self.B, self.Hkv, self.D, self.r, self.W, self.sinks, self.dt, _stream()),
+                                       self.B, self.Hkv, self.D, self.r, self.W, self.sinks, self.mode, self.dt, _stream()),
                "unigist_cache_from_ring")
         ragged.cur, ragged.s, ragged.t = [0] * self.B, s, t
         return rows

@@ -281,8 +281,9 @@ extern "C" unigist_status unigist_cache_update_ragged(const void* kc_in, const v
 
 // ---------------------------------------------------------------- ring layout for token-by-token decoding
 namespace {
-unigist_status check_ring(int B, int Hkv, int D, int r, int W, int sinks, unigist_dtype dt) {
+unigist_status check_ring(int B, int Hkv, int D, int r, int W, int sinks, int window_mode, unigist_dtype dt) {
     if (B < 1 || Hkv < 1 || D < 1 || r < 1 || W < 1 || sinks < 0) return UNIGIST_EINVAL;
+    if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
     if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
     if (B > 65535 || Hkv > 65535) return UNIGIST_EUNSUPPORTED;
@@ -291,53 +292,62 @@ unigist_status check_ring(int B, int Hkv, int D, int r, int W, int sinks, unigis
 int dt_bytes(unigist_dtype dt) { return dt == UNIGIST_E4M3 ? 1 : dt == UNIGIST_BF16 ? 2 : 4; }
 }  // namespace
 
-extern "C" int unigist_cache_ring_rows(int t, int r, int W, int sinks) {
+extern "C" int unigist_cache_ring_rows(int t, int r, int W, int sinks, int window_mode) {
     if (t < -1 || r < 1 || W < 1 || sinks < 0) return -1;
-    const long long left = (long long)t - W + 1 > 0 ? (long long)t - W + 1 : 0;  // positions that have left the window
-    const long long far = left <= sinks ? left : sinks + (left - sinks) / ((long long)r + 1);
-    return (int)((t + 1 < W ? t + 1 : W) + far);
+    if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return -1;
+    if (window_mode == UNIGIST_WINDOW_SLIDING) {
+        const long long left = (long long)t - W + 1 > 0 ? (long long)t - W + 1 : 0;  // positions that have left the window
+        const long long far = left <= sinks ? left : sinks + (left - sinks) / ((long long)r + 1);
+        return (int)((t + 1 < W ? t + 1 : W) + far);
+    }
+    if (t < sinks) return t + 1;
+    const long long u = (long long)r + 1, kc = (t - sinks) / u, c = (t - sinks) % u + 1;
+    // the sinks, the gists of the units left of the window, W complete units, the positions of the current unit
+    return kc <= W ? t + 1 : (int)(sinks + (kc - W) + W * u + c);
 }
 
 static unigist_status ring_convert(bool to_ring, const void* kc_in, const void* vc_in, const int* s, const int* t,
                                    int cap_in, void* kc_out, void* vc_out, int cap_out, int* rows_out, int B, int Hkv,
-                                   int D, int r, int W, int sinks, unigist_dtype dt, void* hip_stream) {
-    unigist_status st = check_ring(B, Hkv, D, r, W, sinks, dt);
+                                   int D, int r, int W, int sinks, int window_mode, unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_ring(B, Hkv, D, r, W, sinks, window_mode, dt);
     if (st != UNIGIST_OK) return st;
     if (cap_in < 1 || cap_out < 1) return UNIGIST_EINVAL;
     if (!kc_in || !vc_in || !kc_out || !vc_out || !s || !t || !rows_out) return UNIGIST_EINVAL;
     hipError_t e = launch_cache_ring_convert(to_ring, kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv,
                                              D, r >= kMaxL ? kMaxL + 1 : r + 1, sinks > kMaxL ? kMaxL : sinks,
-                                             W > kMaxL ? kMaxL : W, dt_bytes(dt), kMaxL, (hipStream_t)hip_stream);
+                                             W > kMaxL ? kMaxL : W, window_mode == UNIGIST_WINDOW_UNITS, dt_bytes(dt),
+                                             kMaxL, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
 extern "C" unigist_status unigist_cache_to_ring(const void* kc_in, const void* vc_in, const int* s, const int* t,
                                                 int cap_in, void* kc_out, void* vc_out, int cap_out, int* rows_out,
-                                                int B, int Hkv, int D, int r, int W, int sinks, unigist_dtype dt,
-                                                void* hip_stream) {
-    return ring_convert(true, kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
-                        hip_stream);
+                                                int B, int Hkv, int D, int r, int W, int sinks, int window_mode,
+                                                unigist_dtype dt, void* hip_stream) {
+    return ring_convert(true, kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks,
+                        window_mode, dt, hip_stream);
 }
 
 extern "C" unigist_status unigist_cache_from_ring(const void* kc_in, const void* vc_in, const int* s, const int* t,
                                                   int cap_in, void* kc_out, void* vc_out, int cap_out, int* rows_out,
-                                                  int B, int Hkv, int D, int r, int W, int sinks, unigist_dtype dt,
-                                                  void* hip_stream) {
-    return ring_convert(false, kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks, dt,
-                        hip_stream);
+                                                  int B, int Hkv, int D, int r, int W, int sinks, int window_mode,
+                                                  unigist_dtype dt, void* hip_stream) {
+    return ring_convert(false, kc_in, vc_in, s, t, cap_in, kc_out, vc_out, cap_out, rows_out, B, Hkv, D, r, W, sinks,
+                        window_mode, dt, hip_stream);
 }
 
 extern "C" unigist_status unigist_cache_ring_append(void* kc, void* vc, const void* k_new, const void* v_new,
                                                     int new_rows, const int* t_old, const int* n_new, int cap,
                                                     int* rows_out, int B, int Hkv, int D, int r, int W, int sinks,
-                                                    unigist_dtype dt, void* hip_stream) {
-    unigist_status st = check_ring(B, Hkv, D, r, W, sinks, dt);
+                                                    int window_mode, unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_ring(B, Hkv, D, r, W, sinks, window_mode, dt);
     if (st != UNIGIST_OK) return st;
     if (cap < 1 || new_rows < 1) return UNIGIST_EINVAL;
     if (!kc || !vc || !k_new || !v_new || !t_old || !n_new || !rows_out) return UNIGIST_EINVAL;
     hipError_t e = launch_cache_ring_append(kc, vc, k_new, v_new, new_rows, t_old, n_new, cap, rows_out, B, Hkv, D,
                                             r >= kMaxL ? kMaxL + 1 : r + 1, sinks > kMaxL ? kMaxL : sinks,
-                                            W > kMaxL ? kMaxL : W, dt_bytes(dt), kMaxL, (hipStream_t)hip_stream);
+                                            W > kMaxL ? kMaxL : W, window_mode == UNIGIST_WINDOW_UNITS, dt_bytes(dt), kMaxL,
+                                            (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 

@@ -93,56 +93,98 @@ __global__ __launch_bounds__(256) void cache_update_ragged_kernel(
     *(u32x4*)(vc_out + o) = *(const u32x4*)(vs + off + ch * 16);
 }
 
-// ---- ring layout for token-by-token decoding with the sliding window (sinks allowed).  Decode attends to every
-// row of a sequence's slab whatever their order, so a new token can take the row of the token that leaves the
-// window at the same moment: rows [0, W) hold the window, position p in row p % W; rows [W, W + nf) hold the
-// always-visible positions (sinks, gists) that have left the window, in order of position.  Appending a token is
-// then one row written (two when the position leaving the window is a sink or a gist, which first moves to the
-// far region) instead of a gather of the whole cache.
-__device__ __forceinline__ int ring_far(const AttnShape& lay, int W, int t) { return count_always(lay, t - W + 1 > 0 ? t - W + 1 : 0); }
-__device__ __forceinline__ int ring_rows(const AttnShape& lay, int W, int t) { return (t + 1 < W ? t + 1 : W) + ring_far(lay, W, t); }
+// ---- ring layouts for token-by-token decoding.  Decode attends to every row of a sequence's slab whatever their
+// order, so a new token can take the place of what leaves the window instead of the whole cache being gathered
+// again.  In ring state t a slab holds exactly the positions visible to the query at t.
+//
+// Sliding window of W positions: rows [0, W) hold the window, position p in row p % W; rows [W, W + nf) hold the
+// always-visible positions (sinks, gists) that have left the window, in order.  The new token takes the row of the
+// position that leaves the window at that moment (which first moves to the far rows if it is a sink or a gist).
+//
+// Unit-aligned window (the unit of the query plus the W previous units; u = r + 1 positions per unit, units start
+// after the S sinks): a whole unit leaves when a new one starts, while the new one fills one token at a time, so
+// the unit being filled is kept apart.  With kc the unit of position t and c its positions present:
+//   kc <= W: nothing has left the window yet, the slab holds the positions 0 .. t in order;
+//   kc >  W: [S sinks | W complete units, unit k in slot k % W | the gists of the units 0 .. kc-W-1 | c rows of unit kc].
+// When unit kc+1 starts, the complete unit kc moves into the slot of the unit that leaves (whose gist is saved into
+// the far rows first): u rows moved every u tokens.
+struct RingLay {
+    AttnShape lay;  // sink count, gist period, window mode
+    int W;
+};
+__device__ __forceinline__ int ring_rows(const RingLay& g, int t) {
+    const AttnShape& l = g.lay;
+    if (t < 0) return 0;
+    if (!l.umode) return (t + 1 < g.W ? t + 1 : g.W) + count_always(l, t - g.W + 1 > 0 ? t - g.W + 1 : 0);
+    if (t < l.S) return t + 1;
+    const int kc = (t - l.S) / l.rp1, c = (t - l.S) % l.rp1 + 1;
+    return kc <= g.W ? t + 1 : l.S + g.W * l.rp1 + (kc - g.W) + c;
+}
+// row of the (visible) position pos in ring state t
+__device__ __forceinline__ int ring_row_of_pos(const RingLay& g, int t, int pos) {
+    const AttnShape& l = g.lay;
+    if (!l.umode) return pos > t - g.W ? pos % g.W : g.W + count_always(l, pos);
+    if (t < l.S || pos < l.S) return pos;
+    const int u = l.rp1, kc = (t - l.S) / u, k = (pos - l.S) / u, off = (pos - l.S) % u;
+    if (kc <= g.W) return pos;
+    if (k == kc) return l.S + g.W * u + (kc - g.W) + off;
+    if (k >= kc - g.W) return l.S + (k % g.W) * u + off;
+    return l.S + g.W * u + k;  // the gist of a unit that has left the window
+}
+// position held by row n (< ring_rows) in ring state t
+__device__ __forceinline__ int ring_pos_of_row(const RingLay& g, int t, int n) {
+    const AttnShape& l = g.lay;
+    if (!l.umode) {
+        const int nwin = t + 1 < g.W ? t + 1 : g.W;
+        return n < nwin ? t - (t - n) % g.W : pos_of_always(l, n - g.W);
+    }
+    if (t < l.S || n < l.S) return n;
+    const int u = l.rp1, kc = (t - l.S) / u;
+    if (kc <= g.W) return n;
+    const int m = n - l.S;
+    if (m < g.W * u) {
+        const int slot = m / u, k = kc - 1 - (kc - 1 - slot) % g.W;  // the unit in kc-W .. kc-1 with k % W == slot
+        return l.S + k * u + m % u;
+    }
+    const int i = m - g.W * u;
+    return i < kc - g.W ? l.S + i * u + u - 1 : l.S + kc * u + (i - (kc - g.W));
+}
 
-// TO_RING: canonical state (s[b], t[b]) -> ring state t[b].  !TO_RING: ring state t[b] -> canonical (s[b], t[b]).
+// TO_RING: ordered state (s[b], t[b]) -> ring state t[b].  !TO_RING: ring state t[b] -> ordered (s[b], t[b]).
+// s[b] must be the first position of the window of the query at t[b]: both sides then hold the same positions.
 template <bool TO_RING>
 __global__ __launch_bounds__(256) void cache_ring_convert_kernel(const char* __restrict__ kc_in, const char* __restrict__ vc_in,
                                                                 const int* __restrict__ s_v, const int* __restrict__ t_v,
                                                                 int cap_in, char* __restrict__ kc_out, char* __restrict__ vc_out,
-                                                                int cap_out, int* __restrict__ rows_out_v, int Hkv,
-                                                                AttnShape lay, int W, int row_bytes, int max_pos) {
+                                                                int cap_out, int* __restrict__ rows_out_v, int Hkv, RingLay g,
+                                                                int row_bytes, int max_pos) {
     const int b = blockIdx.z, bh = b * Hkv + blockIdx.y;
     const int s = s_v[b], t = t_v[b];
-    const int wfirst = t - W + 1 > 0 ? t - W + 1 : 0;  // first position of the window of a query at t
-    // the canonical side must hold the whole window (s <= wfirst) and nothing the ring cannot hold (s >= wfirst)
-    bool ok = s >= 0 && t >= s - 1 && t < max_pos && (t < 0 ? s == 0 : s == wfirst);
-    int rows_out = -1;
+    AttnShape wl = g.lay;  // win_lo wants the window in the shape
+    wl.W = g.W;
+    bool ok = s >= 0 && t >= -1 && t < max_pos && (t < 0 ? s == 0 : s == win_lo(wl, t));
+    int rows = -1;
     if (ok) {
-        const int rows_can = count_always(lay, s) + (t - s + 1), rows_ring = ring_rows(lay, W, t);
-        rows_out = TO_RING ? rows_ring : rows_can;
-        if ((TO_RING ? rows_can : rows_ring) > cap_in || rows_out > cap_out) {
+        rows = ring_rows(g, t);  // = count_always(s) + t - s + 1: the same positions on either side
+        if (rows > cap_in || rows > cap_out) {
             ok = false;
-            rows_out = -1;
+            rows = -1;
         }
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rows_out_v[b] = rows_out;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rows_out_v[b] = rows;
     if (!ok) return;
     const int cpr = row_bytes / 16;
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const int n = (int)(idx / cpr), ch = (int)(idx % cpr);
-    if (n >= rows_out) return;
-    const int ng = count_always(lay, s);
-    const int nwin = t + 1 < W ? t + 1 : W;
+    if (n >= rows) return;
+    const int ng = count_always(g.lay, s);
     int src;
     if (TO_RING) {
-        // position held by ring row n, then its canonical row (compact entry i sits in row i)
-        if (n < nwin) {
-            const int pos = t - (t - n) % W;
-            src = ng + (pos - s);
-        } else {
-            src = n - W;  // the (n - W)-th always-visible position: left of s, hence compact entry n - W
-        }
+        const int pos = ring_pos_of_row(g, t, n);
+        src = pos < s ? count_always(g.lay, pos) : ng + (pos - s);  // compact entry i sits in row i
     } else {
-        const int pos = n < ng ? pos_of_always(lay, n) : s + (n - ng);
-        src = pos > t - W ? pos % W : W + n;  // far entry n is the n-th always-visible position
+        const int pos = n < ng ? pos_of_always(g.lay, n) : s + (n - ng);
+        src = ring_row_of_pos(g, t, pos);
     }
     const size_t i = ((size_t)bh * cap_in + src) * row_bytes + ch * 16;
     const size_t o = ((size_t)bh * cap_out + n) * row_bytes + ch * 16;
@@ -150,21 +192,23 @@ __global__ __launch_bounds__(256) void cache_ring_convert_kernel(const char* __r
     *(u32x4*)(vc_out + o) = *(const u32x4*)(vc_in + i);
 }
 
-// One token per active sequence, in place.  grid (Hkv, B), 64 lanes: lanes 0 .. cpr-1 move K, lanes 32 .. 32+cpr-1 V.
+// One token per active sequence, in place.  grid (Hkv, B), 64 lanes: lanes 0 .. cpr-1 move K, lanes 32 .. 32+cpr-1 V;
+// a lane only ever touches its own 16-byte column of the rows, so its reads and writes are ordered by the program.
 __global__ __launch_bounds__(64) void cache_ring_append_kernel(char* __restrict__ kc, char* __restrict__ vc,
                                                               const char* __restrict__ k_new, const char* __restrict__ v_new,
                                                               int new_rows, const int* __restrict__ t_old_v,
                                                               const int* __restrict__ n_new_v, int cap,
-                                                              int* __restrict__ rows_out_v, int Hkv, AttnShape lay, int W,
-                                                              int row_bytes, int max_pos) {
+                                                              int* __restrict__ rows_out_v, int Hkv, RingLay g, int row_bytes,
+                                                              int max_pos) {
+    const AttnShape& l = g.lay;
     const int b = blockIdx.y, bh = b * Hkv + blockIdx.x;
     const int t_old = t_old_v[b], act = n_new_v[b];
     int rows = -1;
     const bool ok0 = t_old >= -1 && (act == 0 || act == 1) && t_old < max_pos - act;
     const int t = t_old + act;
     if (ok0) {
-        rows = ring_rows(lay, W, t);
-        if (rows > cap) rows = -1;
+        rows = ring_rows(g, t);
+        if (rows > cap || ring_rows(g, t_old) > cap) rows = -1;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) rows_out_v[b] = rows;
     if (rows < 0 || act == 0) return;
@@ -172,44 +216,72 @@ __global__ __launch_bounds__(64) void cache_ring_append_kernel(char* __restrict_
     const int lane = threadIdx.x & 31;
     if (lane >= cpr) return;
     char* c = (threadIdx.x < 32 ? kc : vc) + (size_t)bh * cap * row_bytes + lane * 16;
-    const char* nw = (threadIdx.x < 32 ? k_new : v_new) + (size_t)bh * new_rows * row_bytes + lane * 16;
-    const int slot = t % W;
-    const int p_out = t - W;  // leaves the window now; its row is the one the new token takes
-    if (p_out >= 0 && is_always(lay, p_out)) {
-        const u32x4 keep = *(const u32x4*)(c + (size_t)slot * row_bytes);
-        *(u32x4*)(c + (size_t)(W + count_always(lay, p_out)) * row_bytes) = keep;  // read before the slot is overwritten below
+    const u32x4 nw = *(const u32x4*)((threadIdx.x < 32 ? k_new : v_new) + (size_t)bh * new_rows * row_bytes + lane * 16);
+    auto row = [&](int n) { return (u32x4*)(c + (size_t)n * row_bytes); };
+    if (!l.umode) {
+        const int slot = t % g.W;
+        const int p_out = t - g.W;  // leaves the window now; its row is the one the new token takes
+        if (p_out >= 0 && is_always(l, p_out)) *row(g.W + count_always(l, p_out)) = *row(slot);
+        *row(slot) = nw;
+        return;
     }
-    *(u32x4*)(c + (size_t)slot * row_bytes) = *(const u32x4*)nw;
+    const int u = l.rp1;
+    const int kc_ = t < l.S ? 0 : (t - l.S) / u, cc = t < l.S ? 0 : (t - l.S) % u + 1;
+    if (t < l.S || kc_ <= g.W) {  // nothing has left the window yet: positions in order
+        *row(t) = nw;
+        return;
+    }
+    const int base = l.S + g.W * u + (kc_ - g.W);  // first row of the unit being filled
+    if (cc > 1) {
+        *row(base + cc - 1) = nw;
+        return;
+    }
+    // A new unit starts: the unit kc-1, complete in the rows base-1 .. base+u-2, moves into the slot of the unit
+    // kc-1-W, whose gist goes to the far row base-1; then the new token becomes row base.
+    const int slot0 = l.S + ((kc_ - 1) % g.W) * u;
+    const u32x4 gist = *row(slot0 + u - 1);
+    for (int i = 0; i < u; ++i) *row(slot0 + i) = *row(base - 1 + i);
+    *row(base - 1) = gist;
+    *row(base) = nw;
 }
 
 }  // namespace
 
+namespace {
+RingLay make_ring_lay(int rp1, int sinks, int W, int umode) {
+    RingLay g{};
+    g.lay.rp1 = rp1;
+    g.lay.S = sinks;
+    g.lay.umode = umode;
+    g.lay.L = 0x7fffffff;  // win_hi clamps to L - 1; unused here
+    g.W = W;
+    return g;
+}
+}  // namespace
+
 hipError_t launch_cache_ring_convert(bool to_ring, const void* kc_in, const void* vc_in, const int* s, const int* t,
                                      int cap_in, void* kc_out, void* vc_out, int cap_out, int* rows_out, int B, int Hkv,
-                                     int D, int rp1, int sinks, int W, int elem_bytes, int max_pos, hipStream_t st) {
-    AttnShape lay{};
-    lay.rp1 = rp1;
-    lay.S = sinks;
+                                     int D, int rp1, int sinks, int W, int umode, int elem_bytes, int max_pos,
+                                     hipStream_t st) {
+    const RingLay g = make_ring_lay(rp1, sinks, W, umode);
     const int row_bytes = D * elem_bytes;
-    const long items = (long)cap_out * (row_bytes / 16);
+    const long items = (long)(cap_out < cap_in ? cap_out : cap_in) * (row_bytes / 16);
     dim3 grid((unsigned)((items + 255) / 256), Hkv, B);
     if (to_ring)
         cache_ring_convert_kernel<true><<<grid, 256, 0, st>>>((const char*)kc_in, (const char*)vc_in, s, t, cap_in, (char*)kc_out,
-                                                              (char*)vc_out, cap_out, rows_out, Hkv, lay, W, row_bytes, max_pos);
+                                                              (char*)vc_out, cap_out, rows_out, Hkv, g, row_bytes, max_pos);
     else
         cache_ring_convert_kernel<false><<<grid, 256, 0, st>>>((const char*)kc_in, (const char*)vc_in, s, t, cap_in, (char*)kc_out,
-                                                               (char*)vc_out, cap_out, rows_out, Hkv, lay, W, row_bytes, max_pos);
+                                                               (char*)vc_out, cap_out, rows_out, Hkv, g, row_bytes, max_pos);
     return hipGetLastError();
 }
 
 hipError_t launch_cache_ring_append(void* kc, void* vc, const void* k_new, const void* v_new, int new_rows, const int* t_old,
                                     const int* n_new, int cap, int* rows_out, int B, int Hkv, int D, int rp1, int sinks,
-                                    int W, int elem_bytes, int max_pos, hipStream_t st) {
-    AttnShape lay{};
-    lay.rp1 = rp1;
-    lay.S = sinks;
+                                    int W, int umode, int elem_bytes, int max_pos, hipStream_t st) {
+    const RingLay g = make_ring_lay(rp1, sinks, W, umode);
     cache_ring_append_kernel<<<dim3(Hkv, B), 64, 0, st>>>((char*)kc, (char*)vc, (const char*)k_new, (const char*)v_new, new_rows,
-                                                          t_old, n_new, cap, rows_out, Hkv, lay, W, D * elem_bytes, max_pos);
+                                                          t_old, n_new, cap, rows_out, Hkv, g, D * elem_bytes, max_pos);
     return hipGetLastError();
 }
 

@@ -193,10 +193,11 @@ hipError_t launch_cache_update_ragged(const void* kc_in, const void* vc_in, cons
 // ring layout of the cache for token-by-token decoding (see cache.hip)
 hipError_t launch_cache_ring_convert(bool to_ring, const void* kc_in, const void* vc_in, const int* s, const int* t,
                                      int cap_in, void* kc_out, void* vc_out, int cap_out, int* rows_out, int B, int Hkv,
-                                     int D, int rp1, int sinks, int W, int elem_bytes, int max_pos, hipStream_t st);
+                                     int D, int rp1, int sinks, int W, int umode, int elem_bytes, int max_pos,
+                                     hipStream_t st);
 hipError_t launch_cache_ring_append(void* kc, void* vc, const void* k_new, const void* v_new, int new_rows, const int* t_old,
                                     const int* n_new, int cap, int* rows_out, int B, int Hkv, int D, int rp1, int sinks,
-                                    int W, int elem_bytes, int max_pos, hipStream_t st);
+                                    int W, int umode, int elem_bytes, int max_pos, hipStream_t st);
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                          int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt,
                          float* ws, hipStream_t st);

@@ -224,18 +224,22 @@ def test_ring_cache_rows_and_argument_validation():
     import oracle
     # rows in use of the ring layout = the number of positions the query at t sees (Sec. 4.1 with the sliding window)
     for r, W, sinks in [(4, 16, 0), (2, 5, 3), (8, 1, 0), (3, 100, 40)]:
-        for t in list(range(0, 60)) + [199, 1000]:
-            assert u.unigist_cache_ring_rows(t, r, W, sinks) == len(oracle.compressed_cache_positions(t, r, W, sinks=sinks))
-        assert u.unigist_cache_ring_rows(-1, r, W, sinks) == 0
-    assert u.unigist_cache_ring_rows(-2, 4, 16, 0) == -1 and u.unigist_cache_ring_rows(5, 0, 16, 0) == -1
+        for units in (False, True):
+            for t in list(range(0, 60)) + [199, 1000]:
+                want = len(oracle.compressed_cache_positions(t, r, W, sinks=sinks, units=units))
+                assert u.unigist_cache_ring_rows(t, r, W, sinks, int(units)) == want, (r, W, sinks, units, t)
+            assert u.unigist_cache_ring_rows(-1, r, W, sinks, int(units)) == 0
+    assert u.unigist_cache_ring_rows(-2, 4, 16, 0, 0) == -1 and u.unigist_cache_ring_rows(5, 0, 16, 0, 0) == -1
+    assert u.unigist_cache_ring_rows(5, 4, 16, 0, 2) == -1
     ok = dict(kc=FAKE, vc=FAKE, k_new=FAKE, v_new=FAKE, new_rows=1, t_old=FAKE, n_new=FAKE, cap=64, rows_out=FAKE, B=2,
-              Hkv=2, D=64, r=4, W=16, sinks=0, dt=0)
+              Hkv=2, D=64, r=4, W=16, sinks=0, window_mode=1, dt=0)
     bad = lambda **kw: u.unigist_cache_ring_append(*dict(ok, **kw).values())
     assert bad(W=0) == 1 and bad(cap=0) == 1 and bad(new_rows=0) == 1 and bad(sinks=-1) == 1 and bad(D=96) == 2 and bad(dt=3) == 2
+    assert bad(window_mode=2) == 1
     for name in ("kc", "vc", "k_new", "v_new", "t_old", "n_new", "rows_out"):
         assert bad(**{name: None}) == 1, name
     cv = dict(kc_in=FAKE, vc_in=FAKE, s=FAKE, t=FAKE, cap_in=64, kc_out=FAKE, vc_out=FAKE, cap_out=64, rows_out=FAKE, B=2,
-              Hkv=2, D=64, r=4, W=16, sinks=0, dt=2)
+              Hkv=2, D=64, r=4, W=16, sinks=0, window_mode=0, dt=2)
     for fn in (u.unigist_cache_to_ring, u.unigist_cache_from_ring):
         assert fn(*dict(cv, W=0).values()) == 1 and fn(*dict(cv, cap_out=0).values()) == 1 and fn(*dict(cv, r=0).values()) == 1
         for name in ("kc_in", "vc_in", "s", "t", "kc_out", "vc_out", "rows_out"):

@@ -377,13 +377,15 @@ def _sorted_rows(kr, vr):
     return x[np.lexsort(x.T[::-1])]
 
 
-@pytest.mark.parametrize("sinks", [0, 7])
-def test_ring_cache_token_by_token_then_back(sinks):
+@pytest.mark.parametrize("sinks,units,W,r", [(0, False, 48, 4), (7, False, 48, 4), (9, True, 6, 4), (0, True, 2, 2),
+                                             (40, True, 1, 7)])
+def test_ring_cache_token_by_token_then_back(sinks, units, W, r):
     # Decoding loop on the ring layout: after every appended token each sequence's slab holds exactly the positions
     # the oracle says the next query sees (as a multiset of (K row, V row) pairs -- decode ignores the order), the
     # reported rows are their number, and decode on the slab matches the oracle.  Sequences pause at random.  At the
     # end the ring is turned back into the ordered layout and must be the exact gather of those positions.
-    B, Hq, Hkv, D, r, W = 4, 8, 2, 128, 4, 48
+    B, Hq, Hkv, D = 4, 8, 2, 128
+    mask = dict(sinks=sinks, units=units)
     prompt = [130, 3, 60, 47]
     steps = 140
     Lmax = max(prompt) + steps
@@ -391,9 +393,9 @@ def test_ring_cache_token_by_token_then_back(sinks):
     kd, vd = k.cuda(), v.cuda()
     rag = u.RaggedKVCache(B, Hkv, Lmax, D, r, sinks=sinks)
     for b, n in enumerate(prompt):
-        rag.update(b, kd[b, :, :n].contiguous(), vd[b, :, :n].contiguous(), max(0, n - 1 - W + 1))
+        rag.update(b, kd[b, :, :n].contiguous(), vd[b, :, :n].contiguous(), _window_start(n - 1, r, W, sinks, units))
     rag.gathered()
-    ring = u.RingKVCache(rag, W)
+    ring = u.RingKVCache(rag, W, window_mode=int(units))
     torch.cuda.synchronize()
     t = [n - 1 for n in prompt]
 
@@ -401,8 +403,8 @@ def test_ring_cache_token_by_token_then_back(sinks):
         rows = ring.rows.cpu().tolist()
         kc, vc = ring.kc.cpu(), ring.vc.cpu()
         for b in range(B):
-            pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
-            assert rows[b] == len(pos) == u.unigist_cache_ring_rows(t[b], r, W, sinks), (when, b)
+            pos = oracle.compressed_cache_positions(t[b], r, W, **mask)
+            assert rows[b] == len(pos) == u.unigist_cache_ring_rows(t[b], r, W, sinks, int(units)), (when, b)
             for h in range(Hkv):
                 assert np.array_equal(_sorted_rows(kc[b, h, :rows[b]], vc[b, h, :rows[b]]),
                                       _sorted_rows(k[b, h][pos], v[b, h][pos])), (when, b, h)
@@ -415,13 +417,13 @@ def test_ring_cache_token_by_token_then_back(sinks):
         vn = torch.stack([vd[b, :, t[b] + 1:t[b] + 2] for b in range(B)]).contiguous()
         ring.append(kn, vn, torch.tensor(act, dtype=torch.int32, device="cuda"))
         t = [t[b] + act[b] for b in range(B)]
-        if step % 9 == 0 or step == steps - 1:
+        if step % 9 == 0 or step % 9 == 4 or step == steps - 1:
             check_content(step)
         if step % 35 == 0 or step == steps - 1:
             qt = torch.stack([q[b, :, t[b]] for b in range(B)]).contiguous()
             out, lse = u.decode(qt.cuda(), ring.kc, ring.vc, ring.rows)
             for b in range(B):
-                pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
+                pos = oracle.compressed_cache_positions(t[b], r, W, **mask)
                 o, l = oracle.decode(to_np(qt[b:b + 1]), to_np(k[b:b + 1][:, :, pos]), to_np(v[b:b + 1][:, :, pos]))
                 # over a handful of keys an output is nearly a raw V value, which can exceed 2: the stored bf16
                 # result then carries half an ulp of 2^-7 and more on top of the arithmetic's error
@@ -433,7 +435,7 @@ def test_ring_cache_token_by_token_then_back(sinks):
     rows = ring.to_ragged(rag).cpu().tolist()
     kc, vc = rag.current()
     for b in range(B):
-        pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
+        pos = oracle.compressed_cache_positions(t[b], r, W, **mask)
         assert rows[b] == len(pos)
         assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
 
@@ -448,16 +450,16 @@ def test_ring_cache_reports_impossible_states():
     # t_old = -2 is no state; 150 positions need 16 + 27 rows > cap; the middle sequence is fine and not active
     t_old, act = dev([-2, 20, 150]), dev([1, 0, 1])
     st = u.unigist_cache_ring_append(kc.data_ptr(), vc.data_ptr(), kn.data_ptr(), kn.data_ptr(), 1, t_old.data_ptr(),
-                                     act.data_ptr(), cap, rows.data_ptr(), B, Hkv, D, r, W, 0, 0,
+                                     act.data_ptr(), cap, rows.data_ptr(), B, Hkv, D, r, W, 0, 0, 0,
                                      torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
-    assert st == 0 and rows.cpu().tolist() == [-1, u.unigist_cache_ring_rows(20, r, W, 0), -1]
+    assert st == 0 and rows.cpu().tolist() == [-1, u.unigist_cache_ring_rows(20, r, W, 0, 0), -1]
     assert not bool(kc.any()) and not bool(vc.any())
     # conversion: the window start must be exactly the first position of the last query's window
     out_k, out_v = torch.zeros_like(kc), torch.zeros_like(kc)
     s, t = dev([3, 5, 0]), dev([20, 20, -1])
     st = u.unigist_cache_to_ring(kc.data_ptr(), vc.data_ptr(), s.data_ptr(), t.data_ptr(), cap, out_k.data_ptr(),
-                                 out_v.data_ptr(), cap, rows.data_ptr(), B, Hkv, D, r, W, 0, 0,
+                                 out_v.data_ptr(), cap, rows.data_ptr(), B, Hkv, D, r, W, 0, 0, 0,
                                  torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert st == 0 and rows.cpu().tolist() == [-1, 16 + 1, 0]
