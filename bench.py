@@ -195,6 +195,27 @@ def main():
     torch.cuda.synchronize()
     dec_ms = e0.elapsed_time(e1) / nd
     dec_bytes = 2.0 * dc["B"] * dc["Hkv"] * dc["Lk"] * dc["D"] * 2
+    # a decoding step = the new token's K/V written into the cache (ring layout: one or two rows per sequence and
+    # kv head) + decode; the cache is in the state whose window and gists fill the cfg5 rows
+    t_ring = (dc["Lk"] - W) * (r + 1) - 64
+    i32 = lambda x: torch.full((dc["B"],), x, dtype=torch.int32, device=dev)
+    rt, ract, rrows = i32(t_ring), i32(1), i32(0)
+    knew = dk_[:, :, :1].contiguous()
+    def decode_step():
+        u.unigist_cache_ring_append(dk_.data_ptr(), dv_.data_ptr(), knew.data_ptr(), knew.data_ptr(), 1, rt.data_ptr(),
+                                    ract.data_ptr(), dc["Lk"], rrows.data_ptr(), dc["B"], dc["Hkv"], dc["D"], r, W, 0,
+                                    u.UNIGIST_WINDOW_SLIDING, u.UNIGIST_BF16, torch.cuda.current_stream().cuda_stream)
+        u.decode(dq_, dk_, dv_, rrows, workspace=dws)
+    for _ in range(3):
+        decode_step()
+    torch.cuda.synchronize()
+    assert int(rrows[0]) == u.unigist_cache_ring_rows(t_ring + 1, r, W, 0, 0) <= dc["Lk"]
+    e0.record()
+    for _ in range(nd):
+        decode_step()
+    e1.record()
+    torch.cuda.synchronize()
+    dec_step_ms = e0.elapsed_time(e1) / nd
     dec_gbs = dec_bytes / dec_ms / 1e6
     # the same cache stored as E4M3 codes (one byte per element, per-kv-head scales): half the bytes to stream
     ks_, vs_ = synth.e4m3_scales(dc["Hkv"], seed=0, device=dev)
@@ -283,7 +304,8 @@ def main():
         "mfma_sustained": probe or None,
         "decode": {"workload": "cfg5_decode", "ms": dec_ms, "roofline": {
             "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-            "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes}},
+            "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes},
+            "step_ms_with_cache_append": dec_step_ms},
         "decode_e4m3": {"workload": "cfg5_decode, cache stored as E4M3 codes", "ms": dec8_ms, "roofline": {
             "bound": "hbm", "achieved": dec8_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec8_gbs / PEAK_HBM_GBS,
             "traffic": TRAFFIC_BYTES.get("decode_e4m3"), "alg_bytes_per_launch": dec8_bytes}},
