@@ -502,8 +502,8 @@ def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None, s
         raise UnigistError("unigist_attn_bwd_varlen_workspace: invalid shape or document bounds")
     if workspace is None:
         workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
-    # rows of no document (none when cu_seqlens covers 0 .. T) would stay unwritten: start from zero
-    dq, dk, dv = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    # cu_seqlens covers 0 .. T (the library checks it), so every row belongs to a document and is written
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     _check(unigist_attn_bwd_varlen_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                       dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D,
                                       int(r), int(W), int(sinks), int(window_mode), cu_seqlens, dt, workspace.data_ptr(),

@@ -199,3 +199,24 @@ def test_back_to_back_backward_calls_share_a_workspace():
     for (q, k, v, dout), f, g in zip(ins, fwd, grads):
         want = oracle_packed(q, k, v, dout, r, W, f[4])
         check(f"docs{np.diff(f[4]).tolist()}", (f[5], f[6]) + tuple(g), want, torch.bfloat16)
+
+
+def test_every_gradient_row_is_written():
+    # the backward fully overwrites dq, dk, dv (no zero-initialisation by the caller): buffers pre-filled with NaN
+    # come back without one, for a pack with empty, one-token and ragged documents
+    Hq, Hkv, D, r, W = 4, 2, 128, 4, 40
+    lens = [0, 1, 300, 0, 129, 64, 1, 777, 0]
+    cu = [0] + np.cumsum(lens).tolist()
+    T = cu[-1]
+    q, k, v, dout = (t.cuda() for t in packed_inputs(Hq, Hkv, T, D, torch.bfloat16, seed=36))
+    out, lse = u.attn_fwd_varlen(q, k, v, r, W, cu)
+    nan = float("nan")
+    dq, dk, dv = torch.full_like(q, nan), torch.full_like(k, nan), torch.full_like(v, nan)
+    ws = torch.empty(u.unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu, u.UNIGIST_BF16), dtype=torch.uint8, device="cuda")
+    st = u.unigist_attn_bwd_varlen(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(),
+                                   dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D, r, W, cu, u.UNIGIST_BF16,
+                                   ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert st == 0
+    assert not bool(torch.isnan(dq).any()) and not bool(torch.isnan(dk).any()) and not bool(torch.isnan(dv).any())
+    assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
