@@ -473,15 +473,33 @@ bool decode_grouped(int Hq, int Hkv, unigist_dtype dt) {
     return dt == UNIGIST_F32 ? G == 4 : G <= 15;
 }
 
-// Enough slices to put several workgroups on each of the 256 CUs, but never slices shorter than 256 keys.
+// Slices per sequence.  The slice kernel saturates HBM with one workgroup per CU, so the time of a launch goes
+// with the number of rounds of 256 workgroups times the slice length: the split is chosen to fill whole rounds
+// (a batch of 48 sequences x 8 kv heads = 384 workgroups would leave half of the second round idle), with a
+// small price per slice for the partial results the combine kernel has to merge, and never slices shorter than
+// 256 keys.  Measured on batches of 1 to 256 sequences: one round is best up to 64 (sequence, head) units, two up
+// to 256 units, four beyond.
 int decode_num_splits(int B, int Hq, int Hkv, int Lk, unigist_dtype dt) {
     const long units = (long)B * (decode_grouped(Hq, Hkv, dt) ? Hkv : Hq);
-    long want = (2048 + units - 1) / units;
-    long cap = (Lk + 255) / 256;
-    long n = want < cap ? want : cap;
-    if (n < 1) n = 1;
-    if (n > 64) n = 64;
-    return (int)n;
+    const long target = units <= 64 ? 256 : units <= 256 ? 512 : 1024;
+    long nmax = (target + units - 1) / units;
+    if (nmax < 4) nmax = 4;
+    if (nmax > 64) nmax = 64;
+    const long cap = (Lk + 255) / 256;
+    if (nmax > cap) nmax = cap;
+    if (nmax < 1) nmax = 1;
+    int best = 1;
+    double best_cost = 1e30;
+    for (long n = 1; n <= nmax; ++n) {
+        const long wgs = units * n;
+        double cost = (double)((wgs + 255) / 256 * 256) / (double)wgs * (1.0 + 0.01 * (double)n);
+        if (wgs < target) cost *= 1.05;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = (int)n;
+        }
+    }
+    return best;
 }
 
 namespace {
