@@ -463,3 +463,58 @@ def test_ring_cache_reports_impossible_states():
                                  torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert st == 0 and rows.cpu().tolist() == [-1, 16 + 1, 0]
+
+
+@pytest.mark.parametrize("sinks,units,W", [(0, False, 40), (9, True, 5)], ids=["sliding", "sinks_units"])
+def test_serving_loop_prefill_then_token_by_token(sinks, units, W):
+    # The whole inference path of Sec. 4.3 on a batch of sequences of different lengths: ragged chunk-wise prefill,
+    # eviction down to each last token's visible set, the ring layout, then token-by-token decoding with the O(1)
+    # append.  Every output row, prefilled or decoded, must equal that row of the one-pass attention over the
+    # sequence so far (the oracle never sees a cache).
+    B, Hq, Hkv, D, r, C = 3, 8, 2, 128, 4, 128
+    prompt, steps = [300, 41, 190], 60
+    Lmax = max(prompt) + steps
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, Lmax, D, seed=31)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    cache = u.RaggedKVCache(B, Hkv, Lmax, D, r, sinks=sinks)
+    got = [torch.zeros(Hq, n + steps, D, dtype=torch.bfloat16) for n in prompt]
+    while any(cache.t[b] < prompt[b] - 1 for b in range(B)):
+        n_new = [min(C, prompt[b] - 1 - cache.t[b]) for b in range(B)]
+        p0 = [cache.t[b] + 1 for b in range(B)]
+        kn = torch.zeros(B, Hkv, C, D, dtype=kd.dtype, device="cuda")
+        vn, qn = torch.zeros_like(kn), torch.zeros(B, Hq, C, D, dtype=qd.dtype, device="cuda")
+        for b in range(B):
+            kn[b, :, :n_new[b]] = kd[b, :, p0[b]:p0[b] + n_new[b]]
+            vn[b, :, :n_new[b]] = vd[b, :, p0[b]:p0[b] + n_new[b]]
+            qn[b, :, :n_new[b]] = qd[b, :, p0[b]:p0[b] + n_new[b]]
+        s_new = [max(cache.s[b], _window_start(p0[b], r, W, sinks, units)) if n_new[b] else cache.s[b] for b in range(B)]
+        cache.update_batch(kn, vn, n_new, s_new)
+        out, _, rows = cache.prefill_batch(qn, n_new, W, window_mode=int(units))
+        assert min(rows.cpu().tolist()) >= 0
+        for b in range(B):
+            got[b][:, p0[b]:p0[b] + n_new[b]] = out[b, :, :n_new[b]].cpu()
+    # evict down to what the last prompt token sees, switch layouts
+    empty = torch.zeros(B, Hkv, 1, D, dtype=kd.dtype, device="cuda")
+    cache.update_batch(empty, empty, [0] * B, [_window_start(prompt[b] - 1, r, W, sinks, units) for b in range(B)])
+    ring = u.RingKVCache(cache, W, window_mode=int(units))
+    t = [n - 1 for n in prompt]
+    for _ in range(steps):
+        kn = torch.stack([kd[b, :, t[b] + 1:t[b] + 2] for b in range(B)]).contiguous()
+        vn = torch.stack([vd[b, :, t[b] + 1:t[b] + 2] for b in range(B)]).contiguous()
+        rows = ring.append(kn, vn)
+        t = [x + 1 for x in t]
+        qt = torch.stack([qd[b, :, t[b]] for b in range(B)]).contiguous()
+        out, _ = u.decode(qt, ring.kc, ring.vc, rows)
+        for b in range(B):
+            got[b][:, t[b]] = out[b].cpu()
+    torch.cuda.synchronize()
+    for b in range(B):
+        n = prompt[b] + steps
+        rows = np.unique(np.concatenate([[0, prompt[b] - 1, prompt[b], n - 1], np.random.default_rng(b).integers(0, n, 16)]))
+        for h in (0, Hq - 1):
+            g = h // (Hq // Hkv)
+            o, _ = oracle.attn_fwd_rows(to_np(q[b, h, :n]), to_np(k[b, g, :n]), to_np(v[b, g, :n]), rows, r, W,
+                                        sinks=sinks, units=units)
+            w = np.abs(o)
+            half_ulp = np.where(w >= 2.0, 2.0 ** (np.floor(np.log2(np.maximum(w, 1e-30))) - 8), 0.0)
+            assert (np.abs(to_np(got[b][h])[rows] - o) <= TOL_OUT_BF16 + half_ulp).all(), (b, h)
