@@ -50,8 +50,9 @@ typedef enum {
 
 /*
  * Element types.  UNIGIST_E4M3 (one byte: E4M3 of the OCP 8-bit floating point format, bias 7, no infinities,
- * largest magnitude 448) is a storage type of the compressed cache only: unigist_cache_update(_ex) moves it,
- * unigist_quantize_e4m3 produces it, unigist_decode_e4m3 reads it; every other call answers
+ * largest magnitude 448) is a storage type of the compressed cache only: unigist_quantize_e4m3 produces it, the
+ * cache maintenance calls (unigist_cache_update, _ex, _ragged, unigist_cache_to_ring / _from_ring / _ring_append)
+ * move it, unigist_decode_e4m3 and unigist_prefill_chunk_e4m3 read it; every other call answers
  * UNIGIST_EUNSUPPORTED to it.
  */
 typedef enum { UNIGIST_BF16 = 0, UNIGIST_F32 = 1, UNIGIST_E4M3 = 2 } unigist_dtype;
