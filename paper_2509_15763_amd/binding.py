@@ -657,7 +657,8 @@ class RaggedKVCache:
         _check(unigist_cache_update_ex(self.k[cur][b].data_ptr(), self.v[cur][b].data_ptr(), self.s[b], self.t[b], self.cap,
                                        k_new.data_ptr() if n else None, v_new.data_ptr() if n else None, n, n,
                                        self.k[nxt][b].data_ptr(), self.v[nxt][b].data_ptr(), s_new, self.cap,
-                                       1, self.Hkv, self.D, self.r, self.sinks, _dt(self.k[0]), _stream()),
+                                       1, self.Hkv, self.D, self.r, self.sinks,
+                                       UNIGIST_E4M3 if self.k[0].dtype == torch.uint8 else _dt(self.k[0]), _stream()),
                "unigist_cache_update_ex")
         self.cur[b], self.s[b], self.t[b] = nxt, s_new, self.t[b] + n
 

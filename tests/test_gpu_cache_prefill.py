@@ -518,3 +518,40 @@ def test_serving_loop_prefill_then_token_by_token(sinks, units, W):
             w = np.abs(o)
             half_ulp = np.where(w >= 2.0, 2.0 ** (np.floor(np.log2(np.maximum(w, 1e-30))) - 8), 0.0)
             assert (np.abs(to_np(got[b][h])[rows] - o) <= TOL_OUT_BF16 + half_ulp).all(), (b, h)
+
+
+def test_ring_cache_moves_one_byte_rows_bit_exactly():
+    # the ring calls are copies of rows of any element size: a cache of E4M3 codes (random bytes here) through
+    # conversion, 90 appended tokens and the conversion back
+    B, Hkv, D, r, W, sinks = 2, 2, 64, 4, 24, 3
+    prompt, steps = [70, 5], 90
+    Lmax = max(prompt) + steps
+    g = torch.Generator().manual_seed(5)
+    k = torch.randint(0, 256, (B, Hkv, Lmax, D), dtype=torch.uint8, generator=g)
+    v = torch.randint(0, 256, (B, Hkv, Lmax, D), dtype=torch.uint8, generator=g)
+    kd, vd = k.cuda(), v.cuda()
+    rag = u.RaggedKVCache(B, Hkv, Lmax, D, r, dtype=torch.uint8, sinks=sinks)
+    for b, n in enumerate(prompt):
+        rag.update(b, kd[b, :, :n].contiguous(), vd[b, :, :n].contiguous(), max(0, n - 1 - W + 1))
+    rag.gathered()
+    ring = u.RingKVCache(rag, W)
+    t = [n - 1 for n in prompt]
+    for step in range(steps):
+        kn = torch.stack([kd[b, :, t[b] + 1:t[b] + 2] for b in range(B)]).contiguous()
+        vn = torch.stack([vd[b, :, t[b] + 1:t[b] + 2] for b in range(B)]).contiguous()
+        ring.append(kn, vn)
+        t = [x + 1 for x in t]
+        if step % 7 == 0 or step == steps - 1:
+            rows = ring.rows.cpu().tolist()
+            kc, vc = ring.kc.cpu(), ring.vc.cpu()
+            for b in range(B):
+                pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
+                assert rows[b] == len(pos)
+                for h in range(Hkv):
+                    assert np.array_equal(_sorted_rows(kc[b, h, :rows[b]], vc[b, h, :rows[b]]),
+                                          _sorted_rows(k[b, h][pos], v[b, h][pos])), (step, b, h)
+    ring.to_ragged(rag)
+    kc, vc = rag.current()
+    for b in range(B):
+        pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
+        assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
