@@ -755,7 +755,7 @@ class RingKVCache:
                                          self.rows.data_ptr(), self.B, self.Hkv, self.D, self.r, self.W, self.sinks,
                                          self.mode, self.dt, _stream()),
                "unigist_cache_ring_append")
-        self.t = self.t + active  # a new tensor: the kernel above still reads the old one
+        self.t.add_(active)  # in place, stream-ordered behind the kernel's read of t: the call can be captured in a graph
         return self.rows
 
     def to_ragged(self, ragged: "RaggedKVCache"):

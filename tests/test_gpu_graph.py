@@ -80,3 +80,63 @@ def test_packed_backward_in_a_graph():
         return [t[0] for t in synth.attn_inputs(1, Hq, Hkv, T, D, seed=90 + n)]
 
     _replay_equals_eager(inputs, run)
+
+
+def test_decoding_steps_in_a_graph():
+    # A decoding step (append the token's K/V to the ring cache, advance the positions, decode) changes state, so the
+    # captured step is replayed to advance one cache while an identical cache is advanced eagerly: every step's
+    # outputs and the caches must stay identical.  One sequence sits out every third step.
+    B, Hq, Hkv, D, r, W, n0, steps = 3, 8, 2, 128, 4, 32, 50, 9
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, n0 + steps, D, seed=77)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+
+    def fresh_ring():
+        rag = u.RaggedKVCache(B, Hkv, n0 + steps + 8, D, r)
+        for b in range(B):
+            rag.update(b, kd[b, :, :n0].contiguous(), vd[b, :, :n0].contiguous(), max(0, n0 - W))
+        rag.gathered()
+        return u.RingKVCache(rag, W)
+
+    ring_g, ring_e, ring_w = fresh_ring(), fresh_ring(), fresh_ring()
+    kn, vn = torch.empty(B, Hkv, 1, D, dtype=torch.bfloat16, device="cuda"), torch.empty(B, Hkv, 1, D, dtype=torch.bfloat16, device="cuda")
+    qt = torch.empty(B, Hq, D, dtype=torch.bfloat16, device="cuda")
+    act = torch.ones(B, dtype=torch.int32, device="cuda")
+    ws = torch.empty(u.unigist_decode_workspace(B, Hq, Hkv, ring_g.cap, D, u.UNIGIST_BF16), dtype=torch.uint8, device="cuda")
+
+    def step(ring):
+        rows = ring.append(kn, vn, act)
+        out, lse = u.decode(qt, ring.kc, ring.vc, rows, workspace=ws)
+        return out, lse, rows
+
+    def feed(n):
+        t = ring_e.t.cpu().tolist()           # the eager cache's positions (the captured one's are the same)
+        a = [1, 1, 0 if n % 3 == 2 else 1]
+        for b in range(B):
+            kn[b] = kd[b, :, t[b] + 1:t[b] + 2]
+            vn[b] = vd[b, :, t[b] + 1:t[b] + 2]
+            qt[b] = qd[b, :, t[b] + a[b]]
+        act.copy_(torch.tensor(a, dtype=torch.int32))
+
+    feed(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(ring_w)                            # warm-up on a cache of its own
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        captured = step(ring_g)
+    # the capture itself ran nothing: ring_g is still in its initial state
+    for n in range(steps):
+        feed(n)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in captured]
+        want = step(ring_e)
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"step {n}"
+        assert torch.equal(ring_g.t, ring_e.t) and torch.equal(ring_g.kc, ring_e.kc) and torch.equal(ring_g.vc, ring_e.vc), f"step {n}"
+    assert ring_e.t.cpu().tolist() == [n0 - 1 + steps, n0 - 1 + steps, n0 - 1 + steps - 3]
