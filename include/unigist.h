@@ -347,6 +347,18 @@ unigist_status unigist_prefill_chunk_view(const void* q, const void* kc, const v
                                           void* hip_stream);
 
 /*
+ * unigist_prefill_chunk_ex with explicit strides of q and out, in elements: element (b, h, i, d) of either lies at
+ * b * q_batch_stride + h * q_head_stride + i * q_row_stride + d.  [B, C, Hq, D] tensors, as projection layers
+ * produce them, are (C * Hq * D, D, Hq * D).  Strides are multiples of 8 elements, q_row_stride >= D, q and out
+ * 16-byte aligned (UNIGIST_EINVAL otherwise); lse stays dense, [B, Hq, C].
+ */
+unigist_status unigist_prefill_chunk_strided(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                             int B, int Hq, int Hkv, int C, int D, int r, int W, int sinks,
+                                             int window_mode, int p0, int s, int cap, long long q_batch_stride,
+                                             long long q_head_stride, long long q_row_stride, unigist_dtype dt,
+                                             void* hip_stream);
+
+/*
  * unigist_prefill_chunk_ex over a cache of E4M3 codes (as unigist_decode_e4m3 reads it: kc/vc uint8
  * [B, Hkv, cap, D], 16-byte aligned, the value of an element is its code times k_scale / v_scale of its kv head,
  * DEVICE arrays of Hkv positive floats).  q, out bf16.  The rows in use are first widened to bf16 in `workspace`

@@ -30,7 +30,7 @@ EXPORTS = [
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
     "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
-    "unigist_prefill_chunk_view",
+    "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
 ]
 
@@ -121,6 +121,8 @@ def load():
         fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
     lib.unigist_cache_ring_append.restype = ip
     lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
+    lib.unigist_prefill_chunk_strided.restype = ip
+    lib.unigist_prefill_chunk_strided.argtypes = [vp, vp, vp, vp, fp] + [ip] * 12 + [C.c_longlong] * 3 + [ip, vp]
     lib.unigist_prefill_chunk_view.restype = ip
     lib.unigist_prefill_chunk_view.argtypes = [vp, vp, vp, vp, fp] + [ip] * 14 + [vp]
     lib.unigist_prefill_chunk_ragged.restype = ip
@@ -341,6 +343,12 @@ def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r,
                                stream=None) -> int:
     return load().unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0,
                                              s, cap, dt, stream)
+
+
+def unigist_prefill_chunk_strided(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s, cap, q_bs, q_hs,
+                                  q_rs, dt, stream=None) -> int:
+    return load().unigist_prefill_chunk_strided(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s,
+                                                cap, q_bs, q_hs, q_rs, dt, stream)
 
 
 def unigist_prefill_chunk_e4m3_workspace(B, Hkv, D, s, t, r, sinks) -> int:
@@ -782,8 +790,24 @@ def prefill_chunk(q, cache: "KVCache", r, W, p0, window_mode=UNIGIST_WINDOW_SLID
     """q [B, Hq, C, D]: queries at positions p0 .. p0+C-1; cache already holds their keys.  -> out, lse.
     A cache of E4M3 codes goes through unigist_prefill_chunk_e4m3 (workspace: a uint8 tensor to reuse, optional).
     q may be a slice along the row axis of a [B, Hq, L, D] tensor if out and lse are given as the same slice of
-    tensors [B, Hq, L, D] and [B, Hq, L] (unigist_prefill_chunk_view: no copies of the chunk)."""
+    tensors [B, Hq, L, D] and [B, Hq, L] (unigist_prefill_chunk_view: no copies of the chunk).  Without out/lse, a q
+    of any strides with a contiguous last axis (e.g. the transposed view of a [B, C, Hq, D] projection output) gets
+    an out of the same strides (unigist_prefill_chunk_strided)."""
     B, Hq, C, D = q.shape
+    if out is None and lse is None and not q.is_contiguous() and cache.kc.dtype != torch.uint8:
+        if not q.is_cuda:
+            raise UnigistError("libunigist takes device tensors only (no CPU path)")
+        st = q.stride()
+        if st[3] != 1:
+            raise UnigistError("the last axis of q must be contiguous")
+        out = torch.empty_strided(q.shape, st, dtype=q.dtype, device=q.device)
+        lse = torch.empty(B, Hq, C, device=q.device, dtype=torch.float32)
+        _check(unigist_prefill_chunk_strided(q.data_ptr(), cache.kc.data_ptr(), cache.vc.data_ptr(), out.data_ptr(),
+                                             lse.data_ptr(), B, Hq, cache.Hkv, C, D, int(r), int(W), cache.sinks,
+                                             int(window_mode), int(p0), cache.s, cache.cap, st[0], st[1], st[2], _dt(q),
+                                             _stream()),
+               "unigist_prefill_chunk_strided")
+        return out, lse
     if out is not None or lse is not None or not q.is_contiguous():
         if out is None or lse is None or cache.kc.dtype == torch.uint8:
             raise UnigistError("a sliced q needs out= and lse= slices of the same layout (bf16 caches only)")

@@ -56,6 +56,9 @@ AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sin
     s.ngb = 0;
     s.kscale = nullptr;
     s.vscale = nullptr;
+    s.q_bs = 0;
+    s.q_hs = 0;
+    s.q_rs = 0;
     return s;
 }
 
@@ -366,12 +369,40 @@ extern "C" unigist_status unigist_prefill_chunk_ex(const void* q, const void* kc
                                       hip_stream);
 }
 
+namespace {
+unigist_status prefill_impl(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq, int Hkv,
+                            int C, int q_rows, int D, int r, int W, int sinks, int window_mode, int p0, int s, int cap,
+                            long long q_bs, long long q_hs, long long q_rs, unigist_dtype dt, void* hip_stream);
+}
+
 extern "C" unigist_status unigist_prefill_chunk_view(const void* q, const void* kc, const void* vc, void* out,
                                                      float* lse, int B, int Hq, int Hkv, int C, int q_rows, int D, int r,
                                                      int W, int sinks, int window_mode, int p0, int s, int cap,
                                                      unigist_dtype dt, void* hip_stream) {
-    if (C < 1 || p0 < 0 || s < 0 || cap < 1 || q_rows < C) return UNIGIST_EINVAL;
+    if (q_rows < C) return UNIGIST_EINVAL;
     if (q_rows > kMaxL) return UNIGIST_EUNSUPPORTED;
+    return prefill_impl(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r, W, sinks, window_mode, p0, s, cap, 0, 0, 0, dt,
+                        hip_stream);
+}
+
+extern "C" unigist_status unigist_prefill_chunk_strided(const void* q, const void* kc, const void* vc, void* out,
+                                                        float* lse, int B, int Hq, int Hkv, int C, int D, int r, int W,
+                                                        int sinks, int window_mode, int p0, int s, int cap,
+                                                        long long q_batch_stride, long long q_head_stride,
+                                                        long long q_row_stride, unigist_dtype dt, void* hip_stream) {
+    // 16-byte vector accesses: strides in multiples of 8 elements, bases aligned; rows must not overlap
+    if (q_row_stride < D || q_head_stride < 1 || q_batch_stride < 0 || q_row_stride > 0x7fffffffLL) return UNIGIST_EINVAL;
+    if ((q_row_stride | q_head_stride | q_batch_stride) & 7) return UNIGIST_EINVAL;
+    if (((uintptr_t)q & 15) != 0 || ((uintptr_t)out & 15) != 0) return UNIGIST_EINVAL;
+    return prefill_impl(q, kc, vc, out, lse, B, Hq, Hkv, C, C, D, r, W, sinks, window_mode, p0, s, cap, q_batch_stride,
+                        q_head_stride, q_row_stride, dt, hip_stream);
+}
+
+namespace {
+unigist_status prefill_impl(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq, int Hkv,
+                            int C, int q_rows, int D, int r, int W, int sinks, int window_mode, int p0, int s, int cap,
+                            long long q_bs, long long q_hs, long long q_rs, unigist_dtype dt, void* hip_stream) {
+    if (C < 1 || p0 < 0 || s < 0 || cap < 1) return UNIGIST_EINVAL;
     const long long Ltot = (long long)p0 + C;
     if (Ltot > kMaxL) return UNIGIST_EUNSUPPORTED;
     unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, dt, sinks, window_mode);
@@ -389,9 +420,13 @@ extern "C" unigist_status unigist_prefill_chunk_view(const void* q, const void* 
     sh.kv_rows = cap;
     sh.s0 = s;
     sh.ngb = count_always(sh, s);
+    sh.q_bs = q_bs;
+    sh.q_hs = q_hs;
+    sh.q_rs = (int)q_rs;
     hipError_t e = launch_fwd_mfma(q, kc, vc, out, lse, sh, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
+}  // namespace
 
 extern "C" size_t unigist_prefill_chunk_e4m3_workspace(int B, int Hkv, int D, int s, int t, int r, int sinks) {
     const int rows = unigist_cache_rows_ex(s, t, r, sinks);

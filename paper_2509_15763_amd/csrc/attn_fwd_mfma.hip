@@ -157,7 +157,9 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     float m[2], l[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const bf16_t* qp = q + (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld[qb] - qpos0)) * D + 8 * g4;
+        const size_t qoff = s.q_rs ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)(qrow_ld[qb] - qpos0) * s.q_rs
+                                   : (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld[qb] - qpos0)) * D;
+        const bf16_t* qp = q + qoff + 8 * g4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
 #pragma unroll
@@ -387,7 +389,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         if (s.vscale) inv *= s.vscale[hk];  // the stored values stand for V * vscale
         if (qrow[qb] < L) {
             const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow[qb] - qpos0);
-            bf16_t* op = out + orow * D + 4 * g4;
+            const size_t ooff = s.q_rs ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)(qrow[qb] - qpos0) * s.q_rs : orow * D;
+            bf16_t* op = out + ooff + 4 * g4;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 u32x2 w2;

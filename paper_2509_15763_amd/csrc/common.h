@@ -71,6 +71,11 @@ struct AttnShape {
     // = 1).  The scales are applied in fp32 to the scores and to the output, never to the bf16 operands.
     const float* kscale;
     const float* vscale;
+    // Forward only: explicit strides of q and out in elements (batch, head, row), for tensors laid out otherwise
+    // than [B, Hq, qhs, D] -- e.g. [B, L, Hq, D] as projection layers produce them.  q_rs = 0: the dense layout above.
+    // lse keeps the dense layout.
+    long long q_bs, q_hs;
+    int q_rs;
 };
 
 // ---- the visibility rule of Sec. 4.1 (Eq. 3) in the closed forms the kernels use.  A key j <= i is visible

@@ -199,6 +199,12 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk_view(*pv.values()) == 2
     pv.update(q_rows=4096, s=402)
     assert u.unigist_prefill_chunk_view(*pv.values()) == 1
+    # prefill with explicit strides: multiples of 8 elements, rows that do not overlap, aligned bases
+    ps = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
+              window_mode=0, p0=500, s=401, cap=1024, q_bs=64 * 256, q_hs=128, q_rs=256, dt=0)
+    bads = lambda **kw: u.unigist_prefill_chunk_strided(*dict(ps, **kw).values())
+    assert bads(q_rs=64) == 1 and bads(q_rs=260) == 1 and bads(q_hs=0) == 1 and bads(q_bs=-8) == 1 and bads(q=FAKE + 8) == 1
+    assert bads(s=402) == 1 and bads(dt=1) == 2 and bads(q=None) == 1
     # prefill over a cache of codes: the same checks plus scales, alignment and workspace
     e = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128,
              r=4, W=100, sinks=0, window_mode=0, p0=500, s=401, cap=1024, ws=FAKE, ws_bytes=1 << 30)

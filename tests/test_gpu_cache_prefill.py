@@ -366,8 +366,6 @@ def test_prefill_on_row_slices_equals_prefill_on_copies():
         assert torch.equal(out[:, :, p0:p0 + n], o) and torch.equal(lse[:, :, p0:p0 + n], l)
         assert bool((out[:, :, p0 + n:] == 7.0).all()) and bool((lse[:, :, p0 + n:] == 7.0).all())
     with pytest.raises(u.UnigistError):
-        u.prefill_chunk(qd[:, :, 0:C], b, r, W, 0)                                  # a slice without out= / lse=
-    with pytest.raises(u.UnigistError):
         u.prefill_chunk(qd[:, :, 0:C], b, r, W, 0, out=out[:, :, 0:C].contiguous(), lse=lse[:, :, 0:C])
 
 
@@ -555,3 +553,20 @@ def test_ring_cache_moves_one_byte_rows_bit_exactly():
     for b in range(B):
         pos = oracle.compressed_cache_positions(t[b], r, W, sinks=sinks)
         assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
+
+
+def test_prefill_on_projection_layout_equals_prefill_on_copies():
+    # q as a projection layer leaves it, [B, C, Hq, D], passed as its transposed view: out comes back in the same
+    # layout, same bits as with a contiguous [B, Hq, C, D] copy; a row slice without out= / lse= takes the same path
+    B, Hq, Hkv, D, r, W, C, L = 2, 4, 2, 128, 4, 60, 300, 900
+    q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=32)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    cache = u.KVCache(B, Hkv, L, D, r)
+    for p0 in range(0, L, C):
+        cache.update(kd[:, :, p0:p0 + C], vd[:, :, p0:p0 + C], max(0, p0 - W + 1))
+        want_o, want_l = u.prefill_chunk(qd[:, :, p0:p0 + C].contiguous(), cache, r, W, p0)
+        q_blhd = qd[:, :, p0:p0 + C].transpose(1, 2).contiguous()          # [B, C, Hq, D] in memory
+        o, l = u.prefill_chunk(q_blhd.transpose(1, 2), cache, r, W, p0)
+        assert o.stride() == q_blhd.transpose(1, 2).stride() and torch.equal(o, want_o) and torch.equal(l, want_l)
+        o2, l2 = u.prefill_chunk(qd[:, :, p0:p0 + C], cache, r, W, p0)     # a row slice of the [B, Hq, L, D] tensor
+        assert torch.equal(o2, want_o) and torch.equal(l2, want_l)

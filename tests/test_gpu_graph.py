@@ -138,5 +138,8 @@ def test_decoding_steps_in_a_graph():
         torch.cuda.synchronize()
         for a, b in zip(got, want):
             assert torch.equal(a, b), f"step {n}"
-        assert torch.equal(ring_g.t, ring_e.t) and torch.equal(ring_g.kc, ring_e.kc) and torch.equal(ring_g.vc, ring_e.vc), f"step {n}"
+        assert torch.equal(ring_g.t, ring_e.t), f"step {n}"
+        for b_, nrows in enumerate(want[2].cpu().tolist()):   # the rows in use (what lies behind them was never written)
+            assert torch.equal(ring_g.kc[b_, :, :nrows], ring_e.kc[b_, :, :nrows]), f"step {n}"
+            assert torch.equal(ring_g.vc[b_, :, :nrows], ring_e.vc[b_, :, :nrows]), f"step {n}"
     assert ring_e.t.cpu().tolist() == [n0 - 1 + steps, n0 - 1 + steps, n0 - 1 + steps - 3]
