@@ -116,3 +116,39 @@ def test_decode_full_size():
         o, l = oracle.decode(qb, kb, vb, [int(sl[b])])
         assert max_abs(to_np(out2[b:b + 1]), o) <= TOL_OUT_BF16 and max_abs(to_np(lse2[b:b + 1]), l) <= TOL_LSE_BF16
     assert torch.isfinite(out.float()).all() and torch.isfinite(out2.float()).all()
+
+
+def test_largest_supported_length_forward():
+    # L = 2^23 positions per head, the most the entry points accept (one more is UNIGIST_EUNSUPPORTED): the
+    # kernels keep byte offsets inside a head in 32 bits, and here they come within one row of 2^30 * 2.  One head of
+    # D = 64; rows at both ends and in the middle against the oracle (1.7 million visible keys for the last ones).
+    L, D, r, W = 1 << 23, 64, 4, 1024
+    g = torch.Generator(device="cuda").manual_seed(6)
+    q, k, v = (torch.randn(1, 1, L, D, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+    out = torch.empty_like(q)
+    lse = torch.empty(1, 1, L, device="cuda", dtype=torch.float32)
+    st = torch.cuda.current_stream().cuda_stream
+    assert u.unigist_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(), 1, 1, 1, L + 1, D, r, W,
+                              u.UNIGIST_BF16, st) == 2
+    assert u.unigist_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(), 1, 1, 1, L, D, r, W,
+                              u.UNIGIST_BF16, st) == 0
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, W, L // 2 + 3, L - 129, L - 2, L - 1])
+    qn, kn, vn = to_np(q[0, 0].cpu()), to_np(k[0, 0].cpu()), to_np(v[0, 0].cpu())
+    o, l = oracle.attn_fwd_rows(qn, kn, vn, rows, r, W)
+    assert out_ok(to_np(out[0, 0, rows].cpu()), o)
+    assert max_abs(to_np(lse[0, 0, rows].cpu()), l) <= TOL_LSE_BF16
+
+
+def test_one_million_positions_forward_and_backward():
+    # 2^20 positions of one head (D = 64): 16384 query chunks, so the gist phase of dK/dV runs with segments of 512
+    # chunks (never more than 32 segments per gist tile), 1639 gist tiles, a 3.4 GB workspace
+    B, Hq, Hkv, L, D, r, W = 1, 1, 1, 1 << 20, 64, 4, 1024
+    q, k, v, dout, *res = run(B, Hq, Hkv, L, D, r, W, seed=8)
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([[0, W, L - 1, L // 2], rng.integers(0, L, 6)]))
+    raw = [j for j in (700000 + rng.integers(0, 300, 4)).tolist() if (j + 1) % (r + 1) != 0]
+    gists = [L - 1 - ((L - 5) % 5) - 5 * t for t in (0, 40)]       # positions with (p + 1) % 5 == 0 near the end
+    assert all((p + 1) % (r + 1) == 0 for p in gists)
+    sampled_check(q, k, v, dout, res, B, Hq, Hkv, L, r, W, [(0, 0)], rows, raw, gists, "1M")
+    identities(dout, res[3], res[4], Hkv, L)
