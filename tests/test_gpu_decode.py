@@ -65,3 +65,21 @@ def test_a_sequence_of_zero_keys_gives_the_empty_sum():
     keep = [0, 2]
     o, l = oracle.decode(to_np(q[keep]), to_np(kc[keep]), to_np(vc[keep]), sl[keep].numpy())
     assert max_abs(to_np(out[keep]), o) <= 2e-2 and max_abs(to_np(lse[keep]), l) <= TOL_LSE_BF16
+
+
+@pytest.mark.parametrize("codes", [False, True], ids=["bf16", "e4m3"])
+def test_decode_over_a_million_keys(codes):
+    # one sequence whose cache holds 2^20 rows (64 slices of 16 384 keys per kv head), bf16 and E4M3 storage
+    B, Hq, Hkv, Lk, D = 1, 4, 2, 1 << 20, 128
+    q, kc, vc = synth.decode_inputs(B, Hq, Hkv, Lk, D, seed=9, device="cuda")
+    if codes:
+        ks, vs = synth.e4m3_scales(Hkv, seed=9, device="cuda")
+        k8, v8 = u.quantize_e4m3(kc, ks), u.quantize_e4m3(vc, vs)
+        out, lse = u.decode_e4m3(q, k8, v8, ks, vs)
+        torch.cuda.synchronize()
+        o, l = oracle.decode_e4m3(to_np(q.cpu()), k8.cpu().numpy(), v8.cpu().numpy(), ks.cpu().numpy(), vs.cpu().numpy())
+    else:
+        out, lse = u.decode(q, kc, vc)
+        torch.cuda.synchronize()
+        o, l = oracle.decode(to_np(q.cpu()), to_np(kc.cpu()), to_np(vc.cpu()))
+    assert max_abs(to_np(out.cpu()), o) <= TOL_OUT_BF16 and max_abs(to_np(lse.cpu()), l) <= TOL_LSE_BF16
