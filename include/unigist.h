@@ -148,6 +148,26 @@ size_t unigist_attn_bwd_workspace_ex(int B, int Hq, int Hkv, int L, int D, int r
                                      int window_mode, unigist_dtype dt);
 
 /*
+ * Forward and backward with explicit strides of the query-side tensors, in elements: element (b, h, i, d) of q, out,
+ * dout and dq lies at b * q_batch_stride + h * q_head_stride + i * q_row_stride + d -- e.g. (L * Hq * D, D, Hq * D)
+ * for [B, L, Hq, D] tensors as projection layers produce them, which then need no transposing copy (with grouped
+ * queries they are the large tensors).  k, v, dk, dv and lse keep the layouts above.  Strides are multiples of 8
+ * elements, q_row_stride >= D, the four tensors 16-byte aligned (UNIGIST_EINVAL otherwise), L * q_row_stride below
+ * 2^31 elements (UNIGIST_EUNSUPPORTED otherwise); bf16 only.  Same kernels,
+ * same arithmetic, same results as unigist_attn_fwd_ex / unigist_attn_bwd_ex; workspace from
+ * unigist_attn_bwd_workspace_ex.
+ */
+unigist_status unigist_attn_fwd_strided(const void* q, const void* k, const void* v, void* out, float* lse,
+                                        int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks, int window_mode,
+                                        long long q_batch_stride, long long q_head_stride, long long q_row_stride,
+                                        unigist_dtype dt, void* hip_stream);
+unigist_status unigist_attn_bwd_strided(const void* q, const void* k, const void* v, const void* out,
+                                        const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                        int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks, int window_mode,
+                                        long long q_batch_stride, long long q_head_stride, long long q_row_stride,
+                                        unigist_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Packed documents (Sec. 5.1: several documents share one training sequence and attention never crosses a
  * document boundary).  The tensors hold T tokens per head -- q, out, dout, dq [Hq, T, D]; k, v, dk, dv
  * [Hkv, T, D]; lse [Hq, T] -- and document d occupies the rows cu_seqlens[d] .. cu_seqlens[d+1]-1.  Inside a

@@ -17,7 +17,10 @@ from . import binding as _b
 class _GistAttention(torch.autograd.Function):
     @staticmethod
     def forward(ctx, q, k, v, r, W, sinks, window_mode):
-        q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+        # a q in the projection layout ([B, L, Hq, D] in memory, passed as its [B, Hq, L, D] view) is used as it is
+        # and out comes back in the same layout; everything else is made contiguous
+        q = q if _b._q_strided(q) else q.contiguous()
+        k, v = k.contiguous(), v.contiguous()
         out, lse = _b.attn_fwd(q, k, v, r, W, sinks=sinks, window_mode=window_mode)
         ctx.save_for_backward(q, k, v, out, lse)
         ctx.mask = (int(r), int(W), int(sinks), int(window_mode))
@@ -27,7 +30,9 @@ class _GistAttention(torch.autograd.Function):
     def backward(ctx, dout):
         q, k, v, out, lse = ctx.saved_tensors
         r, W, sinks, window_mode = ctx.mask
-        dq, dk, dv = _b.attn_bwd(q, k, v, out, lse, dout.contiguous(), r, W, sinks=sinks, window_mode=window_mode)
+        if not _b._q_strided(q):
+            dout = dout.contiguous()
+        dq, dk, dv = _b.attn_bwd(q, k, v, out, lse, dout, r, W, sinks=sinks, window_mode=window_mode)
         return dq, dk, dv, None, None, None, None
 
 

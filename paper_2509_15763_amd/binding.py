@@ -30,7 +30,7 @@ EXPORTS = [
     "unigist_probe_mfma_rate", "unigist_quantize_e4m3", "unigist_decode_e4m3", "unigist_cache_update_ragged",
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
     "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
-    "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided",
+    "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided", "unigist_attn_fwd_strided", "unigist_attn_bwd_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
 ]
 
@@ -121,6 +121,10 @@ def load():
         fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
     lib.unigist_cache_ring_append.restype = ip
     lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
+    lib.unigist_attn_fwd_strided.restype = ip
+    lib.unigist_attn_fwd_strided.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [C.c_longlong] * 3 + [ip, vp]
+    lib.unigist_attn_bwd_strided.restype = ip
+    lib.unigist_attn_bwd_strided.argtypes = [vp] * 9 + [ip] * 9 + [C.c_longlong] * 3 + [ip, vp, sz, vp]
     lib.unigist_prefill_chunk_strided.restype = ip
     lib.unigist_prefill_chunk_strided.argtypes = [vp, vp, vp, vp, fp] + [ip] * 12 + [C.c_longlong] * 3 + [ip, vp]
     lib.unigist_prefill_chunk_view.restype = ip
@@ -345,6 +349,18 @@ def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r,
                                              s, cap, dt, stream)
 
 
+def unigist_attn_fwd_strided(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, q_bs, q_hs, q_rs, dt,
+                             stream=None) -> int:
+    return load().unigist_attn_fwd_strided(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, q_bs, q_hs, q_rs,
+                                           dt, stream)
+
+
+def unigist_attn_bwd_strided(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, sinks, window_mode, q_bs, q_hs,
+                             q_rs, dt, ws, ws_bytes, stream=None) -> int:
+    return load().unigist_attn_bwd_strided(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, L, D, r, W, sinks, window_mode,
+                                           q_bs, q_hs, q_rs, dt, ws, ws_bytes, stream)
+
+
 def unigist_prefill_chunk_strided(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s, cap, q_bs, q_hs,
                                   q_rs, dt, stream=None) -> int:
     return load().unigist_prefill_chunk_strided(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, sinks, window_mode, p0, s,
@@ -437,13 +453,30 @@ def n_vis(L, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:
 
 
 # ---------------------------------------------------------------- conveniences (allocate outputs, check status)
+def _q_strided(q) -> bool:
+    """Is q a bf16 view with a contiguous last axis but not contiguous as a whole (e.g. the transposed view of a
+    [B, L, Hq, D] projection output)?  Such a q goes through the *_strided entry points without a copy."""
+    return (q.dtype == torch.bfloat16 and q.is_cuda and not q.is_contiguous() and q.stride(-1) == 1
+            and all(s % 8 == 0 for s in q.stride()[:-1]) and q.stride(2) >= q.shape[3])
+
+
 def attn_fwd(q, k, v, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
-    """q [B,Hq,L,D], k/v [B,Hkv,L,D] on the GPU -> out [B,Hq,L,D], lse [B,Hq,L] fp32."""
-    _dev(q, k, v)
+    """q [B,Hq,L,D], k/v [B,Hkv,L,D] on the GPU -> out [B,Hq,L,D], lse [B,Hq,L] fp32.  A bf16 q that is a strided view
+    (see _q_strided) is taken as it is and out gets the same strides."""
     B, Hq, L, D = q.shape
     Hkv = k.shape[1]
     if k.shape != (B, Hkv, L, D) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
         raise UnigistError("q/k/v shapes or dtypes disagree")
+    if _q_strided(q):
+        _dev(k, v)
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        lse = torch.empty(B, Hq, L, device=q.device, dtype=torch.float32)
+        _check(unigist_attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                        B, Hq, Hkv, L, D, int(r), int(W), int(sinks), int(window_mode), q.stride(0),
+                                        q.stride(1), q.stride(2), _dt(q), _stream()),
+               "unigist_attn_fwd_strided")
+        return out, lse
+    _dev(q, k, v)
     out = torch.empty_like(q)
     lse = torch.empty(B, Hq, L, device=q.device, dtype=torch.float32)
     _check(unigist_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
@@ -455,8 +488,8 @@ def attn_fwd(q, k, v, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
 def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_ALL, grads=None, sinks=0,
              window_mode=UNIGIST_WINDOW_SLIDING):
     """-> dq [B,Hq,L,D], dk, dv [B,Hkv,L,D].  `stages`/`grads` let a caller run the backward one
-    stage at a time into the same output tensors (per-kernel timing)."""
-    _dev(q, k, v, out, lse, dout)
+    stage at a time into the same output tensors (per-kernel timing).  A strided bf16 q (see attn_fwd) with out of
+    the same strides takes the strided entry point: dq gets q's strides, dout is brought to them if it differs."""
     B, Hq, L, D = q.shape
     Hkv = k.shape[1]
     dt = _dt(q)
@@ -464,6 +497,25 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_A
         raise UnigistError("out/dout/lse shapes or dtypes disagree")
     if k.shape != (B, Hkv, L, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:
         raise UnigistError("q/k/v/out/dout shapes or dtypes disagree")
+    if _q_strided(q) and out.stride() == q.stride() and stages == UNIGIST_BWD_ALL and grads is None:
+        _dev(k, v, lse)
+        if dout.stride() != q.stride():
+            dout = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device).copy_(dout)
+        need = unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, int(r), int(W), int(sinks), int(window_mode), dt)
+        if need == 0:
+            raise UnigistError("unigist_attn_bwd_workspace_ex: invalid or unsupported shape")
+        if workspace is None:
+            workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+        dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        dk, dv = torch.empty_like(k), torch.empty_like(v)
+        _check(unigist_attn_bwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                        dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, L, D,
+                                        int(r), int(W), int(sinks), int(window_mode), q.stride(0), q.stride(1),
+                                        q.stride(2), dt, workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream()),
+               "unigist_attn_bwd_strided")
+        return dq, dk, dv
+    _dev(q, k, v, out, lse, dout)
     need = unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, int(r), int(W), int(sinks), int(window_mode), dt)
     if need == 0:
         raise UnigistError("unigist_attn_bwd_workspace_ex: invalid or unsupported shape")

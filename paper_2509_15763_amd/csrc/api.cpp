@@ -111,6 +111,59 @@ extern "C" unigist_status unigist_attn_fwd_ex(const void* q, const void* k, cons
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
 }
 
+// ---- q, out, dout, dq with explicit strides (k, v, dk, dv, lse dense)
+namespace {
+unigist_status check_qstrides(const void* a, const void* b, int L, int D, long long q_bs, long long q_hs, long long q_rs,
+                              unigist_dtype dt) {
+    if (dt != UNIGIST_BF16 || plain_alu_forced()) return UNIGIST_EUNSUPPORTED;  // the bf16 matrix-core kernels only
+    // 16-byte vector accesses: strides in multiples of 8 elements, aligned bases; rows must not overlap
+    if (q_rs < D || q_hs < 1 || q_bs < 0 || q_rs > 0x7fffffffLL) return UNIGIST_EINVAL;
+    if ((q_rs | q_hs | q_bs) & 7) return UNIGIST_EINVAL;
+    if (((uintptr_t)a & 15) != 0 || ((uintptr_t)b & 15) != 0) return UNIGIST_EINVAL;
+    if ((long long)L * q_rs * 2 > 0xffffffffLL) return UNIGIST_EUNSUPPORTED;  // byte offsets inside a head stay in 32 bits
+    return UNIGIST_OK;
+}
+}  // namespace
+
+extern "C" unigist_status unigist_attn_fwd_strided(const void* q, const void* k, const void* v, void* out, float* lse,
+                                                   int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                                   int window_mode, long long q_batch_stride, long long q_head_stride,
+                                                   long long q_row_stride, unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt, sinks, window_mode);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
+    if ((st = check_qstrides(q, out, L, D, q_batch_stride, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
+    s.q_bs = q_batch_stride;
+    s.q_hs = q_head_stride;
+    s.q_rs = (int)q_row_stride;
+    return launch_fwd_mfma(q, k, v, out, lse, s, (hipStream_t)hip_stream) == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" unigist_status unigist_attn_bwd_strided(const void* q, const void* k, const void* v, const void* out,
+                                                   const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                                   int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                                   int window_mode, long long q_batch_stride, long long q_head_stride,
+                                                   long long q_row_stride, unigist_dtype dt, void* workspace,
+                                                   size_t workspace_bytes, void* hip_stream) {
+    unigist_status st = check_attn(B, Hq, Hkv, L, D, r, W, dt, sinks, window_mode);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
+    if ((st = check_qstrides(q, out, L, D, q_batch_stride, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    if ((st = check_qstrides(dout, dq, L, D, q_batch_stride, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    if (workspace_bytes < unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, sinks, window_mode, dt))
+        return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
+    s.q_bs = q_batch_stride;
+    s.q_hs = q_head_stride;
+    s.q_rs = (int)q_row_stride;
+    return launch_bwd_mfma(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, UNIGIST_BWD_ALL, (hipStream_t)hip_stream) ==
+                   hipSuccess
+               ? UNIGIST_OK
+               : UNIGIST_ELAUNCH;
+}
+
 extern "C" size_t unigist_attn_bwd_workspace(int B, int Hq, int Hkv, int L, int D, int r, int W,
                                              unigist_dtype dt) {
     return unigist_attn_bwd_workspace_ex(B, Hq, Hkv, L, D, r, W, 0, UNIGIST_WINDOW_SLIDING, dt);

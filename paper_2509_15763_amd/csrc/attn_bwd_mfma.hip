@@ -139,15 +139,19 @@ BwdPlan make_plan(const AttnShape& s) {
 template <int D>
 __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
                                                   const float* __restrict__ lse, float* __restrict__ delta,
-                                                  float* __restrict__ lse2, long nrows, int L, int qhs) {
+                                                  float* __restrict__ lse2, long nrows, int L, int qhs, int Hq,
+                                                  long long q_bs, long long q_hs, int q_rs) {
     constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
     const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;  // dense: (b, h, i) -> (b Hq + h) L + i
     const int sub = threadIdx.x % LPR;
     const long grow = L == qhs ? row : (row / L) * qhs + row % L;        // the same row in the caller's tensors
     float acc = 0.f;
     if (row < nrows) {
-        u32x4 a = *(const u32x4*)(out + grow * D + sub * 8);
-        u32x4 b = *(const u32x4*)(dout + grow * D + sub * 8);
+        // element offset of the row in out / dout: dense, or with the caller's explicit strides (q_rs != 0)
+        const long bh = row / L;
+        const long eoff = q_rs ? (bh / Hq) * q_bs + (bh % Hq) * q_hs + (row % L) * (long)q_rs : grow * D;
+        u32x4 a = *(const u32x4*)(out + eoff + sub * 8);
+        u32x4 b = *(const u32x4*)(dout + eoff + sub * 8);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             acc += __uint_as_float(a[t] << 16) * __uint_as_float(b[t] << 16);
@@ -180,7 +184,8 @@ struct DkdvSmem {
 // PACK = true (here and in dq_kernel): the launch covers the documents of a packed buffer (docs), s_arg is the shape
 // of the whole pack, delta and lse2 have the layout of the caller's lse ([Hq, T]), and every document has its
 // own run of slots in part and comp.
-template <int D, bool GIST, bool GEN, bool PACK>
+// QSTR = true: q and dout have the explicit strides of s_arg (q_bs, q_hs, q_rs) instead of the dense layout.
+template <int D, bool GIST, bool GEN, bool PACK, bool QSTR = false>
 __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                     const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                     const bf16_t* __restrict__ dout, const float* __restrict__ delta,
@@ -309,17 +314,19 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         asm volatile("" : "+v"(ln));  // opaque: keeps the address arithmetic below inside this call
         const int lrow_ = ln / CH;
         int lanepart[NLP];
+        const unsigned rsb = QSTR ? (unsigned)s.q_rs * 2u : (unsigned)ROWB;  // bytes between consecutive rows in q / dout
 #pragma unroll
-        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * ROWB + (((ln % CH) ^ swz16<CH>(i * RPI + lrow_)) << 4);
+        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * (int)rsb + (((ln % CH) ^ swz16<CH>(i * RPI + lrow_)) << 4);
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * (PACK ? s.qhs : L);  // wave-uniform; workspace rows
-        const size_t hg = ((size_t)b * s.Hq + hk * G + g) * s.qhs;       // the head in the caller's tensors
-        const char* qh = (const char*)(q + hg * D);
-        const char* gh = (const char*)(dout + hg * D);
+        // the head in the caller's tensors
+        const size_t hg = QSTR ? (size_t)b * s.q_bs + (size_t)(hk * G + g) * s.q_hs : ((size_t)b * s.Hq + hk * G + g) * s.qhs * D;
+        const char* qh = (const char*)(q + hg);
+        const char* gh = (const char*)(dout + hg);
         if (cc * MQ + MQ <= L) {  // the whole chunk exists (wave-uniform)
-            const size_t cb = (size_t)(cc * MQ + w * IPW * RPI) * ROWB;
+            const size_t cb = (size_t)(cc * MQ + w * IPW * RPI) * rsb;
 #pragma unroll
             for (int i = 0; i < IPW; ++i) {
-                const unsigned off = (unsigned)lanepart[i % NLP] + (unsigned)(i * RPI * ROWB);
+                const unsigned off = (unsigned)lanepart[i % NLP] + (unsigned)(i * RPI) * rsb;
                 g2l16(qh + cb + off, &sm.q[buf][(w * IPW + i) * 1024]);
                 g2l16(gh + cb + off, &sm.g[buf][(w * IPW + i) * 1024]);
             }
@@ -328,7 +335,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             for (int i = 0; i < IPW; ++i) {
                 const int rr = (w * IPW + i) * RPI + lrow_;
                 const int row = min(cc * MQ + rr, L - 1);
-                const unsigned off = (unsigned)row * (unsigned)ROWB + (unsigned)(lanepart[i % NLP] - lrow_ * ROWB);
+                const unsigned off = (unsigned)row * rsb + (unsigned)(lanepart[i % NLP] - lrow_ * (int)rsb);
                 g2l16(qh + off, &sm.q[buf][(w * IPW + i) * 1024]);
                 g2l16(gh + off, &sm.g[buf][(w * IPW + i) * 1024]);
             }
@@ -620,7 +627,7 @@ struct DqSmem {
     char v[2][BNQ * D * 2];
 };
 
-template <int D, bool GEN, bool PACK>
+template <int D, bool GEN, bool PACK, bool QSTR = false>
 __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                   const bf16_t* __restrict__ v, const float* __restrict__ lse2,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ delta,
@@ -691,10 +698,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         qrow[qb] = wrow0 + 16 * qb + (lane & 15);
         const int qrow_ld = min(qrow[qb], L - 1);
         span_q[qb] = qrow[qb] - win_lo(s, qrow[qb]);  // this row's window reaches span_q positions back
-        rowoff[qb] = ((size_t)b * s.Hq + hq) * s.qhs + qrow_ld;           // in the caller's tensors
+        // element offset of the row in the caller's q, dout and dq
+        rowoff[qb] = QSTR ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)qrow_ld * s.q_rs
+                          : (((size_t)b * s.Hq + hq) * s.qhs + qrow_ld) * D;
         const size_t wrow = ((size_t)b * s.Hq + hq) * (PACK ? s.qhs : L) + qrow_ld;  // in the workspace
-        const bf16_t* qp = q + rowoff[qb] * D + 8 * g4;
-        const bf16_t* gp = dout + rowoff[qb] * D + 8 * g4;
+        const bf16_t* qp = q + rowoff[qb] + 8 * g4;
+        const bf16_t* gp = dout + rowoff[qb] + 8 * g4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
@@ -862,7 +871,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
         if (qrow[qb] < L) {
-            bf16_t* op = dq + rowoff[qb] * D + 4 * g4;
+            bf16_t* op = dq + rowoff[qb] + 4 * g4;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 u32x2 w2;
@@ -879,6 +888,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
                       unsigned stages, hipStream_t st) {
     const BwdPlan pl = make_plan(s);
     const bool gen = s.S != 0 || s.umode != 0;
+    const bool qstr = s.q_rs != 0;  // q, out, dout, dq with the caller's explicit strides
     float* delta = (float*)ws;
     float* lse2 = (float*)(ws + pl.off_lse2);
     float* part = (float*)(ws + pl.off_part);
@@ -888,12 +898,15 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.B * s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
-            out, dout, lse, delta, lse2, nrows, s.L, s.qhs);
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, s.q_bs, s.q_hs, s.q_rs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
         const dim3 grid((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B));
-        if (gen) dkdv_kernel<D, true, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        if (qstr) {
+            if (gen) dkdv_kernel<D, true, true, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+            else dkdv_kernel<D, true, false, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        } else if (gen) dkdv_kernel<D, true, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         else dkdv_kernel<D, true, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -905,7 +918,10 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     }
     if (stages & UNIGIST_BWD_DKDV_WINDOW) {
         const dim3 grid((unsigned)((long)((s.L + BNK - 1) / BNK) * s.Hkv * s.B));
-        if (gen) dkdv_kernel<D, false, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        if (qstr) {
+            if (gen) dkdv_kernel<D, false, true, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+            else dkdv_kernel<D, false, false, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
+        } else if (gen) dkdv_kernel<D, false, true, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         else dkdv_kernel<D, false, false, false><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -913,7 +929,10 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     const int nq = (s.L + BMQ - 1) / BMQ;
     const long nblk = (long)nq * s.Hq * s.B;
     if (nblk > 0x7fffffffL) return hipErrorInvalidValue;
-    if (gen) dq_kernel<D, true, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
+    if (qstr) {
+        if (gen) dq_kernel<D, true, false, true><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
+        else dq_kernel<D, false, false, true><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
+    } else if (gen) dq_kernel<D, true, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
     else dq_kernel<D, false, false><<<dim3((unsigned)nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, nq, NoDocs{});
     return hipGetLastError();
 }
@@ -974,7 +993,7 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
-            out, dout, lse, delta, lse2, nrows, s.L, s.qhs);
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, 0, 0, 0);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const int nd = (int)pp.len.size();

@@ -199,6 +199,16 @@ def test_cache_argument_validation():
     assert u.unigist_prefill_chunk_view(*pv.values()) == 2
     pv.update(q_rows=4096, s=402)
     assert u.unigist_prefill_chunk_view(*pv.values()) == 1
+    # forward / backward with explicit strides of the query-side tensors
+    fs = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, lse=FAKE, B=1, Hq=4, Hkv=2, L=100, D=64, r=4, W=8, sinks=0, window_mode=0,
+              q_bs=100 * 256, q_hs=64, q_rs=256, dt=0)
+    badf = lambda **kw: u.unigist_attn_fwd_strided(*dict(fs, **kw).values())
+    assert badf(q_rs=32) == 1 and badf(q_rs=260) == 1 and badf(q_hs=4) == 1 and badf(out=FAKE + 8) == 1 and badf(dt=1) == 2
+    assert badf(L=1 << 23, q_rs=1 << 12) == 2 and badf(q=None) == 1 and badf(window_mode=3) == 1
+    bs = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, lse=FAKE, dout=FAKE, dq=FAKE, dk=FAKE, dv=FAKE, B=1, Hq=4, Hkv=2, L=100, D=64,
+              r=4, W=8, sinks=0, window_mode=0, q_bs=100 * 256, q_hs=64, q_rs=256, dt=0, ws=FAKE, ws_bytes=1 << 40)
+    badb = lambda **kw: u.unigist_attn_bwd_strided(*dict(bs, **kw).values())
+    assert badb(q_rs=260) == 1 and badb(dq=FAKE + 8) == 1 and badb(ws_bytes=16) == 1 and badb(ws=FAKE + 16) == 1 and badb(dt=1) == 2
     # prefill with explicit strides: multiples of 8 elements, rows that do not overlap, aligned bases
     ps = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
               window_mode=0, p0=500, s=401, cap=1024, q_bs=64 * 256, q_hs=128, q_rs=256, dt=0)

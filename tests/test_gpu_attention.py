@@ -146,3 +146,26 @@ def test_peaked_and_flat_softmax(L, D, r, W, gain, dtype):
     print(case, f"out {err:.3e} bound {2e-3 + vmax * 2.0 ** -8:.3e}", flush=True)
     assert err <= 2e-3 + vmax * 2.0 ** -8, case
     check(case, (torch.from_numpy(o_o),) + tuple(got[1:]), want, dtype)      # lse and the gradients to the usual bar
+
+
+@pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
+def test_projection_layout_gives_the_same_bits(sinks, units, W):
+    # q, out, dout, dq laid out [B, L, Hq, D] in memory (the strided entry points, no transposing copies): the same
+    # kernels on the same numbers, so every result equals the contiguous call's bit for bit; ragged length, two batches
+    B, Hq, Hkv, L, D, r = 2, 8, 2, 1333, 128, 4
+    q, k, v, dout = (t.cuda() for t in synth.attn_inputs(B, Hq, Hkv, L, D, seed=61))
+    out, lse = u.attn_fwd(q, k, v, r, W, sinks=sinks, window_mode=int(units))
+    dq, dk, dv = u.attn_bwd(q, k, v, out, lse, dout, r, W, sinks=sinks, window_mode=int(units))
+    blhd = lambda t: t.transpose(1, 2).contiguous().transpose(1, 2)      # same values, [B, L, H, D] in memory
+    qs, ds = blhd(q), blhd(dout)
+    assert not qs.is_contiguous()
+    out_s, lse_s = u.attn_fwd(qs, k, v, r, W, sinks=sinks, window_mode=int(units))
+    assert out_s.stride() == qs.stride() and torch.equal(out_s, out) and torch.equal(lse_s, lse)
+    dq_s, dk_s, dv_s = u.attn_bwd(qs, k, v, out_s, lse_s, ds, r, W, sinks=sinks, window_mode=int(units))
+    assert dq_s.stride() == qs.stride()
+    assert torch.equal(dq_s, dq) and torch.equal(dk_s, dk) and torch.equal(dv_s, dv)
+    # through autograd, with an upstream gradient in the other layout
+    qa, ka, va = qs.detach().requires_grad_(True), k.detach().requires_grad_(True), v.detach().requires_grad_(True)
+    o = u.gist_attention(qa, ka, va, r, W, sinks=sinks, window_mode=int(units))
+    o.backward(dout)
+    assert torch.equal(o, out) and torch.equal(qa.grad, dq) and torch.equal(ka.grad, dk) and torch.equal(va.grad, dv)
