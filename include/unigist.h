@@ -217,6 +217,22 @@ size_t unigist_attn_bwd_varlen_workspace_ex(int Hq, int Hkv, int T, int D, int r
                                             const int* cu_seqlens, int ndocs, unigist_dtype dt);
 
 /*
+ * The packed calls with explicit strides of q, out, dout, dq, as unigist_attn_fwd_strided has them: element (h, i, d)
+ * lies at h * q_head_stride + i * q_row_stride + d -- (D, Hq * D) for [T, Hq, D] tensors.  k, v, dk, dv stay
+ * [Hkv, T, D], lse [Hq, T]; bf16 only; workspace from unigist_attn_bwd_varlen_workspace_ex.
+ */
+unigist_status unigist_attn_fwd_varlen_strided(const void* q, const void* k, const void* v, void* out, float* lse,
+                                               int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode,
+                                               const int* cu_seqlens, int ndocs, long long q_head_stride,
+                                               long long q_row_stride, unigist_dtype dt, void* hip_stream);
+unigist_status unigist_attn_bwd_varlen_strided(const void* q, const void* k, const void* v, const void* out,
+                                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                                               int Hq, int Hkv, int T, int D, int r, int W, int sinks, int window_mode,
+                                               const int* cu_seqlens, int ndocs, long long q_head_stride,
+                                               long long q_row_stride, unigist_dtype dt, void* workspace,
+                                               size_t workspace_bytes, void* hip_stream);
+
+/*
  * Decode over the compressed KV cache (Sec. 4.3, Fig. 4): the raw tokens that have
  * left the window were physically removed, so every cached key of a sequence is
  * visible; the order of the keys in the cache is irrelevant.

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     unigist_attn_fwd_varlen_ex, unigist_attn_bwd_varlen_ex, unigist_attn_bwd_varlen_workspace_ex,
     unigist_prefill_chunk_view, unigist_prefill_chunk_strided, RingKVCache,
     unigist_attn_fwd_strided, unigist_attn_bwd_strided,
+    unigist_attn_fwd_varlen_strided, unigist_attn_bwd_varlen_strided,
     unigist_cache_ring_rows, unigist_cache_to_ring, unigist_cache_from_ring, unigist_cache_ring_append,
     unigist_cache_rows, unigist_cache_update, unigist_prefill_chunk,
     UNIGIST_WINDOW_SLIDING, UNIGIST_WINDOW_UNITS,

@@ -39,7 +39,8 @@ class _GistAttention(torch.autograd.Function):
 class _GistAttentionVarlen(torch.autograd.Function):
     @staticmethod
     def forward(ctx, q, k, v, r, W, cu_seqlens, sinks, window_mode):
-        q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+        q = q if _b._q_strided(q) else q.contiguous()      # a [T, Hq, D] tensor passed as its [Hq, T, D] view stays
+        k, v = k.contiguous(), v.contiguous()
         cu = [int(x) for x in cu_seqlens]
         out, lse = _b.attn_fwd_varlen(q, k, v, r, W, cu, sinks=sinks, window_mode=window_mode)
         ctx.save_for_backward(q, k, v, out, lse)
@@ -50,8 +51,9 @@ class _GistAttentionVarlen(torch.autograd.Function):
     def backward(ctx, dout):
         q, k, v, out, lse = ctx.saved_tensors
         r, W, cu, sinks, window_mode = ctx.mask
-        dq, dk, dv = _b.attn_bwd_varlen(q, k, v, out, lse, dout.contiguous(), r, W, cu, sinks=sinks,
-                                        window_mode=window_mode)
+        if not _b._q_strided(q):
+            dout = dout.contiguous()
+        dq, dk, dv = _b.attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu, sinks=sinks, window_mode=window_mode)
         return dq, dk, dv, None, None, None, None, None
 
 

@@ -31,6 +31,7 @@ EXPORTS = [
     "unigist_prefill_chunk_ragged", "unigist_prefill_chunk_e4m3", "unigist_prefill_chunk_e4m3_workspace",
     "unigist_attn_fwd_varlen_ex", "unigist_attn_bwd_varlen_ex", "unigist_attn_bwd_varlen_workspace_ex",
     "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided", "unigist_attn_fwd_strided", "unigist_attn_bwd_strided",
+    "unigist_attn_fwd_varlen_strided", "unigist_attn_bwd_varlen_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
 ]
 
@@ -121,6 +122,10 @@ def load():
         fn.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
     lib.unigist_cache_ring_append.restype = ip
     lib.unigist_cache_ring_append.argtypes = [vp, vp, vp, vp, ip, vp, vp, ip, vp] + [ip] * 8 + [vp]
+    lib.unigist_attn_fwd_varlen_strided.restype = ip
+    lib.unigist_attn_fwd_varlen_strided.argtypes = [vp, vp, vp, vp, fp] + [ip] * 8 + [cup, ip] + [C.c_longlong] * 2 + [ip, vp]
+    lib.unigist_attn_bwd_varlen_strided.restype = ip
+    lib.unigist_attn_bwd_varlen_strided.argtypes = [vp] * 9 + [ip] * 8 + [cup, ip] + [C.c_longlong] * 2 + [ip, vp, sz, vp]
     lib.unigist_attn_fwd_strided.restype = ip
     lib.unigist_attn_fwd_strided.argtypes = [vp, vp, vp, vp, fp] + [ip] * 9 + [C.c_longlong] * 3 + [ip, vp]
     lib.unigist_attn_bwd_strided.restype = ip
@@ -349,6 +354,20 @@ def unigist_prefill_chunk_view(q, kc, vc, out, lse, B, Hq, Hkv, C, q_rows, D, r,
                                              s, cap, dt, stream)
 
 
+def unigist_attn_fwd_varlen_strided(q, k, v, out, lse, Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, q_hs, q_rs, dt,
+                                    stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_fwd_varlen_strided(q, k, v, out, lse, Hq, Hkv, T, D, r, W, sinks, window_mode, cu, nd, q_hs,
+                                                  q_rs, dt, stream)
+
+
+def unigist_attn_bwd_varlen_strided(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, sinks, window_mode,
+                                    cu_seqlens, q_hs, q_rs, dt, ws, ws_bytes, stream=None) -> int:
+    cu, nd = _cu(cu_seqlens)
+    return load().unigist_attn_bwd_varlen_strided(q, k, v, out, lse, dout, dq, dk, dv, Hq, Hkv, T, D, r, W, sinks,
+                                                  window_mode, cu, nd, q_hs, q_rs, dt, ws, ws_bytes, stream)
+
+
 def unigist_attn_fwd_strided(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, q_bs, q_hs, q_rs, dt,
                              stream=None) -> int:
     return load().unigist_attn_fwd_strided(q, k, v, out, lse, B, Hq, Hkv, L, D, r, W, sinks, window_mode, q_bs, q_hs, q_rs,
@@ -455,9 +474,9 @@ def n_vis(L, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:
 # ---------------------------------------------------------------- conveniences (allocate outputs, check status)
 def _q_strided(q) -> bool:
     """Is q a bf16 view with a contiguous last axis but not contiguous as a whole (e.g. the transposed view of a
-    [B, L, Hq, D] projection output)?  Such a q goes through the *_strided entry points without a copy."""
+    [B, L, Hq, D] or [T, Hq, D] projection output)?  Such a q goes through the *_strided entry points without a copy."""
     return (q.dtype == torch.bfloat16 and q.is_cuda and not q.is_contiguous() and q.stride(-1) == 1
-            and all(s % 8 == 0 for s in q.stride()[:-1]) and q.stride(2) >= q.shape[3])
+            and all(s % 8 == 0 for s in q.stride()[:-1]) and q.stride(-2) >= q.shape[-1])
 
 
 def attn_fwd(q, k, v, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
@@ -531,12 +550,22 @@ def attn_bwd(q, k, v, out, lse, dout, r, W, workspace=None, stages=UNIGIST_BWD_A
 
 
 def attn_fwd_varlen(q, k, v, r, W, cu_seqlens, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING):
-    """Packed documents: q [Hq,T,D], k/v [Hkv,T,D] on the GPU, cu_seqlens a host sequence -> out, lse [Hq,T]."""
-    _dev(q, k, v)
+    """Packed documents: q [Hq,T,D], k/v [Hkv,T,D] on the GPU, cu_seqlens a host sequence -> out, lse [Hq,T].  A bf16 q
+    that is a strided view (e.g. of a [T, Hq, D] tensor) is taken as it is and out gets the same strides."""
     Hq, T, D = q.shape
     Hkv = k.shape[0]
     if k.shape != (Hkv, T, D) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
         raise UnigistError("q/k/v shapes or dtypes disagree")
+    if _q_strided(q):
+        _dev(k, v)
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        lse = torch.empty(Hq, T, device=q.device, dtype=torch.float32)
+        _check(unigist_attn_fwd_varlen_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                               Hq, Hkv, T, D, int(r), int(W), int(sinks), int(window_mode), cu_seqlens,
+                                               q.stride(0), q.stride(1), _dt(q), _stream()),
+               "unigist_attn_fwd_varlen_strided")
+        return out, lse
+    _dev(q, k, v)
     out = torch.empty_like(q)
     lse = torch.empty(Hq, T, device=q.device, dtype=torch.float32)
     _check(unigist_attn_fwd_varlen_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
@@ -548,11 +577,29 @@ def attn_fwd_varlen(q, k, v, r, W, cu_seqlens, sinks=0, window_mode=UNIGIST_WIND
 
 def attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu_seqlens, workspace=None, sinks=0,
                     window_mode=UNIGIST_WINDOW_SLIDING):
-    """-> dq [Hq,T,D], dk, dv [Hkv,T,D] for packed documents."""
-    _dev(q, k, v, out, lse, dout)
+    """-> dq [Hq,T,D], dk, dv [Hkv,T,D] for packed documents (dq with q's strides if q is a strided view)."""
     Hq, T, D = q.shape
     Hkv = k.shape[0]
     dt = _dt(q)
+    if _q_strided(q) and out.stride() == q.stride() and out.shape == q.shape and dout.shape == q.shape:
+        _dev(k, v, lse)
+        if dout.stride() != q.stride():
+            dout = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device).copy_(dout)
+        need = unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, int(r), int(W), int(sinks), int(window_mode), cu_seqlens, dt)
+        if need == 0:
+            raise UnigistError("unigist_attn_bwd_varlen_workspace_ex: invalid shape or document bounds")
+        if workspace is None:
+            workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+        dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        dk, dv = torch.empty_like(k), torch.empty_like(v)
+        _check(unigist_attn_bwd_varlen_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                               dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), Hq, Hkv, T, D,
+                                               int(r), int(W), int(sinks), int(window_mode), cu_seqlens, q.stride(0),
+                                               q.stride(1), dt, workspace.data_ptr(),
+                                               workspace.numel() * workspace.element_size(), _stream()),
+               "unigist_attn_bwd_varlen_strided")
+        return dq, dk, dv
+    _dev(q, k, v, out, lse, dout)
     if out.shape != q.shape or dout.shape != q.shape or lse.shape != (Hq, T) or lse.dtype != torch.float32:
         raise UnigistError("out/dout/lse shapes or dtypes disagree")
     if k.shape != (Hkv, T, D) or v.shape != k.shape or len({t.dtype for t in (q, k, v, out, dout)}) != 1:

@@ -682,6 +682,47 @@ extern "C" unigist_status unigist_attn_fwd_varlen_ex(const void* q, const void* 
     });
 }
 
+extern "C" unigist_status unigist_attn_fwd_varlen_strided(const void* q, const void* k, const void* v, void* out,
+                                                          float* lse, int Hq, int Hkv, int T, int D, int r, int W,
+                                                          int sinks, int window_mode, const int* cu_seqlens, int ndocs,
+                                                          long long q_head_stride, long long q_row_stride,
+                                                          unigist_dtype dt, void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse) return UNIGIST_EINVAL;
+    if ((st = check_qstrides(q, out, T, D, 0, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, T);
+    s.q_hs = q_head_stride;
+    s.q_rs = (int)q_row_stride;
+    return launch_fwd_mfma_pack(q, k, v, out, lse, s, cu_seqlens, ndocs, (hipStream_t)hip_stream) == hipSuccess
+               ? UNIGIST_OK
+               : UNIGIST_ELAUNCH;
+}
+
+extern "C" unigist_status unigist_attn_bwd_varlen_strided(const void* q, const void* k, const void* v, const void* out,
+                                                          const float* lse, const void* dout, void* dq, void* dk,
+                                                          void* dv, int Hq, int Hkv, int T, int D, int r, int W,
+                                                          int sinks, int window_mode, const int* cu_seqlens, int ndocs,
+                                                          long long q_head_stride, long long q_row_stride,
+                                                          unigist_dtype dt, void* workspace, size_t workspace_bytes,
+                                                          void* hip_stream) {
+    unigist_status st = check_docs(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
+    if (st != UNIGIST_OK) return st;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace) return UNIGIST_EINVAL;
+    if ((st = check_qstrides(q, out, T, D, 0, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    if ((st = check_qstrides(dout, dq, T, D, 0, q_head_stride, q_row_stride, dt)) != UNIGIST_OK) return st;
+    const size_t need = unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, sinks, window_mode, cu_seqlens, ndocs, dt);
+    if (workspace_bytes < need) return UNIGIST_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
+    AttnShape s = doc_shape(Hq, Hkv, T, D, r, W, sinks, window_mode, T);
+    s.q_hs = q_head_stride;
+    s.q_rs = (int)q_row_stride;
+    return launch_bwd_mfma_pack(q, k, v, out, lse, dout, dq, dk, dv, workspace, s, cu_seqlens, ndocs,
+                                (hipStream_t)hip_stream) == hipSuccess
+               ? UNIGIST_OK
+               : UNIGIST_ELAUNCH;
+}
+
 extern "C" size_t unigist_attn_bwd_varlen_workspace(int Hq, int Hkv, int T, int D, int r, int W, const int* cu_seqlens,
                                                     int ndocs, unigist_dtype dt) {
     return unigist_attn_bwd_varlen_workspace_ex(Hq, Hkv, T, D, r, W, 0, UNIGIST_WINDOW_SLIDING, cu_seqlens, ndocs, dt);

@@ -205,10 +205,11 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         s = doc_view(s, docs.len[d]);
         plan_counts(s, pl, pl.segc);  // pl arrives with the launch's segment length only
         const size_t ro = (size_t)docs.c0[d] * D;
-        q += ro;
+        const size_t qro = QSTR ? (size_t)docs.c0[d] * s.q_rs : ro;
+        q += qro;
         k += ro;
         v += ro;
-        dout += ro;
+        dout += qro;
         dk += ro;
         dv += ro;
         lse2 += docs.c0[d];
@@ -645,11 +646,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         s = doc_view(s, docs.len[d]);
         nq = (s.L + BMQ - 1) / BMQ;
         const size_t ro = (size_t)docs.c0[d] * D;
-        q += ro;
+        const size_t qro = QSTR ? (size_t)docs.c0[d] * s.q_rs : ro;
+        q += qro;
         k += ro;
         v += ro;
-        dout += ro;
-        dq += ro;
+        dout += qro;
+        dq += qro;
         lse2 += docs.c0[d];
         delta += docs.c0[d];
     }
@@ -993,7 +995,7 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
-            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, 0, 0, 0);
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, 0, s.q_hs, s.q_rs);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const int nd = (int)pp.len.size();
@@ -1028,15 +1030,12 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     };
     BwdPlan none = {};
     none.segc = pp.segc;
-    const bool gen = s.S != 0 || s.umode != 0;
+    const bool gen = s.S != 0 || s.umode != 0, qstr = s.q_rs != 0;
     e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.n_gt * pl.nseg * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
-                       if (gen)
-                           dkdv_kernel<D, true, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                     part, comp, s, none, t);
-                       else
-                           dkdv_kernel<D, true, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                      part, comp, s, none, t);
+                       auto go = [&](auto kern) { kern<<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, none, t); };
+                       if (qstr) gen ? go(dkdv_kernel<D, true, true, true, true>) : go(dkdv_kernel<D, true, false, true, true>);
+                       else gen ? go(dkdv_kernel<D, true, true, true>) : go(dkdv_kernel<D, true, false, true>);
                    });
     if (e != hipSuccess) return e;
     constexpr int per_tile = 2 * D * BNK;
@@ -1048,18 +1047,16 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     if (e != hipSuccess) return e;
     e = for_chunks([&](int len) { return (long)((len + BNK - 1) / BNK) * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
-                       if (gen)
-                           dkdv_kernel<D, false, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                      part, comp, s, none, t);
-                       else
-                           dkdv_kernel<D, false, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv,
-                                                                                       part, comp, s, none, t);
+                       auto go = [&](auto kern) { kern<<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, none, t); };
+                       if (qstr) gen ? go(dkdv_kernel<D, false, true, true, true>) : go(dkdv_kernel<D, false, false, true, true>);
+                       else gen ? go(dkdv_kernel<D, false, true, true>) : go(dkdv_kernel<D, false, false, true>);
                    });
     if (e != hipSuccess) return e;
     return for_chunks([&](int len) { return (long)((len + BMQ - 1) / BMQ) * s.Hq; },
                       [&](const DocTab& t, unsigned nblk) {
-                          if (gen) dq_kernel<D, true, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
-                          else dq_kernel<D, false, true><<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t);
+                          auto go = [&](auto kern) { kern<<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dq, s, 0, t); };
+                          if (qstr) gen ? go(dq_kernel<D, true, true, true>) : go(dq_kernel<D, false, true, true>);
+                          else gen ? go(dq_kernel<D, true, true>) : go(dq_kernel<D, false, true>);
                       });
 }
 

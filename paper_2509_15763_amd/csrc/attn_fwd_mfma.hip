@@ -76,10 +76,11 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         s = doc_view(s, ext.len[d]);
         nq = (s.L + BM - 1) / BM;
         const size_t ro = (size_t)ext.c0[d] * D;
-        q += ro;
+        const size_t qro = s.q_rs ? (size_t)ext.c0[d] * s.q_rs : ro;  // q and out may have explicit strides
+        q += qro;
         k += ro;
         v += ro;
-        out += ro;
+        out += qro;
         lse += ext.c0[d];
     }
     constexpr int KS = D / 32;            // k-steps of the score MFMA

@@ -209,6 +209,15 @@ def test_cache_argument_validation():
               r=4, W=8, sinks=0, window_mode=0, q_bs=100 * 256, q_hs=64, q_rs=256, dt=0, ws=FAKE, ws_bytes=1 << 40)
     badb = lambda **kw: u.unigist_attn_bwd_strided(*dict(bs, **kw).values())
     assert badb(q_rs=260) == 1 and badb(dq=FAKE + 8) == 1 and badb(ws_bytes=16) == 1 and badb(ws=FAKE + 16) == 1 and badb(dt=1) == 2
+    # the packed calls with explicit strides
+    vs = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, lse=FAKE, Hq=4, Hkv=2, T=100, D=64, r=4, W=8, sinks=0, window_mode=0,
+              cu=[0, 30, 100], q_hs=64, q_rs=256, dt=0)
+    badv = lambda **kw: u.unigist_attn_fwd_varlen_strided(*dict(vs, **kw).values())
+    assert badv(q_rs=260) == 1 and badv(q_rs=32) == 1 and badv(cu=[0, 30, 99]) == 1 and badv(dt=1) == 2 and badv(out=None) == 1
+    wb = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, lse=FAKE, dout=FAKE, dq=FAKE, dk=FAKE, dv=FAKE, Hq=4, Hkv=2, T=100, D=64, r=4,
+              W=8, sinks=0, window_mode=0, cu=[0, 30, 100], q_hs=64, q_rs=256, dt=0, ws=FAKE, ws_bytes=1 << 40)
+    badw = lambda **kw: u.unigist_attn_bwd_varlen_strided(*dict(wb, **kw).values())
+    assert badw(q_hs=12) == 1 and badw(ws_bytes=16) == 1 and badw(dout=FAKE + 8) == 1 and badw(dt=1) == 2
     # prefill with explicit strides: multiples of 8 elements, rows that do not overlap, aligned bases
     ps = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
               window_mode=0, p0=500, s=401, cap=1024, q_bs=64 * 256, q_hs=128, q_rs=256, dt=0)

@@ -220,3 +220,25 @@ def test_every_gradient_row_is_written():
     assert st == 0
     assert not bool(torch.isnan(dq).any()) and not bool(torch.isnan(dk).any()) and not bool(torch.isnan(dv).any())
     assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
+
+
+@pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
+def test_packed_projection_layout_gives_the_same_bits(sinks, units, W):
+    # q, out, dout, dq laid out [T, Hq, D] in memory, as a packed projection output: same bits as the [Hq, T, D] call
+    Hq, Hkv, D, r = 8, 2, 128, 4
+    lens = [700, 0, 33, 1500, 129]
+    cu = [0] + np.cumsum(lens).tolist()
+    q, k, v, dout = (t.cuda() for t in packed_inputs(Hq, Hkv, cu[-1], D, torch.bfloat16, seed=37))
+    kw = dict(sinks=sinks, window_mode=int(units))
+    out, lse = u.attn_fwd_varlen(q, k, v, r, W, cu, **kw)
+    dq, dk, dv = u.attn_bwd_varlen(q, k, v, out, lse, dout, r, W, cu, **kw)
+    thd = lambda t: t.transpose(0, 1).contiguous().transpose(0, 1)        # same values, [T, H, D] in memory
+    qs = thd(q)
+    out_s, lse_s = u.attn_fwd_varlen(qs, k, v, r, W, cu, **kw)
+    assert out_s.stride() == qs.stride() and torch.equal(out_s, out) and torch.equal(lse_s, lse)
+    dq_s, dk_s, dv_s = u.attn_bwd_varlen(qs, k, v, out_s, lse_s, thd(dout), r, W, cu, **kw)
+    assert dq_s.stride() == qs.stride() and torch.equal(dq_s, dq) and torch.equal(dk_s, dk) and torch.equal(dv_s, dv)
+    qa, ka, va = qs.detach().requires_grad_(True), k.detach().requires_grad_(True), v.detach().requires_grad_(True)
+    o = u.gist_attention_varlen(qa, ka, va, r, W, cu, **kw)
+    o.backward(dout)
+    assert torch.equal(o, out) and torch.equal(qa.grad, dq) and torch.equal(ka.grad, dk) and torch.equal(va.grad, dv)
