@@ -148,11 +148,12 @@ def test_peaked_and_flat_softmax(L, D, r, W, gain, dtype):
     check(case, (torch.from_numpy(o_o),) + tuple(got[1:]), want, dtype)      # lse and the gradients to the usual bar
 
 
+@pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
-def test_projection_layout_gives_the_same_bits(sinks, units, W):
+def test_projection_layout_gives_the_same_bits(sinks, units, W, D):
     # q, out, dout, dq laid out [B, L, Hq, D] in memory (the strided entry points, no transposing copies): the same
     # kernels on the same numbers, so every result equals the contiguous call's bit for bit; ragged length, two batches
-    B, Hq, Hkv, L, D, r = 2, 8, 2, 1333, 128, 4
+    B, Hq, Hkv, L, r = 2, 8, 2, 1333, 4
     q, k, v, dout = (t.cuda() for t in synth.attn_inputs(B, Hq, Hkv, L, D, seed=61))
     out, lse = u.attn_fwd(q, k, v, r, W, sinks=sinks, window_mode=int(units))
     dq, dk, dv = u.attn_bwd(q, k, v, out, lse, dout, r, W, sinks=sinks, window_mode=int(units))

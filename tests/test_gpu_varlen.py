@@ -222,10 +222,11 @@ def test_every_gradient_row_is_written():
     assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
 
 
+@pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
-def test_packed_projection_layout_gives_the_same_bits(sinks, units, W):
+def test_packed_projection_layout_gives_the_same_bits(sinks, units, W, D):
     # q, out, dout, dq laid out [T, Hq, D] in memory, as a packed projection output: same bits as the [Hq, T, D] call
-    Hq, Hkv, D, r = 8, 2, 128, 4
+    Hq, Hkv, r = 8, 2, 4
     lens = [700, 0, 33, 1500, 129]
     cu = [0] + np.cumsum(lens).tolist()
     q, k, v, dout = (t.cuda() for t in packed_inputs(Hq, Hkv, cu[-1], D, torch.bfloat16, seed=37))
