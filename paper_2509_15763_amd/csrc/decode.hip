@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __rest
     // G query heads share kv head hk; with G == 1 the grid runs over query heads
     const int hq0 = blockIdx.y * G;
     const int hk = hq0 / (Hq / Hkv);
-    const int n = seqlens ? seqlens[b] : Lk;
+    const int n = seqlens ? min(max(seqlens[b], 0), Lk) : Lk;  // never past the sequence's slab, whatever the caller wrote
     const int per = (((n + nsplit - 1) / nsplit) + kRowsPerIter - 1) / kRowsPerIter * kRowsPerIter;
     const int k0 = split * per;
     const int k1 = min(n, k0 + per);
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
     const int r16 = lane & 15, g4 = lane >> 4;
     const int G = Hq / Hkv;  // <= 15: the merge buffer below holds 4 G (D + 2) floats
     const int split = blockIdx.x, b = blockIdx.z, hk = blockIdx.y, hq0 = hk * G;
-    const int n = seqlens ? seqlens[b] : Lk;
+    const int n = seqlens ? min(max(seqlens[b], 0), Lk) : Lk;  // never past the sequence's slab, whatever the caller wrote
     const int per = (((n + nsplit - 1) / nsplit) + 127) / 128 * 128;
     const int k0 = split * per;
     const int k1 = min(n, k0 + per);
