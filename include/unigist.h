@@ -45,7 +45,8 @@ typedef enum {
     UNIGIST_OK = 0,
     UNIGIST_EINVAL = 1,       /* null pointer, non-positive size, Hq % Hkv != 0, workspace too small */
     UNIGIST_EUNSUPPORTED = 2, /* head dim or dtype the kernels are not built for */
-    UNIGIST_ELAUNCH = 3       /* HIP reported an error at launch */
+    UNIGIST_ELAUNCH = 3,      /* HIP reported an error at launch */
+    UNIGIST_ESCRATCH = 4      /* unigist_decode_noalloc: the problem needs more than the built-in scratch array */
 } unigist_status;
 
 /*
@@ -250,6 +251,25 @@ unigist_status unigist_decode(const void* q, const void* kcache, const void* vca
                               void* hip_stream);
 
 size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt);
+
+/*
+ * unigist_decode for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic and results (bit for bit) as unigist_decode,
+ * without the workspace: the split-K partial results go to a fixed array of
+ * UNIGIST_DECODE_NOALLOC_SCRATCH_BYTES bytes in the library's device image, which every GPU the library runs on
+ * holds until the process ends (its address on the current device is looked up on the first call there; the
+ * stream must belong to the current device).  The call allocates and frees nothing.
+ * A problem for which unigist_decode_workspace(...) exceeds that size is refused with UNIGIST_ESCRATCH and
+ * nothing is launched (the benchmark's serving shape, 64 sequences x 32 heads x 17 408 keys, needs 2.1 MB).
+ * All calls on one GPU share the array: calls that may overlap there (different streams, different host threads)
+ * race on it and must be ordered by the caller; calls on one stream are ordered by the stream.  Nothing of an
+ * earlier call's contents is read: every slot is written before it is used.
+ */
+#define UNIGIST_DECODE_NOALLOC_SCRATCH_BYTES (8u << 20)
+unigist_status unigist_decode_noalloc(const void* q, const void* kcache, const void* vcache, void* out,
+                                      float* lse, int B, int Hq, int Hkv, int Lk_max, const int* seqlens,
+                                      int D, unigist_dtype dt, void* hip_stream);
+size_t unigist_decode_noalloc_scratch_bytes(void);
 
 /*
  * The compressed cache stored in 8 bits (an extension of the decode step of Sec. 4.3, which the paper leaves

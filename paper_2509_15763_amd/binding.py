@@ -33,6 +33,7 @@ EXPORTS = [
     "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided", "unigist_attn_fwd_strided", "unigist_attn_bwd_strided",
     "unigist_attn_fwd_varlen_strided", "unigist_attn_bwd_varlen_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
+    "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes",
 ]
 
 
@@ -97,6 +98,10 @@ def load():
     lib.unigist_attn_bwd_varlen_workspace_ex.argtypes = [ip] * 8 + [cup, ip, ip]
     lib.unigist_decode.restype = ip
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
+    lib.unigist_decode_noalloc.restype = ip
+    lib.unigist_decode_noalloc.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp]
+    lib.unigist_decode_noalloc_scratch_bytes.restype = sz
+    lib.unigist_decode_noalloc_scratch_bytes.argtypes = []
     lib.unigist_quantize_e4m3.restype = ip
     lib.unigist_quantize_e4m3.argtypes = [vp, vp, vp, ip, ip, ip, ip, ip, vp]
     lib.unigist_decode_e4m3.restype = ip
@@ -280,6 +285,14 @@ def unigist_attn_bwd_varlen_workspace(Hq, Hkv, T, D, r, W, cu_seqlens, dt) -> in
 
 def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream=None) -> int:
     return load().unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_bytes, stream)
+
+
+def unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream=None) -> int:
+    return load().unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream)
+
+
+def unigist_decode_noalloc_scratch_bytes() -> int:
+    return load().unigist_decode_noalloc_scratch_bytes()
 
 
 def unigist_quantize_e4m3(x, y, scale, B, H, n, D, dt_in, stream=None) -> int:

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libunigist.so")
-SOURCES = ["api.cpp", "blockmap.cpp", "attn_simple.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "decode.hip", "cache.hip", "probe.hip"]
+SOURCES = ["api.cpp", "blockmap.cpp", "attn_simple.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "decode.hip", "cache.hip", "probe.hip", "noalloc.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

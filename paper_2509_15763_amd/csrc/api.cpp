@@ -72,6 +72,7 @@ extern "C" const char* unigist_status_str(unigist_status s) {
         case UNIGIST_EINVAL: return "invalid argument";
         case UNIGIST_EUNSUPPORTED: return "unsupported head dim, dtype or size";
         case UNIGIST_ELAUNCH: return "HIP launch error";
+        case UNIGIST_ESCRATCH: return "problem exceeds the built-in scratch array of the allocation-free entry point";
     }
     return "unknown status";
 }
