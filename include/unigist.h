@@ -15,8 +15,10 @@
  *
  * Conventions common to every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
- *     allocates and frees no device memory, keeps no state (one exception: the
- *     helper streams of the *_varlen calls, see there), does not synchronise:
+ *     allocates and frees no device memory, keeps no state (exceptions: the
+ *     helper streams of the *_varlen calls, the scratch array of
+ *     unigist_decode_noalloc and the switch of unigist_debug_force_plain_alu, see
+ *     there), does not synchronise:
  *     work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns at once.
  *   - Tensors are contiguous, head-major: q, out, dout, dq are [B, Hq, L, D];
@@ -179,7 +181,7 @@ unigist_status unigist_attn_bwd_strided(const void* q, const void* k, const void
  * bf16: every kernel is launched once for up to 64 documents (the document boundaries travel as a kernel
  * argument and each workgroup looks up the document it belongs to), everything on hip_stream; longer lists of
  * documents take one launch per 64.
- * fp32 (the plain-ALU debug kernels) and bf16 under UNIGIST_DEBUG_PLAIN_ALU=1: one launch sequence per document;
+ * fp32 (the plain-ALU debug kernels) and bf16 under unigist_debug_force_plain_alu(1): one launch sequence per document;
  * the backward spreads the documents over hip_stream and a few helper streams that the library creates once per
  * device (default priority, kept until the process ends -- the one piece of state this library holds); the
  * helpers start after everything already enqueued on hip_stream and hip_stream continues after them, so the
@@ -307,6 +309,14 @@ unigist_status unigist_decode_e4m3(const void* q, const void* kcache, const void
  * cache, k_new/v_new when n_new == 0.  A gather: bit-exact copies, any dtype (UNIGIST_E4M3 included).
  */
 int unigist_cache_rows(int s, int t, int r);
+
+/*
+ * First position inside the local window of query position t (Sec. 4.1, Eq. 3): max(0, t - W + 1) for the sliding
+ * window; for unit windows the first position of the unit W units before t's (t itself for a sink query).  It is
+ * the state `s` a cache evicted down to what query t can see is in (0 for t = -1, the empty cache).  Host
+ * function; -1 for invalid arguments.
+ */
+int unigist_window_start(int t, int r, int W, int sinks, int window_mode);
 unigist_status unigist_cache_update(const void* kc_in, const void* vc_in, int s_old, int t_old, int cap_in,
                                     const void* k_new, const void* v_new, int n_new, int new_rows,
                                     void* kc_out, void* vc_out, int s_new, int cap_out,
@@ -493,6 +503,17 @@ void unigist_blockmap_free(unigist_blockmap* m);
 
 /* Tile sizes the forward / backward kernels use for head dim D (for the live-tile report). */
 void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn);
+
+/*
+ * Debug switch, process-wide: with on != 0 every bf16 call of the attention entry points (forward, backward,
+ * their _ex and _varlen forms) runs on the plain-ALU kernels of the fp32 build instead of the matrix-core
+ * kernels -- a second, independent GPU implementation to compare against (the strided forms, which only the
+ * matrix-core kernels have, then answer UNIGIST_EUNSUPPORTED).  Returns the previous setting.  The initial
+ * setting is 0, or 1 if the environment variable UNIGIST_DEBUG_PLAIN_ALU=1 was set when the library was
+ * loaded; the environment is not consulted afterwards.  Besides the helper streams of the *_varlen calls and the
+ * scratch array of unigist_decode_noalloc this flag is the only state the library keeps.
+ */
+int unigist_debug_force_plain_alu(int on);
 
 /*
  * Measurement aid, not part of the method: the bf16 matrix-core rate the chip sustains on register-resident

@@ -33,7 +33,8 @@ EXPORTS = [
     "unigist_prefill_chunk_view", "unigist_prefill_chunk_strided", "unigist_attn_fwd_strided", "unigist_attn_bwd_strided",
     "unigist_attn_fwd_varlen_strided", "unigist_attn_bwd_varlen_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
-    "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes",
+    "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes", "unigist_debug_force_plain_alu",
+    "unigist_window_start",
 ]
 
 
@@ -100,6 +101,10 @@ def load():
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
     lib.unigist_decode_noalloc.restype = ip
     lib.unigist_decode_noalloc.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp]
+    lib.unigist_window_start.restype = ip
+    lib.unigist_window_start.argtypes = [ip] * 5
+    lib.unigist_debug_force_plain_alu.restype = ip
+    lib.unigist_debug_force_plain_alu.argtypes = [ip]
     lib.unigist_decode_noalloc_scratch_bytes.restype = sz
     lib.unigist_decode_noalloc_scratch_bytes.argtypes = []
     lib.unigist_quantize_e4m3.restype = ip
@@ -289,6 +294,14 @@ def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_b
 
 def unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream=None) -> int:
     return load().unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream)
+
+
+def unigist_window_start(t, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:
+    return load().unigist_window_start(int(t), int(r), int(W), int(sinks), int(window_mode))
+
+
+def unigist_debug_force_plain_alu(on) -> int:
+    return load().unigist_debug_force_plain_alu(int(bool(on)))
 
 
 def unigist_decode_noalloc_scratch_bytes() -> int:
@@ -875,18 +888,16 @@ class RingKVCache:
                                          self.rows.data_ptr(), self.B, self.Hkv, self.D, self.r, self.W, self.sinks,
                                          self.mode, self.dt, _stream()),
                "unigist_cache_ring_append")
-        self.t.add_(active)  # in place, stream-ordered behind the kernel's read of t: the call can be captured in a graph
+        # in place, stream-ordered behind the kernel's read of t (the call can be captured in a graph); a sequence
+        # that did not fit (rows = -1) was left alone and does not advance
+        self.t.add_(active * (self.rows >= 0))
         return self.rows
 
     def to_ragged(self, ragged: "RaggedKVCache"):
         """Back to the layout prefill wants, into `ragged`'s buffers: every sequence in state (first position of the
         window of t, t)."""
-        t = self.t.cpu().tolist()
-        u = self.r + 1
-        if self.mode == UNIGIST_WINDOW_SLIDING:
-            s = [max(0, x - self.W + 1) for x in t]
-        else:
-            s = [x if x < self.sinks else self.sinks + max(0, (x - self.sinks) // u - self.W) * u for x in t]
+        t = self.t.cpu().tolist()  # RaggedKVCache keeps its states on the host: a change of phase, not a per-token step
+        s = [unigist_window_start(x, self.r, self.W, self.sinks, self.mode) for x in t]
         dev = self.kc.device
         sd = torch.tensor(s, dtype=torch.int32).to(dev)
         rows = torch.empty(self.B, dtype=torch.int32, device=dev)

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -18,10 +19,13 @@ namespace {
 
 constexpr int kMaxL = 1 << 23;  // per-head byte offsets (L * D * 2) are kept in 32 bits inside the kernels
 
-bool plain_alu_forced() {
+// Debug switch (unigist_debug_force_plain_alu): bf16 calls take the plain-ALU kernels.  The environment variable
+// UNIGIST_DEBUG_PLAIN_ALU=1 sets its initial value; it is read once, when the library is loaded.
+std::atomic<int> g_plain_alu{[] {
     const char* e = getenv("UNIGIST_DEBUG_PLAIN_ALU");
-    return e && e[0] == '1';
-}
+    return e && e[0] == '1' ? 1 : 0;
+}()};
+bool plain_alu_forced() { return g_plain_alu.load(std::memory_order_relaxed) != 0; }
 
 unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt, int sinks = 0,
                           int window_mode = UNIGIST_WINDOW_SLIDING) {
@@ -31,6 +35,7 @@ unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, un
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
     if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
     if (L > kMaxL || B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
+    if ((long long)B * Hkv > 65535) return UNIGIST_EUNSUPPORTED;  // (batch, kv head) pairs index a grid's z dimension
     return UNIGIST_OK;
 }
 
@@ -76,6 +81,8 @@ extern "C" const char* unigist_status_str(unigist_status s) {
     }
     return "unknown status";
 }
+
+extern "C" int unigist_debug_force_plain_alu(int on) { return g_plain_alu.exchange(on ? 1 : 0); }
 
 extern "C" void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn) {
     (void)D;
@@ -270,6 +277,15 @@ extern "C" unigist_status unigist_decode_e4m3(const void* q, const void* kcache,
     hipError_t e = launch_decode_fp8(q, kcache, vcache, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk_max, seqlens, D,
                                      (float*)workspace, (hipStream_t)hip_stream);
     return e == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
+extern "C" int unigist_window_start(int t, int r, int W, int sinks, int window_mode) {
+    if (t < -1 || r < 1 || W < 1 || sinks < 0) return -1;
+    if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return -1;
+    if (t >= kMaxL) return -1;
+    if (t == -1) return 0;  // no position yet: the empty cache is in state (0, -1)
+    const AttnShape s = make_shape(1, 1, 1, t + 1, 64, r, W, sinks, window_mode);
+    return win_lo(s, t);
 }
 
 extern "C" int unigist_cache_rows(int s, int t, int r) { return unigist_cache_rows_ex(s, t, r, 0); }

@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 import paper_2509_15763_amd as u
@@ -308,3 +310,22 @@ def test_ragged_cache_update_argument_validation():
                             ("kc_out", None, 1), ("kc_in", None, 1), ("k_new", None, 1), ("cap_out", 0, 1), ("r", 0, 1),
                             ("D", 96, 2), ("dt", 7, 2), ("B", 0, 1), ("new_rows", -1, 1)]:
         assert f(**{**good, name: val}) == want, name
+
+
+def test_window_start_gives_the_state_whose_cache_is_the_visible_set():
+    # a cache in state (unigist_window_start(t), t) holds exactly what query t may see (Sec. 4.3 with Eq. 3)
+    import oracle
+    for r, W, sinks, mode in [(4, 7, 0, 0), (2, 1, 0, 0), (3, 50, 0, 0), (4, 2, 5, 1), (2, 1, 0, 1), (3, 3, 9, 0), (5, 1, 2, 1)]:
+        for t in list(range(0, 40)) + [97, 128, 1000]:
+            s = u.unigist_window_start(t, r, W, sinks, mode)
+            assert 0 <= s <= t
+            want = oracle.compressed_cache_positions(t, r, W, sinks=sinks, units=bool(mode))
+            assert np.array_equal(oracle.cache_positions(s, t, r, sinks), want), (r, W, sinks, mode, t)
+    assert u.unigist_window_start(-1, 4, 8) == 0 and u.unigist_window_start(-2, 4, 8) == -1
+    assert u.unigist_window_start(5, 0, 8) == -1 and u.unigist_window_start(5, 4, 0) == -1
+
+
+def test_debug_switch_returns_the_previous_setting():
+    assert u.unigist_debug_force_plain_alu(1) == 0
+    assert u.unigist_debug_force_plain_alu(0) == 1
+    assert u.unigist_debug_force_plain_alu(0) == 0

@@ -20,7 +20,7 @@ def run_gpu(q, k, v, dout, r, W):
     return out, lse, dq, dk, dv
 
 
-def check(case, got, want, dtype, tol_f32=TOL_F32):
+def check(case, got, want, dtype, tol_f32=TOL_F32, tol_lse=TOL_LSE_BF16):
     out, lse, dq, dk, dv = got
     o_o, o_l, o_dq, o_dk, o_dv = want
     errs = dict(out=max_abs(to_np(out), o_o), lse=max_abs(to_np(lse), o_l), dq=rel_l2(to_np(dq), o_dq),
@@ -32,7 +32,7 @@ def check(case, got, want, dtype, tol_f32=TOL_F32):
         assert errs["out"] <= tol_f32 and errs["lse"] <= tol_f32, (case, errs)
         assert max(errs["dq"], errs["dk"], errs["dv"]) <= tol_f32, (case, errs)
     else:
-        assert errs["out"] <= TOL_OUT_BF16 and errs["lse"] <= TOL_LSE_BF16, (case, errs)
+        assert errs["out"] <= TOL_OUT_BF16 and errs["lse"] <= tol_lse, (case, errs)
         assert max(errs["dq"], errs["dk"], errs["dv"]) <= TOL_GRAD_BF16, (case, errs)
 
 
@@ -66,6 +66,11 @@ MID = [
     (1, 2, 1, 9001, 64, 4, 300),
     (1, 4, 1, 5000, 128, 2, 129),
     (2, 4, 2, 4500, 128, 8, 1024),
+    # 8 kv heads (the workgroup order that deals (batch, kv head) pairs to the 8 XCDs) together with a gist phase of
+    # several tiles and several segments, and with a group of two query heads
+    (1, 8, 8, 5000, 128, 4, 129),
+    (1, 16, 8, 9001, 128, 4, 300),
+    (2, 8, 4, 6000, 64, 2, 200),
 ]
 
 
@@ -80,25 +85,27 @@ def test_mid_shapes_match_oracle(B, Hq, Hkv, L, D, r, W):
 
 def test_plain_alu_and_mfma_kernels_agree():
     # the two independent GPU implementations on a shape the oracle would need minutes for
-    import os
     B, Hq, Hkv, L, D, r, W = 1, 8, 2, 20000, 128, 4, 1024
     q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=12)
     a = run_gpu(q, k, v, dout, r, W)
-    os.environ["UNIGIST_DEBUG_PLAIN_ALU"] = "1"
+    assert u.unigist_debug_force_plain_alu(1) == 0
     try:
         b = run_gpu(q, k, v, dout, r, W)
     finally:
-        os.environ["UNIGIST_DEBUG_PLAIN_ALU"] = "0"
+        assert u.unigist_debug_force_plain_alu(0) == 1
     assert max_abs(to_np(a[0]), to_np(b[0])) <= 3.2e-2  # two bf16 roundings of values up to 4
     assert max_abs(to_np(a[1]), to_np(b[1])) <= 1e-4
     for x, y in zip(a[2:], b[2:]):
         assert rel_l2(to_np(x), to_np(y)) <= 1e-2
 
 
-def test_runs_are_bitwise_reproducible():
-    q, k, v, dout = synth.attn_inputs(1, 4, 2, 700, 128, seed=3)
-    a = run_gpu(q, k, v, dout, 4, 64)
-    b = run_gpu(q, k, v, dout, 4, 64)
+@pytest.mark.parametrize("B,Hq,Hkv,L,D,r,W", [(1, 4, 2, 700, 128, 4, 64), (1, 16, 8, 9001, 128, 4, 300),
+                                              (2, 8, 2, 12000, 64, 2, 500)])
+def test_runs_are_bitwise_reproducible(B, Hq, Hkv, L, D, r, W):
+    # no kernel uses atomics: the gist phase's segments (several of them from L > 1024 on) are summed in a fixed order
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=3)
+    a = run_gpu(q, k, v, dout, r, W)
+    b = run_gpu(q, k, v, dout, r, W)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
 
@@ -145,7 +152,8 @@ def test_peaked_and_flat_softmax(L, D, r, W, gain, dtype):
     err = float(np.abs(out - o_o).max())
     print(case, f"out {err:.3e} bound {2e-3 + vmax * 2.0 ** -8:.3e}", flush=True)
     assert err <= 2e-3 + vmax * 2.0 ** -8, case
-    check(case, (torch.from_numpy(o_o),) + tuple(got[1:]), want, dtype)      # lse and the gradients to the usual bar
+    # lse and the gradients to the usual bar (lse is of the size of the logits: a few ulp of them, like the fp32 build)
+    check(case, (torch.from_numpy(o_o),) + tuple(got[1:]), want, dtype, tol_lse=max(TOL_LSE_BF16, 4 * big * 2.0 ** -23))
 
 
 @pytest.mark.parametrize("D", [128, 64])

@@ -1,8 +1,9 @@
 """Parity at the benchmark's full size (32K tokens, GQA 32/8, D=128, r=4, W=1024), in the launch
-configuration bench.py times.  The dense fp64 oracle needs minutes per head at this length, so the
-comparison is on sampled outputs it can compute one by one -- rows of out/lse/dq (row-local) and
-columns of dk/dv (raw keys anywhere, gists whose visibility span is a few thousand rows) -- plus
-identities that hold at any size and cover every element."""
+configuration bench.py times.  One whole kv group (kv head 0 with its four query heads) is compared
+with the dense fp64 oracle element by element: every row of out, lse and dq and every column of
+dk and dv, gist 4 -- which every segment of the gist phase adds to -- included.  The other groups are
+covered on sampled outputs the oracle can compute one by one -- rows of out/lse/dq (row-local) and
+columns of dk/dv -- plus identities that hold at any size and involve every element."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -12,7 +13,7 @@ import torch
 import oracle
 import paper_2509_15763_amd as u
 from paper_2509_15763_amd import synth
-from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, max_abs, rel_l2, to_np
+from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, max_abs, out_ok, rel_l2, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -31,11 +32,51 @@ def full():
     return dict(q=q, k=k, v=v, dout=dout, out=out.cpu(), lse=lse.cpu(), dq=dq.cpu(), dk=dk.cpu(), dv=dv.cpu())
 
 
-def out_tolerance(want):
-    # 1e-2 on the fp32 result; storing out as bf16 adds up to half a bf16 ulp of the value, which by
-    # itself exceeds 1e-2 only where |out| >= 4
-    w = np.abs(want)
-    return np.where(w < 4.0, 1e-2, 1e-2 + w * 2.0 ** -9)
+def test_one_kv_group_element_by_element(full):
+    """kv head 0 and query heads 0-3 against the oracle over all 32768 rows: out to the common bound, lse to 1e-4,
+    dq per 128-row tile and dk, dv per 128-key tile to 2e-2 relative L2 (per tile, so that an error confined to one
+    tile of raw keys cannot hide behind the norm of the gist columns)."""
+    L, r, W, G = CFG["L"], CFG["r"], CFG["W"], CFG["Hq"] // CFG["Hkv"]
+    g = 0
+    k, v = to_np(full["k"][0, g]), to_np(full["v"][0, g])
+
+    def one(h):
+        q, do = to_np(full["q"][0, h]), to_np(full["dout"][0, h])
+        o, l = oracle.attn_fwd_head(q, k, v, r, W)
+        dq, dk, dv = oracle.attn_bwd_head(q, k, v, do, r, W)
+        print(f"  oracle done for head {h}", flush=True)
+        return o, l, dq, dk, dv
+
+    with ThreadPoolExecutor(max_workers=G) as ex:  # one head per thread; numpy releases the GIL inside BLAS
+        res = list(ex.map(one, range(g * G, (g + 1) * G)))
+
+    def tiles(got, want, T=128):
+        e = got - want
+        num = np.sqrt((e.reshape(-1, T, e.shape[-1]) ** 2).sum(axis=(1, 2)))
+        den = np.sqrt((want.reshape(-1, T, want.shape[-1]) ** 2).sum(axis=(1, 2)))
+        return num / den
+
+    assert L % 128 == 0
+    for n, h in enumerate(range(g * G, (g + 1) * G)):
+        o, l, dq, _, _ = res[n]
+        got_o, got_l, got_dq = to_np(full["out"][0, h]), to_np(full["lse"][0, h]), to_np(full["dq"][0, h])
+        eo, el, edq = max_abs(got_o, o), max_abs(got_l, l), tiles(got_dq, dq)
+        print(f"head {h}: out {eo:.3e} lse {el:.3e} dq worst tile {edq.max():.3e} (tile {int(edq.argmax())})", flush=True)
+        assert out_ok(got_o, o), h
+        assert el <= TOL_LSE_BF16, h
+        assert edq.max() <= TOL_GRAD_BF16, (h, int(edq.argmax()))
+    dk = sum(x[3] for x in res)
+    dv = sum(x[4] for x in res)
+    ek, ev = tiles(to_np(full["dk"][0, g]), dk), tiles(to_np(full["dv"][0, g]), dv)
+    print(f"dk worst tile {ek.max():.3e} (tile {int(ek.argmax())}), dv worst tile {ev.max():.3e} "
+          f"(tile {int(ev.argmax())})", flush=True)
+    assert ek.max() <= TOL_GRAD_BF16 and ev.max() <= TOL_GRAD_BF16
+    # the gist columns on their own (each carries contributions of every segment of the gist phase), one by one
+    gists = np.arange(r, L, r + 1)
+    gk = np.linalg.norm(to_np(full["dk"][0, g])[gists] - dk[gists], axis=1) / np.linalg.norm(dk[gists], axis=1)
+    gv = np.linalg.norm(to_np(full["dv"][0, g])[gists] - dv[gists], axis=1) / np.linalg.norm(dv[gists], axis=1)
+    print(f"gist columns: dk worst {gk.max():.3e}, dv worst {gv.max():.3e}", flush=True)
+    assert gk.max() <= TOL_GRAD_BF16 and gv.max() <= TOL_GRAD_BF16
 
 
 def test_sampled_rows(full):
@@ -43,13 +84,13 @@ def test_sampled_rows(full):
     rng = np.random.default_rng(0)
     rows = np.unique(np.concatenate([[0, 1, 4, W - 1, W, W + 1, 127, 128, L - 1, L - 2, L // 2],
                                      rng.integers(0, L, 40)]))
-    for h in (0, 5, 31):
+    for h in (5, 18, 31):
         g = h // G
         q, k, v, do = (to_np(full[n][0, i]) for n, i in (("q", h), ("k", g), ("v", g), ("dout", h)))
         o, l = oracle.attn_fwd_rows(q, k, v, rows, r, W)
         dq = oracle.attn_dq_rows(q, k, v, do, rows, r, W)
         got_o = to_np(full["out"][0, h])[rows]
-        assert (np.abs(got_o - o) <= out_tolerance(o)).all(), h
+        assert out_ok(got_o, o), h
         assert max_abs(to_np(full["lse"][0, h])[rows], l) <= TOL_LSE_BF16
         e = rel_l2(to_np(full["dq"][0, h])[rows], dq)
         print(f"head {h}: out {max_abs(got_o, o):.3e} dq {e:.3e}", flush=True)

@@ -10,14 +10,9 @@ import torch
 import oracle
 import paper_2509_15763_amd as u
 from paper_2509_15763_amd import synth
-from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, TOL_OUT_BF16, max_abs, rel_l2, to_np
+from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, TOL_OUT_BF16, max_abs, out_ok, rel_l2, to_np
 
 pytestmark = pytest.mark.gpu
-
-
-def out_ok(got, want):
-    w = np.abs(want)
-    return (np.abs(got - want) <= np.where(w < 4.0, 1e-2, 1e-2 + w * 2.0 ** -9)).all()
 
 
 def sampled_check(q, k, v, dout, res, B, Hq, Hkv, L, r, W, heads, rows, raw_cols, gist_cols, tag):

@@ -9,7 +9,7 @@ import paper_2509_15763_amd as u
 from paper_2509_15763_amd import synth
 from _parity import max_abs, oracle_fwd_bwd, rel_l2, to_np
 from test_gpu_attention import check
-from test_gpu_full_size import out_tolerance
+from _parity import out_ok
 
 pytestmark = pytest.mark.gpu
 
@@ -103,7 +103,7 @@ def test_full_length_sampled_rows_and_columns():
         hk = h // (Hq // Hkv)
         qn, kn, vn, don = to_np(q[0, h]), to_np(k[0, hk]), to_np(v[0, hk]), to_np(dout[0, h])
         o, l = oracle.attn_fwd_rows(qn, kn, vn, rows, r, W, sinks=sinks, units=True)
-        assert (np.abs(to_np(out[0, h])[rows] - o) <= out_tolerance(o)).all(), h
+        assert out_ok(to_np(out[0, h])[rows], o), h
         assert max_abs(to_np(lse[0, h])[rows], l) <= 1e-2
         g = oracle.attn_dq_rows(qn, kn, vn, don, rows, r, W, sinks=sinks, units=True)
         assert rel_l2(to_np(dq[0, h])[rows], g) <= 2e-2
