@@ -13,7 +13,7 @@ import torch
 import oracle
 import paper_2509_15763_amd as u
 from paper_2509_15763_amd import synth
-from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, max_abs, out_ok, rel_l2, to_np
+from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, check_kv_group, max_abs, out_ok, rel_l2, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -35,48 +35,9 @@ def full():
 def test_one_kv_group_element_by_element(full):
     """kv head 0 and query heads 0-3 against the oracle over all 32768 rows: out to the common bound, lse to 1e-4,
     dq per 128-row tile and dk, dv per 128-key tile to 2e-2 relative L2 (per tile, so that an error confined to one
-    tile of raw keys cannot hide behind the norm of the gist columns)."""
-    L, r, W, G = CFG["L"], CFG["r"], CFG["W"], CFG["Hq"] // CFG["Hkv"]
-    g = 0
-    k, v = to_np(full["k"][0, g]), to_np(full["v"][0, g])
-
-    def one(h):
-        q, do = to_np(full["q"][0, h]), to_np(full["dout"][0, h])
-        o, l = oracle.attn_fwd_head(q, k, v, r, W)
-        dq, dk, dv = oracle.attn_bwd_head(q, k, v, do, r, W)
-        print(f"  oracle done for head {h}", flush=True)
-        return o, l, dq, dk, dv
-
-    with ThreadPoolExecutor(max_workers=G) as ex:  # one head per thread; numpy releases the GIL inside BLAS
-        res = list(ex.map(one, range(g * G, (g + 1) * G)))
-
-    def tiles(got, want, T=128):
-        e = got - want
-        num = np.sqrt((e.reshape(-1, T, e.shape[-1]) ** 2).sum(axis=(1, 2)))
-        den = np.sqrt((want.reshape(-1, T, want.shape[-1]) ** 2).sum(axis=(1, 2)))
-        return num / den
-
-    assert L % 128 == 0
-    for n, h in enumerate(range(g * G, (g + 1) * G)):
-        o, l, dq, _, _ = res[n]
-        got_o, got_l, got_dq = to_np(full["out"][0, h]), to_np(full["lse"][0, h]), to_np(full["dq"][0, h])
-        eo, el, edq = max_abs(got_o, o), max_abs(got_l, l), tiles(got_dq, dq)
-        print(f"head {h}: out {eo:.3e} lse {el:.3e} dq worst tile {edq.max():.3e} (tile {int(edq.argmax())})", flush=True)
-        assert out_ok(got_o, o), h
-        assert el <= TOL_LSE_BF16, h
-        assert edq.max() <= TOL_GRAD_BF16, (h, int(edq.argmax()))
-    dk = sum(x[3] for x in res)
-    dv = sum(x[4] for x in res)
-    ek, ev = tiles(to_np(full["dk"][0, g]), dk), tiles(to_np(full["dv"][0, g]), dv)
-    print(f"dk worst tile {ek.max():.3e} (tile {int(ek.argmax())}), dv worst tile {ev.max():.3e} "
-          f"(tile {int(ev.argmax())})", flush=True)
-    assert ek.max() <= TOL_GRAD_BF16 and ev.max() <= TOL_GRAD_BF16
-    # the gist columns on their own (each carries contributions of every segment of the gist phase), one by one
-    gists = np.arange(r, L, r + 1)
-    gk = np.linalg.norm(to_np(full["dk"][0, g])[gists] - dk[gists], axis=1) / np.linalg.norm(dk[gists], axis=1)
-    gv = np.linalg.norm(to_np(full["dv"][0, g])[gists] - dv[gists], axis=1) / np.linalg.norm(dv[gists], axis=1)
-    print(f"gist columns: dk worst {gk.max():.3e}, dv worst {gv.max():.3e}", flush=True)
-    assert gk.max() <= TOL_GRAD_BF16 and gv.max() <= TOL_GRAD_BF16
+    tile of raw keys cannot hide behind the norm of the gist columns), and every gist column on its own."""
+    res = tuple(full[n] for n in ("out", "lse", "dq", "dk", "dv"))
+    check_kv_group("cfg2", full["q"], full["k"], full["v"], full["dout"], res, 0, 0, CFG["r"], CFG["W"])
 
 
 def test_sampled_rows(full):

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2509_15763_amd as u
 from paper_2509_15763_amd import synth
-from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, TOL_OUT_BF16, max_abs, out_ok, rel_l2, to_np
+from _parity import TOL_GRAD_BF16, TOL_LSE_BF16, TOL_OUT_BF16, check_kv_group, max_abs, out_ok, rel_l2, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -78,6 +78,24 @@ def test_long_context_128k():
     assert all((p + 1) % (r + 1) == 0 for p in gists)
     sampled_check(q, k, v, dout, res, B, Hq, Hkv, L, r, W, [(0, 9), (0, 30)], rows, raw, gists, "cfg3")
     identities(dout, res[3], res[4], Hkv, L)
+    # a whole 128-key tile three quarters into the sequence (raw keys and gists; its gists are reached by the last
+    # 32 768 rows, i.e. by 8 of the gist phase's 32 segments), kv head 6 with its four query heads
+    from concurrent.futures import ThreadPoolExecutor
+    g, G = 6, Hq // Hkv
+    cols = np.arange(3 * L // 4, 3 * L // 4 + 128)
+    kn, vn = to_np(k[0, g]), to_np(v[0, g])
+
+    def one(h):
+        return oracle.attn_dkdv_cols(to_np(q[0, h]), kn, vn, to_np(dout[0, h]), cols, r, W, int(cols[0]), L)
+
+    with ThreadPoolExecutor(max_workers=G) as ex:
+        parts = list(ex.map(one, range(g * G, (g + 1) * G)))
+    gk, gv = sum(p[0] for p in parts), sum(p[1] for p in parts)
+    dk, dv = to_np(res[3][0, g])[cols], to_np(res[4][0, g])[cols]
+    ek = np.linalg.norm(dk - gk, axis=1) / np.linalg.norm(gk, axis=1)
+    ev = np.linalg.norm(dv - gv, axis=1) / np.linalg.norm(gv, axis=1)
+    print(f"cfg3 key tile at {int(cols[0])}: dk worst column {ek.max():.3e}, dv worst column {ev.max():.3e}", flush=True)
+    assert ek.max() <= TOL_GRAD_BF16 and ev.max() <= TOL_GRAD_BF16
 
 
 @pytest.mark.parametrize("r", synth.WORKLOADS["cfg4_ratio_sweep"]["r"])
@@ -93,6 +111,8 @@ def test_ratio_sweep(r):
     gists = [last_gist, last_gist - 40 * (r + 1)]
     sampled_check(q, k, v, dout, res, B, Hq, Hkv, L, r, W, [(3, 17), (1, 2)], rows, raw, gists, f"cfg4 r={r}")
     identities(dout, res[3], res[4], Hkv, L)
+    # one whole kv group (a different batch entry and kv head for every r), every element
+    check_kv_group(f"cfg4 r={r}", q, k, v, dout, res, r % B, (3 * r) % Hkv, r, W)
 
 
 def test_decode_full_size():
