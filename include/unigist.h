@@ -458,7 +458,7 @@ unigist_status unigist_prefill_chunk_ragged(const void* q, const void* kc, const
 /*
  * Block map (Sec. 4.2: with a fixed compression ratio the visible blocks are known in
  * closed form and need not be stored; this builder materialises them on the HOST for
- * tests and for the live-tile report).  The sequence is cut into query tiles of Bm rows
+ * tests and for the live-tile report, from the functions the kernels walk by).  The sequence is cut into query tiles of Bm rows
  * and key tiles of Bn columns.  Query tile t walks two disjoint phases:
  *   window phase: the contiguous key tiles win_first[t] .. win_last[t] (inclusive), pairs
  *                 inside them are subject to the full predicate vis(i,j);
@@ -500,6 +500,57 @@ unigist_status unigist_blockmap_build(int L, int r, int W, int Bm, int Bn, unigi
 unigist_status unigist_blockmap_build_ex(int L, int r, int W, int sinks, int window_mode, int Bm, int Bn,
                                          unigist_blockmap** out);
 void unigist_blockmap_free(unigist_blockmap* m);
+
+/*
+ * The tile walks exactly as the kernels take them (Sec. 4.2: the visible blocks follow from r and W in closed form).
+ * unigist_blockmap_build above and the three calls below evaluate, on the HOST, the very functions the kernels
+ * call for every decision about which tiles to visit, which to skip and which need the in-tile mask, so that the
+ * walks can be checked against the mask rule pair by pair without a GPU.  Step kinds: 0 = not visited (no pair of
+ * it is visible), 1 = visited without mask (every pair of it is visible), 2 = visited with the in-tile mask.
+ *
+ * Row side (forward: 128 query rows per workgroup, 32 keys per step; dQ: 128 rows, 64 keys; a wave owns 32 rows).
+ * Query tile `tile` first walks n_gist_steps steps over the first nfar entries of the compact list of sinks and
+ * gists (entry c < sinks is position c, gist g is position sinks + (r+1) g + r; all of them lie left of wstart and
+ * are visible to every row; only the last step can hold fewer than Bn entries, hence its mask), then
+ * n_window_steps steps over the positions wstart, wstart + Bn, ... .  kind (optional, kind_capacity entries
+ * available): [Bm / 32 waves][n_gist_steps + n_window_steps].
+ */
+typedef enum { UNIGIST_WALK_FWD = 0, UNIGIST_WALK_DQ = 1 } unigist_walk_kernel;
+typedef struct unigist_row_tile_plan {
+    int Bm, Bn, rows_per_wave;
+    int wstart, nfar, n_gist_steps, n_window_steps;
+} unigist_row_tile_plan;
+unigist_status unigist_plan_row_tile(int L, int r, int W, int sinks, int window_mode, int kernel, int tile,
+                                     unigist_row_tile_plan* out, int kind_capacity, signed char* kind);
+/*
+ * Key side (dK/dV; Sec. 4.2 applied in the transposed direction).  Query rows come in chunks of chunk_rows = 64 (two
+ * blocks of 32), keys in tiles of key_tile = 128 (32 per wave).  Chunk c reaches the compact entries at positions
+ * left of far(c) in the gist phase and every key from far(c) on in the window phase.  The gist phase runs one
+ * workgroup per (segment of seg_chunks chunks, compact tile the segment reaches: tiles 0 .. slot0[sg+1]-slot0[sg]-1
+ * for segment sg) and leaves one fp32 partial [dK^T | dV^T] block per such pair in slot slot0[sg] + tile, which a
+ * reduction sums over the segments in ascending order; the window phase runs one workgroup per key tile.
+ * partial_bytes / reduced_bytes: the two parts of unigist_attn_bwd_workspace_ex that hold those blocks
+ * (2 * D * 128 floats each), workspace_bytes: all of it (with two floats per query row and head in front).
+ */
+typedef struct unigist_bwd_plan {
+    int key_tile, chunk_rows;
+    int n_chunks, n_key_tiles, n_gist_tiles;
+    int seg_chunks, n_segs;
+    int slot0[33];
+    size_t partial_bytes, reduced_bytes, workspace_bytes;
+} unigist_bwd_plan;
+unigist_status unigist_bwd_plan_build(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                      int window_mode, unigist_bwd_plan* out);
+/*
+ * One dK/dV workgroup of that plan (bf16 kernels): gist_phase != 0: compact tile `tile` of segment `seg`; else key
+ * tile `tile` of the window phase (seg ignored).  c_lo .. c_hi (out): the chunks it streams, for every query head
+ * of its group.  Optional, for those chunks in order (capacity = chunks the arrays can take): nfar[c] = compact
+ * entries chunk c reaches in the gist phase (entry x of the tile counts for chunk c iff 128 tile + x < nfar[c]; 0 in
+ * the window phase), kind: [4 waves][chunks][2 blocks of 32 rows].
+ */
+unigist_status unigist_plan_key_tile(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks, int window_mode,
+                                     int gist_phase, int tile, int seg, int* c_lo, int* c_hi, int capacity, int* nfar,
+                                     signed char* kind);
 
 /* Tile sizes the forward / backward kernels use for head dim D (for the live-tile report). */
 void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn);

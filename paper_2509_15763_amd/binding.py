@@ -34,7 +34,7 @@ EXPORTS = [
     "unigist_attn_fwd_varlen_strided", "unigist_attn_bwd_varlen_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
     "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes", "unigist_debug_force_plain_alu",
-    "unigist_window_start",
+    "unigist_window_start", "unigist_plan_row_tile", "unigist_bwd_plan_build", "unigist_plan_key_tile",
 ]
 
 
@@ -48,6 +48,16 @@ class _BlockMap(C.Structure):
                                                    "qt_last", "gist_qt_first")] + \
                [(n, C.c_int64) for n in ("live_tiles", "masked_tiles", "causal_tiles", "n_vis")] + \
                [(n, C.c_int) for n in ("sinks", "window_mode")]
+
+
+class _RowTilePlan(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("Bm", "Bn", "rows_per_wave", "wstart", "nfar", "n_gist_steps", "n_window_steps")]
+
+
+class _BwdPlan(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("key_tile", "chunk_rows", "n_chunks", "n_key_tiles", "n_gist_tiles", "seg_chunks",
+                                       "n_segs")] + [("slot0", C.c_int * 33)] + \
+               [(n, C.c_size_t) for n in ("partial_bytes", "reduced_bytes", "workspace_bytes")]
 
 
 def lib_path() -> str:
@@ -101,6 +111,12 @@ def load():
     lib.unigist_decode.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp, sz, vp]
     lib.unigist_decode_noalloc.restype = ip
     lib.unigist_decode_noalloc.argtypes = [vp, vp, vp, vp, fp, ip, ip, ip, ip, vp, ip, ip, vp]
+    lib.unigist_plan_row_tile.restype = ip
+    lib.unigist_plan_row_tile.argtypes = [ip] * 7 + [C.POINTER(_RowTilePlan), ip, vp]
+    lib.unigist_bwd_plan_build.restype = ip
+    lib.unigist_bwd_plan_build.argtypes = [ip] * 9 + [C.POINTER(_BwdPlan)]
+    lib.unigist_plan_key_tile.restype = ip
+    lib.unigist_plan_key_tile.argtypes = [ip] * 12 + [C.POINTER(ip), C.POINTER(ip), ip, vp, vp]
     lib.unigist_window_start.restype = ip
     lib.unigist_window_start.argtypes = [ip] * 5
     lib.unigist_debug_force_plain_alu.restype = ip
@@ -294,6 +310,47 @@ def unigist_decode(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, ws, ws_b
 
 def unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream=None) -> int:
     return load().unigist_decode_noalloc(q, kc, vc, out, lse, B, Hq, Hkv, Lk, seqlens, D, dt, stream)
+
+
+UNIGIST_WALK_FWD, UNIGIST_WALK_DQ = 0, 1
+
+
+def unigist_plan_row_tile(L, r, W, sinks, window_mode, kernel, tile) -> dict:
+    """The forward (kernel = UNIGIST_WALK_FWD) or dQ walk of query tile `tile`, as a dict; "kind" is an int8 numpy
+    array [waves, steps] (0 skipped, 1 no mask, 2 masked)."""
+    import numpy as np
+    p = _RowTilePlan()
+    _check(load().unigist_plan_row_tile(L, r, W, sinks, window_mode, kernel, tile, C.byref(p), 0, None),
+           "unigist_plan_row_tile")
+    nw, ns = p.Bm // p.rows_per_wave, p.n_gist_steps + p.n_window_steps
+    kind = np.zeros((nw, ns), dtype=np.int8)
+    _check(load().unigist_plan_row_tile(L, r, W, sinks, window_mode, kernel, tile, C.byref(p), kind.size,
+                                        kind.ctypes.data), "unigist_plan_row_tile")
+    d = {n: getattr(p, n) for n, _ in _RowTilePlan._fields_}
+    d["kind"] = kind
+    return d
+
+
+def unigist_bwd_plan_build(B, Hq, Hkv, L, D, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> dict:
+    p = _BwdPlan()
+    _check(load().unigist_bwd_plan_build(B, Hq, Hkv, L, D, r, W, sinks, window_mode, C.byref(p)), "unigist_bwd_plan_build")
+    d = {n: getattr(p, n) for n, _ in _BwdPlan._fields_ if n != "slot0"}
+    d["slot0"] = list(p.slot0)[: p.n_segs + 1]
+    return d
+
+
+def unigist_plan_key_tile(B, Hq, Hkv, L, D, r, W, sinks, window_mode, gist_phase, tile, seg=0) -> dict:
+    """One dK/dV workgroup: {"c_lo", "c_hi", "nfar": int32 [chunks], "kind": int8 [4 waves, chunks, 2 row blocks]}."""
+    import numpy as np
+    lo, hi = C.c_int(0), C.c_int(-1)
+    args = (B, Hq, Hkv, L, D, r, W, sinks, window_mode, int(bool(gist_phase)), tile, seg)
+    _check(load().unigist_plan_key_tile(*args, C.byref(lo), C.byref(hi), 0, None, None), "unigist_plan_key_tile")
+    n = max(0, hi.value - lo.value + 1)
+    nfar = np.zeros(max(n, 1), dtype=np.int32)
+    kind = np.zeros((4, max(n, 1), 2), dtype=np.int8)
+    _check(load().unigist_plan_key_tile(*args, C.byref(lo), C.byref(hi), n, nfar.ctypes.data, kind.ctypes.data),
+           "unigist_plan_key_tile")
+    return {"c_lo": lo.value, "c_hi": hi.value, "nfar": nfar[:n], "kind": kind[:, :n]}
 
 
 def unigist_window_start(t, r, W, sinks=0, window_mode=UNIGIST_WINDOW_SLIDING) -> int:

@@ -39,34 +39,6 @@ unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, un
     return UNIGIST_OK;
 }
 
-AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks = 0,
-                     int window_mode = UNIGIST_WINDOW_SLIDING) {
-    AttnShape s;
-    s.B = B;
-    s.Hq = Hq;
-    s.Hkv = Hkv;
-    s.L = L;
-    s.D = D;
-    s.rp1 = r >= L ? L + 1 : r + 1;  // r >= L: no position holds a gist
-    s.W = W > L ? L : W;
-    s.scale = 1.0f / sqrtf((float)D);
-    s.S = sinks > L ? L : sinks;
-    s.umode = window_mode == UNIGIST_WINDOW_UNITS;
-    s.qhs = L;
-    s.kvhs = L;
-    s.Lq = L;
-    s.qpos0 = 0;
-    s.kv_rows = L;
-    s.s0 = 0;
-    s.ngb = 0;
-    s.kscale = nullptr;
-    s.vscale = nullptr;
-    s.q_bs = 0;
-    s.q_hs = 0;
-    s.q_rs = 0;
-    return s;
-}
-
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace

@@ -31,76 +31,19 @@
 #include <vector>
 
 #include "mfma_common.h"
+#include "plan.h"
 
 namespace unigist {
 namespace {
 
 constexpr int NT = 256;
-constexpr int BNK = 128;  // keys per dkdv workgroup
-constexpr int MQ = 64;    // query rows per dkdv step
-constexpr int BMQ = 128;  // query rows per dq workgroup
-constexpr int BNQ = 64;   // keys per dq step
+constexpr int BMQ = kDqBm;  // query rows per dq workgroup
+constexpr int BNQ = kDqBn;  // keys per dq step
 constexpr int PFS = 2, PFT = 2;  // dq: LDS fragment reads issued this many MFMA groups ahead (S/dP phase, dQ phase)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // bits 0 .. n-1 set (none for n <= 0, all for n >= 32)
 __device__ __forceinline__ unsigned below_bits(int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; }
-
-struct BwdPlan {
-    int NC;      // query chunks of MQ rows
-    int n_gt;    // compact gist tiles (BNK gists each) seen by some chunk
-    int segc;    // chunks per segment
-    int nseg;    // segments
-    size_t off_lse2, off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
-};
-
-// A query chunk c (MQ rows from 64 c) reaches the always-visible positions (sinks, gists) left of far(c) in the
-// gist phase and everything from far(c) on in the window phase.  far is a multiple of BNK, non-decreasing in c.
-__host__ __device__ inline int far_of_chunk(const AttnShape& s, int c) { return (win_lo(s, c * MQ) / BNK) * BNK; }
-__host__ __device__ inline int nfar_of_chunk(const AttnShape& s, int c) { return count_always(s, far_of_chunk(s, c)); }
-
-// first chunk in [0, NC] whose gist phase holds more than x entries (NC if none).  The x-th entry of the compact
-// list sits at position p, so the condition is far(c) > p; far is monotone in c and the search needs no division
-// in the sliding mode.
-__host__ __device__ inline int first_chunk_with_more_far(const AttnShape& s, int NC, int x) {
-    const int p = pos_of_always(s, x);
-    if (!s.umode) {  // win_lo(64 c) = 64 c - W + 1 has to reach the 128-boundary right of p
-        const long long c = ((long long)(p / BNK + 1) * BNK + s.W - 1 + MQ - 1) / MQ;
-        return c < NC ? (int)c : NC;
-    }
-    int lo = 0, hi = NC;  // answer in [lo, hi]
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (far_of_chunk(s, mid) > p) hi = mid;
-        else lo = mid + 1;
-    }
-    return lo;
-}
-// last chunk in [c0, NC) whose window phase still starts at or before position j0 (far <= j0); requires far(c0) <= j0
-__host__ __device__ inline int last_chunk_with_far_le(const AttnShape& s, int NC, int c0, int j0) {
-    if (!s.umode) {  // win_lo(64 c) = 64 c - W + 1 has to stay left of j0 + 128
-        const long long c = ((long long)j0 + BNK + s.W - 2) / MQ;
-        return c < NC - 1 ? (int)c : NC - 1;
-    }
-    int lo = c0, hi = NC - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (far_of_chunk(s, mid) <= j0) lo = mid;
-        else hi = mid - 1;
-    }
-    return lo;
-}
-
-// The counts of a plan, given the segment length the launch asks for (pick_segc; the workgroups of a packed
-// launch recompute the counts for their document).  No more than 32 segments per gist tile.
-__host__ __device__ inline void plan_counts(const AttnShape& s, BwdPlan& p, int segc) {
-    p.NC = (s.L + MQ - 1) / MQ;
-    const int nfar_max = nfar_of_chunk(s, p.NC - 1);
-    p.n_gt = (nfar_max + BNK - 1) / BNK;
-    p.segc = segc;
-    while ((p.NC + p.segc - 1) / p.segc > 32) p.segc *= 2;
-    p.nseg = (p.NC + p.segc - 1) / p.segc;
-}
 
 // chunk steps (per kv head) of the gist phase of one sequence: every gist tile is walked by the chunks from the
 // first one that has it left of its window phase to the last
@@ -122,14 +65,15 @@ int pick_segc(long steps) { return steps / (512 * 5) >= 32 ? 32 : 16; }
 BwdPlan make_plan(const AttnShape& s) {
     BwdPlan p;
     plan_counts(s, p, pick_segc(gist_chunk_steps(s) * s.B * s.Hkv));
+    plan_slots(s, p);
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_lse2 = off;  // lse * log2(e), written by the delta pass
     off += ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
-    p.off_part = off;
-    off += (size_t)s.B * s.Hkv * p.n_gt * p.nseg * 2 * s.D * BNK * sizeof(float);
+    p.off_part = off;  // one [2][D][BNK] fp32 block per (batch, kv head, segment, compact tile the segment reaches)
+    off += (size_t)s.B * s.Hkv * p.slot0[p.nseg] * 2 * s.D * BNK * sizeof(float);
     off = (off + a) & ~a;
-    p.off_comp = off;
+    p.off_comp = off;  // their sums over the segments: one block per (batch, kv head, compact tile)
     off += (size_t)s.B * s.Hkv * p.n_gt * 2 * s.D * BNK * sizeof(float);
     p.total = (off + a) & ~a;
     return p;
@@ -248,20 +192,37 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     // ---- which keys, which query chunks
     int tile, c_lo, c_hi;  // chunks c_lo .. c_hi inclusive
     int seg = 0;
+    int slot = 0, nslots = 0;  // gist phase: the workgroup's slot among the nslots partial sums of its (batch, kv head)
     if (GIST) {
-        // segment-major, late (fully populated) segments first: the workgroups running together on an
-        // XCD then stream the same Q/dO chunks of the same head through its L2
-        seg = pl.nseg - 1 - unit / pl.n_gt;
-        tile = unit % pl.n_gt;
-        const int cf = first_chunk_with_more_far(s, pl.NC, tile * BNK);
-        c_lo = max(cf, seg * pl.segc);
-        c_hi = min(pl.NC, (seg + 1) * pl.segc) - 1;
-        if (c_lo > c_hi) return;  // this segment lies before the tile becomes visible (uniform exit)
+        // One workgroup per (segment, compact tile the segment reaches), segment-major, late (fully populated)
+        // segments first: the workgroups running together on an XCD then stream the same Q/dO chunks of the same
+        // head through its L2.  unit counts the slots of pl.slot0 from the last segment down.
+        seg = pl.nseg - 1;
+        if constexpr (PACK) {  // the document's plan has no table: sum the segments' tile counts
+            int rem = unit, nt;
+            while ((nt = seg_tiles(s, pl, seg)) <= rem && seg > 0) {
+                rem -= nt;
+                --seg;
+            }
+            tile = rem;
+            slot = tile;
+            for (int sg = 0; sg < seg; ++sg) slot += seg_tiles(s, pl, sg);
+            nslots = slot - tile + nt + (unit - rem);
+        } else {
+            nslots = pl.slot0[pl.nseg];
+            while (seg > 0 && nslots - pl.slot0[seg] <= unit) --seg;
+            tile = unit - (nslots - pl.slot0[seg + 1]);
+            slot = pl.slot0[seg] + tile;
+        }
+        const ChunkRange cr = gist_tile_chunks(s, pl, tile, seg);
+        c_lo = cr.c_lo;
+        c_hi = cr.c_hi;
+        if (c_lo > c_hi) return;  // cannot happen for a slot of the plan (uniform exit all the same)
     } else {
         tile = unit;
-        const int j0 = tile * BNK;
-        c_lo = j0 / MQ;
-        c_hi = last_chunk_with_far_le(s, pl.NC, c_lo, j0);
+        const ChunkRange cr = window_tile_chunks(s, pl, tile);
+        c_lo = cr.c_lo;
+        c_hi = cr.c_hi;
     }
     const int key0 = tile * BNK + 32 * w;      // first key (position, or compact gist index) of the wave
     // The wave's 32 keys are two 16-key blocks kb = 0, 1; this lane's keys are key0 + 16 kb + r16.
@@ -296,9 +257,9 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             avT[db][kb] = zero4();
         }
     }
-    // last row that has the wave's first key in its window (rows >= L are excluded separately)
+    // last row that has the wave's first key in its window
     int hi_w0 = 0;
-    if constexpr (!GIST && GEN) hi_w0 = win_hi(s, min(key0, L - 1));
+    if constexpr (!GIST) hi_w0 = win_hi(s, min(key0, L - 1));
 
     // ---- staging of the Q / dO chunk: direct global->LDS loads
     const int nch = c_hi - c_lo + 1;
@@ -369,7 +330,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 #pragma unroll
         for (int qb = 0; qb < MQ / 32; ++qb) {
             const int qb0 = q0 + 32 * qb;  // first query row of the block
-            if (!GIST && qb0 + 31 < key0) continue;  // every row is left of every key of the wave
+            // every row left of every key of the wave: nothing to do (the gist phase never skips)
+            if (!GIST && UNIGIST_WINDOW_BLOCK_SKIPPED(key0, qb0)) continue;
 
             // offsets of this query block; the XORs below touch bits 5..7 only, the block offset bits >= 13
             int rb = roff0 + 32 * qb * ROWB, tb = toff0 + 32 * qb * ROWB;
@@ -414,9 +376,8 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             }
             // ---- P and dS
             bool masked;
-            if (GIST) masked = key0 + 31 >= nfar || qb0 + 31 >= L;
-            else if constexpr (GEN) masked = !(key0 + 31 <= qb0 && qb0 + 31 <= hi_w0 && qb0 + 31 < L);
-            else masked = !(key0 + 31 <= qb0 && qb0 + 31 - key0 < s.W && qb0 + 31 < L);
+            if (GIST) masked = UNIGIST_GIST_BLOCK_MASKED(key0, qb0, nfar, L);
+            else masked = UNIGIST_WINDOW_BLOCK_MASKED(key0, qb0, hi_w0, L);
             f32x4 l4[2];
 #pragma unroll
             for (int qs = 0; qs < 2; ++qs) l4[qs] = *(const f32x4*)(&sm.lse2[BUF][32 * qb + 16 * qs + 4 * g4]);
@@ -527,8 +488,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         // fp32 partials, transposed: [dK^T | dV^T][d][BNK keys]
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            float* o = part + ((((size_t)b * s.Hkv + hk) * pl.n_gt + tile) * pl.nseg + seg) * (2 * D * BNK) + 32 * w +
-                       16 * kb + r16;
+            float* o = part + (((size_t)b * s.Hkv + hk) * nslots + slot) * (2 * D * BNK) + 32 * w + 16 * kb + r16;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -584,19 +544,18 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
 
 // ------------------------------------------------------------------ 3. sum the segments of each gist tile
 __global__ __launch_bounds__(NT) void gist_reduce_kernel(const float* __restrict__ part, float* __restrict__ comp,
-                                                        int n_gt, int nseg, int segc, int NC, AttnShape s,
-                                                        int per_tile) {
+                                                        BwdPlan pl, AttnShape s, int per_tile) {
     // grid: x = slices of a tile's 2*D*BNK floats (four per thread, per_tile is a multiple of 4), y = tile,
     // z = (b, hk).  The segments are added in ascending order, so the result does not depend on the launch.
     const int gt = blockIdx.y;
-    const size_t t = (size_t)blockIdx.z * n_gt + gt;
     const int idx = 4 * (blockIdx.x * NT + threadIdx.x);
     if (idx >= per_tile) return;
-    const int cf = first_chunk_with_more_far(s, NC, gt * BNK);
+    const int cf = first_chunk_with_more_far(s, pl.NC, gt * BNK);
+    const float* pp = part + (size_t)blockIdx.z * pl.slot0[pl.nseg] * per_tile;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (cf < NC)
-        for (int sg = cf / segc; sg < nseg; ++sg) acc += *(const f32x4*)(part + (t * nseg + sg) * per_tile + idx);
-    *(f32x4*)(comp + t * per_tile + idx) = acc;
+    if (cf < pl.NC)  // the tile has a slot in every segment from that of its first chunk on
+        for (int sg = cf / pl.segc; sg < pl.nseg; ++sg) acc += *(const f32x4*)(pp + (size_t)(pl.slot0[sg] + gt) * per_tile + idx);
+    *(f32x4*)(comp + ((size_t)blockIdx.z * pl.n_gt + gt) * per_tile + idx) = acc;
 }
 
 // The same for a packed launch.  grid: x = slot of comp (a document's slots are its (kv head, gist tile) pairs,
@@ -612,11 +571,17 @@ __global__ __launch_bounds__(NT) void gist_reduce_pack_kernel(const float* __res
     plan_counts(s, pl, segc);
     const int gt = t % pl.n_gt;
     const int cf = first_chunk_with_more_far(s, pl.NC, gt * BNK);
-    const float* pp = part + (size_t)docs.part0[d] * per_tile;
+    int nslots = 0;
+    for (int sg = 0; sg < pl.nseg; ++sg) nslots += seg_tiles(s, pl, sg);
+    const float* pp = part + ((size_t)docs.part0[d] + (size_t)(t / pl.n_gt) * nslots) * per_tile;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (cf < pl.NC)
-        for (int sg = cf / pl.segc; sg < pl.nseg; ++sg)
-            acc += *(const f32x4*)(pp + ((size_t)t * pl.nseg + sg) * per_tile + idx);
+    if (cf < pl.NC) {
+        int base = 0;  // first slot of segment sg
+        for (int sg = 0; sg < pl.nseg; ++sg) {
+            if (sg >= cf / pl.segc) acc += *(const f32x4*)(pp + (size_t)(base + gt) * per_tile + idx);
+            base += seg_tiles(s, pl, sg);
+        }
+    }
     *(f32x4*)(comp + ((size_t)docs.comp0[d] + t) * per_tile + idx) = acc;
 }
 
@@ -723,12 +688,11 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         for (int db = 0; db < DB; ++db) acc[db][qb] = zero4();
     }
 
-    const int lo = win_lo(s, i0);
-    const int wstart = (lo / BNQ) * BNQ;          // first position of the window phase
-    const int nfar = count_always(s, wstart);      // sinks and gists strictly left of it
-    const int ngt = (nfar + BNQ - 1) / BNQ;
-    const int nwin = (i1 - wstart) / BNQ + 1;
-    const int ntiles = ngt + nwin;
+    const RowWalk walk = row_walk(s, i0, i1, BNQ);
+    const int wstart = walk.wstart;                // first position of the window phase
+    const int nfar = walk.nfar;                    // sinks and gists strictly left of it
+    const int ngt = walk.ngt;
+    const int ntiles = ngt + walk.nwin;
     const int lo_wlast = win_lo(s, wrow0 + 31);    // window start of the wave's last row
     const int S = s.S;
 
@@ -767,17 +731,13 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const char* kt = sm.k[BUF];
         const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
-        const int j0 = gist_tile ? it * BNQ : wstart + (it - ngt) * BNQ;
-        if (!gist_tile && j0 > wrow0 + 31) return;
+        const int j0 = row_step_first(walk, it, BNQ);
+        const int kind = row_step_kind(walk, it, BNQ, wrow0, wrow0 + 31, lo_wlast);
+        if (kind == STEP_SKIP) return;
 
-        bool masked;
+        const bool masked = kind == STEP_MASKED;
         unsigned long long gm = 0ull;  // bit t: the key at offset t from j0 holds a sink or a gist
-        if (gist_tile) {
-            masked = j0 + BNQ > nfar;
-        } else {
-            masked = !(j0 + BNQ - 1 <= wrow0 && j0 >= lo_wlast);
-            if (masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
-        }
+        if (!gist_tile && masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
 
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
@@ -904,7 +864,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
-        const dim3 grid((unsigned)((long)pl.n_gt * pl.nseg * s.Hkv * s.B));
+        const dim3 grid((unsigned)((long)pl.slot0[pl.nseg] * s.Hkv * s.B));
         if (qstr) {
             if (gen) dkdv_kernel<D, true, true, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
             else dkdv_kernel<D, true, false, false, true><<<grid, NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, pl, NoDocs{});
@@ -914,8 +874,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_GIST_REDUCE)) {
         const int per_tile = 2 * D * BNK;
-        gist_reduce_kernel<<<dim3((per_tile / 4 + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(
-            part, comp, pl.n_gt, pl.nseg, pl.segc, pl.NC, s, per_tile);
+        gist_reduce_kernel<<<dim3((per_tile / 4 + NT - 1) / NT, pl.n_gt, s.B * s.Hkv), NT, 0, st>>>(part, comp, pl, s, per_tile);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & UNIGIST_BWD_DKDV_WINDOW) {
@@ -960,11 +919,12 @@ PackPlan make_pack_plan(const AttnShape& s, const int* cu, int ndocs) {
     for (int d : order) {
         BwdPlan pl;
         plan_counts(doc_view(s, cu[d + 1] - cu[d]), pl, pp.segc);
+        plan_slots(doc_view(s, cu[d + 1] - cu[d]), pl);
         pp.c0.push_back(cu[d]);
         pp.len.push_back(cu[d + 1] - cu[d]);
         pp.part0.push_back((int)nslot_part);
         pp.comp0.push_back((int)nslot_comp);
-        nslot_part += (size_t)s.Hkv * pl.n_gt * pl.nseg;
+        nslot_part += (size_t)s.Hkv * pl.slot0[pl.nseg];
         nslot_comp += (size_t)s.Hkv * pl.n_gt;
     }
     const size_t a = 255, per_tile = (size_t)2 * s.D * BNK * sizeof(float);
@@ -1026,12 +986,13 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
     auto counts = [&](int len) {
         BwdPlan pl;
         plan_counts(doc_view(s, len), pl, pp.segc);
+        plan_slots(doc_view(s, len), pl);
         return pl;
     };
     BwdPlan none = {};
     none.segc = pp.segc;
     const bool gen = s.S != 0 || s.umode != 0, qstr = s.q_rs != 0;
-    e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.n_gt * pl.nseg * s.Hkv; },
+    e = for_chunks([&](int len) { const BwdPlan pl = counts(len); return (long)pl.slot0[pl.nseg] * s.Hkv; },
                    [&](const DocTab& t, unsigned nblk) {
                        auto go = [&](auto kern) { kern<<<dim3(nblk), NT, 0, st>>>(q, k, v, lse2, dout, delta, dk, dv, part, comp, s, none, t); };
                        if (qstr) gen ? go(dkdv_kernel<D, true, true, true, true>) : go(dkdv_kernel<D, true, false, true, true>);
@@ -1063,6 +1024,8 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
 }  // namespace
 
 size_t bwd_mfma_workspace(const AttnShape& s) { return make_plan(s).total; }
+
+BwdPlan make_bwd_plan(const AttnShape& s) { return make_plan(s); }
 
 size_t bwd_mfma_pack_workspace(const AttnShape& s, const int* cu, int ndocs) { return make_pack_plan(s, cu, ndocs).total; }
 

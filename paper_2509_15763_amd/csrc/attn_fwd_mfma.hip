@@ -32,12 +32,13 @@
 #include <vector>
 
 #include "mfma_common.h"
+#include "plan.h"
 
 namespace unigist {
 namespace {
 
-constexpr int BM = 128;  // query rows per workgroup
-constexpr int BN = 32;   // keys per step
+constexpr int BM = kFwdBm;  // query rows per workgroup
+constexpr int BN = kFwdBn;  // keys per step
 constexpr int NT = 256;  // threads
 constexpr float kLazy = 8.f;  // slack of the softmax reference, in exp2 units
 constexpr float kBigSum = 16384.f;  // a partial row sum above this sends the step through the maximum search
@@ -173,16 +174,15 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const float c = sc * 1.4426950408889634f;                       // exp(x * sc) = exp2(x * c)
 
     // ---- tile walk
-    const int lo = win_lo(s, i0);                 // leftmost position inside any window of the tile
-    const int wstart = max((lo / BN) * BN, s0);  // first position of the window phase
-    const int nfar = count_always(s, wstart);     // sinks and gists strictly left of the window phase
-    const int ngt = (nfar + BN - 1) / BN;
+    const RowWalk walk = row_walk(s, i0, i1, BN);
+    const int wstart = walk.wstart;               // first position of the window phase
+    const int nfar = walk.nfar;                   // sinks and gists strictly left of the window phase
+    const int ngt = walk.ngt;
     int span_q[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) span_q[qb] = qrow[qb] - win_lo(s, qrow[qb]);  // the window reaches this far back
     const int lo_wlast = win_lo(s, wrow0 + 31);   // window start of the wave's last row
-    const int nwin = (i1 - wstart) / BN + 1;
-    const int ntiles = ngt + nwin;
+    const int ntiles = ngt + walk.nwin;
 
     // ---- staging: direct global->LDS loads; lane fetches chunk (lane % CH) ^ swz(row) of its row.
     const int lrow = lane / CH;
@@ -235,8 +235,9 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         const char* kt = sm.k[BUF];
         const char* vt = sm.v[BUF];
         const bool gist_tile = it < ngt;
-        const int j0 = gist_tile ? it * BN : wstart + (it - ngt) * BN;  // compact index or position
-        if (!gist_tile && j0 > wrow0 + 31) return;
+        const int j0 = row_step_first(walk, it, BN);  // compact index or position
+        const int kind = row_step_kind(walk, it, BN, wrow0, wrow0 + 31, lo_wlast);
+        if (kind == STEP_SKIP) return;
 
         // ---- S^T = K Q^T : sa[kb][qb] register i is key j0 + 16 kb + 4 g4 + i, column = query qrow[qb].
         // The K fragments are read PFK groups ahead of the MFMAs that use them (each feeds both query blocks).
@@ -267,10 +268,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
         // ---- mask.  Bit t of vis[qb]: does query qrow[qb] see the key at offset t from j0?  This lane holds the
         // offsets 16 kb + 4 g4 + i.
-        bool masked;
-        if (gist_tile) masked = j0 + BN > nfar;
-        else masked = !(j0 + BN - 1 <= wrow0 && j0 >= lo_wlast);
-        if (masked) {
+        if (kind == STEP_MASKED) {
             auto below = [](int n) { return n >= 32 ? ~0u : n <= 0 ? 0u : (1u << n) - 1u; };  // bits 0 .. n-1
             unsigned gm = 0u;
             if (!gist_tile) gm = (unsigned)__builtin_amdgcn_ballot_w64(lane < BN && is_always(s, j0 + lane));

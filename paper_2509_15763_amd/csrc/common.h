@@ -1,6 +1,7 @@
 // Internal helpers shared by the libunigist translation units (host + device).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 #include "unigist.h"
 
@@ -104,6 +105,35 @@ __host__ __device__ inline bool is_always(const AttnShape& s, int p) { return p 
 __host__ __device__ inline int count_always(const AttnShape& s, int x) { return x <= s.S ? x : s.S + (x - s.S) / s.rp1; }
 __host__ __device__ inline int pos_of_always(const AttnShape& s, int c) {
     return c < s.S ? c : s.S + (c - s.S) * s.rp1 + s.rp1 - 1;
+}
+
+// the shape of a plain [B, H, L, D] problem (host)
+inline AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks = 0,
+                     int window_mode = UNIGIST_WINDOW_SLIDING) {
+    AttnShape s;
+    s.B = B;
+    s.Hq = Hq;
+    s.Hkv = Hkv;
+    s.L = L;
+    s.D = D;
+    s.rp1 = r >= L ? L + 1 : r + 1;  // r >= L: no position holds a gist
+    s.W = W > L ? L : W;
+    s.scale = 1.0f / sqrtf((float)D);
+    s.S = sinks > L ? L : sinks;
+    s.umode = window_mode == UNIGIST_WINDOW_UNITS;
+    s.qhs = L;
+    s.kvhs = L;
+    s.Lq = L;
+    s.qpos0 = 0;
+    s.kv_rows = L;
+    s.s0 = 0;
+    s.ngb = 0;
+    s.kscale = nullptr;
+    s.vscale = nullptr;
+    s.q_bs = 0;
+    s.q_hs = 0;
+    s.q_rs = 0;
+    return s;
 }
 
 // ---- packed documents: one launch covers up to kMaxDocs documents of a [H, T, D] buffer, each an independent
