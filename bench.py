@@ -54,6 +54,38 @@ def pair_counts(L, r, W):
     return nvis, far_pairs
 
 
+def time_shape(B, Hq, Hkv, L, D, r, W, steps=3, warmup=1, seed=0):
+    """Forward and backward (all stages in one call) of one more shape, each in its own event-timed region."""
+    q, k, v, dout = synth.attn_inputs(B, Hq, Hkv, L, D, seed=seed, device="cuda")
+    ws = torch.empty(u.unigist_attn_bwd_workspace(B, Hq, Hkv, L, D, r, W, u.UNIGIST_BF16), device="cuda", dtype=torch.uint8)
+    grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+    out, lse = u.attn_fwd(q, k, v, r, W)
+    res = {}
+    for name, fn in (("fwd", lambda: u.attn_fwd(q, k, v, r, W)),
+                     ("bwd", lambda: u.attn_bwd(q, k, v, out, lse, dout, r, W, workspace=ws, grads=grads))):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = e0.elapsed_time(e1) / steps
+    nvis = u.n_vis(L, r, W)
+    bm, bn = u.unigist_tile_sizes(D, u.UNIGIST_BF16)
+    m = u.unigist_blockmap_build(L, r, W, bm, bn)
+    tf = lambda per_pair, ms: per_pair * D * nvis * B * Hq / ms / 1e9
+    return {"fwd_ms": res["fwd"], "bwd_ms": res["bwd"],
+            "fwd_pct_of_peak": 100.0 * tf(4.0, res["fwd"]) / PEAK_BF16_TFLOPS,
+            "bwd_pct_of_peak": 100.0 * tf(10.0, res["bwd"]) / PEAK_BF16_TFLOPS,
+            "tflops": tf(14.0, res["fwd"] + res["bwd"]),
+            "live_tile_fraction": m["live_tiles"] / m["causal_tiles"],
+            "visible_fraction": nvis / (L * (L + 1) / 2),
+            "bwd_workspace_mb": ws.numel() / 1e6}
+
+
 def cpu_baseline(cfg, budget_s=15.0):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: blocks of 512
     query rows spread over the sequence, forward and backward, head after head, until about
@@ -102,6 +134,8 @@ def main():
                          "launches the forward kernel under the same name at a smaller size)")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the matrix-core rate probe (profiling runs: its kernel would top the kernel statistics)")
+    ap.add_argument("--no-other-shapes", action="store_true",
+                    help="skip the 128K-token shape and the compression-ratio sweep (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy, so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "can be scaled by what they read for a kernel of known traffic")
@@ -217,6 +251,10 @@ def main():
     torch.cuda.synchronize()
     dec_step_ms = e0.elapsed_time(e1) / nd
     dec_gbs = dec_bytes / dec_ms / 1e6
+    # what a kernel that only reads a buffer of that size reaches on this machine: the ceiling the memory system delivers
+    stream_gbs = None
+    if not args.no_probe:
+        stream_gbs = max(u.probe_read_rate(int(dec_bytes) // 16 * 16, blocks=nb) for nb in (2048, 8192))
     # the same cache stored as E4M3 codes (one byte per element, per-kv-head scales): half the bytes to stream
     ks_, vs_ = synth.e4m3_scales(dc["Hkv"], seed=0, device=dev)
     k8_, v8_ = u.quantize_e4m3(dk_, ks_), u.quantize_e4m3(dv_, vs_)
@@ -304,7 +342,9 @@ def main():
         "mfma_sustained": probe or None,
         "decode": {"workload": "cfg5_decode", "ms": dec_ms, "roofline": {
             "bound": "hbm", "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-            "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes},
+            "traffic": TRAFFIC_BYTES.get("decode"), "alg_bytes_per_launch": dec_bytes,
+            "measured_streaming_read_gbs": stream_gbs,
+            "frac_of_measured_streaming_read": dec_gbs / stream_gbs if stream_gbs else None},
             "step_ms_with_cache_append": dec_step_ms},
         "decode_e4m3": {"workload": "cfg5_decode, cache stored as E4M3 codes", "ms": dec8_ms, "roofline": {
             "bound": "hbm", "achieved": dec8_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec8_gbs / PEAK_HBM_GBS,
@@ -316,6 +356,16 @@ def main():
         res["prefill"] = {"workload": f"{WORKLOAD} in {C}-token chunks through the compressed cache", "ms": prefill_ms,
                           "tflops": flops_fwd / prefill_ms / 1e9,
                           "note": "includes the cache updates; the chunks are row slices, nothing is copied out"}
+    if not args.no_other_shapes:
+        del q, k, v, dout, ws, grads, pout, plse, cache
+        torch.cuda.empty_cache()
+        c3 = synth.WORKLOADS["cfg3_long_128k"]
+        res["cfg3_long_128k"] = dict(B=c3["B"], Hq=c3["Hq"], Hkv=c3["Hkv"], L=c3["L"], D=c3["D"], r=c3["r"], W=c3["W"],
+                                     **time_shape(c3["B"], c3["Hq"], c3["Hkv"], c3["L"], c3["D"], c3["r"], c3["W"]))
+        c4 = synth.WORKLOADS["cfg4_ratio_sweep"]
+        res["cfg4_ratio_sweep"] = {"B": c4["B"], "Hq": c4["Hq"], "Hkv": c4["Hkv"], "L": c4["L"], "D": c4["D"], "W": c4["W"],
+                                   "per_r": {str(rr): time_shape(c4["B"], c4["Hq"], c4["Hkv"], c4["L"], c4["D"], rr, c4["W"],
+                                                                 steps=5) for rr in c4["r"]}}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))

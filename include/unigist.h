@@ -579,6 +579,15 @@ int unigist_debug_force_plain_alu(int on);
 unigist_status unigist_probe_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters,
                                        void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: a kernel that does nothing but read `bytes` bytes (a multiple of 16;
+ * buf DEVICE, 16-byte aligned) with `blocks` workgroups of 256 lanes, 16 bytes per lane and load, and writes
+ * nothing (sink: DEVICE, two zero-initialised 32-bit words, never written in practice).  Timed by the caller, it
+ * gives the streaming-read rate the memory system delivers, the ceiling next to which the decode kernel's
+ * achieved GB/s can be read.  1 <= blocks <= 65536, else UNIGIST_EINVAL.
+ */
+unigist_status unigist_probe_read_rate(const void* buf, size_t bytes, unsigned* sink, int blocks, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

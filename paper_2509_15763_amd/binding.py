@@ -35,6 +35,7 @@ EXPORTS = [
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
     "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes", "unigist_debug_force_plain_alu",
     "unigist_window_start", "unigist_plan_row_tile", "unigist_bwd_plan_build", "unigist_plan_key_tile",
+    "unigist_probe_read_rate",
 ]
 
 
@@ -172,6 +173,8 @@ def load():
     lib.unigist_cache_update.argtypes = [vp, vp, ip, ip, ip, vp, vp, ip, ip, vp, vp, ip, ip, ip, ip, ip, ip, ip, vp]
     lib.unigist_prefill_chunk.restype = ip
     lib.unigist_prefill_chunk.argtypes = [vp, vp, vp, vp, fp] + [ip] * 10 + [ip, vp]
+    lib.unigist_probe_read_rate.restype = ip
+    lib.unigist_probe_read_rate.argtypes = [vp, sz, vp, ip, vp]
     lib.unigist_probe_mfma_rate.restype = ip
     lib.unigist_probe_mfma_rate.argtypes = [vp, vp, vp, ip, ip, vp]
     lib.unigist_tile_sizes.restype = None
@@ -491,6 +494,28 @@ def unigist_prefill_chunk(q, kc, vc, out, lse, B, Hq, Hkv, C, D, r, W, p0, s, ca
 
 def unigist_probe_mfma_rate(operands, clocks, sink, blocks, iters, stream=None) -> int:
     return load().unigist_probe_mfma_rate(operands, clocks, sink, blocks, iters, stream)
+
+
+def unigist_probe_read_rate(buf, nbytes, sink, blocks, stream=None) -> int:
+    return load().unigist_probe_read_rate(buf, nbytes, sink, blocks, stream)
+
+
+def probe_read_rate(nbytes=4 << 30, blocks=2048, reps=5):
+    """GB/s of a kernel that only reads an nbytes buffer (allocated here), best of `reps` launches."""
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    sink = torch.zeros(2, dtype=torch.int32, device="cuda")
+    run = lambda: _check(unigist_probe_read_rate(buf.data_ptr(), nbytes, sink.data_ptr(), blocks, _stream()),
+                         "unigist_probe_read_rate")
+    run()
+    best = float("inf")
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    return nbytes / best / 1e6
 
 
 def probe_mfma_rate(operands, blocks=512, iters=100000):

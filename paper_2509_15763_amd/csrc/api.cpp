@@ -69,6 +69,12 @@ extern "C" unigist_status unigist_probe_mfma_rate(const void* operands, long lon
                                                                                                           : UNIGIST_ELAUNCH;
 }
 
+extern "C" unigist_status unigist_probe_read_rate(const void* buf, size_t bytes, unsigned* sink, int blocks,
+                                                  void* hip_stream) {
+    if (!buf || !sink || bytes < 16 || blocks < 1 || blocks > 65536 || ((uintptr_t)buf & 15) != 0) return UNIGIST_EINVAL;
+    return launch_read_rate(buf, bytes, sink, blocks, (hipStream_t)hip_stream) == hipSuccess ? UNIGIST_OK : UNIGIST_ELAUNCH;
+}
+
 extern "C" unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                                            int B, int Hq, int Hkv, int L, int D, int r, int W, unigist_dtype dt,
                                            void* hip_stream) {

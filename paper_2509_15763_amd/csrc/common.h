@@ -245,6 +245,7 @@ hipError_t launch_widen_e4m3(const void* codes, void* y, int BH, int cap, int ro
 // y = e4m3(x / scale[head]) for x [B, H, n, D] (bf16 or fp32), 16 elements per lane
 hipError_t launch_quantize_e4m3(const void* x, void* y, const float* scale, int B, int H, int n, int D,
                                 unigist_dtype dt_in, hipStream_t st);
+hipError_t launch_read_rate(const void* buf, size_t bytes, unsigned* sink, int blocks, hipStream_t st);
 hipError_t launch_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters, hipStream_t st);
 
 }  // namespace unigist

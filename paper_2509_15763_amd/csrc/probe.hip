@@ -38,7 +38,27 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict
     }
 }
 
+// Streaming read: every lane pulls 16-byte pieces, a wave 1 KiB at a time, the grid striding over the buffer; the
+// values are folded into one word per lane that is written only if it takes an impossible value.
+__global__ __launch_bounds__(256) void read_rate_kernel(const u32x4* __restrict__ buf, size_t n16, unsigned* __restrict__ sink) {
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {  // four independent loads in flight per lane
+        const u32x4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= buf[i];
+    const unsigned x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (x == 0x9e3779b9u && sink[1] == 1u) sink[0] = x;  // keeps the loads alive; sink[1] is never 1
+}
+
 }  // namespace
+
+hipError_t launch_read_rate(const void* buf, size_t bytes, unsigned* sink, int blocks, hipStream_t st) {
+    read_rate_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((const u32x4*)buf, bytes / 16, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_mfma_rate(const void* operands, long long* clocks, float* sink, int blocks, int iters, hipStream_t st) {
     mfma_rate_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16x8*)operands, clocks, sink, iters);
