@@ -739,35 +739,34 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         unsigned long long gm = 0ull;  // bit t: the key at offset t from j0 holds a sink or a gist
         if (!gist_tile && masked) gm = __builtin_amdgcn_ballot_w64(is_always(s, j0 + lane));
 
+        // S^T, dP^T for the 32 keys of half kb2: register i of sa[kb][qb] is key j0 + 32 kb2 + 16 kb + 4 g4 + i, column =
+        // query qrow[qb].  Every K and V fragment serves both query blocks; the reads run PFS groups ahead of their
+        // MFMAs and the scheduling barriers keep them there.
+        auto sdp = [&](int kb2, f32x4 (&sa)[2][2], f32x4 (&dp)[2][2]) __attribute__((always_inline)) {
+            constexpr int N = 2 * KS;  // group n: key block n / KS, k-step n % KS
+            bf16x8 fk[N], fv[N];
+            auto fetch = [&](int n) __attribute__((always_inline)) {
+                const int o = (32 * kb2 + 16 * (n / KS)) * CH * 16 + roff[n % KS];
+                fk[n] = *(const bf16x8*)(kt + o);
+                fv[n] = *(const bf16x8*)(vt + o);
+            };
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-            // S^T, dP^T for 32 keys: register i of sa[kb][qb] is key j0 + 32 kb2 + 16 kb + 4 g4 + i, column = query
-            // qrow[qb].  Every K and V fragment serves both query blocks; the reads run PFS groups ahead of their
-            // MFMAs and the scheduling barriers keep them there.
-            f32x4 sa[2][2], dp[2][2];
-            {
-                constexpr int N = 2 * KS;  // group n: key block n / KS, k-step n % KS
-                bf16x8 fk[N], fv[N];
-                auto fetch = [&](int n) __attribute__((always_inline)) {
-                    const int o = (32 * kb2 + 16 * (n / KS)) * CH * 16 + roff[n % KS];
-                    fk[n] = *(const bf16x8*)(kt + o);
-                    fv[n] = *(const bf16x8*)(vt + o);
-                };
+            for (int n = 0; n < PFS; ++n) fetch(n);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int n = 0; n < PFS; ++n) fetch(n);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int n = 0; n < N; ++n) {
+                if (n + PFS < N) fetch(n + PFS);
+                const int kb = n / KS, ks = n % KS;
 #pragma unroll
-                for (int n = 0; n < N; ++n) {
-                    if (n + PFS < N) fetch(n + PFS);
-                    const int kb = n / KS, ks = n % KS;
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) {
-                        sa[kb][qb] = mfma16(fk[n], qf[qb][ks], ks == 0 ? zero4() : sa[kb][qb]);
-                        dp[kb][qb] = mfma16(fv[n], gf[qb][ks], ks == 0 ? ndl[qb] : dp[kb][qb]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int qb = 0; qb < 2; ++qb) {
+                    sa[kb][qb] = mfma16(fk[n], qf[qb][ks], ks == 0 ? zero4() : sa[kb][qb]);
+                    dp[kb][qb] = mfma16(fv[n], gf[qb][ks], ks == 0 ? ndl[qb] : dp[kb][qb]);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+        };
+        // P = exp2(S c - lse), the mask, dS = P (dP - delta) (dP arrives with -delta in it): dp becomes dS
+        auto soft = [&](int kb2, f32x4 (&sa)[2][2], f32x4 (&dp)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
@@ -797,22 +796,31 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
 #pragma unroll
                     for (int i = 0; i < 4; ++i) dp[kb][qb][i] *= sa[kb][qb][i];
             }
-            // dQ^T += K^T dS^T : contraction slot 8 g4 + 4 kb + i is key 16 kb + 4 g4 + i of the block, on both operands
-            {
-                bf16x8 sb[2], ft[DB];
+        };
+        // dQ^T += K^T dS^T for half kb2: contraction slot 8 g4 + 4 kb + i is key 16 kb + 4 g4 + i of the half, on both
+        // operands
+        auto dqm = [&](int kb2, const bf16x8 (&sb)[2]) __attribute__((always_inline)) {
+            bf16x8 ft[DB];
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) sb[qb] = pack44(dp[0][qb], dp[1][qb]);
+            for (int db = 0; db < PFT; ++db) ft[db] = tr16_frag16<CH>(kt + toff[db], 32 * kb2);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int db = 0; db < PFT; ++db) ft[db] = tr16_frag16<CH>(kt + toff[db], 32 * kb2);
+            for (int db = 0; db < DB; ++db) {
+                if (db + PFT < DB) ft[db + PFT] = tr16_frag16<CH>(kt + toff[db + PFT], 32 * kb2);
+                acc[db][0] = mfma16(ft[db], sb[0], acc[db][0]);
+                acc[db][1] = mfma16(ft[db], sb[1], acc[db][1]);
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    if (db + PFT < DB) ft[db + PFT] = tr16_frag16<CH>(kt + toff[db + PFT], 32 * kb2);
-                    acc[db][0] = mfma16(ft[db], sb[0], acc[db][0]);
-                    acc[db][1] = mfma16(ft[db], sb[1], acc[db][1]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
             }
+        };
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            f32x4 sa[2][2], dp[2][2];
+            bf16x8 sb[2];
+            sdp(kb2, sa, dp);
+            soft(kb2, sa, dp);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) sb[qb] = pack44(dp[0][qb], dp[1][qb]);
+            dqm(kb2, sb);
         }
     };
 
