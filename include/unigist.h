@@ -75,7 +75,10 @@ const char* unigist_status_str(unigist_status s);
  * Forward (Sec. 4.1 Eq. 3 mask, Sec. 4.2 block skipping):
  *   out_i = sum_j softmax_j(scale * q_i . k_j | vis(i,j)) v_j,   lse_i as above.
  * q, k, v: in.  out [B,Hq,L,D] (dt), lse [B,Hq,L] (float): out.
- * Requires B, Hq, Hkv, L, W >= 1, r >= 1, Hq % Hkv == 0, D in {64, 128}.
+ * Requires B, Hq, Hkv, L, W >= 1, r >= 1, Hq % Hkv == 0, and a head dimension D that is a multiple of 8 with
+ * 8 <= D <= 128 (every entry point; a multiple of 16 where E4M3 codes are involved), else UNIGIST_EUNSUPPORTED.  The
+ * matrix-core kernels are built for D = 64 and D = 128; other head dimensions run on the next of the two with
+ * the missing columns taken as zeros, i.e. at the cost of the larger one.
  */
 unigist_status unigist_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                                 int B, int Hq, int Hkv, int L, int D, int r, int W,

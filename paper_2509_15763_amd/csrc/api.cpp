@@ -19,6 +19,12 @@ namespace {
 
 constexpr int kMaxL = 1 << 23;  // per-head byte offsets (L * D * 2) are kept in 32 bits inside the kernels
 
+// Head dimensions: any multiple of 8 up to 128 (rows are moved in 16-byte pieces; of 16 for one-byte E4M3 codes).  The
+// matrix-core kernels are built for 64 and 128 and run smaller ones on the next of the two, the missing columns
+// taken as zeros.  Beyond 128 the dK/dV kernel's register budget ends: its dK^T and dV^T accumulators for a wave's
+// 32 keys would take 256 registers per lane at D = 256 on top of 128 for the K and V operands.
+bool head_dim_ok(int D, unigist_dtype dt) { return D >= 8 && D <= 128 && D % (dt == UNIGIST_E4M3 ? 16 : 8) == 0; }
+
 // Debug switch (unigist_debug_force_plain_alu): bf16 calls take the plain-ALU kernels.  The environment variable
 // UNIGIST_DEBUG_PLAIN_ALU=1 sets its initial value; it is read once, when the library is loaded.
 std::atomic<int> g_plain_alu{[] {
@@ -33,7 +39,7 @@ unigist_status check_attn(int B, int Hq, int Hkv, int L, int D, int r, int W, un
     if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return UNIGIST_EINVAL;
     if (Hq % Hkv != 0) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, dt)) return UNIGIST_EUNSUPPORTED;
     if (L > kMaxL || B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
     if ((long long)B * Hkv > 65535) return UNIGIST_EUNSUPPORTED;  // (batch, kv head) pairs index a grid's z dimension
     return UNIGIST_OK;
@@ -207,9 +213,9 @@ extern "C" unigist_status unigist_attn_bwd(const void* q, const void* k, const v
 
 extern "C" size_t unigist_decode_workspace(int B, int Hq, int Hkv, int Lk_max, int D, unigist_dtype dt) {
     if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || Hq % Hkv != 0) return 0;
-    if ((D != 64 && D != 128) || (dt != UNIGIST_BF16 && dt != UNIGIST_F32)) return 0;
+    if (!head_dim_ok(D, dt) || (dt != UNIGIST_BF16 && dt != UNIGIST_F32)) return 0;
     const int ns = decode_num_splits(B, Hq, Hkv, Lk_max, dt);
-    return align256((size_t)B * Hq * ns * (D + 2) * sizeof(float));
+    return align256((size_t)B * Hq * ns * (padded_head_dim(D) + 2) * sizeof(float));
 }
 
 extern "C" unigist_status unigist_decode(const void* q, const void* kcache, const void* vcache, void* out,
@@ -219,7 +225,7 @@ extern "C" unigist_status unigist_decode(const void* q, const void* kcache, cons
     if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || D < 1) return UNIGIST_EINVAL;
     if (Hq % Hkv != 0) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, dt)) return UNIGIST_EUNSUPPORTED;
     if (B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
     if (!q || !kcache || !vcache || !out || !workspace) return UNIGIST_EINVAL;
     if (workspace_bytes < unigist_decode_workspace(B, Hq, Hkv, Lk_max, D, dt)) return UNIGIST_EINVAL;
@@ -233,7 +239,7 @@ extern "C" unigist_status unigist_quantize_e4m3(const void* x, void* y, const fl
                                                 unigist_dtype dt_in, void* hip_stream) {
     if (B < 1 || H < 1 || n < 0 || D < 1) return UNIGIST_EINVAL;
     if (dt_in != UNIGIST_BF16 && dt_in != UNIGIST_F32) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, UNIGIST_E4M3)) return UNIGIST_EUNSUPPORTED;
     if (!scale || (n > 0 && (!x || !y))) return UNIGIST_EINVAL;
     if (((uintptr_t)x & 15) != 0 || ((uintptr_t)y & 15) != 0) return UNIGIST_EINVAL;
     hipError_t e = launch_quantize_e4m3(x, y, scale, B, H, n, D, dt_in, (hipStream_t)hip_stream);
@@ -246,7 +252,7 @@ extern "C" unigist_status unigist_decode_e4m3(const void* q, const void* kcache,
                                               size_t workspace_bytes, void* hip_stream) {
     if (B < 1 || Hq < 1 || Hkv < 1 || Lk_max < 1 || D < 1) return UNIGIST_EINVAL;
     if (Hq % Hkv != 0) return UNIGIST_EINVAL;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, UNIGIST_E4M3)) return UNIGIST_EUNSUPPORTED;
     if (B > 65535 || Hq > 65535) return UNIGIST_EUNSUPPORTED;
     if (!q || !kcache || !vcache || !k_scale || !v_scale || !out || !workspace) return UNIGIST_EINVAL;
     if (workspace_bytes < unigist_decode_workspace(B, Hq, Hkv, Lk_max, D, UNIGIST_BF16)) return UNIGIST_EINVAL;
@@ -290,7 +296,7 @@ extern "C" unigist_status unigist_cache_update_ex(const void* kc_in, const void*
     if (B < 1 || Hkv < 1 || D < 1 || r < 1 || sinks < 0 || n_new < 0 || new_rows < n_new || cap_in < 0 || cap_out < 1)
         return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, dt)) return UNIGIST_EUNSUPPORTED;
     if (s_old < 0 || t_old < s_old - 1 || s_new < s_old) return UNIGIST_EINVAL;
     const long long t_new = (long long)t_old + n_new;
     if (t_new > kMaxL || s_new > t_new + 1) return UNIGIST_EINVAL;
@@ -316,7 +322,7 @@ extern "C" unigist_status unigist_cache_update_ragged(const void* kc_in, const v
                                                       void* hip_stream) {
     if (B < 1 || Hkv < 1 || D < 1 || r < 1 || sinks < 0 || new_rows < 0 || cap_in < 0 || cap_out < 1) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, dt)) return UNIGIST_EUNSUPPORTED;
     if (B > 65535 || Hkv > 65535) return UNIGIST_EUNSUPPORTED;
     if (!kc_out || !vc_out || !s_old || !t_old || !n_new || !s_new || !rows_out) return UNIGIST_EINVAL;
     if (cap_in > 0 && (!kc_in || !vc_in)) return UNIGIST_EINVAL;
@@ -336,7 +342,7 @@ unigist_status check_ring(int B, int Hkv, int D, int r, int W, int sinks, int wi
     if (B < 1 || Hkv < 1 || D < 1 || r < 1 || W < 1 || sinks < 0) return UNIGIST_EINVAL;
     if (window_mode != UNIGIST_WINDOW_SLIDING && window_mode != UNIGIST_WINDOW_UNITS) return UNIGIST_EINVAL;
     if (dt != UNIGIST_BF16 && dt != UNIGIST_F32 && dt != UNIGIST_E4M3) return UNIGIST_EUNSUPPORTED;
-    if (D != 64 && D != 128) return UNIGIST_EUNSUPPORTED;
+    if (!head_dim_ok(D, dt)) return UNIGIST_EUNSUPPORTED;
     if (B > 65535 || Hkv > 65535) return UNIGIST_EUNSUPPORTED;
     return UNIGIST_OK;
 }
@@ -492,6 +498,7 @@ extern "C" unigist_status unigist_prefill_chunk_e4m3(const void* q, const void* 
     if (Ltot > kMaxL) return UNIGIST_EUNSUPPORTED;
     unigist_status st = check_attn(B, Hq, Hkv, (int)Ltot, D, r, W, UNIGIST_BF16, sinks, window_mode);
     if (st != UNIGIST_OK) return st;
+    if (!head_dim_ok(D, UNIGIST_E4M3)) return UNIGIST_EUNSUPPORTED;
     if (!q || !kc || !vc || !k_scale || !v_scale || !out || !lse || !workspace) return UNIGIST_EINVAL;
     if (((uintptr_t)kc & 15) != 0 || ((uintptr_t)vc & 15) != 0 || ((uintptr_t)workspace & 255) != 0) return UNIGIST_EINVAL;
     AttnShape sh = make_shape(B, Hq, Hkv, (int)Ltot, D, r, W, sinks, window_mode);

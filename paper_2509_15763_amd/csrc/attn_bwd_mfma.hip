@@ -71,10 +71,10 @@ BwdPlan make_plan(const AttnShape& s) {
     p.off_lse2 = off;  // lse * log2(e), written by the delta pass
     off += ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_part = off;  // one [2][D][BNK] fp32 block per (batch, kv head, segment, compact tile the segment reaches)
-    off += (size_t)s.B * s.Hkv * p.slot0[p.nseg] * 2 * s.D * BNK * sizeof(float);
+    off += (size_t)s.B * s.Hkv * p.slot0[p.nseg] * 2 * padded_head_dim(s.D) * BNK * sizeof(float);
     off = (off + a) & ~a;
     p.off_comp = off;  // their sums over the segments: one block per (batch, kv head, compact tile)
-    off += (size_t)s.B * s.Hkv * p.n_gt * 2 * s.D * BNK * sizeof(float);
+    off += (size_t)s.B * s.Hkv * p.n_gt * 2 * padded_head_dim(s.D) * BNK * sizeof(float);
     p.total = (off + a) & ~a;
     return p;
 }
@@ -84,8 +84,8 @@ template <int D>
 __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ out, const bf16_t* __restrict__ dout,
                                                   const float* __restrict__ lse, float* __restrict__ delta,
                                                   float* __restrict__ lse2, long nrows, int L, int qhs, int Hq,
-                                                  long long q_bs, long long q_hs, int q_rs) {
-    constexpr int LPR = D / 8;  // lanes per row, 16 bytes each
+                                                  long long q_bs, long long q_hs, int q_rs, int Dt) {
+    constexpr int LPR = D / 8;  // lanes per row, 16 bytes each (Dt <= D elements per row in memory)
     const long row = (long)blockIdx.x * (NT / LPR) + threadIdx.x / LPR;  // dense: (b, h, i) -> (b Hq + h) L + i
     const int sub = threadIdx.x % LPR;
     const long grow = L == qhs ? row : (row / L) * qhs + row % L;        // the same row in the caller's tensors
@@ -93,9 +93,12 @@ __global__ __launch_bounds__(NT) void delta_kernel(const bf16_t* __restrict__ ou
     if (row < nrows) {
         // element offset of the row in out / dout: dense, or with the caller's explicit strides (q_rs != 0)
         const long bh = row / L;
-        const long eoff = q_rs ? (bh / Hq) * q_bs + (bh % Hq) * q_hs + (row % L) * (long)q_rs : grow * D;
-        u32x4 a = *(const u32x4*)(out + eoff + sub * 8);
-        u32x4 b = *(const u32x4*)(dout + eoff + sub * 8);
+        const long eoff = q_rs ? (bh / Hq) * q_bs + (bh % Hq) * q_hs + (row % L) * (long)q_rs : grow * Dt;
+        u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+        if (sub * 8 < Dt) {
+            a = *(const u32x4*)(out + eoff + sub * 8);
+            b = *(const u32x4*)(dout + eoff + sub * 8);
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             acc += __uint_as_float(a[t] << 16) * __uint_as_float(b[t] << 16);
@@ -128,7 +131,10 @@ struct DkdvSmem {
 // PACK = true (here and in dq_kernel): the launch covers the documents of a packed buffer (docs), s_arg is the shape
 // of the whole pack, delta and lse2 have the layout of the caller's lse ([Hq, T]), and every document has its
 // own run of slots in part and comp.
-// QSTR = true: q and dout have the explicit strides of s_arg (q_bs, q_hs, q_rs) instead of the dense layout.
+// QSTR = true: q and dout have the explicit strides of s_arg (q_bs, q_hs, q_rs) instead of the dense layout.  Tensors
+// whose head dimension s.D is smaller than the D the kernel is built for (any multiple of 8) also come this way, with
+// the strides of their dense layout: rows in memory are s.D elements long, LDS tiles and fragments have D columns,
+// of which those from s.D on are zero in the K and V fragments (so they add nothing to S and dP) and are never stored.
 template <int D, bool GIST, bool GEN, bool PACK, bool QSTR = false>
 __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                     const bf16_t* __restrict__ v, const float* __restrict__ lse2,
@@ -148,7 +154,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         n -= docs.blk0[d];
         s = doc_view(s, docs.len[d]);
         plan_counts(s, pl, pl.segc);  // pl arrives with the launch's segment length only
-        const size_t ro = (size_t)docs.c0[d] * D;
+        const size_t ro = (size_t)docs.c0[d] * (QSTR ? s.D : D);
         const size_t qro = QSTR ? (size_t)docs.c0[d] * s.q_rs : ro;
         q += qro;
         k += ro;
@@ -173,6 +179,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     const int L = s.L;
     const int G = s.Hq / s.Hkv;
     const float c = s.scale * kLog2e;
+    const int Dt = QSTR ? s.D : D;  // elements per row in memory
 
     // ---- which (batch, kv head) and which unit of work.  Workgroup ids go round-robin over the 8
     // XCDs, so with id % 8 selecting the (batch, kv head) pair every XCD gets the same amount of work
@@ -245,11 +252,16 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         // the key stays in the window for span_j more rows (W - 1 for every key in the sliding mode)
         span_j[kb] = 0;
         if constexpr (!GIST && GEN) span_j[kb] = key[kb] < L ? win_hi(s, key[kb]) - key[kb] : 0;
-        const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + krow) * D + 8 * g4;
+        const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + krow) * Dt + 8 * g4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[kb][ks] = *(const bf16x8*)(k + base + 32 * ks);
-            vf[kb][ks] = *(const bf16x8*)(v + base + 32 * ks);
+            u32x4 zk = {0u, 0u, 0u, 0u}, zv = {0u, 0u, 0u, 0u};  // columns past the tensors' head dimension are zero
+            if (!QSTR || 32 * ks + 8 * g4 < Dt) {
+                zk = *(const u32x4*)(k + base + 32 * ks);
+                zv = *(const u32x4*)(v + base + 32 * ks);
+            }
+            kf[kb][ks] = __builtin_bit_cast(bf16x8, zk);
+            vf[kb][ks] = __builtin_bit_cast(bf16x8, zv);
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
@@ -278,7 +290,11 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
         int lanepart[NLP];
         const unsigned rsb = QSTR ? (unsigned)s.q_rs * 2u : (unsigned)ROWB;  // bytes between consecutive rows in q / dout
 #pragma unroll
-        for (int i = 0; i < NLP; ++i) lanepart[i] = lrow_ * (int)rsb + (((ln % CH) ^ swz16<CH>(i * RPI + lrow_)) << 4);
+        for (int i = 0; i < NLP; ++i) {
+            int sc = (ln % CH) ^ swz16<CH>(i * RPI + lrow_);  // the source chunk of this lane's LDS position
+            if (QSTR && 8 * sc >= Dt) sc = 0;                  // a chunk the rows do not have: any chunk will do
+            lanepart[i] = lrow_ * (int)rsb + (sc << 4);
+        }
         const size_t hb = ((size_t)b * s.Hq + hk * G + g) * (PACK ? s.qhs : L);  // wave-uniform; workspace rows
         // the head in the caller's tensors
         const size_t hg = QSTR ? (size_t)b * s.q_bs + (size_t)(hk * G + g) * s.q_hs : ((size_t)b * s.Hq + hk * G + g) * s.qhs * D;
@@ -526,9 +542,10 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
                     for (int i = 0; i < 4; ++i) akT[db][kb][i] *= s.scale;
             }
             if (key[kb] < L) {
-                const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + key[kb]) * D + 4 * g4;
+                const size_t base = (((size_t)b * s.Hkv + hk) * s.kvhs + key[kb]) * Dt + 4 * g4;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
+                    if (QSTR && 16 * db + 4 * g4 >= Dt) continue;
                     u32x2 a, bb;
                     a[0] = pack_bf16x2(akT[db][kb][0], akT[db][kb][1]);
                     a[1] = pack_bf16x2(akT[db][kb][2], akT[db][kb][3]);
@@ -610,7 +627,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         n -= docs.blk0[d];
         s = doc_view(s, docs.len[d]);
         nq = (s.L + BMQ - 1) / BMQ;
-        const size_t ro = (size_t)docs.c0[d] * D;
+        const size_t ro = (size_t)docs.c0[d] * (QSTR ? s.D : D);
         const size_t qro = QSTR ? (size_t)docs.c0[d] * s.q_rs : ro;
         q += qro;
         k += ro;
@@ -646,8 +663,9 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int L = s.L, rp1 = s.rp1;
     const int i0 = qt * BMQ, i1 = min(L, i0 + BMQ) - 1;
     const int wrow0 = i0 + 32 * w;  // first row of the wave; the lane's two rows are wrow0 + 16 qb + r16
-    const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
-    const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * s.kvhs * D);
+    const int Dt = QSTR ? s.D : D;  // elements per row in memory (see dkdv_kernel)
+    const char* kbytes = (const char*)(k + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt);
+    const char* vbytes = (const char*)(v + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt);
     const float c = s.scale * kLog2e;
 
     // B operands Q and dO of this lane's two query rows, their lse * log2(e), and -delta in the 4 registers of an
@@ -673,8 +691,13 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         const bf16_t* gp = dout + rowoff[qb] + 8 * g4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
-            gf[qb][ks] = *(const bf16x8*)(gp + 32 * ks);
+            u32x4 zq = {0u, 0u, 0u, 0u}, zg = {0u, 0u, 0u, 0u};  // columns past the tensors' head dimension are zero
+            if (!QSTR || 32 * ks + 8 * g4 < Dt) {
+                zq = *(const u32x4*)(qp + 32 * ks);
+                zg = *(const u32x4*)(gp + 32 * ks);
+            }
+            qf[qb][ks] = __builtin_bit_cast(bf16x8, zq);
+            gf[qb][ks] = __builtin_bit_cast(bf16x8, zg);
         }
         ls[qb] = lse2[wrow];
         const float dl = delta[wrow];
@@ -701,7 +724,10 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
     const int wv = __builtin_amdgcn_readfirstlane(w);
     int choff[IPW];
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    for (int i = 0; i < IPW; ++i) {
+        const int sc = (lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow);
+        choff[i] = (!QSTR || 8 * sc < Dt) ? sc * 16 : 0;  // a chunk the rows do not have: any chunk will do
+    }
     auto issue = [&](int it, int buf) {
         const bool gphase = it < ngt;
 #pragma unroll
@@ -714,7 +740,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
             } else {
                 row = min(wstart + (it - ngt) * BNQ + rr, L - 1);
             }
-            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];
+            const unsigned off = (unsigned)row * (unsigned)(Dt * 2) + (unsigned)choff[i];
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
         }
@@ -844,6 +870,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
             bf16_t* op = dq + rowoff[qb] + 4 * g4;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
+                if (QSTR && 16 * db + 4 * g4 >= Dt) continue;
                 u32x2 w2;
                 w2[0] = pack_bf16x2(acc[db][qb][0] * s.scale, acc[db][qb][1] * s.scale);
                 w2[1] = pack_bf16x2(acc[db][qb][2] * s.scale, acc[db][qb][3] * s.scale);
@@ -868,7 +895,7 @@ hipError_t bwd_launch(const bf16_t* q, const bf16_t* k, const bf16_t* v, const b
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.B * s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
-            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, s.q_bs, s.q_hs, s.q_rs);
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, s.q_bs, s.q_hs, s.q_rs, s.D);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (pl.n_gt > 0 && (stages & UNIGIST_BWD_DKDV_GIST)) {
@@ -935,7 +962,7 @@ PackPlan make_pack_plan(const AttnShape& s, const int* cu, int ndocs) {
         nslot_part += (size_t)s.Hkv * pl.slot0[pl.nseg];
         nslot_comp += (size_t)s.Hkv * pl.n_gt;
     }
-    const size_t a = 255, per_tile = (size_t)2 * s.D * BNK * sizeof(float);
+    const size_t a = 255, per_tile = (size_t)2 * padded_head_dim(s.D) * BNK * sizeof(float);
     size_t off = ((size_t)s.Hq * s.L * sizeof(float) + a) & ~a;  // delta, [Hq, T] like the caller's lse
     pp.off_lse2 = off;
     off += ((size_t)s.Hq * s.L * sizeof(float) + a) & ~a;
@@ -963,7 +990,7 @@ hipError_t bwd_launch_pack(const bf16_t* q, const bf16_t* k, const bf16_t* v, co
         constexpr int rows_per_blk = NT / (D / 8);
         const long nrows = (long)s.Hq * s.L;
         delta_kernel<D><<<dim3((unsigned)((nrows + rows_per_blk - 1) / rows_per_blk)), NT, 0, st>>>(
-            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, 0, s.q_hs, s.q_rs);
+            out, dout, lse, delta, lse2, nrows, s.L, s.qhs, s.Hq, 0, s.q_hs, s.q_rs, s.D);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const int nd = (int)pp.len.size();
@@ -1037,10 +1064,22 @@ BwdPlan make_bwd_plan(const AttnShape& s) { return make_plan(s); }
 
 size_t bwd_mfma_pack_workspace(const AttnShape& s, const int* cu, int ndocs) { return make_pack_plan(s, cu, ndocs).total; }
 
+// A head dimension below the one the kernels are built for goes through the instantiations for explicit strides of
+// q, out, dout and dq, with the strides of the dense layout.
+static AttnShape with_dense_strides_if_padded(AttnShape s) {
+    if (s.D != padded_head_dim(s.D) && s.q_rs == 0) {
+        s.q_rs = s.D;
+        s.q_hs = (long long)s.qhs * s.D;
+        s.q_bs = (long long)s.Hq * s.q_hs;
+    }
+    return s;
+}
+
 hipError_t launch_bwd_mfma_pack(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                                const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
+                                const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s_in,
                                 const int* cu, int ndocs, hipStream_t st) {
-    if (s.D == 64)
+    const AttnShape s = with_dense_strides_if_padded(s_in);
+    if (s.D <= 64)
         return bwd_launch_pack<64>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
                                    (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, cu, ndocs, st);
     return bwd_launch_pack<128>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
@@ -1048,9 +1087,10 @@ hipError_t launch_bwd_mfma_pack(const void* q, const void* k, const void* v, con
 }
 
 hipError_t launch_bwd_mfma(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                           const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s,
+                           const void* dout, void* dq, void* dk, void* dv, void* ws, const AttnShape& s_in,
                            unsigned stages, hipStream_t st) {
-    if (s.D == 64)
+    const AttnShape s = with_dense_strides_if_padded(s_in);
+    if (s.D <= 64)
         return bwd_launch<64>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,
                               (const bf16_t*)dout, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, (char*)ws, s, stages, st);
     return bwd_launch<128>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)out, lse,

@@ -57,6 +57,9 @@ template <int MODE> struct ModeArg { typedef NoDocs type; };
 template <> struct ModeArg<PACK> { typedef DocTab type; };
 template <> struct ModeArg<RAGGED> { typedef RaggedSeqs type; };
 
+// D is the head dimension the kernel is built for (64 or 128); the tensors' head dimension s.D may be any smaller
+// multiple of 8.  Rows in memory are s.D elements long; LDS tiles and fragments have D columns, of which the ones
+// from s.D on hold zeros in Q (so they add nothing to the scores) and are never stored on the output side.
 // MODE = PACK: the launch covers the documents of a packed buffer (ext), s_arg is the shape of the whole pack.
 // MODE = RAGGED: chunk-wise prefill of a batch whose sequences are in different states (ext: device arrays);
 // s_arg is the launch's shape and each workgroup derives its sequence's (seq_view).
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         n -= ext.blk0[d];
         s = doc_view(s, ext.len[d]);
         nq = (s.L + BM - 1) / BM;
-        const size_t ro = (size_t)ext.c0[d] * D;
+        const size_t ro = (size_t)ext.c0[d] * s.D;
         const size_t qro = s.q_rs ? (size_t)ext.c0[d] * s.q_rs : ro;  // q and out may have explicit strides
         q += qro;
         k += ro;
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 
     // Positions are absolute; q/out/lse hold the rows qpos0 .. L-1, K/V hold ngb compact gist rows followed
     // by the positions s0 .. L-1 (training: everything from position 0, no compact rows).
-    const int L = s.L, rp1 = s.rp1;
+    const int L = s.L, rp1 = s.rp1, Dt = s.D;
     const int qpos0 = s.qpos0, s0 = s.s0, ngb = s.ngb;
     const int i0 = qpos0 + qt * BM;
     const int i1 = min(L, i0 + BM) - 1;
@@ -150,8 +153,8 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         qrow_ld[qb] = min(qrow[qb], L - 1);  // rows past the end shadow the last row and are never stored
     }
 
-    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
-    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * s.kv_rows * D;
+    const bf16_t* kb = k + ((size_t)b * s.Hkv + hk) * s.kv_rows * Dt;
+    const bf16_t* vb = v + ((size_t)b * s.Hkv + hk) * s.kv_rows * Dt;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[qrow[qb]][32 ks + 8 g4 .. +7]
     bf16x8 qf[2][KS];
@@ -160,10 +163,14 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const size_t qoff = s.q_rs ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)(qrow_ld[qb] - qpos0) * s.q_rs
-                                   : (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld[qb] - qpos0)) * D;
+                                   : (((size_t)b * s.Hq + hq) * s.qhs + (qrow_ld[qb] - qpos0)) * Dt;
         const bf16_t* qp = q + qoff + 8 * g4;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + 32 * ks);
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 z = {0u, 0u, 0u, 0u};  // columns past the tensors' head dimension are zero
+            if (32 * ks + 8 * g4 < Dt) z = *(const u32x4*)(qp + 32 * ks);
+            qf[qb][ks] = __builtin_bit_cast(bf16x8, z);
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         m[qb] = -INFINITY;
@@ -189,7 +196,10 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
     const int wv = __builtin_amdgcn_readfirstlane(w);
     int choff[IPW];  // byte offset of the lane's (swizzled) chunk inside its row, per load slot
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) choff[i] = ((lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow)) * 16;
+    for (int i = 0; i < IPW; ++i) {
+        const int sc = (lane % CH) ^ swz16<CH>((wv * IPW + i) * RPI + lrow);
+        choff[i] = 8 * sc < Dt ? sc * 16 : 0;  // a chunk the rows do not have: any chunk will do (see above)
+    }
     const int S = s.S;
     const char* kbytes = (const char*)kb;
     const char* vbytes = (const char*)vb;
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
             } else {
                 row = min(wstart + (it - ngt) * BN + rr, L - 1) - s0 + ngb;
             }
-            const unsigned off = (unsigned)row * (unsigned)(D * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
+            const unsigned off = (unsigned)row * (unsigned)(Dt * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);
         }
@@ -388,10 +398,11 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         if (s.vscale) inv *= s.vscale[hk];  // the stored values stand for V * vscale
         if (qrow[qb] < L) {
             const size_t orow = ((size_t)b * s.Hq + hq) * s.qhs + (qrow[qb] - qpos0);
-            const size_t ooff = s.q_rs ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)(qrow[qb] - qpos0) * s.q_rs : orow * D;
+            const size_t ooff = s.q_rs ? (size_t)b * s.q_bs + (size_t)hq * s.q_hs + (size_t)(qrow[qb] - qpos0) * s.q_rs : orow * Dt;
             bf16_t* op = out + ooff + 4 * g4;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
+                if (16 * db + 4 * g4 >= Dt) continue;
                 u32x2 w2;
                 w2[0] = pack_bf16x2(o[db][qb][0] * inv, o[db][qb][1] * inv);
                 w2[1] = pack_bf16x2(o[db][qb][2] * inv, o[db][qb][3] * inv);
@@ -414,7 +425,7 @@ hipError_t launch_fwd_mfma(const void* q, const void* k, const void* v, void* ou
         kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
                                                   s, nq, NoDocs{});
     };
-    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, PLAIN>) : go(fwd_mfma_kernel<64, false, PLAIN>);
+    if (s.D <= 64) gen ? go(fwd_mfma_kernel<64, true, PLAIN>) : go(fwd_mfma_kernel<64, false, PLAIN>);
     else gen ? go(fwd_mfma_kernel<128, true, PLAIN>) : go(fwd_mfma_kernel<128, false, PLAIN>);
     return hipGetLastError();
 }
@@ -429,7 +440,7 @@ hipError_t launch_fwd_mfma_ragged(const void* q, const void* k, const void* v, v
         kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, lse,
                                                   s, nq, seqs);
     };
-    if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, RAGGED>) : go(fwd_mfma_kernel<64, false, RAGGED>);
+    if (s.D <= 64) gen ? go(fwd_mfma_kernel<64, true, RAGGED>) : go(fwd_mfma_kernel<64, false, RAGGED>);
     else gen ? go(fwd_mfma_kernel<128, true, RAGGED>) : go(fwd_mfma_kernel<128, false, RAGGED>);
     return hipGetLastError();
 }
@@ -460,7 +471,7 @@ hipError_t launch_fwd_mfma_pack(const void* q, const void* k, const void* v, voi
             kern<<<dim3((unsigned)nblk), NT, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out,
                                                       lse, s, 0, t);
         };
-        if (s.D == 64) gen ? go(fwd_mfma_kernel<64, true, PACK>) : go(fwd_mfma_kernel<64, false, PACK>);
+        if (s.D <= 64) gen ? go(fwd_mfma_kernel<64, true, PACK>) : go(fwd_mfma_kernel<64, false, PACK>);
         else gen ? go(fwd_mfma_kernel<128, true, PACK>) : go(fwd_mfma_kernel<128, false, PACK>);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -6,7 +6,9 @@
 // wave-uniform address, and apply the visibility rule of Sec. 4.1, Eq. 3 per pair.
 // No tiles, no MFMA, fp32 accumulation throughout; slow, but short enough to
 // check by eye.  The bf16 instantiations exist so that the MFMA kernels can be
-// cross-checked against them on the GPU.
+// cross-checked against them on the GPU.  D is the head dimension a kernel is built for
+// (64 or 128); the tensors' head dimension s.D may be anything up to it: rows in memory are
+// s.D elements long and the loops over d skip the rest.
 #include "common.h"
 
 namespace unigist {
@@ -33,11 +35,13 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
     const int i_last = min(s.L, i_first + kRows) - 1;
     const int i = min(i_first + lane, s.L - 1);  // lanes past the end shadow the last row, never store
     const bool live = i_first + lane < s.L;
-    const size_t qoff = (((size_t)b * s.Hq + h) * s.qhs + i) * D;
-    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
-    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
+    const int Dt = s.D;
+    const size_t qoff = (((size_t)b * s.Hq + h) * s.qhs + i) * Dt;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt;
 #pragma unroll
-    for (int d = 0; d < D; ++d) qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
+    for (int d = 0; d < D; ++d)
+        if (d < Dt) qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
 
     float o[D];
 #pragma unroll
@@ -45,10 +49,11 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
     float m = -INFINITY, l = 0.f;
 
     auto visit = [&](int j) {
-        const T* kr = kb + (size_t)j * D;
+        const T* kr = kb + (size_t)j * Dt;
         float sc = 0.f;
 #pragma unroll
-        for (int d = 0; d < D; ++d) sc += qs[d][lane] * Elem<T>::load(kr + d);
+        for (int d = 0; d < D; ++d)
+            if (d < Dt) sc += qs[d][lane] * Elem<T>::load(kr + d);
         if (sc > m) {
             float a = expf(m - sc);
             l *= a;
@@ -58,9 +63,10 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
         }
         float p = expf(sc - m);
         l += p;
-        const T* vr = vb + (size_t)j * D;
+        const T* vr = vb + (size_t)j * Dt;
 #pragma unroll
-        for (int d = 0; d < D; ++d) o[d] += p * Elem<T>::load(vr + d);
+        for (int d = 0; d < D; ++d)
+            if (d < Dt) o[d] += p * Elem<T>::load(vr + d);
     };
 
     // sinks and gists left of every window of this wave's rows, then the union of the windows
@@ -75,7 +81,8 @@ __global__ __launch_bounds__(kRows) void fwd_simple_kernel(const T* __restrict__
     if (live) {
         float inv = 1.f / l;
 #pragma unroll
-        for (int d = 0; d < D; ++d) Elem<T>::store(out + qoff + d, o[d] * inv);
+        for (int d = 0; d < D; ++d)
+            if (d < Dt) Elem<T>::store(out + qoff + d, o[d] * inv);
         lse[((size_t)b * s.Hq + h) * s.qhs + i] = m + logf(l);
     }
 }
@@ -97,12 +104,14 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
     const bool live = i_first + lane < s.L;
     const size_t row = ((size_t)b * s.Hq + h) * s.qhs + i;   // in the caller's tensors
     const size_t wrow = ((size_t)b * s.Hq + h) * s.L + i;    // in the dense workspace
-    const size_t qoff = row * D;
-    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
-    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * D;
+    const int Dt = s.D;
+    const size_t qoff = row * Dt;
+    const T* kb = k + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt;
+    const T* vb = v + ((size_t)b * s.Hkv + hk) * s.kvhs * Dt;
     float dl = 0.f;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
+        if (d >= Dt) continue;
         qs[d][lane] = Elem<T>::load(q + qoff + d) * s.scale;
         float g = Elem<T>::load(dout + qoff + d);
         dos[d][lane] = g;
@@ -116,17 +125,19 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
     for (int d = 0; d < D; ++d) acc[d] = 0.f;
 
     auto visit = [&](int j) {
-        const T* kr = kb + (size_t)j * D;
-        const T* vr = vb + (size_t)j * D;
+        const T* kr = kb + (size_t)j * Dt;
+        const T* vr = vb + (size_t)j * Dt;
         float sc = 0.f, dp = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
+            if (d >= Dt) continue;
             sc += qs[d][lane] * Elem<T>::load(kr + d);
             dp += dos[d][lane] * Elem<T>::load(vr + d);
         }
         float ds = expf(sc - ls) * (dp - dl);
 #pragma unroll
-        for (int d = 0; d < D; ++d) acc[d] += ds * Elem<T>::load(kr + d);
+        for (int d = 0; d < D; ++d)
+            if (d < Dt) acc[d] += ds * Elem<T>::load(kr + d);
     };
 
     const int lo_wave = win_lo(s, i_first);
@@ -139,7 +150,8 @@ __global__ __launch_bounds__(kRows) void dq_simple_kernel(const T* __restrict__ 
     }
     if (live) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) Elem<T>::store(dq + qoff + d, acc[d] * s.scale);
+        for (int d = 0; d < D; ++d)
+            if (d < Dt) Elem<T>::store(dq + qoff + d, acc[d] * s.scale);
     }
 }
 
@@ -158,9 +170,11 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
     const int j_last = min(s.L, j_first + kRows) - 1;
     const int j = min(j_first + lane, s.L - 1);
     const bool live = j_first + lane < s.L;
-    const size_t koff = (((size_t)b * s.Hkv + hk) * s.kvhs + j) * D;
+    const int Dt = s.D;
+    const size_t koff = (((size_t)b * s.Hkv + hk) * s.kvhs + j) * Dt;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
+        if (d >= Dt) continue;
         ks[d][lane] = Elem<T>::load(k + koff + d) * s.scale;
         vs[d][lane] = Elem<T>::load(v + koff + d);
     }
@@ -182,11 +196,12 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
         for (int i = j_first; i <= i_end; ++i) {
             bool ok = j <= i && (always_j || i <= hi_j);
             if (!ok) continue;
-            const T* qr = q + (base + i) * D;
-            const T* gr = dout + (base + i) * D;
+            const T* qr = q + (base + i) * Dt;
+            const T* gr = dout + (base + i) * Dt;
             float sc = 0.f, dp = 0.f;
 #pragma unroll
             for (int d = 0; d < D; ++d) {
+                if (d >= Dt) continue;
                 sc += ks[d][lane] * Elem<T>::load(qr + d);
                 dp += vs[d][lane] * Elem<T>::load(gr + d);
             }
@@ -194,6 +209,7 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
             float ds = p * (dp - delta[wbase + i]);
 #pragma unroll
             for (int d = 0; d < D; ++d) {
+                if (d >= Dt) continue;
                 av[d] += p * Elem<T>::load(gr + d);
                 ak[d] += ds * Elem<T>::load(qr + d);
             }
@@ -202,6 +218,7 @@ __global__ __launch_bounds__(kRows) void dkdv_simple_kernel(const T* __restrict_
     if (live) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
+            if (d >= Dt) continue;
             Elem<T>::store(dk + koff + d, ak[d] * s.scale);
             Elem<T>::store(dv + koff + d, av[d]);
         }
@@ -236,9 +253,9 @@ hipError_t bwd_launch(const void* q, const void* k, const void* v, const void* o
 hipError_t launch_fwd_simple(const void* q, const void* k, const void* v, void* out, float* lse,
                              const AttnShape& s, unigist_dtype dt, hipStream_t st) {
     if (dt == UNIGIST_F32)
-        return s.D == 64 ? fwd_launch<float, 64>(q, k, v, out, lse, s, st)
+        return s.D <= 64 ? fwd_launch<float, 64>(q, k, v, out, lse, s, st)
                          : fwd_launch<float, 128>(q, k, v, out, lse, s, st);
-    return s.D == 64 ? fwd_launch<bf16_t, 64>(q, k, v, out, lse, s, st)
+    return s.D <= 64 ? fwd_launch<bf16_t, 64>(q, k, v, out, lse, s, st)
                      : fwd_launch<bf16_t, 128>(q, k, v, out, lse, s, st);
 }
 
@@ -246,9 +263,9 @@ hipError_t launch_bwd_simple(const void* q, const void* k, const void* v, const 
                              const void* dout, void* dq, void* dk, void* dv, float* delta, const AttnShape& s,
                              unigist_dtype dt, hipStream_t st) {
     if (dt == UNIGIST_F32)
-        return s.D == 64 ? bwd_launch<float, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
+        return s.D <= 64 ? bwd_launch<float, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
                          : bwd_launch<float, 128>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st);
-    return s.D == 64 ? bwd_launch<bf16_t, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
+    return s.D <= 64 ? bwd_launch<bf16_t, 64>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st)
                      : bwd_launch<bf16_t, 128>(q, k, v, out, lse, dout, dq, dk, dv, delta, s, st);
 }
 

@@ -151,7 +151,7 @@ extern "C" unigist_status unigist_plan_row_tile(int L, int r, int W, int sinks, 
 
 extern "C" unigist_status unigist_bwd_plan_build(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
                                                  int window_mode, unigist_bwd_plan* out) {
-    if (!out || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || (D != 64 && D != 128)) return UNIGIST_EINVAL;
+    if (!out || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || (D < 8 || D > 128 || D % 8 != 0)) return UNIGIST_EINVAL;
     if (!shape_ok(L, r, W, sinks, window_mode)) return UNIGIST_EINVAL;
     const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
     const BwdPlan p = make_bwd_plan(s);
@@ -164,8 +164,8 @@ extern "C" unigist_status unigist_bwd_plan_build(int B, int Hq, int Hkv, int L, 
     out->seg_chunks = p.segc;
     out->n_segs = p.nseg;
     for (int i = 0; i <= p.nseg; ++i) out->slot0[i] = p.slot0[i];
-    out->partial_bytes = (size_t)B * Hkv * p.slot0[p.nseg] * 2 * D * BNK * sizeof(float);
-    out->reduced_bytes = (size_t)B * Hkv * p.n_gt * 2 * D * BNK * sizeof(float);
+    out->partial_bytes = (size_t)B * Hkv * p.slot0[p.nseg] * 2 * padded_head_dim(D) * BNK * sizeof(float);
+    out->reduced_bytes = (size_t)B * Hkv * p.n_gt * 2 * padded_head_dim(D) * BNK * sizeof(float);
     out->workspace_bytes = p.total;
     return UNIGIST_OK;
 }
@@ -173,7 +173,7 @@ extern "C" unigist_status unigist_bwd_plan_build(int B, int Hq, int Hkv, int L, 
 extern "C" unigist_status unigist_plan_key_tile(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
                                                 int window_mode, int gist_phase, int tile, int seg, int* c_lo,
                                                 int* c_hi, int capacity, int* nfar, signed char* kind) {
-    if (!c_lo || !c_hi || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || (D != 64 && D != 128)) return UNIGIST_EINVAL;
+    if (!c_lo || !c_hi || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || (D < 8 || D > 128 || D % 8 != 0)) return UNIGIST_EINVAL;
     if (!shape_ok(L, r, W, sinks, window_mode)) return UNIGIST_EINVAL;
     const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
     const BwdPlan p = make_bwd_plan(s);

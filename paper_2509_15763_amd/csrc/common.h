@@ -107,6 +107,10 @@ __host__ __device__ inline int pos_of_always(const AttnShape& s, int c) {
     return c < s.S ? c : s.S + (c - s.S) * s.rp1 + s.rp1 - 1;
 }
 
+// The matrix-core kernels are built for head dimensions 64 and 128; a smaller one (a multiple of 8) runs on the next
+// of the two with the missing columns treated as zeros.
+__host__ __device__ inline int padded_head_dim(int D) { return D <= 64 ? 64 : 128; }
+
 // the shape of a plain [B, H, L, D] problem (host)
 inline AttnShape make_shape(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks = 0,
                      int window_mode = UNIGIST_WINDOW_SLIDING) {

@@ -99,13 +99,15 @@ __device__ __forceinline__ float row16_sum(float x) {
 // TQ: type of the queries; T: type the cache is stored in.  A cache of E4M3 codes comes with one scale per kv
 // head for K and for V (element = code * scale): the K scale is folded into the query, the V scale into the
 // slice's partial result.
+// D is the head dimension the kernel is built for (64 or 128), Dt <= D (a multiple of 8) the one of the tensors: rows in
+// memory are Dt elements long and the lanes holding columns from Dt on work on zeros; the workspace keeps D columns.
 template <typename TQ, typename T, int D, int G, int U>
 __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __restrict__ q, const T* __restrict__ kc,
                                                                const T* __restrict__ vc, const int* __restrict__ seqlens,
                                                                const float* __restrict__ k_scale,
                                                                const float* __restrict__ v_scale,
                                                                float* __restrict__ ws, int Hq, int Hkv, int Lk,
-                                                               int nsplit, float scale) {
+                                                               int nsplit, float scale, int Dt) {
     constexpr int E = D / kLanesPerRow;
     const int tid = threadIdx.x;
     const int sub = tid % kLanesPerRow;  // which D/16 chunk of a row
@@ -122,9 +124,12 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __rest
     float qr[G][E], acc[G][E], m[G], l[G];
     if (k_scale) scale *= k_scale[hk];
     const float vmul = v_scale ? v_scale[hk] : 1.f;
+    const bool have = sub * E < Dt;  // does this lane's piece of a row exist?
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        RowChunk<TQ, E>::load(q + ((size_t)b * Hq + hq0 + g) * D + sub * E, qr[g]);
+#pragma unroll
+        for (int e = 0; e < E; ++e) qr[g][e] = 0.f;
+        if (have) RowChunk<TQ, E>::load(q + ((size_t)b * Hq + hq0 + g) * Dt + sub * E, qr[g]);
         m[g] = -INFINITY;
         l[g] = 0.f;
 #pragma unroll
@@ -133,8 +138,8 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __rest
             acc[g][e] = 0.f;
         }
     }
-    const T* kb = kc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
-    const T* vb = vc + ((size_t)b * Hkv + hk) * Lk * D + sub * E;
+    const T* kb = kc + ((size_t)b * Hkv + hk) * Lk * Dt + (have ? sub * E : 0);  // a lane without a piece re-reads
+    const T* vb = vc + ((size_t)b * Hkv + hk) * Lk * Dt + (have ? sub * E : 0);  // the first one; its q is zero
 
     for (int base = k0; base < k1; base += kRowsPerIter * U) {
         float kx[U][E], vx[U][E];
@@ -144,8 +149,8 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __rest
             int row = base + u * kRowsPerIter + grp;
             ok[u] = row < k1;
             int rr = ok[u] ? row : k0;  // k0 < k1 <= n whenever this loop runs: always in bounds
-            RowChunk<T, E>::load(kb + (size_t)rr * D, kx[u]);
-            RowChunk<T, E>::load(vb + (size_t)rr * D, vx[u]);
+            RowChunk<T, E>::load(kb + (size_t)rr * Dt, kx[u]);
+            RowChunk<T, E>::load(vb + (size_t)rr * Dt, vx[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -211,13 +216,14 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(const TQ* __rest
 
 template <typename T, int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ ws, T* __restrict__ out,
-                                                          float* __restrict__ lse, int nsplit) {
+                                                          float* __restrict__ lse, int nsplit, int Dt) {
     const int bh = blockIdx.x, d = threadIdx.x;
+    if (d >= Dt) return;  // columns the tensors do not have
     const float* p = ws + (size_t)bh * nsplit * (D + 2);
     float mm = -INFINITY;
     for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, p[s * (D + 2)]);
     if (mm == -INFINITY) {  // a sequence of zero keys (outside the contract): the empty sum, not NaN
-        Elem<T>::store(out + (size_t)bh * D + d, 0.f);
+        Elem<T>::store(out + (size_t)bh * Dt + d, 0.f);
         if (lse && d == 0) lse[bh] = -INFINITY;
         return;
     }
@@ -227,7 +233,7 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
         ll += w * p[s * (D + 2) + 1];
         a += w * p[s * (D + 2) + 2 + d];
     }
-    Elem<T>::store(out + (size_t)bh * D + d, a / ll);
+    Elem<T>::store(out + (size_t)bh * Dt + d, a / ll);
     if (lse && d == 0) lse[bh] = mm + __logf(ll);
 }
 
@@ -253,7 +259,9 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
                                                                          const float* __restrict__ k_scale,
                                                                          const float* __restrict__ v_scale,
                                                                          float* __restrict__ ws, int Hq, int Hkv, int Lk,
-                                                                         int nsplit, float scale) {
+                                                                         int nsplit, float scale, int Dt) {
+    // Dt <= D: the head dimension of the tensors (rows of Dt elements in memory; a multiple of 8, of 16 for E4M3
+    // codes); the K and Q columns from Dt on are zeros, the V columns from Dt on are never stored
     constexpr int KS = D / 32, DB = D / 16, CH = D / 8;  // k-steps, 16-row blocks of O^T, 16-byte chunks per bf16 row
     constexpr int EB = E4M3 ? 1 : 2;                     // bytes per cache element
     constexpr int BPL = D / 4;                           // K elements per lane and key
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         u32x4 z = {0u, 0u, 0u, 0u};
-        if (r16 < G) z = *(const u32x4*)(q + ((size_t)b * Hq + hq0 + r16) * D + BPL * g4 + 8 * ks);
+        if (r16 < G && BPL * g4 + 8 * ks < Dt) z = *(const u32x4*)(q + ((size_t)b * Hq + hq0 + r16) * Dt + BPL * g4 + 8 * ks);
         qf[ks] = __builtin_bit_cast(bf16x8, z);
     }
     f32x4 o[DB];  // O^T: register i of o[db] is d = 16 db + 4 g4 + i, column = head r16
@@ -287,8 +295,9 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
     for (int db = 0; db < DB; ++db) o[db] = zero4();
     float m = -INFINITY, l = 0.f;
 
-    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * (D * EB);
-    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * (D * EB);
+    const uint8_t* kb = kc + ((size_t)b * Hkv + hk) * Lk * (Dt * EB);
+    const uint8_t* vb = vc + ((size_t)b * Hkv + hk) * Lk * (Dt * EB);
+    const int row_bytes = Dt * EB;
     char* vt = smem + w * (32 * D * 2);
     int toff[DB];
 #pragma unroll
@@ -312,13 +321,16 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             const int row = min(base + 16 * kb2 + r16, k1 - 1);
 #pragma unroll
-            for (int t = 0; t < NKL; ++t)
-                kw[kb2][t] = *(const u32x4*)(kb + (size_t)row * (D * EB) + BPL * EB * g4 + 16 * t);
+            for (int t = 0; t < NKL; ++t) {
+                const int o = BPL * EB * g4 + 16 * t;  // a piece the rows do not have: the first one (its q is zero)
+                kw[kb2][t] = *(const u32x4*)(kb + (size_t)row * row_bytes + (o < row_bytes ? o : 0));
+            }
         }
 #pragma unroll
         for (int j = 0; j < NLV; ++j) {
             const int row = min(base + (64 / LPR) * j + lane / LPR, k1 - 1);
-            vw[j] = *(const u32x4*)(vb + (size_t)row * (D * EB) + 16 * (lane % LPR));
+            const int o = 16 * (lane % LPR);
+            vw[j] = *(const u32x4*)(vb + (size_t)row * row_bytes + (o < row_bytes ? o : 0));
         }
         // ---- S^T = K Q^T
         f32x4 sa[2];
@@ -443,24 +455,24 @@ __global__ __launch_bounds__(kThreads) void decode_split_mfma_kernel(const bf16_
 
 template <typename TQ, typename T, int D>
 hipError_t decode_launch(const void* q, const void* kc, const void* vc, const float* k_scale, const float* v_scale,
-                         void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, float* ws,
+                         void* out, float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int Dt, float* ws,
                          hipStream_t st) {
     constexpr int U = kUnroll;
     constexpr unigist_dtype dt = std::is_same<TQ, float>::value ? UNIGIST_F32 : UNIGIST_BF16;
     const int nsplit = decode_num_splits(B, Hq, Hkv, Lk, dt);
-    const float scale = 1.0f / sqrtf((float)D);
+    const float scale = 1.0f / sqrtf((float)Dt);
     if (decode_grouped(Hq, Hkv, dt) && Hq / Hkv == 4) {
         dim3 grid(nsplit, Hkv, B);
         decode_split_kernel<TQ, T, D, 4, U><<<grid, kThreads, 0, st>>>((const TQ*)q, (const T*)kc, (const T*)vc, seqlens,
-                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
+                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale, Dt);
     } else {
         dim3 grid(nsplit, Hq, B);
         decode_split_kernel<TQ, T, D, 1, U><<<grid, kThreads, 0, st>>>((const TQ*)q, (const T*)kc, (const T*)vc, seqlens,
-                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
+                                                                       k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale, Dt);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_combine_kernel<TQ, D><<<B * Hq, D, 0, st>>>(ws, (TQ*)out, lse, nsplit);
+    decode_combine_kernel<TQ, D><<<B * Hq, D, 0, st>>>(ws, (TQ*)out, lse, nsplit, Dt);
     return hipGetLastError();
 }
 
@@ -510,22 +522,22 @@ hipError_t decode_bf16q(const void* q, const void* kc, const void* vc, const flo
                         float* lse, int B, int Hq, int Hkv, int Lk, const int* seqlens, int D, float* ws, hipStream_t st) {
     if (!decode_grouped(Hq, Hkv, UNIGIST_BF16)) {
         using T = std::conditional_t<E4M3, fp8_t, bf16_t>;
-        return D == 64 ? decode_launch<bf16_t, T, 64>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                       : decode_launch<bf16_t, T, 128>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+        return D <= 64 ? decode_launch<bf16_t, T, 64>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st)
+                       : decode_launch<bf16_t, T, 128>(q, kc, vc, k_scale, v_scale, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st);
     }
     const int nsplit = decode_num_splits(B, Hq, Hkv, Lk, UNIGIST_BF16);
     const float scale = 1.0f / sqrtf((float)D);
     const dim3 grid(nsplit, Hkv, B);
-    if (D == 64)
+    if (D <= 64)
         decode_split_mfma_kernel<64, E4M3><<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc,
-                                                                      seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
+                                                                      seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale, D);
     else
         decode_split_mfma_kernel<128, E4M3><<<grid, kThreads, 0, st>>>((const bf16_t*)q, (const uint8_t*)kc, (const uint8_t*)vc,
-                                                                       seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale);
+                                                                       seqlens, k_scale, v_scale, ws, Hq, Hkv, Lk, nsplit, scale, D);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (D == 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
-    else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit);
+    if (D <= 64) decode_combine_kernel<bf16_t, 64><<<B * Hq, 64, 0, st>>>(ws, (bf16_t*)out, lse, nsplit, D);
+    else decode_combine_kernel<bf16_t, 128><<<B * Hq, 128, 0, st>>>(ws, (bf16_t*)out, lse, nsplit, D);
     return hipGetLastError();
 }
 }  // namespace
@@ -533,8 +545,8 @@ hipError_t decode_bf16q(const void* q, const void* kc, const void* vc, const flo
 hipError_t launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse, int B, int Hq,
                          int Hkv, int Lk, const int* seqlens, int D, unigist_dtype dt, float* ws, hipStream_t st) {
     if (dt == UNIGIST_F32)
-        return D == 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st)
-                       : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, ws, st);
+        return D <= 64 ? decode_launch<float, float, 64>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st)
+                       : decode_launch<float, float, 128>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st);
     return decode_bf16q<false>(q, kc, vc, nullptr, nullptr, out, lse, B, Hq, Hkv, Lk, seqlens, D, ws, st);
 }
 

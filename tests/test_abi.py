@@ -49,7 +49,7 @@ FAKE = 0x1000  # non-null pointer that is never dereferenced: every call below f
 @pytest.mark.parametrize("kw,want", [
     (dict(), None),
     (dict(B=0), 1), (dict(L=0), 1), (dict(W=0), 1), (dict(r=0), 1), (dict(Hq=6, Hkv=4), 1),
-    (dict(D=96), 2), (dict(dt=7), 2), (dict(L=(1 << 23) + 1), 2),
+    (dict(D=100), 2), (dict(D=256), 2), (dict(D=4), 2), (dict(dt=7), 2), (dict(L=(1 << 23) + 1), 2),
 ])
 def test_attn_argument_validation(kw, want):
     a = dict(B=1, Hq=4, Hkv=2, L=64, D=64, r=4, W=8, dt=0)
@@ -148,7 +148,7 @@ def test_decode_argument_validation():
                                 ws_ptr, ws_bytes)
     assert call(q=None) == 1
     assert call(B=0) == 1 and call(Lk=0) == 1 and call(Hq=3) == 1
-    assert call(D=32) == 2 and call(dt=5) == 2
+    assert call(D=20) == 2 and call(D=256) == 2 and call(dt=5) == 2
     assert call(ws_bytes=ws - 1) == 1
     assert call(ws_ptr=0x10010) == 1  # misaligned workspace
     assert u.unigist_decode_workspace(2, 3, 2, 100, 128, 0) == 0
@@ -182,7 +182,7 @@ def test_cache_argument_validation():
     assert call(cap_out=8) == 1         # 1 gist + 9 rows do not fit
     assert call(n_new=5) == 1           # more rows than the new buffer holds
     assert call(kc_out=None) == 1 and call(k_new=None) == 1 and call(kc_in=None) == 1
-    assert call(D=96) == 2 and call(dt=3) == 2
+    assert call(D=100) == 2 and call(D=192) == 2 and call(dt=3) == 2
     # prefill: f32 is not built, sizes are checked before anything is launched
     p = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=1, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, p0=500, s=401,
              cap=1024, dt=1)
@@ -233,7 +233,7 @@ def test_cache_argument_validation():
     need = u.unigist_prefill_chunk_e4m3_workspace(1, 1, 128, 401, 563, 4, 0)
     assert need == 2 * (80 + 163) * 128 * 2                  # 80 gists left of 401, positions 401 .. 563, K and V
     assert u.unigist_prefill_chunk_e4m3_workspace(1, 1, 128, 401, 399, 4, 0) == 0
-    assert bad(s=402) == 1 and bad(cap=100) == 1 and bad(ws_bytes=need - 1) == 1 and bad(D=96) == 2
+    assert bad(s=402) == 1 and bad(cap=100) == 1 and bad(ws_bytes=need - 1) == 1 and bad(D=100) == 2
     assert bad(kc=FAKE + 8) == 1 and bad(ws=FAKE + 16) == 1
     for name in ("q", "kc", "vc", "k_scale", "v_scale", "out", "lse", "ws"):
         assert bad(**{name: None}) == 1, name
@@ -241,7 +241,7 @@ def test_cache_argument_validation():
     g = dict(q=FAKE, kc=FAKE, vc=FAKE, out=FAKE, lse=FAKE, B=2, Hq=2, Hkv=1, C=64, D=128, r=4, W=100, sinks=0,
              window_mode=0, p0=FAKE, n=FAKE, s=FAKE, cap=1024, rows_out=FAKE, dt=0)
     bad = lambda **kw: u.unigist_prefill_chunk_ragged(*dict(g, **kw).values())
-    assert bad(dt=1) == 2 and bad(D=96) == 2
+    assert bad(dt=1) == 2 and bad(D=100) == 2
     assert bad(C=0) == 1 and bad(cap=0) == 1 and bad(window_mode=2) == 1 and bad(sinks=-1) == 1 and bad(Hq=3, Hkv=2) == 1
     for name in ("q", "kc", "vc", "out", "lse", "p0", "n", "s", "rows_out"):
         assert bad(**{name: None}) == 1, name
@@ -261,7 +261,7 @@ def test_ring_cache_rows_and_argument_validation():
     ok = dict(kc=FAKE, vc=FAKE, k_new=FAKE, v_new=FAKE, new_rows=1, t_old=FAKE, n_new=FAKE, cap=64, rows_out=FAKE, B=2,
               Hkv=2, D=64, r=4, W=16, sinks=0, window_mode=1, dt=0)
     bad = lambda **kw: u.unigist_cache_ring_append(*dict(ok, **kw).values())
-    assert bad(W=0) == 1 and bad(cap=0) == 1 and bad(new_rows=0) == 1 and bad(sinks=-1) == 1 and bad(D=96) == 2 and bad(dt=3) == 2
+    assert bad(W=0) == 1 and bad(cap=0) == 1 and bad(new_rows=0) == 1 and bad(sinks=-1) == 1 and bad(D=100) == 2 and bad(dt=3) == 2
     assert bad(window_mode=2) == 1
     for name in ("kc", "vc", "k_new", "v_new", "t_old", "n_new", "rows_out"):
         assert bad(**{name: None}) == 1, name
@@ -287,14 +287,15 @@ def test_e4m3_argument_validation():
     assert q(FAKE, FAKE, None, 1, 2, 3, 128, 0) == 1
     assert q(None, FAKE, FAKE, 1, 2, 3, 128, 0) == 1
     assert q(FAKE, FAKE, FAKE, 0, 2, 3, 128, 0) == 1
-    assert q(FAKE, FAKE, FAKE, 1, 2, 3, 96, 0) == 2
+    assert q(FAKE, FAKE, FAKE, 1, 2, 3, 100, 0) == 2
+    assert q(FAKE, FAKE, FAKE, 1, 2, 3, 104, 0) == 2            # one-byte codes: head dimensions in multiples of 16
     assert q(FAKE, FAKE, FAKE, 1, 2, 3, 128, 2) == 2            # E4M3 is not an input type
     assert q(FAKE + 8, FAKE, FAKE, 1, 2, 3, 128, 0) == 1        # 16-byte alignment
     d = u.unigist_decode_e4m3
     ws = u.unigist_decode_workspace(2, 8, 2, 100, 128, 0)
     good = dict(q=FAKE, kc=FAKE, vc=FAKE, k_scale=FAKE, v_scale=FAKE, out=FAKE, lse=None, B=2, Hq=8, Hkv=2, Lk=100,
                 seqlens=None, D=128, ws=FAKE, ws_bytes=ws)
-    for name, val, want in [("k_scale", None, 1), ("v_scale", None, 1), ("kc", None, 1), ("Hkv", 3, 1), ("D", 96, 2),
+    for name, val, want in [("k_scale", None, 1), ("v_scale", None, 1), ("kc", None, 1), ("Hkv", 3, 1), ("D", 100, 2),
                             ("ws_bytes", ws - 1, 1), ("ws", FAKE + 64, 1), ("kc", FAKE + 8, 1), ("q", FAKE + 8, 1), ("B", 0, 1)]:
         assert d(**{**good, name: val}) == want, name
     # the attention calls do not take the storage type
@@ -308,7 +309,7 @@ def test_ragged_cache_update_argument_validation():
                 kc_out=FAKE, vc_out=FAKE, s_new=FAKE, cap_out=64, rows_out=FAKE, B=2, Hkv=2, D=128, r=4, sinks=0, dt=0)
     for name, val, want in [("s_old", None, 1), ("t_old", None, 1), ("n_new", None, 1), ("s_new", None, 1), ("rows_out", None, 1),
                             ("kc_out", None, 1), ("kc_in", None, 1), ("k_new", None, 1), ("cap_out", 0, 1), ("r", 0, 1),
-                            ("D", 96, 2), ("dt", 7, 2), ("B", 0, 1), ("new_rows", -1, 1)]:
+                            ("D", 100, 2), ("dt", 7, 2), ("B", 0, 1), ("new_rows", -1, 1)]:
         assert f(**{**good, name: val}) == want, name
 
 

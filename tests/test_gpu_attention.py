@@ -47,6 +47,12 @@ SMALL = [
     (1, 1, 1, 1, 64, 4, 4),           # a single token
     (1, 2, 2, 63, 128, 1, 3),         # r = 1: every other token is a gist
     (1, 8, 8, 200, 64, 16, 64),       # 8 kv heads: XCD-aware block order
+    # head dimensions other than the two the matrix-core kernels are built for (run on the next one, zero-padded)
+    (1, 4, 2, 700, 96, 4, 100),
+    (2, 2, 1, 333, 80, 2, 40),
+    (1, 4, 4, 257, 32, 8, 64),
+    (1, 2, 1, 300, 120, 4, 33),
+    (1, 2, 2, 200, 8, 4, 16),
 ]
 
 
@@ -71,6 +77,8 @@ MID = [
     (1, 8, 8, 5000, 128, 4, 129),
     (1, 16, 8, 9001, 128, 4, 300),
     (2, 8, 4, 6000, 64, 2, 200),
+    (1, 8, 8, 5000, 96, 4, 129),
+    (1, 4, 2, 4200, 48, 8, 500),
 ]
 
 
@@ -156,7 +164,7 @@ def test_peaked_and_flat_softmax(L, D, r, W, gain, dtype):
     check(case, (torch.from_numpy(o_o),) + tuple(got[1:]), want, dtype, tol_lse=max(TOL_LSE_BF16, 4 * big * 2.0 ** -23))
 
 
-@pytest.mark.parametrize("D", [128, 64])
+@pytest.mark.parametrize("D", [128, 64, 96])
 @pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
 def test_projection_layout_gives_the_same_bits(sinks, units, W, D):
     # q, out, dout, dq laid out [B, L, Hq, D] in memory (the strided entry points, no transposing copies): the same

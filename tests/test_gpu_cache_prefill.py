@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "f32"])
-@pytest.mark.parametrize("B,Hkv,D,r,L", [(2, 2, 128, 4, 700), (1, 3, 64, 8, 513), (1, 1, 128, 1, 64), (2, 1, 64, 10**6, 300)])
+@pytest.mark.parametrize("B,Hkv,D,r,L", [(2, 2, 128, 4, 700), (1, 3, 64, 8, 513), (1, 1, 128, 1, 64), (2, 1, 64, 10**6, 300),
+                                          (2, 2, 96, 4, 700), (1, 1, 8, 2, 300)])
 def test_cache_updates_are_exact_gathers(B, Hkv, D, r, L, dtype):
     print("case", B, Hkv, D, r, L, dtype, flush=True)
     _, k, v, _ = synth.attn_inputs(B, Hkv, Hkv, L, D, dtype=dtype, seed=21)
@@ -41,6 +42,8 @@ def test_cache_updates_are_exact_gathers(B, Hkv, D, r, L, dtype):
     (2, 4, 2, 2500, 128, 8, 1024, 1000),    # ragged last chunk, window longer than a chunk
     (1, 2, 2, 1100, 64, 4, 100, 300),       # D = 64
     (1, 2, 1, 900, 128, 2**31 - 2, 50, 256),  # no gists
+    (2, 4, 2, 2000, 96, 4, 256, 512),       # head dimension 96
+    (1, 2, 1, 1100, 24, 4, 100, 300),       # ... and 24
 ])
 def test_chunkwise_prefill_equals_one_pass(B, Hq, Hkv, L, D, r, W, C):
     case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} C{C}"
@@ -112,6 +115,7 @@ def test_cache_updates_with_sinks_are_exact_gathers(B, Hkv, D, r, L, sinks):
     (2, 4, 2, 2500, 128, 8, 110, 1000, 7, True),     # window longer than a chunk
     (1, 2, 2, 1100, 64, 4, 100, 300, 33, False),     # sinks with the sliding window, D = 64
     (1, 2, 1, 900, 128, 4, 3, 256, 300, True),       # the first chunk lies inside the sinks
+    (1, 4, 2, 1500, 96, 4, 25, 400, 128, True),      # head dimension 96
 ])
 def test_chunkwise_prefill_with_sinks_equals_one_pass(B, Hq, Hkv, L, D, r, W, C, sinks, units):
     case = f"B{B} Hq{Hq} Hkv{Hkv} L{L} D{D} r{r} W{W} C{C} sinks{sinks} units{int(units)}"

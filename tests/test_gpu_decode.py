@@ -17,6 +17,9 @@ CASES = [
     (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
     (2, 4, 2, 500, 128, True), (1, 8, 1, 700, 128, False), (3, 16, 2, 129, 64, True), (1, 32, 1, 300, 128, False),
     (2, 16, 1, 200, 64, True), (2, 15, 1, 333, 128, True), (1, 12, 4, 1000, 128, False),
+    # other head dimensions: the matrix-core kernel (groups up to 15 heads) and the vector kernel (fp32; larger groups)
+    (2, 8, 2, 700, 96, True), (1, 4, 1, 300, 80, False), (3, 4, 4, 129, 32, True), (1, 32, 1, 300, 96, False),
+    (2, 16, 1, 200, 48, True), (1, 8, 2, 2100, 112, False),
 ]
 
 

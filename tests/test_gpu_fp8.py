@@ -26,7 +26,7 @@ def special_values():
     return np.concatenate([x, np.zeros(pad, np.float32)])
 
 
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [64, 128, 32])
 def test_quantiser_is_bit_exact_on_the_special_values(D):
     x = special_values().reshape(1, 1, -1, D)
     for c in (1.0, 0.75, 1.1, 0.013):
@@ -39,7 +39,8 @@ def test_quantiser_is_bit_exact_on_the_special_values(D):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32], ids=["bf16", "f32"])
-@pytest.mark.parametrize("B,H,n,D", [(2, 3, 517, 128), (1, 8, 64, 64), (3, 1, 1, 128), (1, 2, 0, 64)])
+@pytest.mark.parametrize("B,H,n,D", [(2, 3, 517, 128), (1, 8, 64, 64), (3, 1, 1, 128), (1, 2, 0, 64), (2, 2, 77, 96),
+                                     (1, 3, 130, 48)])
 def test_quantiser_is_bit_exact_on_cache_rows(B, H, n, D, dtype):
     _, k, v, _ = synth.attn_inputs(B, H, H, max(n, 1), D, dtype=dtype, seed=51)
     k = (k[:, :, :n] * 1.7).to(dtype).contiguous()      # wider than the scales assume: some values saturate
@@ -57,6 +58,8 @@ CASES = [
     (2, 8, 2, 300, 64, True), (1, 4, 1, 2100, 64, False), (64, 4, 1, 40, 128, True),
     (2, 4, 2, 500, 128, True), (1, 8, 1, 700, 128, False), (3, 16, 2, 129, 64, True), (1, 32, 1, 300, 128, False),
     (2, 16, 1, 200, 64, True), (2, 15, 1, 333, 128, True), (1, 12, 4, 1000, 128, False),
+    # other head dimensions (multiples of 16 for one-byte codes): matrix-core kernel and, for a group of 16, the vector kernel
+    (2, 8, 2, 700, 96, True), (1, 4, 1, 300, 80, False), (3, 4, 4, 129, 32, True), (1, 16, 1, 300, 112, False),
 ]
 
 
@@ -112,6 +115,7 @@ def test_quantised_cache_through_updates_then_decode():
 @pytest.mark.parametrize("Hq,Hkv,D,L,C,r,W,sinks,units", [
     (8, 2, 128, 1500, 400, 4, 64, 0, False),
     (4, 1, 64, 900, 256, 4, 5, 40, True),       # sinks and a window of whole units, D = 64, ragged last chunk
+    (4, 2, 96, 1100, 300, 4, 64, 0, False),     # head dimension 96
 ])
 def test_chunkwise_prefill_over_codes(Hq, Hkv, D, L, C, r, W, sinks, units):
     # the prompt goes through a cache of one-byte rows chunk by chunk: every chunk's rows equal attention over the

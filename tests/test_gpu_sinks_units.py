@@ -35,6 +35,8 @@ SMALL = [
     (1, 2, 2, 63, 128, 1, 3, 2, True),       # r = 1
     (1, 2, 2, 90, 64, 4, 3, 500, True),      # more sinks than tokens: causal
     (1, 8, 8, 200, 64, 16, 2, 9, True),      # 8 kv heads
+    (1, 4, 2, 700, 96, 4, 11, 130, True),    # head dimension 96
+    (2, 2, 1, 333, 56, 4, 8, 7, True),       # ... and 56
 ]
 
 

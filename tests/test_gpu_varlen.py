@@ -44,6 +44,8 @@ SMALL = [
     (2, 1, 128, 2**31 - 2, 33, [150, 150]),            # no gists
     (8, 8, 64, 16, 64, [100, 100]),                    # 8 kv heads
     (2, 2, 128, 4, 16, [700]),                         # one document == the plain entry point's case
+    (4, 2, 96, 4, 40, [257, 1, 300, 130]),             # head dimension 96
+    (2, 1, 40, 2, 50, [200, 333]),                     # ... and 40
 ]
 
 

@@ -62,5 +62,5 @@ def test_refuses_what_does_not_fit():
                                   u.UNIGIST_BF16, None)
     assert rc == 4 and "scratch" in u.unigist_status_str(rc)
     assert u.unigist_decode_noalloc(None, None, None, None, None, 1, 4, 1, 100, None, 128, u.UNIGIST_BF16, None) == 1
-    assert u.unigist_decode_noalloc(x.data_ptr(), x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 1, 4, 1, 100, None, 96,
+    assert u.unigist_decode_noalloc(x.data_ptr(), x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 1, 4, 1, 100, None, 100,
                                     u.UNIGIST_BF16, None) == 2
