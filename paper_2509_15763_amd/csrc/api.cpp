@@ -50,7 +50,11 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 }  // namespace
 
 extern "C" const char* unigist_status_str(unigist_status s) {
-    switch (s) {
+    // callers in other languages pass any integer: read it as one (an out-of-range value held in the enum type is
+    // undefined behaviour to load in C++)
+    int code;
+    memcpy(&code, &s, sizeof code);
+    switch (code) {
         case UNIGIST_OK: return "ok";
         case UNIGIST_EINVAL: return "invalid argument";
         case UNIGIST_EUNSUPPORTED: return "unsupported head dim, dtype or size";
