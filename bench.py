@@ -254,7 +254,7 @@ def main():
     # what a kernel that only reads a buffer of that size reaches on this machine: the ceiling the memory system delivers
     stream_gbs = None
     if not args.no_probe:
-        stream_gbs = max(u.probe_read_rate(int(dec_bytes) // 16 * 16, blocks=nb) for nb in (2048, 8192))
+        stream_gbs = max(u.probe_read_rate(int(dec_bytes) // 16 * 16, blocks=nb) for nb in (2048, 4096, 8192, 16384))
     # the same cache stored as E4M3 codes (one byte per element, per-kv-head scales): half the bytes to stream
     ks_, vs_ = synth.e4m3_scales(dc["Hkv"], seed=0, device=dev)
     k8_, v8_ = u.quantize_e4m3(dk_, ks_), u.quantize_e4m3(dv_, vs_)

@@ -38,19 +38,23 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict
     }
 }
 
-// Streaming read: every lane pulls 16-byte pieces, a wave 1 KiB at a time, the grid striding over the buffer; the
-// values are folded into one word per lane that is written only if it takes an impossible value.
+// Streaming read: a workgroup takes 32 KiB pieces of the buffer (eight 16-byte loads in flight per lane, each wave
+// reading 1 KiB runs), the grid striding over the buffer; the values are folded into one word per lane that is
+// written only if it takes an impossible value.
 __global__ __launch_bounds__(256) void read_rate_kernel(const u32x4* __restrict__ buf, size_t n16, unsigned* __restrict__ sink) {
-    u32x4 acc = {0u, 0u, 0u, 0u};
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {  // four independent loads in flight per lane
-        const u32x4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
-        acc ^= a ^ b ^ c ^ d;
+    constexpr int U = 8;
+    unsigned acc = 0u;
+    const size_t stride = (size_t)gridDim.x * 256 * U;
+    size_t i = (size_t)blockIdx.x * 256 * U + threadIdx.x;
+    for (; i + 256 * (U - 1) < n16; i += stride) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = buf[i + 256 * u];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
     }
-    for (; i < n16; i += stride) acc ^= buf[i];
-    const unsigned x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
-    if (x == 0x9e3779b9u && sink[1] == 1u) sink[0] = x;  // keeps the loads alive; sink[1] is never 1
+    for (; i < n16; i += 256) acc ^= buf[i][0];  // the ragged end of the last piece
+    if (acc == 0x9e3779b9u && sink[1] == 1u) sink[0] = acc;  // keeps the loads alive; sink[1] is never 1
 }
 
 }  // namespace

@@ -15,7 +15,7 @@ def _replay_equals_eager(make_inputs, run, n_replays=3):
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        run(*static)                       # warm-up outside the capture (loads the library, creates helper streams)
+        run(*static)                       # warm-up outside the capture (loads the library)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
@@ -61,8 +61,8 @@ def test_decode_in_a_graph():
 
 
 def test_packed_backward_in_a_graph():
-    # the packed backward forks onto the library's helper streams and joins them again: inside a capture the
-    # helpers become branches of the same graph
+    # the bf16 packed backward is one launch of each kernel over a document table that travels as a kernel argument:
+    # the table is baked into the captured launches, so the replays must reproduce the eager result bit for bit
     Hq, Hkv, D, r, W = 4, 2, 128, 4, 64
     lens = [700, 90, 1300, 257, 33, 410]
     cu = [0]
