@@ -64,3 +64,35 @@ def test_refuses_what_does_not_fit():
     assert u.unigist_decode_noalloc(None, None, None, None, None, 1, 4, 1, 100, None, 128, u.UNIGIST_BF16, None) == 1
     assert u.unigist_decode_noalloc(x.data_ptr(), x.data_ptr(), x.data_ptr(), x.data_ptr(), None, 1, 4, 1, 100, None, 100,
                                     u.UNIGIST_BF16, None) == 2
+
+
+def test_under_graph_capture():
+    # what the entry point is for: a captured decode step that allocates nothing; replays with new cache contents
+    # equal the eager unigist_decode bit for bit
+    B, Hq, Hkv, Lk, D = 3, 8, 2, 1500, 128
+    q, kc, vc = (t.cuda() for t in synth.decode_inputs(B, Hq, Hkv, Lk, D, seed=21))
+    out = torch.zeros_like(q)
+    lse = torch.zeros(B, Hq, device="cuda")
+    dt = u.binding._dt(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):   # first call outside the capture: looks up the scratch array's address on this device
+        assert u.unigist_decode_noalloc(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), lse.data_ptr(), B, Hq, Hkv,
+                                        Lk, None, D, dt, side.cuda_stream) == 0
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        rc = u.unigist_decode_noalloc(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), lse.data_ptr(), B, Hq, Hkv,
+                                      Lk, None, D, dt, torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    for n in range(3):
+        q2, k2, v2 = (t.cuda() for t in synth.decode_inputs(B, Hq, Hkv, Lk, D, seed=30 + n))
+        q.copy_(q2), kc.copy_(k2), vc.copy_(v2)
+        out.zero_(), lse.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want_o, want_l = u.decode(q, kc, vc)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want_o) and torch.equal(lse, want_l), n
