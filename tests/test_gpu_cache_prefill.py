@@ -554,10 +554,11 @@ def test_ring_cache_moves_one_byte_rows_bit_exactly():
         assert torch.equal(kc[b, :, :len(pos)].cpu(), k[b][:, pos]) and torch.equal(vc[b, :, :len(pos)].cpu(), v[b][:, pos])
 
 
-def test_prefill_on_projection_layout_equals_prefill_on_copies():
+@pytest.mark.parametrize("D", [128, 96])
+def test_prefill_on_projection_layout_equals_prefill_on_copies(D):
     # q as a projection layer leaves it, [B, C, Hq, D], passed as its transposed view: out comes back in the same
     # layout, same bits as with a contiguous [B, Hq, C, D] copy; a row slice without out= / lse= takes the same path
-    B, Hq, Hkv, D, r, W, C, L = 2, 4, 2, 128, 4, 60, 300, 900
+    B, Hq, Hkv, r, W, C, L = 2, 4, 2, 4, 60, 300, 900
     q, k, v, _ = synth.attn_inputs(B, Hq, Hkv, L, D, seed=32)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     cache = u.KVCache(B, Hkv, L, D, r)

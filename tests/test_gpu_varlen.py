@@ -224,7 +224,7 @@ def test_every_gradient_row_is_written():
     assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
 
 
-@pytest.mark.parametrize("D", [128, 64])
+@pytest.mark.parametrize("D", [128, 64, 96])
 @pytest.mark.parametrize("sinks,units,W", [(0, False, 100), (20, True, 7)], ids=["sliding", "sinks_units"])
 def test_packed_projection_layout_gives_the_same_bits(sinks, units, W, D):
     # q, out, dout, dq laid out [T, Hq, D] in memory, as a packed projection output: same bits as the [Hq, T, D] call
