@@ -729,17 +729,23 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const bf16_t* __restrict__ q,
         choff[i] = (!QSTR || 8 * sc < Dt) ? sc * 16 : 0;  // a chunk the rows do not have: any chunk will do
     }
     auto issue = [&](int it, int buf) {
+        // Tile row rr is, in the gist phase, the (it * BNQ + rr)-th always-visible position, clamped to the last far
+        // one; in the window phase position wstart + (it - ngt) * BNQ + rr, clamped to the last position.  The phase
+        // only selects wave-uniform parameters, so the per-lane arithmetic has no branch.
         const bool gphase = it < ngt;
+        const int a = gphase ? it * BNQ : wstart + (it - ngt) * BNQ;
+        const int bnd = gphase ? nfar - 1 : L - 1;
+        const int first_gist = gphase ? S : 0x7fffffff;  // entries from here on are gists
+        const int gm = gphase ? rp1 : 1, go = gphase ? 1 : 0;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int rr = (wv * IPW + i) * RPI + lrow;
+            const int c = min(a + rr, bnd);
             int row;
-            if (gphase) {  // the (it * BNQ + rr)-th always-visible position, clamped to the last far one
-                const int c = min(it * BNQ + rr, nfar - 1);
-                row = c < S ? c : S + (c - S) * rp1 + rp1 - 1;
-            } else {
-                row = min(wstart + (it - ngt) * BNQ + rr, L - 1);
-            }
+            if constexpr (GEN)  // entry c >= S is gist c - S at S + (c - S)(r+1) + r; factors < 2^24 by the size limit
+                row = c < first_gist ? c : S + mul24(c - S + 1, rp1) - 1;
+            else
+                row = mul24(c + go, gm) - go;
             const unsigned off = (unsigned)row * (unsigned)(Dt * 2) + (unsigned)choff[i];
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);

@@ -207,19 +207,24 @@ __global__ __launch_bounds__(NT, 3) void fwd_mfma_kernel(const bf16_t* __restric
         // Tile row rr is, in the gist phase, the (it * BN + rr)-th always-visible position (a sink, or gist g at
         // S + (r+1) g + r), clamped to the last far one; in the window phase position wstart + (it - ngt) * BN + rr,
         // clamped to the last position.  Its row in the buffer: position - s0 + ngb, except for the entries in
-        // front (entry c < ngb sits in row c).
+        // front (entry c < ngb sits in row c).  The phase only selects wave-uniform parameters, so the per-lane
+        // arithmetic has no branch.
         const bool gphase = it < ngt;
+        const int a = gphase ? it * BN : wstart + (it - ngt) * BN;
+        const int bnd = gphase ? nfar - 1 : L - 1;
+        const int first_gist = gphase ? S : 0x7fffffff;  // entries from here on are gists
+        const int in_front = gphase ? ngb : 0;           // entries below this sit in the row of their own number
+        const int gm = gphase ? rp1 : 1, go = gphase ? 1 : 0;
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int rr = (wv * IPW + i) * RPI + lrow;
-            int row;
-            if (gphase) {
-                const int c = min(it * BN + rr, nfar - 1);
-                const int pos = c < S ? c : S + (c - S) * rp1 + rp1 - 1;
-                row = c < ngb ? c : pos - s0 + ngb;
-            } else {
-                row = min(wstart + (it - ngt) * BN + rr, L - 1) - s0 + ngb;
-            }
+            const int c = min(a + rr, bnd);
+            int pos;
+            if constexpr (GEN)  // entry c >= S is gist c - S at S + (c - S)(r+1) + r; factors < 2^24 by the size limit
+                pos = c < first_gist ? c : S + mul24(c - S + 1, rp1) - 1;
+            else
+                pos = mul24(c + go, gm) - go;
+            const int row = c < in_front ? c : pos - s0 + ngb;
             const unsigned off = (unsigned)row * (unsigned)(Dt * 2) + (unsigned)choff[i];  // < 2^32 by the size limit
             g2l16(kbytes + off, &sm.k[buf][(wv * IPW + i) * 1024]);
             g2l16(vbytes + off, &sm.v[buf][(wv * IPW + i) * 1024]);

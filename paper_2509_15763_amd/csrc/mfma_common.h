@@ -33,6 +33,13 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 }
 __device__ __forceinline__ f32x4 zero4() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
 
+// a * b for factors below 2^24 on the full-rate 24-bit multiplier (the compiler picks the quarter-rate 32-bit one).
+__device__ __forceinline__ int mul24(int a, int b) {
+    int r;
+    asm("v_mul_u32_u24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Chunk swizzle for tiles read in that shape: chunk ch of tile row r is stored at chunk position ch ^ swz16(r).
 // Its period of 16 rows puts the 16 rows of a row-wise fragment read and the 4 rows of a transposing read on
 // distinct banks; the two transposing reads of a fragment lie 16 rows apart and so share one address register.
