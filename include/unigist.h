@@ -555,6 +555,16 @@ unigist_status unigist_plan_key_tile(int B, int Hq, int Hkv, int L, int D, int r
                                      int gist_phase, int tile, int seg, int* c_lo, int* c_hi, int capacity, int* nfar,
                                      signed char* kind);
 
+/*
+ * Launch order of the gist phase of that plan (dense bf16 launches; Sec. 4.2): workgroup `unit` (0 .. slot0[n_segs]-1
+ * per batch entry and kv head) handles compact tile *tile of segment *seg.  Units that walk a whole segment come
+ * first, segment-major from the last segment down; the shorter ones (tiles first reached inside their segment) come
+ * last, longest first, so that the end of the launch is filled evenly.  Every (segment, tile) slot of the plan occurs
+ * exactly once.  UNIGIST_EINVAL for a unit outside the plan or invalid arguments.
+ */
+unigist_status unigist_plan_gist_unit(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks, int window_mode,
+                                      int unit, int* seg, int* tile);
+
 /* Tile sizes the forward / backward kernels use for head dim D (for the live-tile report). */
 void unigist_tile_sizes(int D, unigist_dtype dt, int* Bm, int* Bn);
 

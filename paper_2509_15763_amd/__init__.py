@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     unigist_attn_fwd, unigist_attn_bwd, unigist_attn_bwd_stages, unigist_attn_bwd_workspace,
     BWD_STAGES, UNIGIST_BWD_ALL,
     unigist_decode, unigist_decode_workspace, unigist_decode_noalloc, unigist_decode_noalloc_scratch_bytes, unigist_debug_force_plain_alu, unigist_window_start,
-    unigist_plan_row_tile, unigist_bwd_plan_build, unigist_plan_key_tile, UNIGIST_WALK_FWD, UNIGIST_WALK_DQ,
+    unigist_plan_row_tile, unigist_bwd_plan_build, unigist_plan_key_tile, unigist_plan_gist_unit, UNIGIST_WALK_FWD, UNIGIST_WALK_DQ,
     unigist_blockmap_build,
     unigist_status_str, unigist_tile_sizes, unigist_probe_mfma_rate, probe_mfma_rate, unigist_probe_read_rate, probe_read_rate,
     UNIGIST_E4M3, unigist_quantize_e4m3, unigist_decode_e4m3, quantize_e4m3, decode_e4m3,

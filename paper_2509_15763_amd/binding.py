@@ -34,7 +34,7 @@ EXPORTS = [
     "unigist_attn_fwd_varlen_strided", "unigist_attn_bwd_varlen_strided",
     "unigist_cache_ring_rows", "unigist_cache_to_ring", "unigist_cache_from_ring", "unigist_cache_ring_append",
     "unigist_decode_noalloc", "unigist_decode_noalloc_scratch_bytes", "unigist_debug_force_plain_alu",
-    "unigist_window_start", "unigist_plan_row_tile", "unigist_bwd_plan_build", "unigist_plan_key_tile",
+    "unigist_window_start", "unigist_plan_row_tile", "unigist_bwd_plan_build", "unigist_plan_key_tile", "unigist_plan_gist_unit",
     "unigist_probe_read_rate",
 ]
 
@@ -116,6 +116,8 @@ def load():
     lib.unigist_plan_row_tile.argtypes = [ip] * 7 + [C.POINTER(_RowTilePlan), ip, vp]
     lib.unigist_bwd_plan_build.restype = ip
     lib.unigist_bwd_plan_build.argtypes = [ip] * 9 + [C.POINTER(_BwdPlan)]
+    lib.unigist_plan_gist_unit.restype = ip
+    lib.unigist_plan_gist_unit.argtypes = [ip] * 10 + [C.POINTER(ip), C.POINTER(ip)]
     lib.unigist_plan_key_tile.restype = ip
     lib.unigist_plan_key_tile.argtypes = [ip] * 12 + [C.POINTER(ip), C.POINTER(ip), ip, vp, vp]
     lib.unigist_window_start.restype = ip
@@ -340,6 +342,14 @@ def unigist_bwd_plan_build(B, Hq, Hkv, L, D, r, W, sinks=0, window_mode=UNIGIST_
     d = {n: getattr(p, n) for n, _ in _BwdPlan._fields_ if n != "slot0"}
     d["slot0"] = list(p.slot0)[: p.n_segs + 1]
     return d
+
+
+def unigist_plan_gist_unit(B, Hq, Hkv, L, D, r, W, sinks, window_mode, unit) -> tuple:
+    """-> (segment, compact tile) of the gist-phase workgroup `unit` in launch order."""
+    seg, tile = C.c_int(0), C.c_int(0)
+    _check(load().unigist_plan_gist_unit(B, Hq, Hkv, L, D, r, W, sinks, window_mode, unit, C.byref(seg), C.byref(tile)),
+           "unigist_plan_gist_unit")
+    return seg.value, tile.value
 
 
 def unigist_plan_key_tile(B, Hq, Hkv, L, D, r, W, sinks, window_mode, gist_phase, tile, seg=0) -> dict:

@@ -66,6 +66,7 @@ BwdPlan make_plan(const AttnShape& s) {
     BwdPlan p;
     plan_counts(s, p, pick_segc(gist_chunk_steps(s) * s.B * s.Hkv));
     plan_slots(s, p);
+    plan_order(s, p);
     const size_t a = 255;
     size_t off = ((size_t)s.B * s.Hq * s.L * sizeof(float) + a) & ~a;
     p.off_lse2 = off;  // lse * log2(e), written by the delta pass
@@ -203,7 +204,9 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
     if (GIST) {
         // One workgroup per (segment, compact tile the segment reaches), segment-major, late (fully populated)
         // segments first: the workgroups running together on an XCD then stream the same Q/dO chunks of the same
-        // head through its L2.  unit counts the slots of pl.slot0 from the last segment down.
+        // head through its L2.  A dense launch puts the shorter units -- tiles first reached inside their segment --
+        // at the end, longest first, where they even out the last round (gist_unit); a document of a pack counts
+        // the slots of its own plan from the last segment down.
         seg = pl.nseg - 1;
         if constexpr (PACK) {  // the document's plan has no table: sum the segments' tile counts
             int rem = unit, nt;
@@ -217,8 +220,7 @@ __global__ __launch_bounds__(NT, 2) void dkdv_kernel(const bf16_t* __restrict__ 
             nslots = slot - tile + nt + (unit - rem);
         } else {
             nslots = pl.slot0[pl.nseg];
-            while (seg > 0 && nslots - pl.slot0[seg] <= unit) --seg;
-            tile = unit - (nslots - pl.slot0[seg + 1]);
+            gist_unit(pl, unit, seg, tile);
             slot = pl.slot0[seg] + tile;
         }
         const ChunkRange cr = gist_tile_chunks(s, pl, tile, seg);

@@ -206,3 +206,14 @@ extern "C" unigist_status unigist_plan_key_tile(int B, int Hq, int Hkv, int L, i
     }
     return UNIGIST_OK;
 }
+
+extern "C" unigist_status unigist_plan_gist_unit(int B, int Hq, int Hkv, int L, int D, int r, int W, int sinks,
+                                                 int window_mode, int unit, int* seg, int* tile) {
+    if (!seg || !tile || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || (D < 8 || D > 128 || D % 8 != 0)) return UNIGIST_EINVAL;
+    if (!shape_ok(L, r, W, sinks, window_mode)) return UNIGIST_EINVAL;
+    const AttnShape s = make_shape(B, Hq, Hkv, L, D, r, W, sinks, window_mode);
+    const BwdPlan p = make_bwd_plan(s);
+    if (unit < 0 || unit >= p.slot0[p.nseg]) return UNIGIST_EINVAL;
+    gist_unit(p, unit, *seg, *tile);
+    return UNIGIST_OK;
+}

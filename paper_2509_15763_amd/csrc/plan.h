@@ -12,6 +12,8 @@
 //     workgroup per compact tile of BNK entries and segment of chunks) and every key from far(c) on in the window
 //     phase (one workgroup per BNK contiguous keys).
 #pragma once
+#include <algorithm>
+
 #include "common.h"
 
 namespace unigist {
@@ -58,6 +60,7 @@ __host__ __device__ inline int row_step_kind(const RowWalk& w, int it, int Bn, i
 constexpr int BNK = 128;        // keys (or compact entries) per dK/dV workgroup, 32 per wave
 constexpr int MQ = 64;          // query rows per chunk, two blocks of 32
 constexpr int kMaxSegs = 32;    // segments per gist tile at most
+constexpr int kMaxLateUnits = 512;  // gist-phase units ordered by length at the end of a launch at most
 
 struct BwdPlan {
     int NC;      // query chunks of MQ rows
@@ -68,6 +71,15 @@ struct BwdPlan {
     // one per compact tile some chunk of the segment reaches (tiles 0 .. slot0[sg+1]-slot0[sg]-1: a tile is reached
     // by every chunk from its first one on).  slot0[nseg] = slots in all.
     int slot0[kMaxSegs + 1];
+    // Launch order of the gist-phase workgroups of a dense launch.  First the n_even units that walk their whole
+    // segment (the tile is reached from the segment's first chunk on; all of one length), segment-major from the last
+    // segment down: even0[i] = such units in the i segments launched first, so the workgroups running together still
+    // stream the same Q/dO chunks.  Then the n_late units of the tiles first reached inside their segment, longest
+    // first, which fill the end of the launch: late[u] = segment << 10 | tile - (even units of the segment).
+    // n_even < 0: plain segment-major order (packed launches, and plans whose late units do not fit the table).
+    int n_even = -1, n_late = 0;
+    int even0[kMaxSegs + 1];
+    unsigned short late[kMaxLateUnits];
     size_t off_lse2, off_part, off_comp, total;  // byte offsets into the workspace (delta sits at 0)
 };
 
@@ -130,6 +142,26 @@ inline void plan_slots(const AttnShape& s, BwdPlan& p) {
     for (int sg = 0; sg < p.nseg; ++sg) p.slot0[sg + 1] = p.slot0[sg] + seg_tiles(s, p, sg);
 }
 
+// gist-phase unit (workgroup) -> segment and compact tile of a dense launch, in the order described at BwdPlan
+__host__ __device__ inline void gist_unit(const BwdPlan& p, int unit, int& seg, int& tile) {
+    if (p.n_even < 0) {  // segment-major from the last segment down, the tiles of a segment in order
+        const int nslots = p.slot0[p.nseg];
+        seg = p.nseg - 1;
+        while (seg > 0 && nslots - p.slot0[seg] <= unit) --seg;
+        tile = unit - (nslots - p.slot0[seg + 1]);
+    } else if (unit < p.n_even) {
+        int i = 0;
+        while (p.even0[i + 1] <= unit) ++i;
+        seg = p.nseg - 1 - i;
+        tile = unit - p.even0[i];
+    } else {
+        const int e = p.late[unit - p.n_even];
+        seg = e >> 10;
+        const int i = p.nseg - 1 - seg;
+        tile = p.even0[i + 1] - p.even0[i] + (e & 1023);
+    }
+}
+
 // chunks c_lo .. c_hi (inclusive; none if c_lo > c_hi) a dK/dV workgroup streams
 struct ChunkRange {
     int c_lo, c_hi;
@@ -142,6 +174,32 @@ __host__ __device__ inline ChunkRange gist_tile_chunks(const AttnShape& s, const
     r.c_hi = ((seg + 1) * p.segc < p.NC ? (seg + 1) * p.segc : p.NC) - 1;
     return r;
 }
+// fills the launch order (host; needs slot0)
+inline void plan_order(const AttnShape& s, BwdPlan& p) {
+    p.n_even = -1;
+    p.n_late = 0;
+    int even[kMaxSegs], nl = 0;
+    struct Late { int len, code; } late[kMaxLateUnits];
+    for (int sg = p.nseg - 1; sg >= 0; --sg) {
+        const int nt = p.slot0[sg + 1] - p.slot0[sg];
+        const int ne = (nfar_of_chunk(s, sg * p.segc) + BNK - 1) / BNK;  // tiles the segment's first chunk reaches
+        even[sg] = ne < nt ? ne : nt;
+        for (int t = even[sg]; t < nt; ++t) {
+            if (nl == kMaxLateUnits || t - even[sg] > 1023) return;
+            const ChunkRange cr = gist_tile_chunks(s, p, t, sg);
+            late[nl++] = Late{cr.c_hi - cr.c_lo + 1, sg << 10 | (t - even[sg])};
+        }
+    }
+    std::stable_sort(late, late + nl, [](const Late& a, const Late& b) { return a.len > b.len; });  // longest first
+    p.even0[0] = 0;
+    for (int i = 0; i < p.nseg; ++i) p.even0[i + 1] = p.even0[i] + even[p.nseg - 1 - i];
+    for (int i = p.nseg + 1; i <= kMaxSegs; ++i) p.even0[i] = p.even0[p.nseg];
+    for (int i = 0; i < nl; ++i) p.late[i] = (unsigned short)late[i].code;
+    for (int i = nl; i < kMaxLateUnits; ++i) p.late[i] = 0;
+    p.n_even = p.even0[p.nseg];
+    p.n_late = nl;
+}
+
 // window phase: the keys BNK tile .. BNK tile + BNK - 1
 __host__ __device__ inline ChunkRange window_tile_chunks(const AttnShape& s, const BwdPlan& p, int tile) {
     ChunkRange r;

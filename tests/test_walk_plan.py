@@ -40,15 +40,29 @@ class KeySide:
         segc, nseg, slot0 = bp["seg_chunks"], bp["n_segs"], bp["slot0"]
         assert slot0[0] == 0 and len(slot0) == nseg + 1 and nseg <= 32
         segs_of_tile = defaultdict(list)
+        chunks_of = {}
         for sg in range(nseg):
             assert slot0[sg + 1] >= slot0[sg]
             for t in range(slot0[sg + 1] - slot0[sg]):
                 p = u.unigist_plan_key_tile(B, Hq, Hkv, L, D, r, W, sinks, mode, 1, t, sg)
+                chunks_of[(sg, t)] = (p["c_lo"], p["c_hi"])
                 # a workgroup of the plan has work, inside its segment
                 assert sg * segc <= p["c_lo"] <= p["c_hi"] < min((sg + 1) * segc, bp["n_chunks"]), (sg, t, p["c_lo"], p["c_hi"])
                 segs_of_tile[t].append(sg)
                 for n, c in enumerate(range(p["c_lo"], p["c_hi"] + 1)):
                     self.gist[c].append((t, int(p["nfar"][n]), p["kind"][:, n]))
+        # launch order of the gist phase: every slot exactly once; either plain segment-major from the last segment
+        # down, or the units that walk a whole segment first (in that order) and the shorter ones last, longest first
+        order = [u.unigist_plan_gist_unit(B, Hq, Hkv, L, D, r, W, sinks, mode, n) for n in range(slot0[nseg])]
+        assert sorted(order) == sorted(chunks_of)
+        plain = [(sg, t) for sg in range(nseg - 1, -1, -1) for t in range(slot0[sg + 1] - slot0[sg])]
+        if order != plain:
+            whole = [chunks_of[x][0] == x[0] * segc for x in order]
+            k = whole.index(False) if False in whole else len(order)
+            assert not any(whole[k:]) and order[:k] == [x for x in plain if chunks_of[x][0] == x[0] * segc]
+            lens = [chunks_of[x][1] - chunks_of[x][0] + 1 for x in order[k:]]
+            assert lens == sorted(lens, reverse=True) and (not lens or lens[0] <= segc)
+        self.reordered = order != plain
         # the reduction adds, for every compact tile, the slots of all segments from its first one to the last
         assert sorted(segs_of_tile) == list(range(bp["n_gist_tiles"]))
         for t, sgs in segs_of_tile.items():
@@ -158,6 +172,7 @@ def test_benchmark_shape_32k_every_row():
     assert bp["slot0"][-1] <= 0.55 * bp["n_gist_tiles"] * bp["n_segs"]
     assert bp["workspace_bytes"] == u.unigist_attn_bwd_workspace(c["B"], c["Hq"], c["Hkv"], c["L"], c["D"], c["r"], c["W"], 0)
     assert bp["workspace_bytes"] <= 510e6
+    assert ks.reordered  # the short units of this shape fit the launch-order table
 
 
 def test_long_context_128k_spread_of_tiles():
