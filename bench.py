@@ -194,11 +194,19 @@ def main():
     # pair), its recomputed S and dP are overhead and not counted.
     alg = {"fwd": flops_fwd, "dkdv_gist": 8.0 * D * far_pairs * B * Hq,
            "dkdv_window": 8.0 * D * (nvis - far_pairs) * B * Hq, "dq": 2.0 * D * nvis * B * Hq}
-    dom = max(alg, key=lambda n: ms[n])
+    # Dominant = the launch that carries most of the step's algorithmic FLOPs (the gist-phase dK/dV kernel: 43 % of
+    # the step's 14*D per pair on this workload).  It and the dQ kernel take the same time to within a percent,
+    # so "the longest" would flip from box to box; every kernel's own figure is in `kernels` beside it.
+    dom = max(alg, key=lambda n: alg[n])
     achieved = alg[dom] / ms[dom] / 1e9
     roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom),
-                "avg_ms": ms[dom], "alg_flops_per_launch": alg[dom]}
+                "avg_ms": ms[dom], "alg_flops_per_launch": alg[dom],
+                "kernels": {n: {"avg_ms": ms[n], "alg_flops_per_launch": alg[n],
+                                "frac": alg[n] / ms[n] / 1e9 / PEAK_BF16_TFLOPS,
+                                # the dQ kernel executes three contractions (S, dP, dQ) to count one
+                                "executed_frac": (3.0 if n == "dq" else 1.0) * alg[n] / ms[n] / 1e9 / PEAK_BF16_TFLOPS,
+                                "traffic": TRAFFIC_BYTES.get(n)} for n in alg}}
 
     # what the matrix cores sustain on register-resident operands, outside the timed region: the chip is
     # power-limited, so the rate with operands like the workload's (random) is below the published peak
