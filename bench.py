@@ -36,8 +36,8 @@ WORKLOAD = "cfg2_llama8b_32k"
 
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy); see profiles/.  None = not measured yet.
-TRAFFIC_BYTES = {"fwd": 1033400000, "dkdv_gist": 2584000000, "dkdv_window": 1464600000, "dq": 1401100000,
-                 "decode": 4669900000, "decode_e4m3": 2285100000}
+TRAFFIC_BYTES = {"fwd": 1038100000, "dkdv_gist": 2257700000, "dkdv_window": 1473500000, "dq": 1408400000,
+                 "decode": 4669700000, "decode_e4m3": 2285100000}
 
 
 def pair_counts(L, r, W):
