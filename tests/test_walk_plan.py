@@ -218,6 +218,25 @@ def test_other_shapes(B, Hq, Hkv, L, D, r, W, sinks, units):
     run_shape(B, Hq, Hkv, L, D, r, W, sinks, units, tiles)
 
 
+def test_launch_order_falls_back_to_segment_major_when_the_short_units_do_not_fit_the_table():
+    # ratio 1 at 196 608 tokens: 128-chunk segments, each first reaching 17 compact tiles inside it -- more short
+    # units than the 512 the plan carries, so the gist phase is launched in plain segment-major order
+    B, Hq, Hkv, L, D, r, W = 1, 2, 1, 196608, 64, 1, 64
+    bp = u.unigist_bwd_plan_build(B, Hq, Hkv, L, D, r, W)
+    nseg, slot0 = bp["n_segs"], bp["slot0"]
+    plain = [(sg, t) for sg in range(nseg - 1, -1, -1) for t in range(slot0[sg + 1] - slot0[sg])]
+    assert len(plain) == slot0[nseg] > 9000
+    for n in list(range(0, len(plain), 37)) + [len(plain) - 1]:
+        assert u.unigist_plan_gist_unit(B, Hq, Hkv, L, D, r, W, 0, 0, n) == plain[n]
+    # half the length fits: a permutation that is not the plain order
+    L = 98304
+    bp = u.unigist_bwd_plan_build(B, Hq, Hkv, L, D, r, W)
+    nseg, slot0 = bp["n_segs"], bp["slot0"]
+    plain = [(sg, t) for sg in range(nseg - 1, -1, -1) for t in range(slot0[sg + 1] - slot0[sg])]
+    order = [u.unigist_plan_gist_unit(B, Hq, Hkv, L, D, r, W, 0, 0, n) for n in range(slot0[nseg])]
+    assert sorted(order) == sorted(plain) and order != plain
+
+
 def test_closed_forms_of_the_sliding_mode_agree_with_the_search():
     # In the sliding mode the first and last chunk of a dK/dV workgroup come from closed forms, in the unit mode from
     # a binary search over the monotone far(c).  A unit window of W units and r = 1 ... is not a sliding window, so
