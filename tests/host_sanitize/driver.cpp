@@ -63,6 +63,20 @@ static void walk_plans(const Shape& s) {
                                         nullptr) == UNIGIST_EINVAL);
         }
     }
+    // the gist phase's launch order: every slot of the plan exactly once
+    const int nslots = bp.slot0[bp.n_segs];
+    std::vector<char> seen(nslots, 0);
+    for (int unit = 0; unit < nslots; ++unit) {
+        int sg = -1, t = -1;
+        CHECK(unigist_plan_gist_unit(s.B, s.Hq, s.Hkv, s.L, s.D, s.r, s.W, s.sinks, s.mode, unit, &sg, &t) == UNIGIST_OK);
+        CHECK(sg >= 0 && sg < bp.n_segs && t >= 0 && t < bp.slot0[sg + 1] - bp.slot0[sg]);
+        CHECK(!seen[bp.slot0[sg] + t]);
+        seen[bp.slot0[sg] + t] = 1;
+    }
+    int sg, t;
+    CHECK(unigist_plan_gist_unit(s.B, s.Hq, s.Hkv, s.L, s.D, s.r, s.W, s.sinks, s.mode, nslots, &sg, &t) == UNIGIST_EINVAL);
+    CHECK(unigist_plan_gist_unit(s.B, s.Hq, s.Hkv, s.L, s.D, s.r, s.W, s.sinks, s.mode, -1, &sg, &t) == UNIGIST_EINVAL);
+    CHECK(unigist_plan_gist_unit(s.B, s.Hq, s.Hkv, s.L, s.D, s.r, s.W, s.sinks, s.mode, 0, nullptr, &t) == UNIGIST_EINVAL);
 }
 
 static void block_maps(const Shape& s) {
